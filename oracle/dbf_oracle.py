@@ -1,0 +1,179 @@
+"""CPU oracle for the Double Binary Factorization (DBF) layer forward.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP
+path is checked against.  Only tests/, __graft_entry__.smoke() and bench.py's
+cpu_baseline leg may import it; the product path never does.  It shares no
+code with the HIP path and imports nothing from it.
+
+What it computes (paper, section 3, "Double binary factorization"):
+
+    W' = (a . A . m^T)(B . b^T)          -- the factorised weight, n_out x n_in
+    Y  = X W'^T                          -- the layer output, batch x n_out
+
+with A (n_out x k) and B (k x n_in) sign matrices, a, m, b vectors.  The
+method reaches exactly this dense product (it only re-associates it), so the
+oracle is the definition written out in IEEE fp64: decode the signs, form W'
+densely, multiply.  `forward_staged` evaluates the paper's forward-pass
+expression left to right instead; both must agree to rounding.
+
+Parity pins (tests/test_oracle_pins.py): k=1 rank-one closed form, brute-force
+sum of outer products on tiny shapes (exhaustive for <= 2x2x2), all-ones
+closed form, pure-Python fsum re-evaluation, invariances of the middle index,
+variance law for random signs, packing round trip, the bits-per-weight
+numbers the paper prints.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# ---------------------------------------------------------------------------
+# Decoding of the interchange formats
+# ---------------------------------------------------------------------------
+
+
+def f16_bits_to_f64(u16) -> np.ndarray:
+    """IEEE binary16 bit patterns (uint16) -> float64, exactly."""
+    u16 = np.ascontiguousarray(u16, dtype=np.uint16)
+    return u16.view(np.float16).astype(np.float64)
+
+
+def unpack_signs(words, rows: int, cols: int) -> np.ndarray:
+    """Canonical packed words -> float64 matrix of +-1.
+
+    Element c of row r is bit (c mod 32), least significant first, of word
+    (c div 32) of that row; a set bit is +1, a clear bit is -1.
+    """
+    words = np.asarray(words, dtype=np.uint32).reshape(rows, -1)
+    need = (cols + 31) // 32
+    if words.shape[1] != need:
+        raise ValueError("expected %d words per row, got %d" % (need, words.shape[1]))
+    out = np.empty((rows, cols), dtype=np.float64)
+    for c in range(cols):
+        bit = (words[:, c // 32] >> np.uint32(c % 32)) & np.uint32(1)
+        out[:, c] = np.where(bit == 1, 1.0, -1.0)
+    return out
+
+
+def pack_signs(S) -> np.ndarray:
+    """Matrix of +-1 -> canonical packed words (inverse of unpack_signs)."""
+    S = np.asarray(S)
+    if S.ndim != 2:
+        raise ValueError("sign matrix must be 2-D")
+    if not np.all((S == 1) | (S == -1)):
+        raise ValueError("entries must be -1 or +1")
+    rows, cols = S.shape
+    words = np.zeros((rows, (cols + 31) // 32), dtype=np.uint32)
+    for c in range(cols):
+        plus = (S[:, c] == 1).astype(np.uint32)
+        words[:, c // 32] |= plus << np.uint32(c % 32)
+    return words
+
+
+# ---------------------------------------------------------------------------
+# The forward product
+# ---------------------------------------------------------------------------
+
+
+def dense_weight(a, A, m, B, b) -> np.ndarray:
+    """W' = diag(a) A diag(m) B diag(b) in fp64 (section 3, factorisation)."""
+    a = np.asarray(a, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    n_out, k = A.shape
+    k2, n_in = B.shape
+    if k != k2 or a.shape != (n_out,) or m.shape != (k,) or b.shape != (n_in,):
+        raise ValueError("shape mismatch")
+    left = a[:, None] * A * m[None, :]      # a . A . m^T
+    right = B * b[None, :]                  # B . b^T
+    return left @ right
+
+
+def forward_dense(X, a, A, m, B, b) -> np.ndarray:
+    """Y = X W'^T with W' formed densely (section 3, forward pass)."""
+    X = np.asarray(X, dtype=np.float64)
+    W = dense_weight(a, A, m, B, b)
+    return X @ W.T
+
+
+def forward_staged(X, a, A, m, B, b) -> np.ndarray:
+    """((((X . b^T) B^T) . m^T) A^T) . a^T, left to right, fp64."""
+    X = np.asarray(X, dtype=np.float64)
+    a = np.asarray(a, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    B = np.asarray(B, dtype=np.float64)
+    u = X * b[None, :]
+    t = u @ B.T
+    t = t * m[None, :]
+    v = t @ A.T
+    return v * a[None, :]
+
+
+def forward_from_packed(X_f16_bits, layer, mode: str = "dense") -> np.ndarray:
+    """Decode a packed layer (canonical words + fp16 bit patterns) and run it.
+
+    `layer` needs attributes n_in, n_out, k, A_bits, B_bits, a, m, b.
+    X_f16_bits is (batch, n_in) uint16.  Returns float64 (batch, n_out).
+    """
+    A = unpack_signs(layer.A_bits, layer.n_out, layer.k)
+    B = unpack_signs(layer.B_bits, layer.k, layer.n_in)
+    a = f16_bits_to_f64(layer.a)
+    m = f16_bits_to_f64(layer.m)
+    b = f16_bits_to_f64(layer.b)
+    X = f16_bits_to_f64(X_f16_bits).reshape(-1, layer.n_in)
+    if mode == "dense":
+        return forward_dense(X, a, A, m, B, b)
+    if mode == "staged":
+        return forward_staged(X, a, A, m, B, b)
+    raise ValueError("mode must be 'dense' or 'staged'")
+
+
+# ---------------------------------------------------------------------------
+# Storage accounting (section 3, "Middle dimension size" / "Storage size")
+# ---------------------------------------------------------------------------
+
+
+def bits_per_weight(n: int, m: int, k: int) -> float:
+    """Sign bits stored per original weight: k (n + m) / (n m)."""
+    return k * (n + m) / (n * m)
+
+
+def middle_dim_for_bits(bits: float, n: int, m: int) -> int:
+    """k = bits * n m / (n + m), rounded down to an integer."""
+    return int(np.floor(bits * n * m / (n + m)))
+
+
+def scale_vector_bits_per_weight(n: int, m: int, k: int) -> float:
+    """Cost of the three fp16 vectors (sizes n, k, m) per original weight."""
+    return 16.0 * (n + k + m) / (n * m)
+
+
+def step_bits_per_weight(n: int, m: int, step: int = 32) -> float:
+    """Change in bits/weight when the middle size moves by `step`."""
+    return step * (n + m) / (n * m)
+
+
+# ---------------------------------------------------------------------------
+# Error measure used by the parity gate
+# ---------------------------------------------------------------------------
+
+
+def gated_relative_error(y_test, y_ref) -> float:
+    """max_i |y_test - y_ref| / max(|y_ref|, rms(y_ref)), per output row.
+
+    A pure element-wise relative error is meaningless where random-sign sums
+    cancel to almost zero, so each element is measured against the larger of
+    its own magnitude and the row's rms.
+    """
+    y_test = np.asarray(y_test, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    if y_ref.ndim == 1:
+        y_ref = y_ref[None, :]
+        y_test = y_test[None, :]
+    rms = np.sqrt(np.mean(y_ref * y_ref, axis=1, keepdims=True))
+    denom = np.maximum(np.abs(y_ref), rms)
+    denom = np.where(denom == 0.0, 1.0, denom)
+    return float(np.max(np.abs(y_test - y_ref) / denom)) if y_ref.size else 0.0

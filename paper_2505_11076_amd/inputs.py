@@ -1,0 +1,123 @@
+"""Seeded synthetic inputs for Double Binary Factorization (DBF) layers.
+
+This module only draws random numbers and arranges them in the canonical
+interchange formats.  It holds none of the method's arithmetic (no products,
+no rescales), so the CPU oracle's tests and the HIP path's tests can both feed
+from it without sharing any code that computes a result.
+
+Operands of one layer (paper, section 3, "Double binary factorization" and
+"Middle dimension size"): sign matrices A (n_out x k) and B (k x n_in) with
+entries in {-1,+1}, fp16 vectors a (n_out), m (k), b (n_in), fp16 input X
+(batch x n_in).
+
+Canonical bit format (the paper fixes none; this is the interchange format of
+this library): row-major, the reduction dimension runs fastest, element c of a
+row is bit (c & 31), LSB first, of 32-bit word (c >> 5); bit 1 means +1, bit 0
+means -1; the unused high bits of a row's last word are zero.
+
+Recipe (stands in for the compressed Llama layers the paper times): signs are
+i.i.d. +-1 with p = 1/2, the three scale vectors are fp16(0.02 * U[0.5, 1.5)),
+activations are fp16(N(0, 1)).  Seed = 1000 * config + index.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+def seed_for(config: int, index: int = 0) -> int:
+    return 1000 * int(config) + int(index)
+
+
+def words_per_row(cols: int) -> int:
+    return (int(cols) + 31) // 32
+
+
+def random_sign_words(rng: np.random.Generator, rows: int, cols: int) -> np.ndarray:
+    """rows x ceil(cols/32) uint32 words of i.i.d. fair bits, tail bits cleared."""
+    w = words_per_row(cols)
+    words = rng.integers(0, 1 << 32, size=(rows, w), dtype=np.uint64).astype(np.uint32)
+    tail = cols & 31
+    if tail:
+        words[:, -1] &= np.uint32((1 << tail) - 1)
+    return words
+
+
+def random_signs(rng: np.random.Generator, rows: int, cols: int) -> np.ndarray:
+    """rows x cols int8 matrix of i.i.d. +-1."""
+    return (rng.integers(0, 2, size=(rows, cols), dtype=np.int8) * 2 - 1).astype(np.int8)
+
+
+def random_scale_fp16(rng: np.random.Generator, n: int) -> np.ndarray:
+    """fp16(0.02 * U[0.5, 1.5)) returned as fp16 bit patterns (uint16)."""
+    v = (0.02 * rng.uniform(0.5, 1.5, size=n)).astype(np.float16)
+    return v.view(np.uint16).copy()
+
+
+def random_activations_fp16(rng: np.random.Generator, batch: int, n_in: int) -> np.ndarray:
+    """fp16(N(0,1)) of shape (batch, n_in) as fp16 bit patterns (uint16)."""
+    v = rng.standard_normal(size=(batch, n_in)).astype(np.float16)
+    return v.view(np.uint16).copy()
+
+
+@dataclass
+class LayerInputs:
+    n_in: int
+    n_out: int
+    k: int
+    A_bits: np.ndarray  # uint32 [n_out, ceil(k/32)]   canonical words
+    B_bits: np.ndarray  # uint32 [k, ceil(n_in/32)]    canonical words
+    a: np.ndarray       # uint16 [n_out]  fp16 bit patterns
+    m: np.ndarray       # uint16 [k]
+    b: np.ndarray       # uint16 [n_in]
+
+
+def make_layer(n_in: int, n_out: int, k: int, seed: int) -> LayerInputs:
+    rng = np.random.default_rng(seed)
+    A_bits = random_sign_words(rng, n_out, k)
+    B_bits = random_sign_words(rng, k, n_in)
+    a = random_scale_fp16(rng, n_out)
+    m = random_scale_fp16(rng, k)
+    b = random_scale_fp16(rng, n_in)
+    return LayerInputs(n_in, n_out, k, A_bits, B_bits, a, m, b)
+
+
+def make_activations(batch: int, n_in: int, seed: int) -> np.ndarray:
+    rng = np.random.default_rng(seed + 500)
+    return random_activations_fp16(rng, batch, n_in)
+
+
+# ---------------------------------------------------------------------------
+# The five workload families (shapes only; sizes follow Llama-2-7B).
+# ---------------------------------------------------------------------------
+
+CONFIG1 = dict(n_in=512, n_out=512, k=256)                       # ~1 bit/weight, smoke size
+CONFIG2 = dict(n_in=4096, n_out=4096, k=2048)                    # attention projection, 1.0 bpw
+CONFIG3 = [                                                      # MLP shapes, ~1 and ~2 bpw
+    dict(n_in=4096, n_out=11008, k=2985),
+    dict(n_in=4096, n_out=11008, k=5970),
+    dict(n_in=11008, n_out=4096, k=2985),
+    dict(n_in=11008, n_out=4096, k=5970),
+]
+CONFIG4 = [                                                      # prefill shapes, T = 2048
+    dict(n_in=4096, n_out=4096, k=4096, T=2048),
+    dict(n_in=11008, n_out=4096, k=5970, T=2048),
+]
+
+
+def llama2_7b_stack_shapes(n_blocks: int = 32) -> list[dict]:
+    """Linear layers of a Llama-2-7B-shaped decoder at 1.5 bits per weight.
+
+    Per block: q, k, v, o (4096 -> 4096), gate, up (4096 -> 11008),
+    down (11008 -> 4096).  The middle size is floor(1.5 * n*m / (n+m)):
+    3072 for the square layers and 4477 for the MLP layers.
+    """
+    out = []
+    for _ in range(n_blocks):
+        for _ in range(4):
+            out.append(dict(n_in=4096, n_out=4096, k=3072))
+        for _ in range(2):
+            out.append(dict(n_in=4096, n_out=11008, k=4477))
+        out.append(dict(n_in=11008, n_out=4096, k=4477))
+    return out
