@@ -1,0 +1,172 @@
+/*
+ * libdbf -- Double Binary Factorization (DBF) layer products on AMD MI355X (gfx950).
+ *
+ * One DBF layer stands for a weight matrix W (n_out x n_in) through
+ *
+ *     W' = diag(a) * A * diag(m) * B * diag(b)
+ *
+ * with sign matrices A (n_out x k) and B (k x n_in), entries in {-1,+1}, and
+ * fp16 vectors a (n_out), m (k), b (n_in).  The layer product is
+ *
+ *     Y = X * W'^T = ((((X . b^T) B^T) . m^T) A^T) . a^T          (batch x n_out)
+ *
+ * (paper, section 3: the factorisation, the forward-pass expression that follows
+ * it, and "Middle dimension size" for the shapes).  Inside the two sign products
+ * only additions and subtractions are needed (section 3.1, "Inference costs").
+ *
+ * Conventions common to every entry point
+ *   - Plain C ABI.  Every function that can fail returns one of the DBF_* codes
+ *     below and never throws or aborts.  Arguments are validated before any GPU
+ *     call, so all argument errors are reported even on a machine without a GPU.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device memory of the GPU the layer was packed on.  The caller owns every
+ *     buffer it passes in; the library owns what a dbf_layer / dbf_stack holds
+ *     until dbf_free / dbf_stack_free.
+ *   - fp16 values cross the boundary as IEEE binary16 bit patterns (uint16_t on
+ *     the host, 2-byte elements on the device).
+ *   - Launching entry points (dbf_gemv*, dbf_gemm, dbf_stack_gemv) are
+ *     asynchronous on the caller's HIP stream (a hipStream_t passed as void*,
+ *     NULL = the default stream), allocate nothing and do not synchronise.  A
+ *     layer holds scratch for its middle activations, so one layer (or stack)
+ *     must not run on two streams at the same time.
+ *   - Non-finite activations give unspecified (but memory-safe) results.
+ *
+ * Canonical sign-bit format (the paper defines none; this is the interchange
+ * format): row-major, reduction dimension fastest; element c of a row is bit
+ * (c & 31), least significant first, of 32-bit word (c >> 5) of that row; a set
+ * bit means +1, a clear bit -1; unused high bits of a row's last word are zero.
+ * A is n_out rows of ceil(k/32) words, B is k rows of ceil(n_in/32) words.
+ */
+#ifndef DBF_H
+#define DBF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dbf_layer dbf_layer; /* one packed layer; opaque; owns device memory */
+typedef struct dbf_stack dbf_stack; /* a group of layers run in one launch; opaque  */
+
+enum {
+    DBF_OK = 0,
+    DBF_EINVAL = -1,     /* null pointer, bad enum value, batch/T out of range     */
+    DBF_ESHAPE = -2,     /* n_in, n_out or k < 1, or beyond the supported maximum  */
+    DBF_ENOTSIGN = -3,   /* a sign entry other than -1/+1, or dirty tail bits      */
+    DBF_ENOMEM = -4,     /* host or device allocation failed                       */
+    DBF_EHIP = -5,       /* a HIP runtime call or kernel launch failed             */
+    DBF_EWORKSPACE = -6  /* workspace missing, misaligned or too small             */
+};
+
+/* Which decode kernel dbf_gemv_kind runs. */
+enum {
+    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses: the fastest variant for the shape             */
+    DBF_GEMV_VALU = 1, /* fp32 add/subtract per sign bit on the vector ALU (exact fp32 sums) */
+    DBF_GEMV_MFMA = 2  /* sign bytes fed to the int8 matrix cores as the adder; the input
+                          vector of each stage is rounded once to 16-bit fixed point       */
+};
+
+#define DBF_MAX_BATCH 16       /* largest batch dbf_gemv / dbf_stack_gemv accept */
+#define DBF_MAX_DIM (1 << 20)  /* largest n_in, n_out or k                       */
+
+/* ---- packing (offline, once per layer) -------------------------------------------------
+ * Section 3 ("Double binary factorization"): the five operands of a layer.
+ *
+ * dbf_pack: A_pm1 (host, n_out*k int8, row-major) and B_pm1 (host, k*n_in int8, row-major)
+ * hold -1/+1; a, m, b (host) hold n_out, k, n_in fp16 bit patterns.  Converts the signs to
+ * bits, re-tiles them into the device layout, uploads everything to the current HIP device
+ * and returns a new layer in *out.  Any k >= 1 is accepted (padding is internal).
+ * Errors: DBF_EINVAL (null), DBF_ESHAPE, DBF_ENOTSIGN (entry not -1/+1), DBF_ENOMEM,
+ * DBF_EHIP (no usable GPU).  On error *out is set to NULL.
+ *
+ * dbf_pack_bits: the same from canonical packed words (host).  DBF_ENOTSIGN if a row's
+ * unused tail bits are not zero.
+ *
+ * dbf_unpack_bits: inverse of dbf_pack_bits; copies the layer back from the device into
+ * host buffers of the canonical sizes (any output pointer may be NULL to skip it).
+ * Synchronises the device.  Bit-exact round trip.
+ */
+int dbf_pack(int n_in, int n_out, int k, const int8_t* A_pm1, const int8_t* B_pm1,
+             const uint16_t* a, const uint16_t* m, const uint16_t* b, dbf_layer** out);
+int dbf_pack_bits(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32_t* B_bits,
+                  const uint16_t* a, const uint16_t* m, const uint16_t* b, dbf_layer** out);
+int dbf_unpack_bits(const dbf_layer* layer, uint32_t* A_bits, uint32_t* B_bits,
+                    uint16_t* a, uint16_t* m, uint16_t* b);
+/* Shapes and the device memory the layer holds (any output pointer may be NULL). */
+int dbf_dims(const dbf_layer* layer, int* n_in, int* n_out, int* k, size_t* device_bytes);
+void dbf_free(dbf_layer* layer); /* NULL is allowed */
+
+/* ---- host-side layout helpers (no GPU needed) ------------------------------------------
+ * The device layout of a rows x cols sign matrix (reduction over cols): rows are padded to
+ * a multiple of 128 and cols to a multiple of 64 with zero bits; the matrix is cut into
+ * tiles of 128 rows x 64 cols stored row-tile major, 1024 bytes each.  In a tile, byte
+ * (256*g + 16*r + j), 0<=g<4, 0<=r<16, 0<=j<16, holds in its bit s (0<=s<8) the sign of
+ * element (row 16*s + r, col 16*g + j) of the tile.  A wavefront reads one tile with one
+ * coalesced 16-byte load per lane and owns, per lane, sixteen columns of eight rows.
+ *
+ * dbf_tiled_bytes: size of the tiled image (0 if rows or cols is out of range).
+ * dbf_signs_to_bits_host: int8 -1/+1 (rows*cols) -> canonical words; DBF_ENOTSIGN otherwise.
+ * dbf_tile_host / dbf_untile_host: canonical words <-> tiled image (both host), bit-exact
+ * inverses of each other; dbf_tile_host returns DBF_ENOTSIGN for dirty tail bits.
+ */
+size_t dbf_tiled_bytes(int rows, int cols);
+int dbf_signs_to_bits_host(int rows, int cols, const int8_t* pm1, uint32_t* bits);
+int dbf_tile_host(int rows, int cols, const uint32_t* bits, uint8_t* tiled);
+int dbf_untile_host(int rows, int cols, const uint8_t* tiled, uint32_t* bits);
+
+/* ---- decode: Y = X W'^T for a few tokens -----------------------------------------------
+ * The forward-pass expression of section 3, evaluated in two launches: the B stage
+ * t = ((x . b) B^T) . m (the middle rescale is fused into its epilogue), then the A stage
+ * y = (t A^T) . a.  fp32 (or exact integer) accumulation, fp32 middle activations.
+ *
+ * x_dev: device, fp16 [batch][n_in] row-major, tightly packed.
+ * y_dev: device, fp16 [batch][n_out] row-major, written in full.
+ * batch: 1..DBF_MAX_BATCH.  Errors: DBF_EINVAL, DBF_EHIP.
+ * dbf_gemv_kind selects the kernel variant (DBF_GEMV_*); dbf_gemv is DBF_GEMV_AUTO.
+ */
+int dbf_gemv(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, void* hip_stream);
+int dbf_gemv_kind(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, int kind,
+                  void* hip_stream);
+
+/* ---- prefill: the same product for T tokens as two matrix-core contractions ------------
+ * (The paper times batch 1 only, section 4.4; rows of X are independent, so the product is
+ * defined for any T by the same expression.)  Sign tiles are expanded to +-scale fp16 in
+ * registers and multiplied with fp16 X on the matrix cores with fp32 accumulation; the
+ * middle activations are rounded once to fp16.
+ *
+ * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1.
+ * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes,
+ * 256-byte aligned, contents undefined on return.  Errors: DBF_EINVAL, DBF_EWORKSPACE,
+ * DBF_EHIP.  dbf_gemm_workspace_bytes returns 0 for a NULL layer or T < 1.
+ */
+size_t dbf_gemm_workspace_bytes(const dbf_layer* layer, int T);
+int dbf_gemm(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
+             void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* ---- a group of independent layer products in one launch pair --------------------------
+ * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
+ * benchmark stream of layers): all B stages run in one launch and all A stages in a second,
+ * so the sign bits stream from HBM without a launch gap per layer.
+ *
+ * dbf_stack_create: layers[0..n_layers) must stay alive while the stack exists; the stack
+ * only holds a device table describing them.  n_layers >= 1.
+ * dbf_stack_gemv: x_dev is the concatenation over layers of fp16 [batch][n_in_i] blocks,
+ * y_dev the concatenation of fp16 [batch][n_out_i] blocks; layer i's blocks start at
+ * element offsets batch * (sum of n_in_j, j<i) and batch * (sum of n_out_j, j<i), which
+ * dbf_stack_offsets also reports.
+ */
+int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** out);
+int dbf_stack_offsets(const dbf_stack* stack, int layer_index, int batch,
+                      size_t* x_offset_elems, size_t* y_offset_elems);
+int dbf_stack_gemv(const dbf_stack* stack, const void* x_dev, void* y_dev, int batch, int kind,
+                   void* hip_stream);
+void dbf_stack_free(dbf_stack* stack); /* NULL is allowed */
+
+const char* dbf_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBF_H */

@@ -1,0 +1,199 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared entry
+point, its host-side packer and tile layout are bit-exact, and every argument
+error is reported before any GPU call.  No kernel is launched here.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2505_11076_amd import binding as B
+from paper_2505_11076_amd import inputs as I
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dbf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dbf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared_symbols()
+    assert len(names) >= 18
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(B.EXPORTS) == names
+
+
+def test_strerror_covers_all_codes():
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        msg = B.strerror(code)
+        assert msg and msg != "unknown error code"
+        seen.add(msg)
+    assert len(seen) == 7
+    assert B.strerror(-99) == "unknown error code"
+
+
+# ---- sign -> bit conversion -----------------------------------------------------------------------
+
+
+def _bits_by_hand(S):
+    """Canonical words by Python integer arithmetic (independent of both packers)."""
+    rows, cols = S.shape
+    out = np.zeros((rows, (cols + 31) // 32), dtype=np.uint32)
+    for r in range(rows):
+        for c in range(cols):
+            if S[r, c] == 1:
+                out[r, c // 32] |= np.uint32(1 << (c % 32))
+    return out
+
+
+@pytest.mark.parametrize("cols", [1, 31, 32, 33, 64, 100, 256])
+def test_signs_to_bits_host(cols):
+    rng = np.random.default_rng(cols)
+    S = I.random_signs(rng, 7, cols)
+    got = B.dbf_signs_to_bits_host(S)
+    assert np.array_equal(got, _bits_by_hand(S))
+
+
+def test_signs_to_bits_rejects_non_signs():
+    for bad in (0, 2, -2, 127):
+        S = np.ones((3, 40), dtype=np.int8)
+        S[2, 39] = bad
+        with pytest.raises(B.DbfError) as e:
+            B.dbf_signs_to_bits_host(S)
+        assert e.value.code == B.DBF_ENOTSIGN
+
+
+# ---- tile layout --------------------------------------------------------------------------------------
+
+
+def _tile_by_formula(rows, cols, bits):
+    """The documented layout, element by element: byte 256g+16r+j, bit s of tile
+    (rt, ct) is the sign at (128rt + 16s + r, 64ct + 16g + j)."""
+    n_rt, n_ct = (rows + 127) // 128, (cols + 63) // 64
+    out = np.zeros(n_rt * n_ct * 1024, dtype=np.uint8)
+    for row in range(rows):
+        rt, s, r = row // 128, (row % 128) // 16, row % 16
+        for col in range(cols):
+            if (int(bits[row, col // 32]) >> (col % 32)) & 1:
+                ct, g, j = col // 64, (col % 64) // 16, col % 16
+                out[(rt * n_ct + ct) * 1024 + 256 * g + 16 * r + j] |= np.uint8(1 << s)
+    return out
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (16, 64), (128, 64), (129, 65), (200, 130), (300, 97), (17, 200)])
+def test_tile_host_matches_documented_layout(shape):
+    rows, cols = shape
+    rng = np.random.default_rng(rows * 1000 + cols)
+    bits = I.random_sign_words(rng, rows, cols)
+    tiled = B.dbf_tile_host(rows, cols, bits)
+    assert tiled.size == B.dbf_tiled_bytes(rows, cols) == ((rows + 127) // 128) * ((cols + 63) // 64) * 1024
+    assert np.array_equal(tiled, _tile_by_formula(rows, cols, bits))
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (5, 31), (128, 64), (2985, 100), (100, 2985), (256, 5970), (513, 4096)])
+def test_tile_round_trip(shape):
+    rows, cols = shape
+    rng = np.random.default_rng(rows * 7 + cols)
+    bits = I.random_sign_words(rng, rows, cols)
+    tiled = B.dbf_tile_host(rows, cols, bits)
+    back = B.dbf_untile_host(rows, cols, tiled)
+    assert np.array_equal(back, bits)
+
+
+def test_tile_host_padding_is_zero():
+    rows, cols = 130, 70
+    bits = np.full((rows, 3), 0xFFFFFFFF, dtype=np.uint32)
+    bits[:, 2] = (1 << (cols - 64)) - 1
+    tiled = B.dbf_tile_host(rows, cols, bits)
+    total_set = int(np.unpackbits(tiled).sum())
+    assert total_set == rows * cols
+
+
+def test_tile_host_rejects_dirty_tail():
+    bits = np.zeros((4, 2), dtype=np.uint32)
+    bits[3, 1] = 1 << 20  # column 52 of a 40-column matrix
+    lib = B.lib()
+    out = np.zeros(B.dbf_tiled_bytes(4, 40), dtype=np.uint8)
+    assert lib.dbf_tile_host(4, 40, bits.ctypes.data, out.ctypes.data) == B.DBF_ENOTSIGN
+
+
+def test_tiled_bytes_out_of_range():
+    assert B.dbf_tiled_bytes(0, 5) == 0
+    assert B.dbf_tiled_bytes(5, -1) == 0
+    assert B.dbf_tiled_bytes(1 << 21, 5) == 0
+
+
+# ---- argument errors of the GPU entry points (reported with no GPU present) ------------------
+
+
+def _small_operands():
+    L = I.make_layer(n_in=40, n_out=24, k=33, seed=5)
+    return L
+
+
+def test_pack_argument_errors():
+    lib = B.lib()
+    L = _small_operands()
+    h = C.c_void_p(123)
+    p = lambda arr: arr.ctypes.data
+    # null pointers
+    assert lib.dbf_pack_bits(40, 24, 33, None, p(L.B_bits), p(L.a), p(L.m), p(L.b), C.byref(h)) == B.DBF_EINVAL
+    assert h.value is None
+    assert lib.dbf_pack_bits(40, 24, 33, p(L.A_bits), p(L.B_bits), p(L.a), p(L.m), p(L.b), None) == B.DBF_EINVAL
+    assert lib.dbf_pack(40, 24, 33, None, None, p(L.a), p(L.m), p(L.b), C.byref(h)) == B.DBF_EINVAL
+    # shapes
+    for bad in ((0, 24, 33), (40, 0, 33), (40, 24, 0), (-1, 24, 33), ((1 << 20) + 1, 24, 33)):
+        assert lib.dbf_pack_bits(*bad, p(L.A_bits), p(L.B_bits), p(L.a), p(L.m), p(L.b), C.byref(h)) == B.DBF_ESHAPE
+    # non-sign entries are found before the GPU is touched
+    A = np.ones((24, 33), dtype=np.int8)
+    Bm = np.ones((33, 40), dtype=np.int8)
+    Bm[32, 39] = 0
+    assert lib.dbf_pack(40, 24, 33, p(A), p(Bm), p(L.a), p(L.m), p(L.b), C.byref(h)) == B.DBF_ENOTSIGN
+    # dirty tail bits in canonical words
+    Ab = L.A_bits.copy()
+    Ab[0, -1] |= np.uint32(1 << 31)
+    assert lib.dbf_pack_bits(40, 24, 33, p(Ab), p(L.B_bits), p(L.a), p(L.m), p(L.b), C.byref(h)) == B.DBF_ENOTSIGN
+
+
+def test_launch_argument_errors():
+    lib = B.lib()
+    assert lib.dbf_gemv(None, 1, 1, 1, None) == B.DBF_EINVAL
+    assert lib.dbf_gemv_kind(None, 1, 1, 1, 0, None) == B.DBF_EINVAL
+    assert lib.dbf_gemm(None, 1, 1, 1, 1, 1, None) == B.DBF_EINVAL
+    assert lib.dbf_gemm_workspace_bytes(None, 5) == 0
+    assert lib.dbf_unpack_bits(None, None, None, None, None, None) == B.DBF_EINVAL
+    assert lib.dbf_dims(None, None, None, None, None) == B.DBF_EINVAL
+    h = C.c_void_p(0)
+    assert lib.dbf_stack_create(None, 1, C.byref(h)) == B.DBF_EINVAL
+    arr = (C.c_void_p * 1)(None)
+    assert lib.dbf_stack_create(arr, 1, C.byref(h)) == B.DBF_EINVAL
+    assert lib.dbf_stack_create(arr, 0, C.byref(h)) == B.DBF_EINVAL
+    assert lib.dbf_stack_gemv(None, 1, 1, 1, 0, None) == B.DBF_EINVAL
+    assert lib.dbf_stack_offsets(None, 0, 1, None, None) == B.DBF_EINVAL
+    lib.dbf_free(None)
+    lib.dbf_stack_free(None)
+
+
+def test_binding_rejects_wrong_host_sizes():
+    L = _small_operands()
+    with pytest.raises(B.DbfError) as e:
+        B.dbf_pack_bits(40, 24, 33, L.A_bits[:-1], L.B_bits, L.a, L.m, L.b)
+    assert e.value.code == B.DBF_ESHAPE
+
+
+def test_pack_without_gpu_reports_hip_error():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present; covered by the gpu tests")
+    L = _small_operands()
+    with pytest.raises(B.DbfError) as e:
+        B.dbf_pack_bits(40, 24, 33, L.A_bits, L.B_bits, L.a, L.m, L.b)
+    assert e.value.code == B.DBF_EHIP
