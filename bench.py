@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the DBF decode hot path on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): Llama-2-7B
+attention-projection shape n_in = n_out = 4096, k = 2048 (1.0 bit/weight), batch-1
+decode.  One layer holds only 2 MiB of sign bits -- less than a kernel launch
+costs and small enough to sit in cache -- so the sustained number is measured on
+a stream of 256 DISTINCT layers (512 MiB of signs, twice the 256 MB last-level
+cache) with independent inputs, run as one dbf_stack_gemv call.  One "step" is
+one pass of the whole path (x.b -> B stage -> .m -> A stage -> .a -> fp16 y) over
+all 256 layers.  Inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line.  `value` is the achieved rate on ALGORITHMIC bytes
+(sign bits + fp16 scale vectors + x + y; no padding, no scratch, no re-reads).
+Extra keys report the per-layer time in the stream, the cache-warm latency of a
+single isolated layer, the prefill rate, and the CPU oracle timed on this machine.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix-core peak
+
+
+def algorithmic_bytes(n_in, n_out, k, batch):
+    """Bytes one layer product has to move: packed signs, three fp16 vectors, x in, y out."""
+    bits = k * (n_in + n_out) / 8.0
+    vecs = 2.0 * (n_in + n_out + k)
+    io = 2.0 * batch * (n_in + n_out)
+    stage_b = k * n_in / 8.0 + 2.0 * (n_in + k) + 2.0 * batch * n_in
+    stage_a = k * n_out / 8.0 + 2.0 * n_out + 2.0 * batch * n_out
+    return bits + vecs + io, stage_b, stage_a
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=256, help="distinct layers in the stream")
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--kind", choices=["auto", "valu", "mfma"], default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path uses no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2505_11076_amd import binding as B
+    from paper_2505_11076_amd import inputs as I
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+    kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA}[args.kind]
+    cfg = I.CONFIG2
+    n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
+    batch, R = args.batch, args.layers
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- the stream of distinct layers ----------------------------------------------------------
+    t0 = time.time()
+    layers = []
+    for i in range(R):
+        L = I.make_layer(n_in, n_out, k, seed=I.seed_for(2, i))
+        layers.append(B.dbf_pack_bits(n_in, n_out, k, L.A_bits, L.B_bits, L.a, L.m, L.b))
+    stack = B.dbf_stack_create(layers)
+    rng = np.random.default_rng(I.seed_for(2, 999))
+    x_host = I.random_activations_fp16(rng, R * batch, n_in)
+    x_all = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
+    y_all = torch.zeros(R * batch * n_out, dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step():
+        B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # per-kernel durations, HIP events around each launch on the same stream
+    msB, msA = [], []
+    for _ in range(max(5, min(args.steps, 30))):
+        b_, a_ = B.dbf_stack_gemv_timed(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
+        msB.append(b_)
+        msA.append(a_)
+    msB_avg, msA_avg = float(np.mean(msB)), float(np.mean(msA))
+
+    bytes_layer, bytes_b, bytes_a = algorithmic_bytes(n_in, n_out, k, batch)
+    value = bytes_layer * R / (ms_per_step * 1e-3) / 1e9
+    if msB_avg >= msA_avg:
+        dom, dom_ms, dom_bytes = "B stage (dbf_stage_mfma_kernel<false,1>)", msB_avg, bytes_b * R
+    else:
+        dom, dom_ms, dom_bytes = "A stage (dbf_stage_mfma_kernel<true,1>)", msA_avg, bytes_a * R
+    if args.kind == "valu":
+        dom = dom.replace("mfma", "valu").replace(",1>", ">")
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("bench_default_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    # ---- isolated single layer, cache warm -----------------------------------------------------
+    lat = []
+    xs, ys = x_all[: batch * n_in], y_all[: batch * n_out]
+    for _ in range(20):
+        B.dbf_gemv(layers[0], xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
+    torch.cuda.synchronize()
+    for _ in range(200):
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        B.dbf_gemv(layers[0], xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
+        a1.record()
+        a1.synchronize()
+        lat.append(a0.elapsed_time(a1) * 1e3)
+    lat = np.sort(np.array(lat))
+    # back-to-back launches of the same layer (launch-rate bound)
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a0.record()
+    for _ in range(500):
+        B.dbf_gemv(layers[0], xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
+    a1.record()
+    torch.cuda.synchronize()
+    b2b_us = a0.elapsed_time(a1) * 1e3 / 500
+
+    out = {
+        "metric": "DBF layer decode achieved HBM GB/s on algorithmic bytes (batch %d, 4096x4096, k=2048, "
+                  "stream of %d distinct layers)" % (batch, R),
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32 (int8 x int8 matrix-core sums of 16-bit fixed-point inputs; fp32 scales)"
+                 if args.kind != "valu" else "f32",
+        "data": "synthetic",
+        "config": {"workload": "llama2-7b attention projection n_in=4096 n_out=4096 k=2048 (1.0 bpw), "
+                               "batch-%d decode GEMV, %d distinct layers per step" % (batch, R),
+                   "kernel_variant": args.kind, "layers_per_step": R, "batch": batch},
+        "us_per_layer_in_stream": round(ms_per_step * 1e3 / R, 4),
+        "layer_products_per_s": round(R / (ms_per_step * 1e-3), 1),
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "isolated_layer_us": {"p10": round(float(lat[20]), 2), "p50": round(float(lat[100]), 2),
+                              "p90": round(float(lat[180]), 2), "note": "one layer, cache warm, launch bound"},
+        "back_to_back_same_layer_us": round(b2b_us, 3),
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "avg_launch_ms": round(dom_ms, 5),
+                     "stage_b_ms": round(msB_avg, 5), "stage_a_ms": round(msA_avg, 5),
+                     "algorithmic_bytes_per_launch": dom_bytes},
+        "setup_s": round(setup_s, 2),
+    }
+
+    # ---- prefill (matrix-core path) ---------------------------------------------------------------
+    if not args.no_prefill:
+        try:
+            out["prefill"] = prefill_bench(B, I, torch, np, stream)
+        except Exception as exc:  # reported, never hidden
+            out["prefill"] = {"error": repr(exc)}
+
+    # ---- the CPU oracle on this machine's cores (a baseline, not the target) ---------------------
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer)
+
+    stack.close()
+    for l in layers:
+        l.close()
+    print(json.dumps(out))
+
+
+def prefill_bench(B, I, torch, np, stream):
+    res = {}
+    for cfg in I.CONFIG4:
+        n_in, n_out, k, T = cfg["n_in"], cfg["n_out"], cfg["k"], cfg["T"]
+        L = I.make_layer(n_in, n_out, k, seed=I.seed_for(4, n_in))
+        layer = B.dbf_pack_bits(n_in, n_out, k, L.A_bits, L.B_bits, L.a, L.m, L.b)
+        ws_bytes = B.dbf_gemm_workspace_bytes(layer, T)
+        if ws_bytes == 0:
+            layer.close()
+            raise RuntimeError("dbf_gemm not available")
+        X = I.make_activations(T, n_in, I.seed_for(4, n_in))
+        x = torch.from_numpy(X.view(np.int16).copy()).cuda().view(torch.float16)
+        y = torch.zeros((T, n_out), dtype=torch.float16, device="cuda")
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 10
+        e0.record()
+        for _ in range(n):
+            B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        flops = 2.0 * T * k * (n_in + n_out)
+        tf = flops / (ms * 1e-3) / 1e12
+        res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)] = {
+            "ms": round(ms, 4), "tflops": round(tf, 2), "frac_of_f16_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
+        layer.close()
+    return res
+
+
+def cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer):
+    """Times the oracle as it stands on a bounded sample: one layer of the stream, dense mode
+    (decode signs, form W' in fp64, multiply), repeated a few times."""
+    from oracle import dbf_oracle as O
+    threads = os.cpu_count() or 1
+    try:
+        from threadpoolctl import threadpool_info
+        for info in threadpool_info():
+            if info.get("user_api") == "blas":
+                threads = int(info.get("num_threads", threads))
+    except Exception:
+        pass
+    L = I.make_layer(n_in, n_out, k, seed=I.seed_for(2, 0))
+    X = I.make_activations(batch, n_in, I.seed_for(2, 0))
+    times = []
+    t_end = time.time() + 20.0
+    while len(times) < 3 or (time.time() < t_end and len(times) < 8):
+        t0 = time.time()
+        O.forward_from_packed(X, L, "dense")
+        times.append(time.time() - t0)
+        if time.time() > t_end + 40:
+            break
+    sec = float(np.median(times))
+    return {"value": round(bytes_layer / sec / 1e9, 6), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of the %s-layer stream: one 4096x4096 k=2048 layer, batch %d, dense fp64 oracle "
+                      "(decode signs, form W', multiply), median of %d runs" % (1, "256", batch, len(times)),
+            "seconds_per_layer": round(sec, 4), "layer_products_per_s": round(1.0 / sec, 4)}
+
+
+if __name__ == "__main__":
+    main()

@@ -164,6 +164,13 @@ int dbf_stack_gemv(const dbf_stack* stack, const void* x_dev, void* y_dev, int b
                    void* hip_stream);
 void dbf_stack_free(dbf_stack* stack); /* NULL is allowed */
 
+/* Measurement aid: dbf_stack_gemv with HIP events recorded on `hip_stream` around each of
+ * the two launches.  Blocks until the second launch has finished and returns the elapsed
+ * milliseconds of the B-stage kernel and of the A-stage kernel (either pointer may be NULL).
+ * Same arguments and errors as dbf_stack_gemv. */
+int dbf_stack_gemv_timed(const dbf_stack* stack, const void* x_dev, void* y_dev, int batch,
+                         int kind, void* hip_stream, float* ms_stage_b, float* ms_stage_a);
+
 const char* dbf_strerror(int code);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ EXPORTS = [
     "dbf_pack", "dbf_pack_bits", "dbf_unpack_bits", "dbf_dims", "dbf_free",
     "dbf_tiled_bytes", "dbf_signs_to_bits_host", "dbf_tile_host", "dbf_untile_host",
     "dbf_gemv", "dbf_gemv_kind", "dbf_gemm_workspace_bytes", "dbf_gemm",
-    "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_free",
+    "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed", "dbf_stack_free",
     "dbf_strerror",
 ]
 
@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
     L.dbf_stack_create.argtypes = [pp, i32, pp]
     L.dbf_stack_offsets.argtypes = [vp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
     L.dbf_stack_gemv.argtypes = [vp, vp, vp, i32, i32, vp]
+    L.dbf_stack_gemv_timed.argtypes = [vp, vp, vp, i32, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     L.dbf_stack_free.argtypes = [vp]
     L.dbf_stack_free.restype = None
     L.dbf_strerror.argtypes = [i32]
@@ -242,3 +243,12 @@ def dbf_stack_create(layers) -> Stack:
 def dbf_stack_gemv(stack: Stack, x_ptr: int, y_ptr: int, batch: int, stream: int = 0,
                    kind: int = GEMV_AUTO) -> None:
     _check(lib().dbf_stack_gemv(stack.handle, x_ptr, y_ptr, batch, kind, stream), "dbf_stack_gemv")
+
+
+def dbf_stack_gemv_timed(stack: Stack, x_ptr: int, y_ptr: int, batch: int, stream: int = 0,
+                         kind: int = GEMV_AUTO):
+    """Returns (ms of the B-stage kernel, ms of the A-stage kernel); blocks until done."""
+    mb, ma = C.c_float(0), C.c_float(0)
+    _check(lib().dbf_stack_gemv_timed(stack.handle, x_ptr, y_ptr, batch, kind, stream, C.byref(mb), C.byref(ma)),
+           "dbf_stack_gemv_timed")
+    return float(mb.value), float(ma.value)

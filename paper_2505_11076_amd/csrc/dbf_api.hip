@@ -25,12 +25,21 @@ inline bool shape_ok(int n_in, int n_out, int k) {
         }                                  \
     } while (0)
 
+// Row tiles of one stage cut into work items of at most `span` tiles.
+void append_items(std::vector<DbfWorkItem>& out, int layer, int n_rt, int span) {
+    for (int rt = 0; rt < n_rt; rt += span) {
+        const int n = (n_rt - rt < span) ? (n_rt - rt) : span;
+        out.push_back(DbfWorkItem{layer, rt, n, 0});
+    }
+}
+
 // Builds the device image of a layer from canonical words and uploads it.
 int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32_t* B_bits,
                 const uint16_t* a, const uint16_t* m, const uint16_t* b, dbf_layer** out) {
     const size_t bytesA = dbf_tiled_bytes(n_out, k), bytesB = dbf_tiled_bytes(k, n_in);
-    const int a_len = dbf_row_tiles(n_out) * DBF_TILE_ROWS;
-    const int m_len = dbf_row_tiles(k) * DBF_TILE_ROWS;
+    const int rtA = dbf_row_tiles(n_out), rtB = dbf_row_tiles(k);
+    const int a_len = rtA * DBF_TILE_ROWS;
+    const int m_len = rtB * DBF_TILE_ROWS;
     const int b_len = dbf_col_tiles(n_in) * DBF_TILE_COLS;
     const int t_stride = m_len;  // >= col_tiles(k)*64, so the A stage may read its padded columns
 
@@ -42,6 +51,8 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     const size_t offm = off;  off = align_up(off + 2 * (size_t)m_len, 256);
     const size_t offb = off;  off = align_up(off + 2 * (size_t)b_len, 256);
     const size_t offs = off;  off = align_up(off + 2 * sizeof(DbfStage), 256);
+    const size_t offwB = off; off = align_up(off + sizeof(DbfWorkItem) * rtB, 256);
+    const size_t offwA = off; off = align_up(off + sizeof(DbfWorkItem) * rtA, 256);
     const size_t image_bytes = off;  // everything up to here is uploaded
     const size_t offt = off;  off = align_up(off + 4 * (size_t)DBF_MAX_BATCH * t_stride, 256);
     const size_t total = off;
@@ -82,18 +93,25 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     L->dt = reinterpret_cast<float*>(d + offt);
     L->t_stride = t_stride;
     L->d_stages = reinterpret_cast<DbfStage*>(d + offs);
+    L->d_workB = reinterpret_cast<DbfWorkItem*>(d + offwB);
+    L->d_workA = reinterpret_cast<DbfWorkItem*>(d + offwA);
 
     DbfStage& sb = L->h_stages[0];
     sb.bits = L->dB;  sb.in_scale = L->db;  sb.row_scale = L->dm;  sb.t = L->dt;
     sb.x_off = 0;  sb.y_off = 0;
-    sb.n_rt = dbf_row_tiles(k);  sb.n_ct = dbf_col_tiles(n_in);
+    sb.n_rt = rtB;  sb.n_ct = dbf_col_tiles(n_in);
     sb.rows = k;  sb.cols = n_in;  sb.t_stride = t_stride;  sb.pad_ = 0;
     DbfStage& sa = L->h_stages[1];
     sa.bits = L->dA;  sa.in_scale = nullptr;  sa.row_scale = L->da;  sa.t = L->dt;
     sa.x_off = 0;  sa.y_off = 0;
-    sa.n_rt = dbf_row_tiles(n_out);  sa.n_ct = dbf_col_tiles(k);
+    sa.n_rt = rtA;  sa.n_ct = dbf_col_tiles(k);
     sa.rows = n_out;  sa.cols = k;  sa.t_stride = t_stride;  sa.pad_ = 0;
     std::memcpy(image + offs, L->h_stages, 2 * sizeof(DbfStage));
+    std::vector<DbfWorkItem> wB, wA;
+    append_items(wB, 0, rtB, 1);
+    append_items(wA, 0, rtA, 1);
+    std::memcpy(image + offwB, wB.data(), sizeof(DbfWorkItem) * wB.size());
+    std::memcpy(image + offwA, wA.data(), sizeof(DbfWorkItem) * wA.size());
 
     hipError_t e = hipMemcpy(dev, image, image_bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(d + offt, 0, total - offt);
@@ -109,22 +127,92 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     return DBF_OK;
 }
 
-int launch_pair(int kind, const DbfStage* dB, const DbfStage* dA, const DbfBlockRef* mapB,
-                const DbfBlockRef* mapA, int blocksB, int blocksA, int max_cols_B, int max_cols_A,
-                const void* x, void* y, int batch, hipStream_t stream) {
+// Everything a launch of the two stages needs.
+struct LaunchPlan {
+    const DbfStage* stagesB;
+    const DbfStage* stagesA;
+    const DbfWorkItem* workB1;  // one row tile per workgroup
+    const DbfWorkItem* workA1;
+    const DbfWorkItem* workBn;  // several row tiles per workgroup (may equal work*1)
+    const DbfWorkItem* workAn;
+    int blocksB1, blocksA1, blocksBn, blocksAn;
+    int max_cols_B, max_cols_A;
+};
+
+// Launches the B stage and then the A stage on `stream`.  If `mid` is not NULL it is
+// recorded between the two launches (used only by the timed entry point).
+int launch_pair(int kind, const LaunchPlan& p, const void* x, void* y, int batch,
+                hipStream_t stream, hipEvent_t mid = nullptr) {
     if (kind == DBF_GEMV_AUTO) kind = DBF_GEMV_MFMA;
-    if (kind == DBF_GEMV_VALU) {
-        DBF_HIP_TRY(dbf_launch_stage_valu(false, dB, mapB, blocksB, x, y, batch, max_cols_B, stream));
-        DBF_HIP_TRY(dbf_launch_stage_valu(true, dA, mapA, blocksA, x, y, batch, max_cols_A, stream));
-    } else {
-        DBF_HIP_TRY(dbf_launch_stage_mfma(false, dB, mapB, blocksB, x, y, batch, max_cols_B, stream));
-        DBF_HIP_TRY(dbf_launch_stage_mfma(true, dA, mapA, blocksA, x, y, batch, max_cols_A, stream));
+#ifdef DBF_DEBUG_KINDS
+    if (kind == 3 || kind == 4) {  // 3: MFMA B stage + VALU A stage, 4: VALU B + MFMA A
+        if (kind == 3) DBF_HIP_TRY(dbf_launch_stage_mfma(false, p.stagesB, p.workB1, p.blocksB1, x, y, batch, p.max_cols_B, stream));
+        else DBF_HIP_TRY(dbf_launch_stage_valu(false, p.stagesB, p.workB1, p.blocksB1, x, y, batch, p.max_cols_B, stream));
+        if (kind == 3) DBF_HIP_TRY(dbf_launch_stage_valu(true, p.stagesA, p.workA1, p.blocksA1, x, y, batch, p.max_cols_A, stream));
+        else DBF_HIP_TRY(dbf_launch_stage_mfma(true, p.stagesA, p.workA1, p.blocksA1, x, y, batch, p.max_cols_A, stream));
+        return DBF_OK;
     }
+#endif
+    if (kind == DBF_GEMV_VALU) {
+        DBF_HIP_TRY(dbf_launch_stage_valu(false, p.stagesB, p.workB1, p.blocksB1, x, y, batch,
+                                          p.max_cols_B, stream));
+        if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
+        DBF_HIP_TRY(dbf_launch_stage_valu(true, p.stagesA, p.workA1, p.blocksA1, x, y, batch,
+                                          p.max_cols_A, stream));
+        return DBF_OK;
+    }
+    // several row tiles per workgroup only if all columns of the stage fit one LDS chunk
+    const bool spanB = dbf_mfma_chunk_tiles(batch, p.max_cols_B) >= dbf_col_tiles(p.max_cols_B);
+    const bool spanA = dbf_mfma_chunk_tiles(batch, p.max_cols_A) >= dbf_col_tiles(p.max_cols_A);
+    DBF_HIP_TRY(dbf_launch_stage_mfma(false, p.stagesB, spanB ? p.workBn : p.workB1,
+                                      spanB ? p.blocksBn : p.blocksB1, x, y, batch, p.max_cols_B, stream));
+    if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
+    DBF_HIP_TRY(dbf_launch_stage_mfma(true, p.stagesA, spanA ? p.workAn : p.workA1,
+                                      spanA ? p.blocksAn : p.blocksA1, x, y, batch, p.max_cols_A, stream));
     return DBF_OK;
 }
 
 inline bool kind_ok(int kind) {
+#ifdef DBF_DEBUG_KINDS
+    if (kind == 3 || kind == 4) return true;
+#endif
     return kind == DBF_GEMV_AUTO || kind == DBF_GEMV_VALU || kind == DBF_GEMV_MFMA;
+}
+
+LaunchPlan plan_of(const dbf_layer* L) {
+    LaunchPlan p;
+    p.stagesB = L->d_stages;
+    p.stagesA = L->d_stages + 1;
+    p.workB1 = p.workBn = L->d_workB;
+    p.workA1 = p.workAn = L->d_workA;
+    p.blocksB1 = p.blocksBn = L->h_stages[0].n_rt;
+    p.blocksA1 = p.blocksAn = L->h_stages[1].n_rt;
+    p.max_cols_B = L->n_in;
+    p.max_cols_A = L->k;
+    return p;
+}
+
+LaunchPlan plan_of(const dbf_stack* S) {
+    LaunchPlan p;
+    p.stagesB = S->d_stagesB;
+    p.stagesA = S->d_stagesA;
+    p.workB1 = S->d_workB1;  p.workA1 = S->d_workA1;
+    p.workBn = S->d_workBn;  p.workAn = S->d_workAn;
+    p.blocksB1 = S->blocksB1;  p.blocksA1 = S->blocksA1;
+    p.blocksBn = S->blocksBn;  p.blocksAn = S->blocksAn;
+    p.max_cols_B = S->max_cols_B;
+    p.max_cols_A = S->max_cols_A;
+    return p;
+}
+
+int stack_span() {
+    // Row tiles per workgroup in stack launches: the input vector is quantised once per
+    // workgroup, so a larger span amortises that prologue; DBF_STACK_SPAN overrides (1..16).
+    const char* e = std::getenv("DBF_STACK_SPAN");
+    int v = e ? std::atoi(e) : 4;
+    if (v < 1) v = 1;
+    if (v > 16) v = 16;
+    return v;
 }
 
 }  // namespace
@@ -197,9 +285,7 @@ int dbf_gemv_kind(const dbf_layer* L, const void* x_dev, void* y_dev, int batch,
                   void* hip_stream) {
     if (!L || !x_dev || !y_dev) return DBF_EINVAL;
     if (batch < 1 || batch > DBF_MAX_BATCH || !kind_ok(kind)) return DBF_EINVAL;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    return launch_pair(kind, L->d_stages, L->d_stages + 1, nullptr, nullptr, L->h_stages[0].n_rt,
-                       L->h_stages[1].n_rt, L->n_in, L->k, x_dev, y_dev, batch, stream);
+    return launch_pair(kind, plan_of(L), x_dev, y_dev, batch, static_cast<hipStream_t>(hip_stream));
 }
 
 int dbf_gemv(const dbf_layer* L, const void* x_dev, void* y_dev, int batch, void* hip_stream) {
@@ -219,13 +305,14 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
     dbf_stack* S = new (std::nothrow) dbf_stack();
     if (!S) return DBF_ENOMEM;
     std::vector<DbfStage> sB(n_layers), sA(n_layers);
-    std::vector<DbfBlockRef> mB, mA;
+    std::vector<DbfWorkItem> wB1, wA1, wBn, wAn;
     S->h_x_prefix = static_cast<long long*>(std::malloc(sizeof(long long) * (n_layers + 1)));
     S->h_y_prefix = static_cast<long long*>(std::malloc(sizeof(long long) * (n_layers + 1)));
     if (!S->h_x_prefix || !S->h_y_prefix) {
         dbf_stack_free(S);
         return DBF_ENOMEM;
     }
+    const int span = stack_span();
     S->n_layers = n_layers;
     S->device = layers[0]->device;
     S->h_x_prefix[0] = S->h_y_prefix[0] = 0;
@@ -237,24 +324,30 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
         sB[i].y_off = sA[i].y_off = S->h_y_prefix[i];
         S->h_x_prefix[i + 1] = S->h_x_prefix[i] + L->n_in;
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
-        for (int rt = 0; rt < sB[i].n_rt; ++rt) mB.push_back(DbfBlockRef{i, rt});
-        for (int rt = 0; rt < sA[i].n_rt; ++rt) mA.push_back(DbfBlockRef{i, rt});
+        append_items(wB1, i, sB[i].n_rt, 1);
+        append_items(wA1, i, sA[i].n_rt, 1);
+        append_items(wBn, i, sB[i].n_rt, span);
+        append_items(wAn, i, sA[i].n_rt, span);
         if (L->n_in > S->max_cols_B) S->max_cols_B = L->n_in;
         if (L->k > S->max_cols_A) S->max_cols_A = L->k;
     }
-    S->blocksB = (int)mB.size();
-    S->blocksA = (int)mA.size();
+    S->blocksB1 = (int)wB1.size();  S->blocksA1 = (int)wA1.size();
+    S->blocksBn = (int)wBn.size();  S->blocksAn = (int)wAn.size();
 
     size_t off = 0;
     const size_t o_sB = off;  off = align_up(off + sizeof(DbfStage) * n_layers, 256);
     const size_t o_sA = off;  off = align_up(off + sizeof(DbfStage) * n_layers, 256);
-    const size_t o_mB = off;  off = align_up(off + sizeof(DbfBlockRef) * mB.size(), 256);
-    const size_t o_mA = off;  off = align_up(off + sizeof(DbfBlockRef) * mA.size(), 256);
+    const size_t o_B1 = off;  off = align_up(off + sizeof(DbfWorkItem) * wB1.size(), 256);
+    const size_t o_A1 = off;  off = align_up(off + sizeof(DbfWorkItem) * wA1.size(), 256);
+    const size_t o_Bn = off;  off = align_up(off + sizeof(DbfWorkItem) * wBn.size(), 256);
+    const size_t o_An = off;  off = align_up(off + sizeof(DbfWorkItem) * wAn.size(), 256);
     std::vector<uint8_t> image(off, 0);
     std::memcpy(image.data() + o_sB, sB.data(), sizeof(DbfStage) * n_layers);
     std::memcpy(image.data() + o_sA, sA.data(), sizeof(DbfStage) * n_layers);
-    std::memcpy(image.data() + o_mB, mB.data(), sizeof(DbfBlockRef) * mB.size());
-    std::memcpy(image.data() + o_mA, mA.data(), sizeof(DbfBlockRef) * mA.size());
+    std::memcpy(image.data() + o_B1, wB1.data(), sizeof(DbfWorkItem) * wB1.size());
+    std::memcpy(image.data() + o_A1, wA1.data(), sizeof(DbfWorkItem) * wA1.size());
+    std::memcpy(image.data() + o_Bn, wBn.data(), sizeof(DbfWorkItem) * wBn.size());
+    std::memcpy(image.data() + o_An, wAn.data(), sizeof(DbfWorkItem) * wAn.size());
     void* dev = nullptr;
     hipError_t e = hipMalloc(&dev, off);
     if (e == hipSuccess) e = hipMemcpy(dev, image.data(), off, hipMemcpyHostToDevice);
@@ -269,8 +362,10 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
     S->dev_block = dev;
     S->d_stagesB = reinterpret_cast<DbfStage*>(d + o_sB);
     S->d_stagesA = reinterpret_cast<DbfStage*>(d + o_sA);
-    S->d_mapB = reinterpret_cast<DbfBlockRef*>(d + o_mB);
-    S->d_mapA = reinterpret_cast<DbfBlockRef*>(d + o_mA);
+    S->d_workB1 = reinterpret_cast<DbfWorkItem*>(d + o_B1);
+    S->d_workA1 = reinterpret_cast<DbfWorkItem*>(d + o_A1);
+    S->d_workBn = reinterpret_cast<DbfWorkItem*>(d + o_Bn);
+    S->d_workAn = reinterpret_cast<DbfWorkItem*>(d + o_An);
     *out = S;
     return DBF_OK;
 }
@@ -287,9 +382,31 @@ int dbf_stack_gemv(const dbf_stack* S, const void* x_dev, void* y_dev, int batch
                    void* hip_stream) {
     if (!S || !x_dev || !y_dev) return DBF_EINVAL;
     if (batch < 1 || batch > DBF_MAX_BATCH || !kind_ok(kind)) return DBF_EINVAL;
+    return launch_pair(kind, plan_of(S), x_dev, y_dev, batch, static_cast<hipStream_t>(hip_stream));
+}
+
+int dbf_stack_gemv_timed(const dbf_stack* S, const void* x_dev, void* y_dev, int batch, int kind,
+                         void* hip_stream, float* ms_stage_b, float* ms_stage_a) {
+    if (!S || !x_dev || !y_dev) return DBF_EINVAL;
+    if (batch < 1 || batch > DBF_MAX_BATCH || !kind_ok(kind)) return DBF_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    return launch_pair(kind, S->d_stagesB, S->d_stagesA, S->d_mapB, S->d_mapA, S->blocksB,
-                       S->blocksA, S->max_cols_B, S->max_cols_A, x_dev, y_dev, batch, stream);
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    int rc = DBF_OK;
+    for (int i = 0; i < 3 && rc == DBF_OK; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) rc = DBF_EHIP;
+    if (rc == DBF_OK && hipEventRecord(ev[0], stream) != hipSuccess) rc = DBF_EHIP;
+    if (rc == DBF_OK) rc = launch_pair(kind, plan_of(S), x_dev, y_dev, batch, stream, ev[1]);
+    if (rc == DBF_OK && hipEventRecord(ev[2], stream) != hipSuccess) rc = DBF_EHIP;
+    if (rc == DBF_OK && hipEventSynchronize(ev[2]) != hipSuccess) rc = DBF_EHIP;
+    float mb = 0.f, ma = 0.f;
+    if (rc == DBF_OK && hipEventElapsedTime(&mb, ev[0], ev[1]) != hipSuccess) rc = DBF_EHIP;
+    if (rc == DBF_OK && hipEventElapsedTime(&ma, ev[1], ev[2]) != hipSuccess) rc = DBF_EHIP;
+    for (int i = 0; i < 3; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
+    if (rc != DBF_OK) (void)hipGetLastError();
+    if (ms_stage_b) *ms_stage_b = mb;
+    if (ms_stage_a) *ms_stage_a = ma;
+    return rc;
 }
 
 void dbf_stack_free(dbf_stack* S) {

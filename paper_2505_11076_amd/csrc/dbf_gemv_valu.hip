@@ -27,19 +27,15 @@ __device__ inline uint16_t float_to_half_bits(float f) {
 
 template <bool STAGE_A>
 __global__ __launch_bounds__(256) void dbf_stage_valu_kernel(const DbfStage* __restrict__ table,
-                                                             const DbfBlockRef* __restrict__ map,
+                                                             const DbfWorkItem* __restrict__ work,
                                                              const uint16_t* __restrict__ x_base,
                                                              uint16_t* __restrict__ y_base,
                                                              int batch) {
     __shared__ float su[VALU_CHUNK_TILES * DBF_TILE_COLS];
     __shared__ float red[4][DBF_TILE_ROWS];
 
-    int layer = 0, rt = blockIdx.x;
-    if (map) {
-        layer = map[blockIdx.x].layer;
-        rt = map[blockIdx.x].rt;
-    }
-    const DbfStage st = table[layer];
+    const int rt = work[blockIdx.x].rt0;  // items of this kernel span one row tile
+    const DbfStage st = table[work[blockIdx.x].layer];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int g = lane >> 4, r = lane & 15;
     const uint4* tiles = reinterpret_cast<const uint4*>(st.bits) + (size_t)rt * st.n_ct * 64;
@@ -109,7 +105,7 @@ __global__ __launch_bounds__(256) void dbf_stage_valu_kernel(const DbfStage* __r
 
 }  // namespace
 
-hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfBlockRef* map,
+hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfWorkItem* work,
                                  int blocks, const void* x_base, void* y_base, int batch,
                                  int /*max_cols*/, hipStream_t stream) {
     if (blocks <= 0) return hipSuccess;
@@ -117,9 +113,9 @@ hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfB
     uint16_t* y = static_cast<uint16_t*>(y_base);
     if (stage_a)
         hipLaunchKernelGGL(dbf_stage_valu_kernel<true>, dim3(blocks), dim3(256), 0, stream, table,
-                           map, x, y, batch);
+                           work, x, y, batch);
     else
         hipLaunchKernelGGL(dbf_stage_valu_kernel<false>, dim3(blocks), dim3(256), 0, stream, table,
-                           map, x, y, batch);
+                           work, x, y, batch);
     return hipGetLastError();
 }

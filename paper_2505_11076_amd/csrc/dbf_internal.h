@@ -29,10 +29,12 @@ struct DbfStage {
     int pad_;
 };
 
-// Work item of a stack launch: which layer and which 128-row tile a workgroup handles.
-struct DbfBlockRef {
+// Work item of one workgroup: `nrt` consecutive 128-row tiles of one layer, starting at rt0.
+struct DbfWorkItem {
     int layer;
-    int rt;
+    int rt0;
+    int nrt;
+    int pad_;
 };
 
 struct dbf_layer {
@@ -49,6 +51,8 @@ struct dbf_layer {
     int t_stride;
     DbfStage* d_stages;     // device copy of {B stage, A stage}
     DbfStage h_stages[2];   // host copy
+    DbfWorkItem* d_workB;   // device [n_rt of B]: one row tile per workgroup
+    DbfWorkItem* d_workA;   // device [n_rt of A]
 };
 
 struct dbf_stack {
@@ -57,9 +61,12 @@ struct dbf_stack {
     void* dev_block;
     DbfStage* d_stagesB;    // device [n_layers]
     DbfStage* d_stagesA;    // device [n_layers]
-    DbfBlockRef* d_mapB;    // device [blocksB]
-    DbfBlockRef* d_mapA;    // device [blocksA]
-    int blocksB, blocksA;
+    DbfWorkItem* d_workB1;  // device [blocksB1]: one row tile per workgroup
+    DbfWorkItem* d_workA1;  // device [blocksA1]
+    DbfWorkItem* d_workBn;  // device [blocksBn]: several row tiles per workgroup
+    DbfWorkItem* d_workAn;  // device [blocksAn]
+    int blocksB1, blocksA1, blocksBn, blocksAn;
+    int max_ct_B, max_ct_A; // largest number of column tiles over the layers
     int max_cols_B, max_cols_A;
     long long* h_x_prefix;  // host [n_layers+1] prefix sums of n_in
     long long* h_y_prefix;  // host [n_layers+1] prefix sums of n_out
