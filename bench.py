@@ -48,9 +48,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=256, help="distinct layers in the stream")
     ap.add_argument("--batch", type=int, default=1)
-    ap.add_argument("--kind", choices=["auto", "valu", "mfma"], default="auto")
+    ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--stream-only", action="store_true",
+                    help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path uses no collectives); "
@@ -66,7 +68,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.lib()
-    kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA}[args.kind]
+    kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA,
+            "mfma_split": B.GEMV_MFMA_SPLIT}[args.kind]
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
     batch, R = args.batch, args.layers
@@ -110,12 +113,17 @@ def main():
 
     bytes_layer, bytes_b, bytes_a = algorithmic_bytes(n_in, n_out, k, batch)
     value = bytes_layer * R / (ms_per_step * 1e-3) / 1e9
-    if msB_avg >= msA_avg:
-        dom, dom_ms, dom_bytes = "B stage (dbf_stage_mfma_kernel<false,1>)", msB_avg, bytes_b * R
+    ncg = 1 if batch <= 8 else 2
+    if args.kind in ("auto", "mfma"):  # one launch does both stages of every layer
+        dom, dom_ms, dom_bytes = "dbf_items_mfma_kernel<%d> (B and A stages fused)" % ncg, msB_avg, bytes_layer * R
+    elif msB_avg >= msA_avg:
+        dom, dom_ms, dom_bytes = "B-stage launch", msB_avg, bytes_b * R
     else:
-        dom, dom_ms, dom_bytes = "A stage (dbf_stage_mfma_kernel<true,1>)", msA_avg, bytes_a * R
+        dom, dom_ms, dom_bytes = "A-stage launch", msA_avg, bytes_a * R
     if args.kind == "valu":
-        dom = dom.replace("mfma", "valu").replace(",1>", ">")
+        dom += " of dbf_stage_valu_kernel"
+    elif args.kind == "mfma_split":
+        dom += " of dbf_items_mfma_kernel<%d>" % ncg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -126,27 +134,10 @@ def main():
             traffic = None
 
     # ---- isolated single layer, cache warm -----------------------------------------------------
-    lat = []
-    xs, ys = x_all[: batch * n_in], y_all[: batch * n_out]
-    for _ in range(20):
-        B.dbf_gemv(layers[0], xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
-    torch.cuda.synchronize()
-    for _ in range(200):
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a0.record()
-        B.dbf_gemv(layers[0], xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
-        a1.record()
-        a1.synchronize()
-        lat.append(a0.elapsed_time(a1) * 1e3)
-    lat = np.sort(np.array(lat))
-    # back-to-back launches of the same layer (launch-rate bound)
-    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a0.record()
-    for _ in range(500):
-        B.dbf_gemv(layers[0], xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
-    a1.record()
-    torch.cuda.synchronize()
-    b2b_us = a0.elapsed_time(a1) * 1e3 / 500
+    iso = None
+    if not args.stream_only:
+        iso = isolated_latency(B, torch, np, layers[0], x_all[: batch * n_in], y_all[: batch * n_out],
+                               batch, stream, kind)
 
     out = {
         "metric": "DBF layer decode achieved HBM GB/s on algorithmic bytes (batch %d, 4096x4096, k=2048, "
@@ -169,32 +160,79 @@ def main():
         "us_per_layer_in_stream": round(ms_per_step * 1e3 / R, 4),
         "layer_products_per_s": round(R / (ms_per_step * 1e-3), 1),
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
-        "isolated_layer_us": {"p10": round(float(lat[20]), 2), "p50": round(float(lat[100]), 2),
-                              "p90": round(float(lat[180]), 2), "note": "one layer, cache warm, launch bound"},
-        "back_to_back_same_layer_us": round(b2b_us, 3),
+        "isolated_layer_us": iso,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "avg_launch_ms": round(dom_ms, 5),
-                     "stage_b_ms": round(msB_avg, 5), "stage_a_ms": round(msA_avg, 5),
+                     "first_launch_ms": round(msB_avg, 5), "second_launch_ms": round(msA_avg, 5),
                      "algorithmic_bytes_per_launch": dom_bytes},
         "setup_s": round(setup_s, 2),
     }
 
+    # ---- practical HBM read ceiling: a plain streaming read of 1 GiB ---------------------------
+    if not args.stream_only:
+        ceiling = read_ceiling(B, torch, stream)
+        out["hbm_read_ceiling_GBps"] = round(ceiling, 1)
+        out["frac_of_read_ceiling"] = round(value / ceiling, 4)
+        out["roofline"]["frac_of_read_ceiling"] = round(achieved / ceiling, 4)
+
     # ---- prefill (matrix-core path) ---------------------------------------------------------------
-    if not args.no_prefill:
+    if not args.no_prefill and not args.stream_only:
         try:
             out["prefill"] = prefill_bench(B, I, torch, np, stream)
         except Exception as exc:  # reported, never hidden
             out["prefill"] = {"error": repr(exc)}
 
     # ---- the CPU oracle on this machine's cores (a baseline, not the target) ---------------------
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.stream_only:
         out["cpu_baseline"] = cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer)
 
     stack.close()
     for l in layers:
         l.close()
     print(json.dumps(out))
+
+
+def isolated_latency(B, torch, np, layer, xs, ys, batch, stream, kind):
+    """One layer launched alone, cache warm: per-call latency (two dependent launches) and the
+    back-to-back rate of the same call."""
+    lat = []
+    for _ in range(20):
+        B.dbf_gemv(layer, xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
+    torch.cuda.synchronize()
+    for _ in range(200):
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        B.dbf_gemv(layer, xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
+        a1.record()
+        a1.synchronize()
+        lat.append(a0.elapsed_time(a1) * 1e3)
+    lat = np.sort(np.array(lat))
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a0.record()
+    for _ in range(500):
+        B.dbf_gemv(layer, xs.data_ptr(), ys.data_ptr(), batch, stream, kind)
+    a1.record()
+    torch.cuda.synchronize()
+    return {"p10": round(float(lat[20]), 2), "p50": round(float(lat[100]), 2), "p90": round(float(lat[180]), 2),
+            "back_to_back_us": round(a0.elapsed_time(a1) * 1e3 / 500, 3),
+            "note": "one layer, cache warm, launch bound"}
+
+
+def read_ceiling(B, torch, stream):
+    probe = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    probe.random_(0, 255)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(2):
+        B.dbf_probe_read(probe.data_ptr(), probe.numel(), sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    for _ in range(5):
+        B.dbf_probe_read(probe.data_ptr(), probe.numel(), sink.data_ptr(), stream)
+    p1.record()
+    torch.cuda.synchronize()
+    return probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
 
 
 def prefill_bench(B, I, torch, np, stream):

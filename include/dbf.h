@@ -64,8 +64,11 @@ enum {
 enum {
     DBF_GEMV_AUTO = 0, /* what dbf_gemv uses: the fastest variant for the shape             */
     DBF_GEMV_VALU = 1, /* fp32 add/subtract per sign bit on the vector ALU (exact fp32 sums) */
-    DBF_GEMV_MFMA = 2  /* sign bytes fed to the int8 matrix cores as the adder; the input
-                          vector of each stage is rounded once to 16-bit fixed point       */
+    DBF_GEMV_MFMA = 2, /* sign bytes fed to the int8 matrix cores as the adder; the input
+                          vector of each stage is rounded once to 16-bit fixed point.  Both
+                          stages run in ONE launch: A-stage workgroups wait on the device for
+                          their layer's B stage                                             */
+    DBF_GEMV_MFMA_SPLIT = 3 /* the same kernel in two launches (B stage, then A stage)      */
 };
 
 #define DBF_MAX_BATCH 16       /* largest batch dbf_gemv / dbf_stack_gemv accept */
@@ -117,9 +120,10 @@ int dbf_tile_host(int rows, int cols, const uint32_t* bits, uint8_t* tiled);
 int dbf_untile_host(int rows, int cols, const uint8_t* tiled, uint32_t* bits);
 
 /* ---- decode: Y = X W'^T for a few tokens -----------------------------------------------
- * The forward-pass expression of section 3, evaluated in two launches: the B stage
+ * The forward-pass expression of section 3, evaluated in two stages: the B stage
  * t = ((x . b) B^T) . m (the middle rescale is fused into its epilogue), then the A stage
- * y = (t A^T) . a.  fp32 (or exact integer) accumulation, fp32 middle activations.
+ * y = (t A^T) . a.  fp32 (or exact integer) accumulation, fp32 middle activations.  The
+ * default kernel runs both stages in one launch (see DBF_GEMV_MFMA).
  *
  * x_dev: device, fp16 [batch][n_in] row-major, tightly packed.
  * y_dev: device, fp16 [batch][n_out] row-major, written in full.
@@ -129,6 +133,13 @@ int dbf_untile_host(int rows, int cols, const uint8_t* tiled, uint32_t* bits);
 int dbf_gemv(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, void* hip_stream);
 int dbf_gemv_kind(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, int kind,
                   void* hip_stream);
+/* In the one-launch kernel an A-stage workgroup waits on the device, with a bound of about
+ * half a second, for the B stage of its layer.  The bound is never expected to be hit (a
+ * B-stage workgroup never waits and is always dispatched before any A-stage one); if it is,
+ * the workgroup goes on, its outputs are wrong, and a sticky counter is raised.  This call
+ * synchronises the device and returns that counter in *timeouts (0 = every result is good).
+ * Errors: DBF_EINVAL, DBF_EHIP. */
+int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
 
 /* ---- prefill: the same product for T tokens as two matrix-core contractions ------------
  * (The paper times batch 1 only, section 4.4; rows of X are independent, so the product is
@@ -145,10 +156,11 @@ size_t dbf_gemm_workspace_bytes(const dbf_layer* layer, int T);
 int dbf_gemm(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
              void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
-/* ---- a group of independent layer products in one launch pair --------------------------
+/* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
- * benchmark stream of layers): all B stages run in one launch and all A stages in a second,
- * so the sign bits stream from HBM without a launch gap per layer.
+ * benchmark stream of layers): the B and A stages of all layers run in one launch (two for
+ * DBF_GEMV_VALU and DBF_GEMV_MFMA_SPLIT), so the sign bits stream from HBM without a launch
+ * gap per layer.
  *
  * dbf_stack_create: layers[0..n_layers) must stay alive while the stack exists; the stack
  * only holds a device table describing them.  n_layers >= 1.
@@ -162,14 +174,23 @@ int dbf_stack_offsets(const dbf_stack* stack, int layer_index, int batch,
                       size_t* x_offset_elems, size_t* y_offset_elems);
 int dbf_stack_gemv(const dbf_stack* stack, const void* x_dev, void* y_dev, int batch, int kind,
                    void* hip_stream);
+int dbf_stack_sync_timeouts(const dbf_stack* stack, int* timeouts); /* as dbf_sync_timeouts */
 void dbf_stack_free(dbf_stack* stack); /* NULL is allowed */
 
-/* Measurement aid: dbf_stack_gemv with HIP events recorded on `hip_stream` around each of
- * the two launches.  Blocks until the second launch has finished and returns the elapsed
- * milliseconds of the B-stage kernel and of the A-stage kernel (either pointer may be NULL).
+/* Measurement aid: dbf_stack_gemv with HIP events recorded on `hip_stream` around its
+ * launches.  Blocks until the last launch has finished.  *ms_first is the elapsed time of the
+ * first kernel (the whole pass for DBF_GEMV_MFMA, the B stage for the two-launch kinds),
+ * *ms_second that of the second kernel (0 for DBF_GEMV_MFMA).  Either pointer may be NULL.
  * Same arguments and errors as dbf_stack_gemv. */
 int dbf_stack_gemv_timed(const dbf_stack* stack, const void* x_dev, void* y_dev, int batch,
-                         int kind, void* hip_stream, float* ms_stage_b, float* ms_stage_a);
+                         int kind, void* hip_stream, float* ms_first, float* ms_second);
+
+/* Measurement aid: launches a kernel on `hip_stream` that reads the first
+ * floor(bytes / 65536) * 65536 bytes of src_dev (device, 16-byte aligned, bytes >= 65536) once
+ * with 16-byte per-lane loads and does nothing else; timing it gives the practical HBM read
+ * ceiling the decode kernels are compared with.  sink_dev: device, 4 bytes, or NULL.
+ * Asynchronous.  Errors: DBF_EINVAL, DBF_EHIP. */
+int dbf_probe_read(const void* src_dev, size_t bytes, void* sink_dev, void* hip_stream);
 
 const char* dbf_strerror(int code);
 

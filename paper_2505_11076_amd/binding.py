@@ -18,15 +18,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdbf.so")
 
 DBF_OK, DBF_EINVAL, DBF_ESHAPE, DBF_ENOTSIGN, DBF_ENOMEM, DBF_EHIP, DBF_EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
-GEMV_AUTO, GEMV_VALU, GEMV_MFMA = 0, 1, 2
+GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT = 0, 1, 2, 3
 MAX_BATCH = 16
 
 EXPORTS = [
     "dbf_pack", "dbf_pack_bits", "dbf_unpack_bits", "dbf_dims", "dbf_free",
     "dbf_tiled_bytes", "dbf_signs_to_bits_host", "dbf_tile_host", "dbf_untile_host",
-    "dbf_gemv", "dbf_gemv_kind", "dbf_gemm_workspace_bytes", "dbf_gemm",
-    "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed", "dbf_stack_free",
-    "dbf_strerror",
+    "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm",
+    "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
+    "dbf_stack_sync_timeouts", "dbf_stack_free",
+    "dbf_probe_read", "dbf_strerror",
 ]
 
 _lib = None
@@ -62,6 +63,8 @@ def lib() -> C.CDLL:
     L.dbf_untile_host.argtypes = [i32, i32, vp, vp]
     L.dbf_gemv.argtypes = [vp, vp, vp, i32, vp]
     L.dbf_gemv_kind.argtypes = [vp, vp, vp, i32, i32, vp]
+    L.dbf_sync_timeouts.argtypes = [vp, C.POINTER(i32)]
+    L.dbf_stack_sync_timeouts.argtypes = [vp, C.POINTER(i32)]
     L.dbf_gemm_workspace_bytes.argtypes = [vp, i32]
     L.dbf_gemm_workspace_bytes.restype = sz
     L.dbf_gemm.argtypes = [vp, vp, vp, i32, vp, sz, vp]
@@ -71,6 +74,7 @@ def lib() -> C.CDLL:
     L.dbf_stack_gemv_timed.argtypes = [vp, vp, vp, i32, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     L.dbf_stack_free.argtypes = [vp]
     L.dbf_stack_free.restype = None
+    L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
     L.dbf_strerror.argtypes = [i32]
     L.dbf_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -252,3 +256,19 @@ def dbf_stack_gemv_timed(stack: Stack, x_ptr: int, y_ptr: int, batch: int, strea
     _check(lib().dbf_stack_gemv_timed(stack.handle, x_ptr, y_ptr, batch, kind, stream, C.byref(mb), C.byref(ma)),
            "dbf_stack_gemv_timed")
     return float(mb.value), float(ma.value)
+
+
+def dbf_probe_read(src_ptr: int, nbytes: int, sink_ptr: int = 0, stream: int = 0) -> None:
+    _check(lib().dbf_probe_read(src_ptr, nbytes, sink_ptr, stream), "dbf_probe_read")
+
+
+def dbf_sync_timeouts(layer: Layer) -> int:
+    n = C.c_int(0)
+    _check(lib().dbf_sync_timeouts(layer.handle, C.byref(n)), "dbf_sync_timeouts")
+    return int(n.value)
+
+
+def dbf_stack_sync_timeouts(stack: Stack) -> int:
+    n = C.c_int(0)
+    _check(lib().dbf_stack_sync_timeouts(stack.handle, C.byref(n)), "dbf_stack_sync_timeouts")
+    return int(n.value)

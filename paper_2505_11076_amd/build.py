@@ -23,6 +23,7 @@ SOURCES = [
     "dbf_gemv_valu.hip",
     "dbf_gemv_mfma.hip",
     "dbf_gemm_mfma.hip",
+    "dbf_probe.hip",
 ]
 
 FLAGS = [

@@ -25,12 +25,99 @@ inline bool shape_ok(int n_in, int n_out, int k) {
         }                                  \
     } while (0)
 
-// Row tiles of one stage cut into work items of at most `span` tiles.
-void append_items(std::vector<DbfWorkItem>& out, int layer, int n_rt, int span) {
-    for (int rt = 0; rt < n_rt; rt += span) {
-        const int n = (n_rt - rt < span) ? (n_rt - rt) : span;
-        out.push_back(DbfWorkItem{layer, rt, n, 0});
+// Matrix-core items of one stage of one layer, at most `span` row tiles each.
+void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool stage_a,
+                  int need, int span) {
+    const int peers = (st.n_rt + span - 1) / span;  // items this call appends
+    for (int rt = 0; rt < st.n_rt; rt += span) {
+        DbfItem it;
+        std::memset(&it, 0, sizeof(it));
+        it.bits = st.bits + (size_t)rt * st.n_ct * DBF_TILE_BYTES;
+        it.in_scale = st.in_scale;
+        it.row_scale = st.row_scale + (size_t)rt * DBF_TILE_ROWS;
+        it.t = st.t;
+        it.io_off = stage_a ? st.y_off : st.x_off;
+        it.n_ct = st.n_ct;
+        it.nrt = (st.n_rt - rt < span) ? (st.n_rt - rt) : span;
+        it.row0 = rt * DBF_TILE_ROWS;
+        it.rows = st.rows;
+        it.cols = st.cols;
+        it.t_stride = st.t_stride;
+        it.layer = layer;
+        it.need = need;
+        it.stage_a = stage_a ? 1 : 0;
+        it.peers = peers;
+        out.push_back(it);
     }
+}
+
+void free_plan(DbfPlan& p) {
+    if (p.dev_block) (void)hipFree(p.dev_block);
+    p.dev_block = nullptr;
+}
+
+// Builds and uploads the launch tables for `n` layers whose stages (with their x/y offsets
+// already set) are given in sB / sA.
+int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA, int span, DbfPlan* p) {
+    const int n = (int)sB.size();
+    std::vector<DbfWorkItem> wB1, wA1;
+    std::vector<DbfItem> items_n, items_1;
+    int nBn = 0, nB1 = 0;
+    std::memset(p, 0, sizeof(*p));
+    for (int i = 0; i < n; ++i) {
+        for (int rt = 0; rt < sB[i].n_rt; ++rt) wB1.push_back(DbfWorkItem{i, rt, 1, 0});
+        for (int rt = 0; rt < sA[i].n_rt; ++rt) wA1.push_back(DbfWorkItem{i, rt, 1, 0});
+        if (sB[i].cols > p->max_cols_B) p->max_cols_B = sB[i].cols;
+        if (sA[i].cols > p->max_cols_A) p->max_cols_A = sA[i].cols;
+    }
+    for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, span);
+    nBn = (int)items_n.size();
+    for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span);
+    for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, 1);
+    nB1 = (int)items_1.size();
+    for (int i = 0; i < n; ++i) append_items(items_1, sA[i], i, true, sB[i].n_rt, 1);
+
+    size_t off = 0;
+    const size_t o_sB = off;  off = align_up(off + sizeof(DbfStage) * n, 256);
+    const size_t o_sA = off;  off = align_up(off + sizeof(DbfStage) * n, 256);
+    const size_t o_wB = off;  off = align_up(off + sizeof(DbfWorkItem) * wB1.size(), 256);
+    const size_t o_wA = off;  off = align_up(off + sizeof(DbfWorkItem) * wA1.size(), 256);
+    const size_t o_in = off;  off = align_up(off + sizeof(DbfItem) * items_n.size(), 256);
+    const size_t o_i1 = off;  off = align_up(off + sizeof(DbfItem) * items_1.size(), 256);
+    const size_t o_sy = off;  off = align_up(off + sizeof(int) * (2 * (size_t)n + 1), 256);
+    std::vector<uint8_t> image(off, 0);
+    std::memcpy(image.data() + o_sB, sB.data(), sizeof(DbfStage) * n);
+    std::memcpy(image.data() + o_sA, sA.data(), sizeof(DbfStage) * n);
+    std::memcpy(image.data() + o_wB, wB1.data(), sizeof(DbfWorkItem) * wB1.size());
+    std::memcpy(image.data() + o_wA, wA1.data(), sizeof(DbfWorkItem) * wA1.size());
+    std::memcpy(image.data() + o_in, items_n.data(), sizeof(DbfItem) * items_n.size());
+    std::memcpy(image.data() + o_i1, items_1.data(), sizeof(DbfItem) * items_1.size());
+    void* dev = nullptr;
+    hipError_t e = hipMalloc(&dev, off);
+    if (e == hipSuccess) e = hipMemcpy(dev, image.data(), off, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        if (dev) (void)hipFree(dev);
+        return DBF_EHIP;
+    }
+    uint8_t* d = static_cast<uint8_t*>(dev);
+    p->dev_block = dev;
+    p->n_layers = n;
+    p->d_stagesB = reinterpret_cast<DbfStage*>(d + o_sB);
+    p->d_stagesA = reinterpret_cast<DbfStage*>(d + o_sA);
+    p->d_workB1 = reinterpret_cast<DbfWorkItem*>(d + o_wB);
+    p->d_workA1 = reinterpret_cast<DbfWorkItem*>(d + o_wA);
+    p->blocksB1 = (int)wB1.size();
+    p->blocksA1 = (int)wA1.size();
+    p->d_items_n = reinterpret_cast<DbfItem*>(d + o_in);
+    p->nBn = nBn;
+    p->nAn = (int)items_n.size() - nBn;
+    p->d_items_1 = reinterpret_cast<DbfItem*>(d + o_i1);
+    p->nB1 = nB1;
+    p->nA1 = (int)items_1.size() - nB1;
+    p->d_sync = reinterpret_cast<int*>(d + o_sy);
+    return DBF_OK;
 }
 
 // Builds the device image of a layer from canonical words and uploads it.
@@ -50,9 +137,6 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     const size_t offa = off;  off = align_up(off + 2 * (size_t)a_len, 256);
     const size_t offm = off;  off = align_up(off + 2 * (size_t)m_len, 256);
     const size_t offb = off;  off = align_up(off + 2 * (size_t)b_len, 256);
-    const size_t offs = off;  off = align_up(off + 2 * sizeof(DbfStage), 256);
-    const size_t offwB = off; off = align_up(off + sizeof(DbfWorkItem) * rtB, 256);
-    const size_t offwA = off; off = align_up(off + sizeof(DbfWorkItem) * rtA, 256);
     const size_t image_bytes = off;  // everything up to here is uploaded
     const size_t offt = off;  off = align_up(off + 4 * (size_t)DBF_MAX_BATCH * t_stride, 256);
     const size_t total = off;
@@ -92,9 +176,6 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     L->db = reinterpret_cast<uint16_t*>(d + offb);
     L->dt = reinterpret_cast<float*>(d + offt);
     L->t_stride = t_stride;
-    L->d_stages = reinterpret_cast<DbfStage*>(d + offs);
-    L->d_workB = reinterpret_cast<DbfWorkItem*>(d + offwB);
-    L->d_workA = reinterpret_cast<DbfWorkItem*>(d + offwA);
 
     DbfStage& sb = L->h_stages[0];
     sb.bits = L->dB;  sb.in_scale = L->db;  sb.row_scale = L->dm;  sb.t = L->dt;
@@ -106,17 +187,16 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     sa.x_off = 0;  sa.y_off = 0;
     sa.n_rt = rtA;  sa.n_ct = dbf_col_tiles(k);
     sa.rows = n_out;  sa.cols = k;  sa.t_stride = t_stride;  sa.pad_ = 0;
-    std::memcpy(image + offs, L->h_stages, 2 * sizeof(DbfStage));
-    std::vector<DbfWorkItem> wB, wA;
-    append_items(wB, 0, rtB, 1);
-    append_items(wA, 0, rtA, 1);
-    std::memcpy(image + offwB, wB.data(), sizeof(DbfWorkItem) * wB.size());
-    std::memcpy(image + offwA, wA.data(), sizeof(DbfWorkItem) * wA.size());
 
     hipError_t e = hipMemcpy(dev, image, image_bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(d + offt, 0, total - offt);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     std::free(image);
+    if (e == hipSuccess) {
+        // a single layer runs alone: one row tile per workgroup gives the most parallelism
+        std::vector<DbfStage> vB(1, sb), vA(1, sa);
+        if (build_plan(vB, vA, 1, &L->plan) != DBF_OK) e = hipErrorOutOfMemory;
+    }
     if (e != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(dev);
@@ -127,82 +207,44 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     return DBF_OK;
 }
 
-// Everything a launch of the two stages needs.
-struct LaunchPlan {
-    const DbfStage* stagesB;
-    const DbfStage* stagesA;
-    const DbfWorkItem* workB1;  // one row tile per workgroup
-    const DbfWorkItem* workA1;
-    const DbfWorkItem* workBn;  // several row tiles per workgroup (may equal work*1)
-    const DbfWorkItem* workAn;
-    int blocksB1, blocksA1, blocksBn, blocksAn;
-    int max_cols_B, max_cols_A;
-};
+inline bool kind_ok(int kind) {
+    return kind == DBF_GEMV_AUTO || kind == DBF_GEMV_VALU || kind == DBF_GEMV_MFMA ||
+           kind == DBF_GEMV_MFMA_SPLIT;
+}
 
-// Launches the B stage and then the A stage on `stream`.  If `mid` is not NULL it is
-// recorded between the two launches (used only by the timed entry point).
-int launch_pair(int kind, const LaunchPlan& p, const void* x, void* y, int batch,
-                hipStream_t stream, hipEvent_t mid = nullptr) {
+// Launches one decode pass of a plan on `stream`.  `mid`, if not NULL, is recorded between the
+// B-stage launch and the A-stage launch of the two-launch kinds (timed entry point only).
+int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, hipStream_t stream,
+                hipEvent_t mid = nullptr) {
     if (kind == DBF_GEMV_AUTO) kind = DBF_GEMV_MFMA;
-#ifdef DBF_DEBUG_KINDS
-    if (kind == 3 || kind == 4) {  // 3: MFMA B stage + VALU A stage, 4: VALU B + MFMA A
-        if (kind == 3) DBF_HIP_TRY(dbf_launch_stage_mfma(false, p.stagesB, p.workB1, p.blocksB1, x, y, batch, p.max_cols_B, stream));
-        else DBF_HIP_TRY(dbf_launch_stage_valu(false, p.stagesB, p.workB1, p.blocksB1, x, y, batch, p.max_cols_B, stream));
-        if (kind == 3) DBF_HIP_TRY(dbf_launch_stage_valu(true, p.stagesA, p.workA1, p.blocksA1, x, y, batch, p.max_cols_A, stream));
-        else DBF_HIP_TRY(dbf_launch_stage_mfma(true, p.stagesA, p.workA1, p.blocksA1, x, y, batch, p.max_cols_A, stream));
-        return DBF_OK;
-    }
-#endif
     if (kind == DBF_GEMV_VALU) {
-        DBF_HIP_TRY(dbf_launch_stage_valu(false, p.stagesB, p.workB1, p.blocksB1, x, y, batch,
-                                          p.max_cols_B, stream));
+        DBF_HIP_TRY(dbf_launch_stage_valu(false, p.d_stagesB, p.d_workB1, p.blocksB1, x, y, batch, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-        DBF_HIP_TRY(dbf_launch_stage_valu(true, p.stagesA, p.workA1, p.blocksA1, x, y, batch,
-                                          p.max_cols_A, stream));
+        DBF_HIP_TRY(dbf_launch_stage_valu(true, p.d_stagesA, p.d_workA1, p.blocksA1, x, y, batch, stream));
         return DBF_OK;
     }
-    // several row tiles per workgroup only if all columns of the stage fit one LDS chunk
-    const bool spanB = dbf_mfma_chunk_tiles(batch, p.max_cols_B) >= dbf_col_tiles(p.max_cols_B);
-    const bool spanA = dbf_mfma_chunk_tiles(batch, p.max_cols_A) >= dbf_col_tiles(p.max_cols_A);
-    DBF_HIP_TRY(dbf_launch_stage_mfma(false, p.stagesB, spanB ? p.workBn : p.workB1,
-                                      spanB ? p.blocksBn : p.blocksB1, x, y, batch, p.max_cols_B, stream));
+    // several row tiles per workgroup only if all columns of both stages fit one LDS chunk
+    const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
+    const bool span = dbf_mfma_chunk_tiles(batch, max_cols) >= dbf_col_tiles(max_cols);
+    const DbfItem* items = span ? p.d_items_n : p.d_items_1;
+    const int nB = span ? p.nBn : p.nB1, nA = span ? p.nAn : p.nA1;
+    if (kind == DBF_GEMV_MFMA) {
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, stream));
+        if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
+        return DBF_OK;
+    }
+    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, stream));
     if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-    DBF_HIP_TRY(dbf_launch_stage_mfma(true, p.stagesA, spanA ? p.workAn : p.workA1,
-                                      spanA ? p.blocksAn : p.blocksA1, x, y, batch, p.max_cols_A, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, stream));
     return DBF_OK;
 }
 
-inline bool kind_ok(int kind) {
-#ifdef DBF_DEBUG_KINDS
-    if (kind == 3 || kind == 4) return true;
-#endif
-    return kind == DBF_GEMV_AUTO || kind == DBF_GEMV_VALU || kind == DBF_GEMV_MFMA;
-}
-
-LaunchPlan plan_of(const dbf_layer* L) {
-    LaunchPlan p;
-    p.stagesB = L->d_stages;
-    p.stagesA = L->d_stages + 1;
-    p.workB1 = p.workBn = L->d_workB;
-    p.workA1 = p.workAn = L->d_workA;
-    p.blocksB1 = p.blocksBn = L->h_stages[0].n_rt;
-    p.blocksA1 = p.blocksAn = L->h_stages[1].n_rt;
-    p.max_cols_B = L->n_in;
-    p.max_cols_A = L->k;
-    return p;
-}
-
-LaunchPlan plan_of(const dbf_stack* S) {
-    LaunchPlan p;
-    p.stagesB = S->d_stagesB;
-    p.stagesA = S->d_stagesA;
-    p.workB1 = S->d_workB1;  p.workA1 = S->d_workA1;
-    p.workBn = S->d_workBn;  p.workAn = S->d_workAn;
-    p.blocksB1 = S->blocksB1;  p.blocksA1 = S->blocksA1;
-    p.blocksBn = S->blocksBn;  p.blocksAn = S->blocksAn;
-    p.max_cols_B = S->max_cols_B;
-    p.max_cols_A = S->max_cols_A;
-    return p;
+int read_timeouts(const DbfPlan& p, int* timeouts) {
+    int v = 0;
+    DBF_HIP_TRY(hipDeviceSynchronize());
+    DBF_HIP_TRY(hipMemcpy(&v, p.d_sync + 2 * p.n_layers, sizeof(int), hipMemcpyDeviceToHost));
+    if (timeouts) *timeouts = v;
+    return DBF_OK;
 }
 
 int stack_span() {
@@ -211,7 +253,7 @@ int stack_span() {
     const char* e = std::getenv("DBF_STACK_SPAN");
     int v = e ? std::atoi(e) : 4;
     if (v < 1) v = 1;
-    if (v > 16) v = 16;
+    if (v > DBF_MAX_SPAN) v = DBF_MAX_SPAN;
     return v;
 }
 
@@ -277,6 +319,7 @@ int dbf_dims(const dbf_layer* L, int* n_in, int* n_out, int* k, size_t* device_b
 
 void dbf_free(dbf_layer* L) {
     if (!L) return;
+    free_plan(L->plan);
     if (L->dev_block) (void)hipFree(L->dev_block);
     delete L;
 }
@@ -285,11 +328,16 @@ int dbf_gemv_kind(const dbf_layer* L, const void* x_dev, void* y_dev, int batch,
                   void* hip_stream) {
     if (!L || !x_dev || !y_dev) return DBF_EINVAL;
     if (batch < 1 || batch > DBF_MAX_BATCH || !kind_ok(kind)) return DBF_EINVAL;
-    return launch_pair(kind, plan_of(L), x_dev, y_dev, batch, static_cast<hipStream_t>(hip_stream));
+    return launch_plan(kind, L->plan, x_dev, y_dev, batch, static_cast<hipStream_t>(hip_stream));
 }
 
 int dbf_gemv(const dbf_layer* L, const void* x_dev, void* y_dev, int batch, void* hip_stream) {
     return dbf_gemv_kind(L, x_dev, y_dev, batch, DBF_GEMV_AUTO, hip_stream);
+}
+
+int dbf_sync_timeouts(const dbf_layer* L, int* timeouts) {
+    if (!L) return DBF_EINVAL;
+    return read_timeouts(L->plan, timeouts);
 }
 
 // ---- stacks ---------------------------------------------------------------------------------
@@ -305,14 +353,12 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
     dbf_stack* S = new (std::nothrow) dbf_stack();
     if (!S) return DBF_ENOMEM;
     std::vector<DbfStage> sB(n_layers), sA(n_layers);
-    std::vector<DbfWorkItem> wB1, wA1, wBn, wAn;
     S->h_x_prefix = static_cast<long long*>(std::malloc(sizeof(long long) * (n_layers + 1)));
     S->h_y_prefix = static_cast<long long*>(std::malloc(sizeof(long long) * (n_layers + 1)));
     if (!S->h_x_prefix || !S->h_y_prefix) {
         dbf_stack_free(S);
         return DBF_ENOMEM;
     }
-    const int span = stack_span();
     S->n_layers = n_layers;
     S->device = layers[0]->device;
     S->h_x_prefix[0] = S->h_y_prefix[0] = 0;
@@ -324,48 +370,12 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
         sB[i].y_off = sA[i].y_off = S->h_y_prefix[i];
         S->h_x_prefix[i + 1] = S->h_x_prefix[i] + L->n_in;
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
-        append_items(wB1, i, sB[i].n_rt, 1);
-        append_items(wA1, i, sA[i].n_rt, 1);
-        append_items(wBn, i, sB[i].n_rt, span);
-        append_items(wAn, i, sA[i].n_rt, span);
-        if (L->n_in > S->max_cols_B) S->max_cols_B = L->n_in;
-        if (L->k > S->max_cols_A) S->max_cols_A = L->k;
     }
-    S->blocksB1 = (int)wB1.size();  S->blocksA1 = (int)wA1.size();
-    S->blocksBn = (int)wBn.size();  S->blocksAn = (int)wAn.size();
-
-    size_t off = 0;
-    const size_t o_sB = off;  off = align_up(off + sizeof(DbfStage) * n_layers, 256);
-    const size_t o_sA = off;  off = align_up(off + sizeof(DbfStage) * n_layers, 256);
-    const size_t o_B1 = off;  off = align_up(off + sizeof(DbfWorkItem) * wB1.size(), 256);
-    const size_t o_A1 = off;  off = align_up(off + sizeof(DbfWorkItem) * wA1.size(), 256);
-    const size_t o_Bn = off;  off = align_up(off + sizeof(DbfWorkItem) * wBn.size(), 256);
-    const size_t o_An = off;  off = align_up(off + sizeof(DbfWorkItem) * wAn.size(), 256);
-    std::vector<uint8_t> image(off, 0);
-    std::memcpy(image.data() + o_sB, sB.data(), sizeof(DbfStage) * n_layers);
-    std::memcpy(image.data() + o_sA, sA.data(), sizeof(DbfStage) * n_layers);
-    std::memcpy(image.data() + o_B1, wB1.data(), sizeof(DbfWorkItem) * wB1.size());
-    std::memcpy(image.data() + o_A1, wA1.data(), sizeof(DbfWorkItem) * wA1.size());
-    std::memcpy(image.data() + o_Bn, wBn.data(), sizeof(DbfWorkItem) * wBn.size());
-    std::memcpy(image.data() + o_An, wAn.data(), sizeof(DbfWorkItem) * wAn.size());
-    void* dev = nullptr;
-    hipError_t e = hipMalloc(&dev, off);
-    if (e == hipSuccess) e = hipMemcpy(dev, image.data(), off, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipDeviceSynchronize();
-    if (e != hipSuccess) {
-        (void)hipGetLastError();
-        if (dev) (void)hipFree(dev);
+    const int rc = build_plan(sB, sA, stack_span(), &S->plan);
+    if (rc != DBF_OK) {
         dbf_stack_free(S);
-        return DBF_EHIP;
+        return rc;
     }
-    uint8_t* d = static_cast<uint8_t*>(dev);
-    S->dev_block = dev;
-    S->d_stagesB = reinterpret_cast<DbfStage*>(d + o_sB);
-    S->d_stagesA = reinterpret_cast<DbfStage*>(d + o_sA);
-    S->d_workB1 = reinterpret_cast<DbfWorkItem*>(d + o_B1);
-    S->d_workA1 = reinterpret_cast<DbfWorkItem*>(d + o_A1);
-    S->d_workBn = reinterpret_cast<DbfWorkItem*>(d + o_Bn);
-    S->d_workAn = reinterpret_cast<DbfWorkItem*>(d + o_An);
     *out = S;
     return DBF_OK;
 }
@@ -382,11 +392,11 @@ int dbf_stack_gemv(const dbf_stack* S, const void* x_dev, void* y_dev, int batch
                    void* hip_stream) {
     if (!S || !x_dev || !y_dev) return DBF_EINVAL;
     if (batch < 1 || batch > DBF_MAX_BATCH || !kind_ok(kind)) return DBF_EINVAL;
-    return launch_pair(kind, plan_of(S), x_dev, y_dev, batch, static_cast<hipStream_t>(hip_stream));
+    return launch_plan(kind, S->plan, x_dev, y_dev, batch, static_cast<hipStream_t>(hip_stream));
 }
 
 int dbf_stack_gemv_timed(const dbf_stack* S, const void* x_dev, void* y_dev, int batch, int kind,
-                         void* hip_stream, float* ms_stage_b, float* ms_stage_a) {
+                         void* hip_stream, float* ms_first, float* ms_second) {
     if (!S || !x_dev || !y_dev) return DBF_EINVAL;
     if (batch < 1 || batch > DBF_MAX_BATCH || !kind_ok(kind)) return DBF_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -395,7 +405,7 @@ int dbf_stack_gemv_timed(const dbf_stack* S, const void* x_dev, void* y_dev, int
     for (int i = 0; i < 3 && rc == DBF_OK; ++i)
         if (hipEventCreate(&ev[i]) != hipSuccess) rc = DBF_EHIP;
     if (rc == DBF_OK && hipEventRecord(ev[0], stream) != hipSuccess) rc = DBF_EHIP;
-    if (rc == DBF_OK) rc = launch_pair(kind, plan_of(S), x_dev, y_dev, batch, stream, ev[1]);
+    if (rc == DBF_OK) rc = launch_plan(kind, S->plan, x_dev, y_dev, batch, stream, ev[1]);
     if (rc == DBF_OK && hipEventRecord(ev[2], stream) != hipSuccess) rc = DBF_EHIP;
     if (rc == DBF_OK && hipEventSynchronize(ev[2]) != hipSuccess) rc = DBF_EHIP;
     float mb = 0.f, ma = 0.f;
@@ -404,14 +414,19 @@ int dbf_stack_gemv_timed(const dbf_stack* S, const void* x_dev, void* y_dev, int
     for (int i = 0; i < 3; ++i)
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     if (rc != DBF_OK) (void)hipGetLastError();
-    if (ms_stage_b) *ms_stage_b = mb;
-    if (ms_stage_a) *ms_stage_a = ma;
+    if (ms_first) *ms_first = mb;
+    if (ms_second) *ms_second = ma;
     return rc;
+}
+
+int dbf_stack_sync_timeouts(const dbf_stack* S, int* timeouts) {
+    if (!S) return DBF_EINVAL;
+    return read_timeouts(S->plan, timeouts);
 }
 
 void dbf_stack_free(dbf_stack* S) {
     if (!S) return;
-    if (S->dev_block) (void)hipFree(S->dev_block);
+    free_plan(S->plan);
     std::free(S->h_x_prefix);
     std::free(S->h_y_prefix);
     delete S;

@@ -1,4 +1,4 @@
-// Decode stage with the int8 matrix cores as the adder.
+// Decode kernel with the int8 matrix cores as the adder.
 //
 // One sign-matrix product of the forward-pass expression (paper, section 3):
 //     out[row] = row_scale[row] * sum_col S[row][col] * u[col],
@@ -19,18 +19,42 @@
 //   * acc_s = 2^s * sum_{bit=1} q.  With sigma = sum_col q, the signed sum is
 //     2 * (acc_s >> s) - sigma, exactly, in int32.
 //
-// Work split: a workgroup (4 wavefronts) takes `nrt` consecutive 128-row tiles of one layer
-// and quantises the input vector once for all of them.  Within a row tile wavefront w walks
-// column tiles w, w+4, ... with PF tiles of sign bits in flight (buffer loads whose
-// out-of-range lanes return zero, so the steady-state loop has no branches); the loads for
-// the next row tile are already in flight while the current one is reduced.  The four
-// partial results are added with integer LDS atomics (exact, order independent).
+// Work split: a workgroup (4 wavefronts) takes one item: `nrt` consecutive 128-row tiles of
+// one stage of one layer; it quantises the input vector once for all of them.  Within a row
+// tile wavefront w walks column tiles w, w+4, ... with PF tiles of sign bits in flight
+// (buffer loads whose out-of-range lanes return zero, so the steady-state loop has no
+// branches); the loads for the next row tile are already in flight while the current one is
+// reduced.  The four partial results are added with integer LDS atomics (exact, order
+// independent).  Between the prologue and the end of the item no load other than the
+// sign-bit stream is issued (row scales are staged in LDS up front), so nothing drains the
+// load pipeline.
+//
+// Fused launch: the item list holds every B-stage item before any A-stage item, and
+// workgroups are dispatched in list order.  An A-stage workgroup issues its first sign-bit
+// loads, then waits (bounded) until the layer's B-stage workgroups have published all their
+// rows of t, so both stages of all layers run in ONE launch and HBM never drains in between.
+// A B-stage workgroup never waits, so every wait ends; should the bound be hit anyway the
+// workgroup goes on (its result is then wrong) and counts a time-out the host can read.
 #include "dbf_kernels.h"
 
 // 1: tile loads by inline assembly with exact hand-placed waits (the fast path).
 // 0: the same loads through the compiler builtin (it then waits with vmcnt(0) per group).
 #ifndef DBF_ASM_LOADS
 #define DBF_ASM_LOADS 1
+#endif
+// Cache-policy bits of the sign-bit loads.  Every sign bit is read exactly once per token, so
+// the stream is marked non-temporal (measured: +10% over default-policy loads).
+#ifndef DBF_LOAD_BITS
+#define DBF_LOAD_BITS "nt"
+#endif
+#ifndef DBF_PF
+#define DBF_PF 4
+#endif
+#ifndef DBF_UNR
+#define DBF_UNR 2
+#endif
+#ifndef DBF_WAVES_PER_EU
+#define DBF_WAVES_PER_EU 4
 #endif
 
 namespace {
@@ -41,11 +65,12 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned short us8 __attribute__((ext_vector_type(8)));
 
-constexpr int PF = 8;              // tiles of sign bits kept in flight per wavefront
-constexpr int UNR = 4;             // independent 16-byte loads per thread in the prologue
+constexpr int PF = DBF_PF;         // tiles of sign bits kept in flight per wavefront
+constexpr int UNR = DBF_UNR;       // independent 16-byte loads per thread in the prologue
 constexpr float QMAX = 32512.f;    // 127*256: largest |q| so that hi and lo fit int8
 constexpr int XQ_PAD = 16;         // bytes of padding per operand row (LDS bank spread)
 constexpr unsigned OOB = 0x80000000u;  // buffer offset that is out of range for any span
+constexpr int SPIN_LIMIT = 1 << 18;    // polls of a producer counter before giving up (~0.5 s)
 
 __device__ inline float half_bits_to_float(uint16_t h) {
     return (float)__builtin_bit_cast(_Float16, h);
@@ -64,12 +89,13 @@ __device__ inline int wave_sum(int v) {
     return v;
 }
 
-// LDS carve-up (dynamic): red | misc | xq
+// Fixed part of the LDS carve-up (the quantised operand and the reduction buffers follow).
 struct Misc {
-    float scale[DBF_MAX_BATCH];   // u ~= q * scale
-    float inv[DBF_MAX_BATCH];     // q = rint(u * inv)
-    int sigma[DBF_MAX_BATCH];     // sum over all columns of q
-    float wmax[4][DBF_MAX_BATCH]; // per-wavefront max|u|
+    float scale[DBF_MAX_BATCH];    // u ~= q * scale
+    float inv[DBF_MAX_BATCH];      // q = rint(u * inv)
+    int sigma[DBF_MAX_BATCH];      // sum over all columns of q
+    float wmax[4][DBF_MAX_BATCH];  // per-wavefront max|u|
+    uint16_t rscale[DBF_MAX_SPAN * DBF_TILE_ROWS];  // fp16 row scales of this workgroup's rows
 };
 
 // Eight consecutive input values u[8*v .. 8*v+7] of batch row bi (vector item v).
@@ -77,15 +103,23 @@ struct Misc {
 template <bool STAGE_A>
 struct InputVec {
     v4u r0, r1;
-    __device__ inline void load(const DbfStage& st, const uint16_t* x, int bi, int v, bool x_ok) {
+    __device__ inline void load(const DbfItem& it, const uint16_t* x, int bi, int v, bool x_ok) {
         if (STAGE_A) {
-            const v4f* p = reinterpret_cast<const v4f*>(st.t + (size_t)bi * st.t_stride) + 2 * (size_t)v;
-            r0 = __builtin_bit_cast(v4u, p[0]);
-            r1 = __builtin_bit_cast(v4u, p[1]);
+            // t may have been written by another compute die during this very launch: read it
+            // with agent-scope loads, which never return a stale line of this die's L2
+            const unsigned* p = reinterpret_cast<const unsigned*>(it.t + (size_t)bi * it.t_stride) + 8 * (size_t)v;
+            r0.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r0.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r0.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r0.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1.x = __hip_atomic_load(p + 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1.y = __hip_atomic_load(p + 5, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1.z = __hip_atomic_load(p + 6, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1.w = __hip_atomic_load(p + 7, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
-            r1 = __builtin_bit_cast(v4u, reinterpret_cast<const us8*>(st.in_scale)[v]);
+            r1 = __builtin_bit_cast(v4u, reinterpret_cast<const us8*>(it.in_scale)[v]);
             r0 = (v4u){0, 0, 0, 0};
-            if (x_ok) r0 = __builtin_bit_cast(v4u, reinterpret_cast<const us8*>(x + (size_t)bi * st.cols)[v]);
+            if (x_ok) r0 = __builtin_bit_cast(v4u, reinterpret_cast<const us8*>(x + (size_t)bi * it.cols)[v]);
         }
     }
     __device__ inline void get(float (&u)[8]) const {
@@ -99,49 +133,189 @@ struct InputVec {
             for (int i = 0; i < 8; ++i) u[i] = (float)xv[i] * (float)bv[i];
         }
     }
+    __device__ inline float absmax() const {
+        float u[8], m = 0.f;
+        get(u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(u[i]));
+        return m;
+    }
+    // Quantises the eight values, stores the two int8 planes, returns the sum of the q.
+    __device__ inline int quantise_to(signed char* hi_dst, signed char* lo_dst, float inv) const {
+        float u[8];
+        get(u);
+        unsigned hi4[2] = {0, 0}, lo4[2] = {0, 0};
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float f = rintf(u[i] * inv);
+            f = fminf(fmaxf(f, -QMAX), QMAX);
+            const int q = (int)f;
+            const int lo = ((q + 128) & 255) - 128;
+            const int hi = (q - lo) >> 8;
+            hi4[i >> 2] |= (unsigned)(hi & 255) << (8 * (i & 3));
+            lo4[i >> 2] |= (unsigned)(lo & 255) << (8 * (i & 3));
+            sum += q;
+        }
+        *reinterpret_cast<uint2*>(hi_dst) = make_uint2(hi4[0], hi4[1]);
+        *reinterpret_cast<uint2*>(lo_dst) = make_uint2(lo4[0], lo4[1]);
+        return sum;
+    }
 };
 
 template <bool STAGE_A>
-__device__ inline float load_u_scalar(const DbfStage& st, const uint16_t* x, int bi, int l) {
-    if (STAGE_A) return st.t[(size_t)bi * st.t_stride + l];
-    return half_bits_to_float(x[(size_t)bi * st.cols + l]) * half_bits_to_float(st.in_scale[l]);
+__device__ inline float load_u_scalar(const DbfItem& it, const uint16_t* x, int bi, int l) {
+    if (STAGE_A)
+        return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const unsigned*>(it.t) + (size_t)bi * it.t_stride + l,
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    return half_bits_to_float(x[(size_t)bi * it.cols + l]) * half_bits_to_float(it.in_scale[l]);
 }
 
-__device__ inline int quantise(float u, float inv) {
-    float f = rintf(u * inv);
-    f = fminf(fmaxf(f, -QMAX), QMAX);
-    return (int)f;
+// What the input helpers need to know about the workgroup.
+struct Ctx {
+    Misc* misc;
+    signed char* xq;
+    const uint16_t* x;  // B stage input rows (fp16), unused in the A stage
+    int chs;            // bytes per operand row in LDS
+    int tid, lane, w;
+    int batch;
+    bool fast;          // 16-byte vector loads are possible
+    int nvec, nvec_x;   // vector items per row incl. padding / items backed by x
+};
+
+// The decode case in one pass: load the row once, reduce max|u|, quantise from registers.
+// Contains one barrier; ends with the operand in LDS (not yet synchronised).
+template <bool STAGE_A>
+__device__ inline void input_one_pass(const DbfItem& it, const Ctx& c) {
+    InputVec<STAGE_A> iv[UNR];
+    float mx = 0.f;
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) {
+        const int v = 256 * j + c.tid;
+        if (v < c.nvec) iv[j].load(it, c.x, 0, v, v < c.nvec_x);
+    }
+#pragma unroll
+    for (int j = 0; j < UNR; ++j)
+        if (256 * j + c.tid < c.nvec) mx = fmaxf(mx, iv[j].absmax());
+    mx = wave_max(mx);
+    if (c.lane == 0) c.misc->wmax[c.w][0] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(c.misc->wmax[0][0], c.misc->wmax[1][0]), fmaxf(c.misc->wmax[2][0], c.misc->wmax[3][0]));
+    const float inv = mx > 0.f ? QMAX / mx : 0.f;
+    if (c.tid == 0) c.misc->scale[0] = mx / QMAX;
+    int local = 0;
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) {
+        const int v = 256 * j + c.tid;
+        if (v < c.nvec) local += iv[j].quantise_to(c.xq + v * 8, c.xq + c.chs + v * 8, inv);
+    }
+    local = wave_sum(local);
+    if (c.lane == 0) atomicAdd(&c.misc->sigma[0], local);
 }
 
-template <bool STAGE_A, int NCG>
-__global__ __launch_bounds__(256) void dbf_stage_mfma_kernel(const DbfStage* __restrict__ table,
-                                                             const DbfWorkItem* __restrict__ work,
-                                                             const uint16_t* __restrict__ x_base,
-                                                             uint16_t* __restrict__ y_base,
-                                                             int batch, int ch_tiles) {
+// General case, first pass: max|u| of every batch row -> scale / inv.  Two barriers.
+template <bool STAGE_A>
+__device__ inline void input_scales(const DbfItem& it, const Ctx& c) {
+    for (int bi = 0; bi < c.batch; ++bi) {
+        float mx = 0.f;
+        if (c.fast) {
+            for (int base = 0; base < c.nvec; base += 256 * UNR) {
+                InputVec<STAGE_A> iv[UNR];
+#pragma unroll
+                for (int j = 0; j < UNR; ++j) {
+                    const int v = base + 256 * j + c.tid;
+                    if (v < c.nvec) iv[j].load(it, c.x, bi, v, v < c.nvec_x);
+                }
+#pragma unroll
+                for (int j = 0; j < UNR; ++j)
+                    if (base + 256 * j + c.tid < c.nvec) mx = fmaxf(mx, iv[j].absmax());
+            }
+        } else {
+            for (int l = c.tid; l < it.cols; l += 256) mx = fmaxf(mx, fabsf(load_u_scalar<STAGE_A>(it, c.x, bi, l)));
+        }
+        mx = wave_max(mx);
+        if (c.lane == 0) c.misc->wmax[c.w][bi] = mx;
+    }
+    __syncthreads();
+    if (c.tid < c.batch) {
+        const float mx = fmaxf(fmaxf(c.misc->wmax[0][c.tid], c.misc->wmax[1][c.tid]),
+                               fmaxf(c.misc->wmax[2][c.tid], c.misc->wmax[3][c.tid]));
+        c.misc->scale[c.tid] = mx / QMAX;
+        c.misc->inv[c.tid] = mx > 0.f ? QMAX / mx : 0.f;
+    }
+    __syncthreads();
+}
+
+// General case, second pass: quantise columns [64*c0, 64*cend) of every batch row into LDS.
+template <bool STAGE_A>
+__device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int c0, int cend) {
+    for (int bi = 0; bi < c.batch; ++bi) {
+        const float inv = c.misc->inv[bi];
+        int local = 0;
+        signed char* hi_row = c.xq + (2 * bi) * c.chs;
+        signed char* lo_row = c.xq + (2 * bi + 1) * c.chs;
+        if (c.fast) {
+            const int v0 = c0 * 8, v1 = cend * 8;
+            for (int base = v0; base < v1; base += 256 * UNR) {
+                InputVec<STAGE_A> iv[UNR];
+#pragma unroll
+                for (int j = 0; j < UNR; ++j) {
+                    const int v = base + 256 * j + c.tid;
+                    if (v < v1) iv[j].load(it, c.x, bi, v, v < c.nvec_x);
+                }
+#pragma unroll
+                for (int j = 0; j < UNR; ++j) {
+                    const int v = base + 256 * j + c.tid;
+                    if (v < v1) local += iv[j].quantise_to(hi_row + (v - v0) * 8, lo_row + (v - v0) * 8, inv);
+                }
+            }
+        } else {
+            for (int l = c0 * 64 + c.tid; l < cend * 64; l += 256) {
+                int q = 0;
+                if (l < it.cols) {
+                    float f = rintf(load_u_scalar<STAGE_A>(it, c.x, bi, l) * inv);
+                    f = fminf(fmaxf(f, -QMAX), QMAX);
+                    q = (int)f;
+                }
+                const int lo = ((q + 128) & 255) - 128;
+                const int hi = (q - lo) >> 8;
+                hi_row[l - c0 * 64] = (signed char)hi;
+                lo_row[l - c0 * 64] = (signed char)lo;
+                local += q;
+            }
+        }
+        local = wave_sum(local);
+        if (c.lane == 0) atomicAdd(&c.misc->sigma[bi], local);
+    }
+}
+
+template <int NCG>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
+void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
+                           int use_sync, const uint16_t* __restrict__ x_base,
+                           uint16_t* __restrict__ y_base, int batch, int ch_tiles) {
     extern __shared__ __align__(16) unsigned char smem[];
-    int* red = reinterpret_cast<int*>(smem);                                   // [NCG][8][64][4]
-    Misc* misc = reinterpret_cast<Misc*>(smem + NCG * 8192);
-    signed char* xq = reinterpret_cast<signed char*>(smem + NCG * 8192 + 512);  // [ncols][chs]
+    const int ncols = 2 * batch;
+    const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
+    Misc* misc = reinterpret_cast<Misc*>(smem);
+    signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
+    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + ((ncols * chs + 15) & ~15));  // [2][128][ncols]
 
-    const DbfWorkItem wi = work[blockIdx.x];
-    const DbfStage st = table[wi.layer];
+    const DbfItem it = items[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
-    const int ncols = 2 * batch;
-    const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
-    const uint16_t* x = x_base + st.x_off * batch;
-    uint16_t* y = y_base + st.y_off * batch;
+    const bool stage_a = it.stage_a != 0;
+    const uint16_t* x = x_base + it.io_off * batch;  // B stage only
+    uint16_t* y = y_base + it.io_off * batch;        // A stage only
 
-    // sign bits of this workgroup's row tiles: one contiguous span, addressed through a buffer
+    // sign bits of this item's row tiles: one contiguous span, addressed through a buffer
     // resource so that out-of-range offsets read as zero without touching memory
-    const uint8_t* span = st.bits + (size_t)wi.rt0 * st.n_ct * DBF_TILE_BYTES;
-    const uint64_t span_addr = reinterpret_cast<uint64_t>(span);
+    const uint64_t span_addr = reinterpret_cast<uint64_t>(it.bits);
     v4u rsrc;  // raw buffer descriptor: base, stride 0, size in bytes, 32-bit raw data format
     rsrc.x = __builtin_amdgcn_readfirstlane((unsigned)span_addr);
     rsrc.y = __builtin_amdgcn_readfirstlane((unsigned)(span_addr >> 32) & 0xFFFFu);
-    rsrc.z = __builtin_amdgcn_readfirstlane((unsigned)(wi.nrt * st.n_ct * DBF_TILE_BYTES));
+    rsrc.z = __builtin_amdgcn_readfirstlane((unsigned)(it.nrt * it.n_ct * DBF_TILE_BYTES));
     rsrc.w = 0x00020000u;
     const unsigned lane_off = lane * 16;
 
@@ -154,20 +328,22 @@ __global__ __launch_bounds__(256) void dbf_stage_mfma_kernel(const DbfStage* __r
     // younger tile loads are outstanding, so vmcnt(PF-1) is the exact wait.  Any other memory
     // operation the compiler issues in between only makes that wait more conservative.
     int c0 = 0;
-    int cend = min(st.n_ct, ch_tiles);
+    int cend = min(it.n_ct, ch_tiles);
     int steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
     int p_rt = 0, p_i = 0;
     v4u buf[PF];
     auto fetch = [&](v4u& dst) {
         const int ct = c0 + w + 4 * p_i;
-        const int ok = (int)(p_rt < wi.nrt) & (int)(ct < cend);
-        const unsigned off = (unsigned)(p_rt * st.n_ct + ct) * DBF_TILE_BYTES;
+        const int ok = (int)(p_rt < it.nrt) & (int)(ct < cend);
+        const unsigned off = (unsigned)(p_rt * it.n_ct + ct) * DBF_TILE_BYTES;
         const unsigned voff = lane_off + (ok ? off : OOB);
 #if DBF_ASM_LOADS
-        asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dst) : "v"(voff), "s"(rsrc) : "memory");
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen " DBF_LOAD_BITS
+                     : "=v"(dst) : "v"(voff), "s"(rsrc) : "memory");
 #else
         dst = __builtin_amdgcn_raw_buffer_load_b128(
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(span), 0, (int)rsrc.z, 0x00020000), voff, 0, 0);
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(it.bits), 0, (int)rsrc.z, 0x00020000),
+            voff, 0, 0);
 #endif
         const int wrap = (int)(p_i + 1 == steps);
         p_i = wrap ? 0 : p_i + 1;
@@ -179,49 +355,41 @@ __global__ __launch_bounds__(256) void dbf_stage_mfma_kernel(const DbfStage* __r
 #endif
     };
 #pragma unroll
-    for (int j = 0; j < PF; ++j) fetch(buf[j]);  // in flight during the prologue
+    for (int j = 0; j < PF; ++j) fetch(buf[j]);  // in flight during the wait and the prologue
 
-    // ---- prologue: per batch row max|u|, then the fixed-point scale ----------------------
-    const int nvec = st.n_ct * 8;  // vector items of 8 values, padding included
-    const bool fast = STAGE_A || ((st.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
-    const int nvec_x = st.cols >> 3;
-    for (int bi = 0; bi < batch; ++bi) {
-        float mx = 0.f;
-        if (fast) {
-            for (int base = 0; base < nvec; base += 256 * UNR) {
-                InputVec<STAGE_A> iv[UNR];
-#pragma unroll
-                for (int j = 0; j < UNR; ++j) {
-                    const int v = base + 256 * j + tid;
-                    if (v < nvec) iv[j].load(st, x, bi, v, v < nvec_x);
-                }
-#pragma unroll
-                for (int j = 0; j < UNR; ++j) {
-                    const int v = base + 256 * j + tid;
-                    if (v < nvec) {
-                        float u[8];
-                        iv[j].get(u);
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[i]));
-                    }
+    // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
+    if (use_sync && stage_a) {
+        if (tid == 0) {
+            int spins = 0;
+            while (__hip_atomic_load(&sync[it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < it.need) {
+                __builtin_amdgcn_s_sleep(16);
+                if (++spins > SPIN_LIMIT) {  // never expected; keeps every wave finite
+                    __hip_atomic_fetch_add(&sync[2 * n_layers], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
                 }
             }
-        } else {
-            for (int l = tid; l < st.cols; l += 256) mx = fmaxf(mx, fabsf(load_u_scalar<STAGE_A>(st, x, bi, l)));
         }
-        mx = wave_max(mx);
-        if (lane == 0) misc->wmax[w][bi] = mx;
+        __syncthreads();  // t is read below with agent-scope loads, so no cache invalidation is needed
     }
-    for (int i = tid; i < NCG * 2048; i += 256) red[i] = 0;
-    __syncthreads();
-    if (tid < batch) {
-        const float mx = fmaxf(fmaxf(misc->wmax[0][tid], misc->wmax[1][tid]),
-                               fmaxf(misc->wmax[2][tid], misc->wmax[3][tid]));
-        misc->scale[tid] = mx / QMAX;
-        misc->inv[tid] = mx > 0.f ? QMAX / mx : 0.f;
-        misc->sigma[tid] = 0;
+
+    // ---- prologue ------------------------------------------------------------------------------
+    Ctx cx;
+    cx.misc = misc;  cx.xq = xq;  cx.x = x;  cx.chs = chs;
+    cx.tid = tid;  cx.lane = lane;  cx.w = w;  cx.batch = batch;
+    cx.nvec = it.n_ct * 8;
+    cx.nvec_x = it.cols >> 3;
+    cx.fast = stage_a || ((it.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
+    // row scales of this item's rows (zero padded in memory up to a full row tile)
+    for (int i = tid; i < it.nrt * DBF_TILE_ROWS; i += 256) misc->rscale[i] = it.row_scale[i];
+    for (int i = tid; i < 2 * DBF_TILE_ROWS * ncols; i += 256) red[i] = 0;
+    if (tid < DBF_MAX_BATCH) misc->sigma[tid] = 0;
+
+    const bool one_pass = cx.fast && batch == 1 && cx.nvec <= 256 * UNR && it.n_ct <= ch_tiles;
+    if (one_pass) {
+        if (stage_a) input_one_pass<true>(it, cx); else input_one_pass<false>(it, cx);
+    } else {
+        if (stage_a) input_scales<true>(it, cx); else input_scales<false>(it, cx);
     }
-    __syncthreads();
 
     v4i acc[NCG][8];
     // operand row this lane feeds to the matrix instruction (unused columns alias a valid row)
@@ -234,62 +402,18 @@ __global__ __launch_bounds__(256) void dbf_stage_mfma_kernel(const DbfStage* __r
     const int xo_max = (ch_tiles - 1) * 64;  // padded steps read a valid (ignored) operand
     // epilogue coordinates: thread -> (row rho of the tile, batch rows bi = tid>>7, +2, ...)
     const int rho = tid & 127;
-    const int e_s = rho >> 4, e_g = (rho & 15) >> 2, e_i = rho & 3;
+    const int e_s = rho >> 4;
+    int tile_no = 0;  // row tiles finished so far: selects the reduction buffer
 
     for (;;) {  // chunks of columns (a single one unless the batch is large)
-        // ---- quantise columns [64*c0, 64*cend) of every batch row into LDS ----------------
-        for (int bi = 0; bi < batch; ++bi) {
-            const float inv = misc->inv[bi];
-            int local = 0;
-            signed char* hi_row = xq + (2 * bi) * chs;
-            signed char* lo_row = xq + (2 * bi + 1) * chs;
-            if (fast) {
-                const int v0 = c0 * 8, v1 = cend * 8;
-                for (int base = v0; base < v1; base += 256 * UNR) {
-                    InputVec<STAGE_A> iv[UNR];
-#pragma unroll
-                    for (int j = 0; j < UNR; ++j) {
-                        const int v = base + 256 * j + tid;
-                        if (v < v1) iv[j].load(st, x, bi, v, v < nvec_x);
-                    }
-#pragma unroll
-                    for (int j = 0; j < UNR; ++j) {
-                        const int v = base + 256 * j + tid;
-                        if (v < v1) {
-                            float u[8];
-                            iv[j].get(u);
-                            unsigned hi4[2] = {0, 0}, lo4[2] = {0, 0};
-#pragma unroll
-                            for (int i = 0; i < 8; ++i) {
-                                const int q = quantise(u[i], inv);
-                                const int lo = ((q + 128) & 255) - 128;
-                                const int hi = (q - lo) >> 8;
-                                hi4[i >> 2] |= (unsigned)(hi & 255) << (8 * (i & 3));
-                                lo4[i >> 2] |= (unsigned)(lo & 255) << (8 * (i & 3));
-                                local += q;
-                            }
-                            *reinterpret_cast<uint2*>(hi_row + (v - v0) * 8) = make_uint2(hi4[0], hi4[1]);
-                            *reinterpret_cast<uint2*>(lo_row + (v - v0) * 8) = make_uint2(lo4[0], lo4[1]);
-                        }
-                    }
-                }
-            } else {
-                for (int l = c0 * 64 + tid; l < cend * 64; l += 256) {
-                    const int q = l < st.cols ? quantise(load_u_scalar<STAGE_A>(st, x, bi, l), inv) : 0;
-                    const int lo = ((q + 128) & 255) - 128;
-                    const int hi = (q - lo) >> 8;
-                    hi_row[l - c0 * 64] = (signed char)hi;
-                    lo_row[l - c0 * 64] = (signed char)lo;
-                    local += q;
-                }
-            }
-            local = wave_sum(local);
-            if (lane == 0) atomicAdd(&misc->sigma[bi], local);
+        if (!one_pass) {
+            if (stage_a) input_quantise_chunk<true>(it, cx, c0, cend);
+            else input_quantise_chunk<false>(it, cx, c0, cend);
         }
         __syncthreads();
-        const bool last_chunk = cend >= st.n_ct;
+        const bool last_chunk = cend >= it.n_ct;
 
-        for (int rtl = 0; rtl < wi.nrt; ++rtl) {
+        for (int rtl = 0; rtl < it.nrt; ++rtl) {
             if (c0 == 0) {
 #pragma unroll
                 for (int gi = 0; gi < NCG; ++gi)
@@ -332,27 +456,30 @@ __global__ __launch_bounds__(256) void dbf_stage_mfma_kernel(const DbfStage* __r
             if (!last_chunk) continue;  // (only with nrt == 1) keep accumulating over chunks
 
             // ---- combine the four wavefronts (integer adds: exact, order independent) -----
+            // acc[gi][s][i] of lane (g, c) is row 16*s + 4*g + i, column 16*gi + c.  The two
+            // reduction buffers alternate, so one barrier per row tile is enough: a buffer is
+            // cleared by its readers one barrier before anybody adds to it again.
+            int* rb = red + (tile_no & 1) * DBF_TILE_ROWS * ncols;
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi) {
-                if (16 * gi + c < ncols) {
+                const int col = 16 * gi + c;
+                if (col < ncols) {
 #pragma unroll
                     for (int s = 0; s < 8; ++s)
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            atomicAdd(&red[((gi * 8 + s) * 64 + lane) * 4 + i], acc[gi][s][i]);
+                            atomicAdd(&rb[(16 * s + 4 * g + i) * ncols + col], acc[gi][s][i]);
                 }
             }
+            ++tile_no;
             __syncthreads();
-            // result element (row 4*g'+i of group s, column) sits in lane 16*g'+column
-            const int row = (wi.rt0 + rtl) * DBF_TILE_ROWS + rho;
-            const float rscale = half_bits_to_float(st.row_scale[row]);
+            const int row = it.row0 + rtl * DBF_TILE_ROWS + rho;
+            const float rscale = half_bits_to_float(misc->rscale[rtl * DBF_TILE_ROWS + rho]);
             for (int bi = tid >> 7; bi < batch; bi += 2) {
-                const int col = 2 * bi;
-                const int gi = col >> 4, cc = col & 15;
-                int* ph = &red[((gi * 8 + e_s) * 64 + 16 * e_g + cc) * 4 + e_i];
-                int vh = ph[0], vl = ph[4];
-                ph[0] = 0;  // ready for the next row tile
-                ph[4] = 0;
+                int* ph = &rb[rho * ncols + 2 * bi];
+                int vh = ph[0], vl = ph[1];
+                ph[0] = 0;
+                ph[1] = 0;
                 if (e_s < 7) {
                     vh >>= e_s;
                     vl >>= e_s;
@@ -362,33 +489,61 @@ __global__ __launch_bounds__(256) void dbf_stage_mfma_kernel(const DbfStage* __r
                 }
                 const int total = 2 * (vh * 256 + vl) - misc->sigma[bi];
                 const float val = (float)total * misc->scale[bi] * rscale;
-                if (STAGE_A) {
-                    if (row < st.rows) y[(size_t)bi * st.rows + row] = float_to_half_bits(val);
+                if (stage_a) {
+                    if (row < it.rows) y[(size_t)bi * it.rows + row] = float_to_half_bits(val);
                 } else {
-                    st.t[(size_t)bi * st.t_stride + row] = val;  // padded rows have scale 0
+                    // agent-scope store: written through to memory, where the A-stage
+                    // workgroups of other compute dies read it (padded rows have scale 0)
+                    __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + (size_t)bi * it.t_stride + row,
+                                       __builtin_bit_cast(unsigned, val), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
-            __syncthreads();
         }
         if (last_chunk) break;
         // next chunk (reached only with nrt == 1): restart the tile cursor there
         __syncthreads();  // every wavefront is done reading this chunk's operand
         c0 = cend;
-        cend = min(st.n_ct, c0 + ch_tiles);
+        cend = min(it.n_ct, c0 + ch_tiles);
         steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
         p_rt = 0;
         p_i = 0;
 #pragma unroll
         for (int j = 0; j < PF; ++j) fetch(buf[j]);
     }
+
+    // ---- fused launch: a B-stage item publishes its rows of t.  The counters are per layer
+    // (one shared counter for the whole grid would serialise thousands of atomics on one
+    // address).  The last A-stage item of a layer to finish clears the layer's two counters
+    // for the next launch: every A-stage item of the layer has passed its wait by then.
+    if (use_sync) {
+        if (!stage_a) {
+            // this wavefront's write-through stores of t have been acknowledged by memory ...
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();  // ... and so have those of the whole workgroup
+            if (tid == 0)
+                __hip_atomic_fetch_add(&sync[it.layer], it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (tid == 0) {
+            const int fin = __hip_atomic_fetch_add(&sync[n_layers + it.layer], 1, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+            if (fin == it.peers - 1) {
+                __hip_atomic_store(&sync[it.layer], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&sync[n_layers + it.layer], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+size_t mfma_smem_bytes(int batch, int ch_tiles) {
+    const int ncols = 2 * batch;
+    const size_t xq = ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
+    return sizeof(Misc) + xq + 2 * (size_t)DBF_TILE_ROWS * ncols * sizeof(int);
 }
 
 }  // namespace
 
 int dbf_mfma_chunk_tiles(int batch, int max_cols) {
-    const int ncg = batch > 8 ? 2 : 1;
     const int ncols = 2 * batch;
-    const int budget = ncg == 2 ? 40960 : 32768;  // LDS bytes for the quantised operand
+    const int budget = batch > 8 ? 32768 : 28672;  // LDS bytes for the quantised operand
     int ch_tiles = ((budget / ncols - XQ_PAD) / DBF_TILE_COLS) & ~3;
     const int need = (dbf_col_tiles(max_cols) + 3) & ~3;
     if (ch_tiles > need) ch_tiles = need;
@@ -396,30 +551,19 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols) {
     return ch_tiles;
 }
 
-hipError_t dbf_launch_stage_mfma(bool stage_a, const DbfStage* table, const DbfWorkItem* work,
-                                 int blocks, const void* x_base, void* y_base, int batch,
+hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
+                                 int use_sync, const void* x_base, void* y_base, int batch,
                                  int max_cols, hipStream_t stream) {
-    if (blocks <= 0) return hipSuccess;
+    if (n_items <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
-    const int ncg = batch > 8 ? 2 : 1;
-    const int ncols = 2 * batch;
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols);
-    const size_t smem = (size_t)ncg * 8192 + 512 + (size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD);
-    if (ncg == 1) {
-        if (stage_a)
-            hipLaunchKernelGGL((dbf_stage_mfma_kernel<true, 1>), dim3(blocks), dim3(256), smem, stream,
-                               table, work, x, y, batch, ch_tiles);
-        else
-            hipLaunchKernelGGL((dbf_stage_mfma_kernel<false, 1>), dim3(blocks), dim3(256), smem, stream,
-                               table, work, x, y, batch, ch_tiles);
-    } else {
-        if (stage_a)
-            hipLaunchKernelGGL((dbf_stage_mfma_kernel<true, 2>), dim3(blocks), dim3(256), smem, stream,
-                               table, work, x, y, batch, ch_tiles);
-        else
-            hipLaunchKernelGGL((dbf_stage_mfma_kernel<false, 2>), dim3(blocks), dim3(256), smem, stream,
-                               table, work, x, y, batch, ch_tiles);
-    }
+    const size_t smem = mfma_smem_bytes(batch, ch_tiles);
+    if (batch <= 8)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
     return hipGetLastError();
 }

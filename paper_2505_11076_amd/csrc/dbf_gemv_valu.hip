@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void dbf_stage_valu_kernel(const DbfStage* __r
 
 hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfWorkItem* work,
                                  int blocks, const void* x_base, void* y_base, int batch,
-                                 int /*max_cols*/, hipStream_t stream) {
+                                 hipStream_t stream) {
     if (blocks <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);

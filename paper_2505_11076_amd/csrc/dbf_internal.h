@@ -7,11 +7,12 @@
 #define DBF_TILE_ROWS 128
 #define DBF_TILE_COLS 64
 #define DBF_TILE_BYTES 1024
+#define DBF_MAX_SPAN 16  /* most row tiles one workgroup takes */
 
 static inline int dbf_row_tiles(int rows) { return (rows + DBF_TILE_ROWS - 1) / DBF_TILE_ROWS; }
 static inline int dbf_col_tiles(int cols) { return (cols + DBF_TILE_COLS - 1) / DBF_TILE_COLS; }
 
-// One sign-matrix stage of one layer as the kernels see it (lives in device memory).
+// One sign-matrix stage of one layer as the vector-ALU kernel sees it (device memory).
 //   B stage: bits = B tiled (k rows, n_in cols), in_scale = b, row_scale = m, input is the
 //            caller's fp16 x, output is the layer's fp32 middle scratch t.
 //   A stage: bits = A tiled (n_out rows, k cols), in_scale = NULL, row_scale = a, input is t,
@@ -29,12 +30,53 @@ struct DbfStage {
     int pad_;
 };
 
-// Work item of one workgroup: `nrt` consecutive 128-row tiles of one layer, starting at rt0.
+// Work item of the vector-ALU kernel: one 128-row tile of one layer.
 struct DbfWorkItem {
     int layer;
     int rt0;
     int nrt;
     int pad_;
+};
+
+// Work item of the matrix-core kernel: `nrt` consecutive row tiles of one stage of one layer,
+// with everything the workgroup needs in one 96-byte record (one scalar load, no second hop
+// through a per-layer table).  A launch list holds all B-stage items first, then all A-stage
+// items, so that a fused launch dispatches every producer before any consumer.
+struct DbfItem {
+    const uint8_t* bits;        // first tile of the item's first row tile
+    const uint16_t* in_scale;   // B stage: b (fp16, zero padded to n_ct*64); A stage: NULL
+    const uint16_t* row_scale;  // fp16 scales starting at the item's first row (zero padded)
+    float* t;                   // the layer's middle activations [DBF_MAX_BATCH][t_stride]
+    long long io_off;           // B: element offset of the layer's x block, A: of its y block
+                                // (both per unit of batch)
+    int n_ct;                   // column tiles of the stage
+    int nrt;                    // row tiles of this item (1..DBF_MAX_SPAN)
+    int row0;                   // first row of the item
+    int rows;                   // valid rows of the stage
+    int cols;                   // valid columns of the stage
+    int t_stride;               // elements between batch rows of t
+    int layer;                  // index of the layer's "B rows done" counter
+    int need;                   // A stage: B-stage row tiles of the layer that must be done
+    int stage_a;                // 0: B stage, 1: A stage
+    int peers;                  // A stage: number of A-stage items of this layer in the list
+    int pad_[2];
+};
+
+// Device-side state of one launch plan: everything a decode call of a layer or a stack needs.
+struct DbfPlan {
+    void* dev_block;            // single allocation holding all tables below
+    int n_layers;
+    DbfStage* d_stagesB;        // [n_layers]
+    DbfStage* d_stagesA;        // [n_layers]
+    DbfWorkItem* d_workB1;      // vector-ALU work lists, one row tile per workgroup
+    DbfWorkItem* d_workA1;
+    int blocksB1, blocksA1;
+    DbfItem* d_items_n;         // matrix-core items, up to `span` row tiles each: B items, then A items
+    int nBn, nAn;
+    DbfItem* d_items_1;         // the same with one row tile per item (used when the columns of
+    int nB1, nA1;               // a stage do not fit one LDS chunk at the requested batch)
+    int* d_sync;                // [n_layers] B-row-tile counters, [n_layers] finished A items, [1] time-outs
+    int max_cols_B, max_cols_A;
 };
 
 struct dbf_layer {
@@ -49,25 +91,14 @@ struct dbf_layer {
     uint16_t* db;           // fp16 [col_tiles(n_in)*64]
     float* dt;              // fp32 [DBF_MAX_BATCH][t_stride]
     int t_stride;
-    DbfStage* d_stages;     // device copy of {B stage, A stage}
-    DbfStage h_stages[2];   // host copy
-    DbfWorkItem* d_workB;   // device [n_rt of B]: one row tile per workgroup
-    DbfWorkItem* d_workA;   // device [n_rt of A]
+    DbfStage h_stages[2];   // {B stage, A stage} with offsets 0
+    DbfPlan plan;           // launch plan of this layer alone
 };
 
 struct dbf_stack {
     int n_layers;
     int device;
-    void* dev_block;
-    DbfStage* d_stagesB;    // device [n_layers]
-    DbfStage* d_stagesA;    // device [n_layers]
-    DbfWorkItem* d_workB1;  // device [blocksB1]: one row tile per workgroup
-    DbfWorkItem* d_workA1;  // device [blocksA1]
-    DbfWorkItem* d_workBn;  // device [blocksBn]: several row tiles per workgroup
-    DbfWorkItem* d_workAn;  // device [blocksAn]
-    int blocksB1, blocksA1, blocksBn, blocksAn;
-    int max_ct_B, max_ct_A; // largest number of column tiles over the layers
-    int max_cols_B, max_cols_A;
+    DbfPlan plan;
     long long* h_x_prefix;  // host [n_layers+1] prefix sums of n_in
     long long* h_y_prefix;  // host [n_layers+1] prefix sums of n_out
 };

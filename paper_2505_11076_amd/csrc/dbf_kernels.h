@@ -6,16 +6,22 @@
 
 #include "dbf_internal.h"
 
-// One stage (B or A): `blocks` workgroups, workgroup i handles work[i].  x_base / y_base are
-// the caller's fp16 buffers (only the one the stage touches is used).  max_cols = largest
-// `cols` over the table (sizes the LDS staging).  The VALU kernel takes items with nrt == 1
-// only; the MFMA kernel takes nrt > 1 only when all columns fit one LDS chunk, i.e. when
-// dbf_mfma_chunk_tiles(batch, max_cols) covers every layer's column tiles.
+// Vector-ALU kernel, one stage (B or A): `blocks` workgroups, workgroup i handles work[i]
+// (one row tile).  x_base / y_base are the caller's fp16 buffers (only the one the stage
+// touches is used).
 hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfWorkItem* work,
                                  int blocks, const void* x_base, void* y_base, int batch,
-                                 int max_cols, hipStream_t stream);
-hipError_t dbf_launch_stage_mfma(bool stage_a, const DbfStage* table, const DbfWorkItem* work,
-                                 int blocks, const void* x_base, void* y_base, int batch,
+                                 hipStream_t stream);
+
+// Matrix-core kernel over items[0..n_items): workgroup i handles items[i].
+//   use_sync != 0 (fused launch of B items followed by A items): an A-stage workgroup waits
+//   until sync[item.layer] reaches item.need before it reads t; B-stage workgroups publish
+//   their rows there; the last workgroup to finish clears the counters for the next launch.
+//   use_sync == 0: no waiting and no counters (the caller orders the stages by launches).
+// Items with nrt > 1 are allowed only if every item's columns fit one LDS chunk, i.e.
+// dbf_mfma_chunk_tiles(batch, max_cols) >= dbf_col_tiles(max_cols).
+hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
+                                 int use_sync, const void* x_base, void* y_base, int batch,
                                  int max_cols, hipStream_t stream);
 int dbf_mfma_chunk_tiles(int batch, int max_cols);
 

@@ -16,7 +16,7 @@ import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
-KINDS = [(B.GEMV_VALU, "valu"), (B.GEMV_MFMA, "mfma")]
+KINDS = [(B.GEMV_VALU, "valu"), (B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split")]
 
 
 def _case(n_in, n_out, k, batch, seed, kinds=KINDS, mode="dense"):
@@ -202,6 +202,45 @@ def test_stack_of_mixed_layers(batch):
                 G.check(y, O.forward_from_packed(Xs[i], L, "dense"), "stack[%s] layer %d" % (name, i))
                 xo_want += batch * L.n_in
                 yo_want += batch * L.n_out
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
+
+
+def test_one_launch_equals_two_launches_bit_for_bit():
+    """The fused launch (A-stage workgroups wait on the device for their layer's B stage) and
+    the two-launch variant run the same integer arithmetic, so their fp16 outputs must be
+    identical; repeated calls exercise the counter reset done by the last workgroup."""
+    shapes = [(512, 512, 256)] * 6 + [(1024, 384, 700), (64, 2048, 64), (2048, 64, 2048)]
+    batch = 2
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 200 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 300 + i)) for i, L in enumerate(Ls)]
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        n_y = sum(batch * L.n_out for L in Ls)
+        outs = {}
+        for kind, name in ((B.GEMV_MFMA_SPLIT, "split"), (B.GEMV_MFMA, "fused")):
+            for rep in range(4):
+                G.say("stack %s rep %d" % (name, rep))
+                y_all = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle(), kind)
+                torch.cuda.synchronize()
+                got = y_all.cpu().view(torch.int16).numpy().copy()
+                if name in outs:
+                    assert np.array_equal(got, outs[name]), (name, rep)
+                outs[name] = got
+        assert np.array_equal(outs["split"], outs["fused"])
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+        # the same for single layers (their B and A workgroups are all resident at once)
+        for i, layer in enumerate(layers[:3] + layers[-2:]):
+            ys = []
+            for kind in (B.GEMV_MFMA_SPLIT, B.GEMV_MFMA, B.GEMV_MFMA):
+                ys.append(G.run_gemv(layer, Xs[layers.index(layer)], kind))
+            assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[1], ys[2])
+            assert B.dbf_sync_timeouts(layer) == 0
     finally:
         stack.close()
         for l in layers:
