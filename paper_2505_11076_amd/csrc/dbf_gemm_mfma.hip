@@ -1,5 +1,261 @@
-// placeholder, replaced below
+// Prefill: the layer product for T tokens as two fp16 matrix-core contractions.
+//
+//   stage 1:  mid = ((X . b) B^T) . m      (T x k,     contraction over n_in)
+//   stage 2:  Y   = (mid A^T) . a          (T x n_out, contraction over k)
+//
+// (forward-pass expression of the paper, section 3; the paper times batch 1 only, so this
+// kernel design is not taken from it).  At hundreds of tokens the sign products really are
+// dense contractions, so they run on v_mfma_f32_16x16x32_f16 with fp32 accumulation:
+//
+//   * The sign matrix is the A operand.  The tile layout already gives lane (r, g) sixteen
+//     columns of row 16*s + r in bit s of its sixteen bytes, which is exactly "row r,
+//     k-group g" of the instruction.  One shift and one bit-field insert turn a loaded word
+//     into a register of two fp16 values -1/+1 (bytes 0 and 2, or 1 and 3, of the word), so a
+//     sign costs one vector-ALU operation and is then used for every token block.
+//   * That pairing fixes the order of the eight k-slots of a lane as columns (0,2,1,3,4,6,5,7)
+//     of its 8-column block; the X tile is written to LDS in the same order, so the B operand
+//     is one 16-byte LDS read.
+//   * The inserted sign bit is set where the stored bit is set (+1), i.e. the operand is the
+//     NEGATED sign matrix; the epilogue multiplies by minus the row scale.
+//   * b is folded into the X tile when it is staged (fp32 product rounded once to fp16),
+//     m and a are applied to the fp32 accumulators in the epilogues, mid is stored as fp16.
+//
+// Work split: a workgroup of 4 wavefronts computes 512 rows x 64 tokens; wavefront w owns the
+// 128-row tile w of the block (8 row groups x 4 token blocks = 32 accumulator tiles) and all
+// four share the 64-token X tile in LDS (double buffered, one barrier per 64 columns).
 #include "dbf_kernels.h"
-extern "C" size_t dbf_gemm_workspace_bytes(const dbf_layer* L, int T) { (void)L; (void)T; return 0; }
-extern "C" int dbf_gemm(const dbf_layer* L, const void* X, void* Y, int T, void* ws, size_t wsb, void* s) {
-    (void)L; (void)X; (void)Y; (void)T; (void)ws; (void)wsb; (void)s; return DBF_EINVAL; }
+
+namespace {
+
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+constexpr int GM_TOKENS = 64;            // tokens per workgroup
+constexpr int GM_ROWTILES = 4;           // 128-row tiles per workgroup (one per wavefront)
+constexpr int XROW_BYTES = 64 * 2 + 16;  // one token's 64 fp16 columns + padding (LDS banks)
+
+struct GemmArgs {
+    const uint8_t* bits;        // tiled sign matrix of the stage: n_rt x n_ct tiles
+    const uint16_t* col_scale;  // fp16 [n_ct*64] (b, zero padded) or NULL
+    const uint16_t* row_scale;  // fp16 [n_rt*128] (m or a, zero padded)
+    const uint16_t* X;          // fp16 [T][ldx]
+    uint16_t* out;              // fp16 [T][ldo]
+    int n_rt, n_ct;
+    int T, ldx, ldo;
+    int k_valid;                // valid columns of X (reads beyond are replaced by zero)
+    int n_valid;                // valid output rows (columns of `out`) to store
+    int x_vec_ok;               // X rows can be read with 16-byte loads
+};
+
+// (mask & a) | (~mask & b): one v_bfi_b32
+__device__ inline unsigned bfi(unsigned mask, unsigned a, unsigned b) { return (mask & a) | (~mask & b); }
+__device__ inline float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ inline unsigned pack2(float lo, float hi) {
+    h2 v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(unsigned, v);
+}
+
+// Sixteen consecutive fp16 columns of one token, loaded from global memory.
+struct XRegs {
+    v4u lo, hi;  // columns 0..7 and 8..15 of the thread's 16-column block
+};
+
+template <bool HAS_COLSCALE>
+__device__ inline XRegs load_x(const GemmArgs& a, int token, int col0) {
+    XRegs r;
+    r.lo = (v4u){0, 0, 0, 0};
+    r.hi = (v4u){0, 0, 0, 0};
+    if (token >= a.T) return r;
+    const uint16_t* row = a.X + (size_t)token * a.ldx;
+    if (a.x_vec_ok && col0 + 16 <= a.k_valid) {
+        const v4u* p = reinterpret_cast<const v4u*>(row + col0);
+        r.lo = p[0];
+        r.hi = p[1];
+    } else if (col0 < a.k_valid) {
+        unsigned w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c0 = col0 + 2 * i, c1 = c0 + 1;
+            const unsigned v0 = c0 < a.k_valid ? row[c0] : 0u;
+            const unsigned v1 = c1 < a.k_valid ? row[c1] : 0u;
+            w[i] = v0 | (v1 << 16);
+        }
+        r.lo = (v4u){w[0], w[1], w[2], w[3]};
+        r.hi = (v4u){w[4], w[5], w[6], w[7]};
+    }
+    return r;
+}
+
+// Scales the 16 columns (stage 1) and writes them to LDS with every group of four columns in
+// the order (0, 2, 1, 3), the order of the k-slots of the expanded sign operand.
+template <bool HAS_COLSCALE>
+__device__ inline void store_x(const GemmArgs& a, const XRegs& r, unsigned char* dst, int col0) {
+    const unsigned in[8] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w, r.hi.x, r.hi.y, r.hi.z, r.hi.w};
+    unsigned out[8];
+    if (HAS_COLSCALE) {
+        const v4u* sp = reinterpret_cast<const v4u*>(a.col_scale + col0);
+        const v4u s0 = sp[0], s1 = sp[1];
+        const unsigned sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {  // four columns 4q .. 4q+3
+            const float u0 = h2f(in[2 * q] & 0xFFFF) * h2f(sc[2 * q] & 0xFFFF);
+            const float u1 = h2f(in[2 * q] >> 16) * h2f(sc[2 * q] >> 16);
+            const float u2 = h2f(in[2 * q + 1] & 0xFFFF) * h2f(sc[2 * q + 1] & 0xFFFF);
+            const float u3 = h2f(in[2 * q + 1] >> 16) * h2f(sc[2 * q + 1] >> 16);
+            out[2 * q] = pack2(u0, u2);
+            out[2 * q + 1] = pack2(u1, u3);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned a01 = in[2 * q], a23 = in[2 * q + 1];
+            out[2 * q] = (a01 & 0xFFFFu) | (a23 << 16);
+            out[2 * q + 1] = (a01 >> 16) | (a23 & 0xFFFF0000u);
+        }
+    }
+    v4u* d = reinterpret_cast<v4u*>(dst);
+    d[0] = (v4u){out[0], out[1], out[2], out[3]};
+    d[1] = (v4u){out[4], out[5], out[6], out[7]};
+}
+
+template <bool HAS_COLSCALE>
+__global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
+    __shared__ __align__(16) unsigned char xs[2][GM_TOKENS * XROW_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int token0 = blockIdx.y * GM_TOKENS;
+    const int rt = blockIdx.x * GM_ROWTILES + w;  // this wavefront's row tile
+    const bool active = rt < a.n_rt;              // wavefronts beyond the matrix only help staging X
+    const v4u* tiles = reinterpret_cast<const v4u*>(a.bits) + (size_t)(active ? rt : 0) * a.n_ct * 64 + lane;
+
+    // staging role: thread -> (token, 16-column block)
+    const int s_tok = tid >> 2, s_col = (tid & 3) * 16;
+    unsigned char* s_dst0 = xs[0] + s_tok * XROW_BYTES + s_col * 2;
+    unsigned char* s_dst1 = xs[1] + s_tok * XROW_BYTES + s_col * 2;
+
+    v4f acc[8][4];
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) acc[s][tb] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    XRegs xr = load_x<HAS_COLSCALE>(a, token0 + s_tok, s_col);
+    v4u bits_cur = tiles[0];
+    store_x<HAS_COLSCALE>(a, xr, s_dst0, s_col);
+    __syncthreads();
+
+    for (int kt = 0; kt < a.n_ct; ++kt) {
+        const bool more = kt + 1 < a.n_ct;
+        v4u bits_next = bits_cur;
+        if (more) {
+            xr = load_x<HAS_COLSCALE>(a, token0 + s_tok, (kt + 1) * 64 + s_col);
+            bits_next = tiles[(size_t)(kt + 1) * 64];
+        }
+        const unsigned char* xb = xs[kt & 1] + c * XROW_BYTES + 32 * g;
+        if (active) {
+            const unsigned wd[4] = {bits_cur.x, bits_cur.y, bits_cur.z, bits_cur.w};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                v8h xf[4];
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb)
+                    xf[tb] = *reinterpret_cast<const v8h*>(xb + tb * 16 * XROW_BYTES + 16 * h);
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    // two fp16 of magnitude 1 whose sign bits are bits (s, 16+s) resp. (8+s, 24+s)
+                    v4u e;
+                    e.x = bfi(0x80008000u, wd[2 * h] << (15 - s), 0x3C003C00u);
+                    e.y = bfi(0x80008000u, wd[2 * h] << (7 - s), 0x3C003C00u);
+                    e.z = bfi(0x80008000u, wd[2 * h + 1] << (15 - s), 0x3C003C00u);
+                    e.w = bfi(0x80008000u, wd[2 * h + 1] << (7 - s), 0x3C003C00u);
+                    const v8h av = __builtin_bit_cast(v8h, e);
+#pragma unroll
+                    for (int tb = 0; tb < 4; ++tb)
+                        acc[s][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[tb], acc[s][tb], 0, 0, 0);
+                }
+            }
+        }
+        if (more) store_x<HAS_COLSCALE>(a, xr, (kt & 1) ? s_dst0 : s_dst1, (kt + 1) * 64 + s_col);
+        __syncthreads();
+        bits_cur = bits_next;
+    }
+
+    // ---- epilogue: acc[s][tb][i] of lane (g, c) is row 16*s + 4*g + i, token 16*tb + c --------
+    if (!active) return;
+    const bool vec_ok = (a.ldo & 3) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 7) == 0;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int n0 = rt * DBF_TILE_ROWS + 16 * s + 4 * g;
+        float rs[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rs[i] = -h2f(a.row_scale[n0 + i]);  // operand was the negated signs
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            const int token = token0 + 16 * tb + c;
+            if (token >= a.T) continue;
+            uint16_t* dst = a.out + (size_t)token * a.ldo + n0;
+            const float v0 = acc[s][tb].x * rs[0], v1 = acc[s][tb].y * rs[1];
+            const float v2 = acc[s][tb].z * rs[2], v3 = acc[s][tb].w * rs[3];
+            if (vec_ok && n0 + 4 <= a.n_valid) {
+                *reinterpret_cast<uint2*>(dst) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+            } else {
+                const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n0 + i < a.n_valid) dst[i] = __builtin_bit_cast(uint16_t, (_Float16)v[i]);
+            }
+        }
+    }
+}
+
+inline size_t mid_stride(const dbf_layer* L) { return (size_t)dbf_row_tiles(L->k) * DBF_TILE_ROWS; }
+
+}  // namespace
+
+extern "C" size_t dbf_gemm_workspace_bytes(const dbf_layer* L, int T) {
+    if (!L || T < 1) return 0;
+    return ((size_t)T * mid_stride(L) * 2 + 255) & ~(size_t)255;
+}
+
+extern "C" int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int T,
+                        void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    if (!L || !X_dev || !Y_dev || T < 1) return DBF_EINVAL;
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) ||
+        workspace_bytes < dbf_gemm_workspace_bytes(L, T))
+        return DBF_EWORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int ks = (int)mid_stride(L);
+    const unsigned tok_blocks = (unsigned)((T + GM_TOKENS - 1) / GM_TOKENS);
+    if (tok_blocks > 65535u) return DBF_EINVAL;
+
+    GemmArgs s1;
+    s1.bits = L->dB;  s1.col_scale = L->db;  s1.row_scale = L->dm;
+    s1.X = static_cast<const uint16_t*>(X_dev);
+    s1.out = static_cast<uint16_t*>(workspace_dev);
+    s1.n_rt = dbf_row_tiles(L->k);  s1.n_ct = dbf_col_tiles(L->n_in);
+    s1.T = T;  s1.ldx = L->n_in;  s1.ldo = ks;
+    s1.k_valid = L->n_in;
+    s1.n_valid = ks;  // padded rows have m = 0 and are written as zeros: stage 2 reads them
+    s1.x_vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(dbf_gemm_stage_kernel<true>,
+                       dim3((s1.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(256), 0, stream, s1);
+    if (hipGetLastError() != hipSuccess) return DBF_EHIP;
+
+    GemmArgs s2;
+    s2.bits = L->dA;  s2.col_scale = nullptr;  s2.row_scale = L->da;
+    s2.X = static_cast<const uint16_t*>(workspace_dev);
+    s2.out = static_cast<uint16_t*>(Y_dev);
+    s2.n_rt = dbf_row_tiles(L->n_out);  s2.n_ct = dbf_col_tiles(L->k);
+    s2.T = T;  s2.ldx = ks;  s2.ldo = L->n_out;
+    s2.k_valid = s2.n_ct * DBF_TILE_COLS;  // <= ks, zero beyond k
+    s2.n_valid = L->n_out;
+    s2.x_vec_ok = 1;
+    hipLaunchKernelGGL(dbf_gemm_stage_kernel<false>,
+                       dim3((s2.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(256), 0, stream, s2);
+    if (hipGetLastError() != hipSuccess) return DBF_EHIP;
+    return DBF_OK;
+}
