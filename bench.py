@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=256, help="distinct layers in the stream")
     ap.add_argument("--batch", type=int, default=1)
-    ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split"], default="auto")
+    ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split", "persist"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--stream-only", action="store_true",
@@ -72,7 +72,7 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
     kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA,
-            "mfma_split": B.GEMV_MFMA_SPLIT}[args.kind]
+            "mfma_split": B.GEMV_MFMA_SPLIT, "persist": B.GEMV_PERSIST}[args.kind]
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
     batch, R = args.batch, args.layers
@@ -126,7 +126,10 @@ def main():
     bytes_layer, bytes_b, bytes_a = algorithmic_bytes(n_in, n_out, k, batch)
     value = bytes_layer * R / (ms_per_step * 1e-3) / 1e9
     ncg = 1 if batch <= 8 else 2
-    if args.kind in ("auto", "mfma"):
+    if args.kind == "persist" and batch == 1:
+        # one persistent launch walks every item of the step
+        dom, dom_ms, dom_bytes = "dbf_decode_persistent_kernel (B and A stages, one launch)", ms_per_step, bytes_layer * R
+    elif args.kind in ("auto", "mfma", "persist"):
         # One launch does both stages of every layer, so a step IS one kernel: its average
         # duration is taken from the HIP events around the back-to-back timed steps (the
         # per-launch events of the timed entry point add a few microseconds of launch latency).

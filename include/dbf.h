@@ -68,7 +68,15 @@ enum {
                           vector of each stage is rounded once to 16-bit fixed point.  Both
                           stages run in ONE launch: A-stage workgroups wait on the device for
                           their layer's B stage                                             */
-    DBF_GEMV_MFMA_SPLIT = 3 /* the same kernel in two launches (B stage, then A stage)      */
+    DBF_GEMV_MFMA_SPLIT = 3, /* the same kernel in two launches (B stage, then A stage)     */
+    DBF_GEMV_PERSIST = 4 /* batch 1 only: the matrix-core adder as one persistent launch whose
+                          workgroups each walk a fixed sequence of work items and prefetch the
+                          next item's record, input and sign bits while streaming the current
+                          one.  Opt-in (AUTO does not pick it).  Runs only when the call
+                          qualifies (batch 1, n_in a multiple of 8, x 16-byte aligned, n_in and
+                          k <= 12288); otherwise it runs as DBF_GEMV_MFMA.  Needs the GPU to
+                          itself for the duration of the launch (all its workgroups must be
+                          resident together); see dbf_sync_timeouts                          */
 };
 
 #define DBF_MAX_BATCH 16       /* largest batch dbf_gemv / dbf_stack_gemv accept */

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdbf.so")
 
 DBF_OK, DBF_EINVAL, DBF_ESHAPE, DBF_ENOTSIGN, DBF_ENOMEM, DBF_EHIP, DBF_EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
-GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT = 0, 1, 2, 3
+GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT, GEMV_PERSIST = 0, 1, 2, 3, 4
 MAX_BATCH = 16
 
 EXPORTS = [

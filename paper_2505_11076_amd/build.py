@@ -22,6 +22,7 @@ SOURCES = [
     "dbf_api.hip",
     "dbf_gemv_valu.hip",
     "dbf_gemv_mfma.hip",
+    "dbf_gemv_persist.hip",
     "dbf_gemm_mfma.hip",
     "dbf_probe.hip",
 ]

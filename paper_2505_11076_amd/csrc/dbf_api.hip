@@ -72,7 +72,13 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, span);
     nBn = (int)items_n.size();
-    for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span);
+    int span_a = span;  // experiment hook: a different span for the A stage
+    if (const char* e = std::getenv("DBF_STACK_SPAN_A")) {
+        span_a = std::atoi(e);
+        if (span_a < 1) span_a = 1;
+        if (span_a > DBF_MAX_SPAN) span_a = DBF_MAX_SPAN;
+    }
+    for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span_a);
     for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, 1);
     nB1 = (int)items_1.size();
     for (int i = 0; i < n; ++i) append_items(items_1, sA[i], i, true, sB[i].n_rt, 1);
@@ -85,6 +91,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     const size_t o_in = off;  off = align_up(off + sizeof(DbfItem) * items_n.size(), 256);
     const size_t o_i1 = off;  off = align_up(off + sizeof(DbfItem) * items_1.size(), 256);
     const size_t o_sy = off;  off = align_up(off + sizeof(int) * (2 * (size_t)n + 1), 256);
+    const size_t o_ps = off;  off = align_up(off + sizeof(unsigned) * ((size_t)n + 3), 256);
     std::vector<uint8_t> image(off, 0);
     std::memcpy(image.data() + o_sB, sB.data(), sizeof(DbfStage) * n);
     std::memcpy(image.data() + o_sA, sA.data(), sizeof(DbfStage) * n);
@@ -117,6 +124,16 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->nB1 = nB1;
     p->nA1 = (int)items_1.size() - nB1;
     p->d_sync = reinterpret_cast<int*>(d + o_sy);
+    p->d_psync = reinterpret_cast<unsigned*>(d + o_ps);
+    p->span = span > span_a ? span : span_a;
+    p->persist_ok = p->span <= DBF_PERSIST_MAX_SPAN && p->max_cols_B <= DBF_PERSIST_MAX_COLS &&
+                    p->max_cols_A <= DBF_PERSIST_MAX_COLS;
+    for (int i = 0; i < n; ++i)
+        if (sB[i].cols & 7) p->persist_ok = 0;  // x rows must be readable in 16-byte pieces
+    if (const char* e = std::getenv("DBF_PERSIST_MAX_WG")) {  // test hook: fewer, longer-lived workgroups
+        p->persist_max_wg = std::atoi(e);
+        if (p->persist_max_wg < 0) p->persist_max_wg = 0;
+    }
     return DBF_OK;
 }
 
@@ -209,14 +226,27 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
 
 inline bool kind_ok(int kind) {
     return kind == DBF_GEMV_AUTO || kind == DBF_GEMV_VALU || kind == DBF_GEMV_MFMA ||
-           kind == DBF_GEMV_MFMA_SPLIT;
+           kind == DBF_GEMV_MFMA_SPLIT || kind == DBF_GEMV_PERSIST;
+}
+
+// The persistent kernel handles batch 1 with 16-byte readable inputs and bounded item sizes.
+inline bool persist_eligible(const DbfPlan& p, const void* x, int batch) {
+    return batch == 1 && p.persist_ok && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
 // Launches one decode pass of a plan on `stream`.  `mid`, if not NULL, is recorded between the
 // B-stage launch and the A-stage launch of the two-launch kinds (timed entry point only).
 int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, hipStream_t stream,
                 hipEvent_t mid = nullptr) {
-    if (kind == DBF_GEMV_AUTO) kind = DBF_GEMV_MFMA;
+    if (kind == DBF_GEMV_AUTO) kind = DBF_GEMV_MFMA;  // the persistent kernel is opt-in: slower so far
+    if (kind == DBF_GEMV_PERSIST && !persist_eligible(p, x, batch)) kind = DBF_GEMV_MFMA;
+    if (kind == DBF_GEMV_PERSIST) {
+        const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
+        DBF_HIP_TRY(dbf_launch_persistent(p.d_items_n, p.nBn + p.nAn, p.d_psync, p.d_sync + 2 * p.n_layers,
+                                          p.n_layers, x, y, max_cols, p.persist_max_wg, stream));
+        if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
+        return DBF_OK;
+    }
     if (kind == DBF_GEMV_VALU) {
         DBF_HIP_TRY(dbf_launch_stage_valu(false, p.d_stagesB, p.d_workB1, p.blocksB1, x, y, batch, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));

@@ -8,6 +8,8 @@
 #define DBF_TILE_COLS 64
 #define DBF_TILE_BYTES 1024
 #define DBF_MAX_SPAN 16  /* most row tiles one workgroup takes */
+#define DBF_PERSIST_MAX_SPAN 4  /* most row tiles per item the persistent decode kernel accepts */
+#define DBF_PERSIST_MAX_COLS 12288  /* most columns of a stage it accepts (LDS staging) */
 
 static inline int dbf_row_tiles(int rows) { return (rows + DBF_TILE_ROWS - 1) / DBF_TILE_ROWS; }
 static inline int dbf_col_tiles(int cols) { return (cols + DBF_TILE_COLS - 1) / DBF_TILE_COLS; }
@@ -76,6 +78,11 @@ struct DbfPlan {
     DbfItem* d_items_1;         // the same with one row tile per item (used when the columns of
     int nB1, nA1;               // a stage do not fit one LDS chunk at the requested batch)
     int* d_sync;                // [n_layers] B-row-tile counters, [n_layers] finished A items, [1] time-outs
+    unsigned* d_psync;          // persistent kernel: [n_layers] ever-growing B-row-tile counters,
+                                // then {exited workgroups, epoch}
+    int span;                   // row tiles per item in d_items_n
+    int persist_ok;             // every item of d_items_n meets the persistent kernel's shape limits
+    int persist_max_wg;         // 0, or a cap on the persistent kernel's workgroups (test hook)
     int max_cols_B, max_cols_A;
 };
 

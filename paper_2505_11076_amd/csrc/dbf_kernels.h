@@ -25,4 +25,14 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
                                  int max_cols, hipStream_t stream);
 int dbf_mfma_chunk_tiles(int batch, int max_cols);
 
+// Batch-1 decode of items[0..n_items) (B items first, then A items) in one persistent launch
+// whose workgroups prefetch their next item while streaming the current one.  Requirements
+// (the caller checks them): every item has nrt <= DBF_PERSIST_MAX_SPAN and 16-byte readable
+// inputs (cols % 8 == 0 for B items, x_base 16-byte aligned), max_cols <= DBF_PERSIST_MAX_COLS.
+// psync: [n_layers + 2] zero-initialised words owned by the plan; timeouts: sticky counter.
+// max_wg > 0 caps the number of workgroups (each then walks more items); 0 = as many as fit.
+hipError_t dbf_launch_persistent(const DbfItem* items, int n_items, unsigned* psync, int* timeouts,
+                                 int n_layers, const void* x_base, void* y_base, int max_cols,
+                                 int max_wg, hipStream_t stream);
+
 #endif  // DBF_KERNELS_H

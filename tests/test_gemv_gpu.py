@@ -16,7 +16,8 @@ import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
-KINDS = [(B.GEMV_VALU, "valu"), (B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split")]
+KINDS = [(B.GEMV_VALU, "valu"), (B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split"),
+         (B.GEMV_PERSIST, "persist")]
 
 
 def _case(n_in, n_out, k, batch, seed, kinds=KINDS, mode="dense"):
@@ -241,6 +242,45 @@ def test_one_launch_equals_two_launches_bit_for_bit():
                 ys.append(G.run_gemv(layer, Xs[layers.index(layer)], kind))
             assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[1], ys[2])
             assert B.dbf_sync_timeouts(layer) == 0
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
+
+
+@pytest.mark.parametrize("max_wg,span", [(1, 1), (3, 1), (5, 2), (7, 4), (0, 4)])
+def test_persistent_kernel_walks_several_items(max_wg, span, monkeypatch):
+    """With few workgroups each one of the persistent kernel walks many items: B then B, B then
+    A (dependency poll, late input), A then A, the tile prefetch running across item ends, items
+    of different shapes.  Outputs must match the oracle, equal the one-item-per-workgroup kernel
+    bit for bit (same integer arithmetic), and stay the same over repeated launches (epochs)."""
+    shapes = [(512, 512, 256), (1024, 384, 700), (64, 2048, 64), (2048, 64, 2048), (104, 77, 33),
+              (512, 512, 256), (4096, 256, 128), (256, 640, 1000)]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 400 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(1, L.n_in, I.seed_for(5, 500 + i)) for i, L in enumerate(Ls)]
+    layers = [G.pack(L) for L in Ls]
+    monkeypatch.setenv("DBF_PERSIST_MAX_WG", str(max_wg))
+    monkeypatch.setenv("DBF_STACK_SPAN", str(span))
+    stack = B.dbf_stack_create(layers)   # the hooks are read when the plan is built
+    try:
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        n_y = sum(L.n_out for L in Ls)
+        outs = []
+        for kind, name, reps in ((B.GEMV_MFMA_SPLIT, "split", 1), (B.GEMV_PERSIST, "persist", 3)):
+            for rep in range(reps):
+                G.say("persistent walk max_wg=%d span=%d [%s] rep %d" % (max_wg, span, name, rep))
+                y_all = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), 1, G.stream_handle(), kind)
+                torch.cuda.synchronize()
+                outs.append(y_all.cpu().view(torch.int16).numpy().copy())
+                yo = 0
+                for i, L in enumerate(Ls):
+                    y = G.dev_to_f64(y_all[yo:yo + L.n_out]).reshape(1, L.n_out)
+                    G.check(y, O.forward_from_packed(Xs[i], L, "dense"), "walk[%s] layer %d" % (name, i))
+                    yo += L.n_out
+        for o in outs[1:]:
+            assert np.array_equal(o, outs[0])
+        assert B.dbf_stack_sync_timeouts(stack) == 0
     finally:
         stack.close()
         for l in layers:
