@@ -49,6 +49,10 @@ def main():
     ap.add_argument("--layers", type=int, default=256, help="distinct layers in the stream")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split", "persist"], default="auto")
+    ap.add_argument("--workload", choices=["config2", "config5"], default="config2",
+                    help="config2: 256 distinct 4096x4096 k=2048 layers (the headline); config5: the 224 linear "
+                         "layers of a Llama-2-7B-shaped decoder at 1.5 bits/weight as the main workload")
+    ap.add_argument("--no-config5", action="store_true", help="skip the extra 224-layer stack measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--stream-only", action="store_true",
@@ -75,21 +79,27 @@ def main():
             "mfma_split": B.GEMV_MFMA_SPLIT, "persist": B.GEMV_PERSIST}[args.kind]
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
-    batch, R = args.batch, args.layers
+    batch = args.batch
     stream = torch.cuda.current_stream().cuda_stream
+    if args.workload == "config2":
+        specs = [dict(n_in=n_in, n_out=n_out, k=k)] * args.layers
+        cfg_no = 2
+        workload = ("llama2-7b attention projection n_in=4096 n_out=4096 k=2048 (1.0 bpw), "
+                    "batch-%d decode GEMV, %d distinct layers per step" % (batch, len(specs)))
+        metric = ("DBF layer decode achieved HBM GB/s on algorithmic bytes (batch %d, 4096x4096, k=2048, "
+                  "stream of %d distinct layers)" % (batch, len(specs)))
+    else:
+        specs = I.llama2_7b_stack_shapes()
+        cfg_no = 5
+        workload = ("llama2-7b decoder, all %d linear layers at 1.5 bpw (4096x4096 k=3072, 4096x11008 and "
+                    "11008x4096 k=4477), batch-%d decode GEMV, independent inputs per layer" % (len(specs), batch))
+        metric = ("DBF layer decode achieved HBM GB/s on algorithmic bytes (batch %d, %d-layer llama2-7b stack "
+                  "at 1.5 bpw)" % (batch, len(specs)))
+    R = len(specs)
 
     # ---- the stream of distinct layers ----------------------------------------------------------
     t0 = time.time()
-    layers = []
-    for i in range(R):
-        L = I.make_layer(n_in, n_out, k, seed=I.seed_for(2, i))
-        layers.append(B.dbf_pack_bits(n_in, n_out, k, L.A_bits, L.B_bits, L.a, L.m, L.b))
-    stack = B.dbf_stack_create(layers)
-    rng = np.random.default_rng(I.seed_for(2, 999))
-    x_host = I.random_activations_fp16(rng, R * batch, n_in)
-    x_all = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
-    y_all = torch.zeros(R * batch * n_out, dtype=torch.float16, device="cuda")
-    torch.cuda.synchronize()
+    layers, stack, x_all, y_all = build_stream(B, I, torch, np, specs, cfg_no, batch)
     setup_s = time.time() - t0
 
     def step():
@@ -123,8 +133,10 @@ def main():
         msA.append(a_)
     msB_avg, msA_avg = float(np.mean(msB)), float(np.mean(msA))
 
-    bytes_layer, bytes_b, bytes_a = algorithmic_bytes(n_in, n_out, k, batch)
-    value = bytes_layer * R / (ms_per_step * 1e-3) / 1e9
+    per_layer = [algorithmic_bytes(sp["n_in"], sp["n_out"], sp["k"], batch) for sp in specs]
+    bytes_step = float(sum(p[0] for p in per_layer))
+    bytes_layer, bytes_b, bytes_a = bytes_step / R, sum(p[1] for p in per_layer) / R, sum(p[2] for p in per_layer) / R
+    value = bytes_step / (ms_per_step * 1e-3) / 1e9
     ncg = 1 if batch <= 8 else 2
     if args.kind == "persist" and batch == 1:
         # one persistent launch walks every item of the step
@@ -145,7 +157,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and args.workload == "config2" and R == 256 and batch == 1:
         try:
             traffic = json.load(open(tpath)).get("bench_default_bytes_per_launch")
         except Exception:
@@ -154,12 +166,11 @@ def main():
     # ---- isolated single layer, cache warm -----------------------------------------------------
     iso = None
     if not args.stream_only:
-        iso = isolated_latency(B, torch, np, layers[0], x_all[: batch * n_in], y_all[: batch * n_out],
-                               batch, stream, kind)
+        iso = isolated_latency(B, torch, np, layers[0], x_all[: batch * specs[0]["n_in"]],
+                               y_all[: batch * specs[0]["n_out"]], batch, stream, kind)
 
     out = {
-        "metric": "DBF layer decode achieved HBM GB/s on algorithmic bytes (batch %d, 4096x4096, k=2048, "
-                  "stream of %d distinct layers)" % (batch, R),
+        "metric": metric,
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
@@ -172,8 +183,7 @@ def main():
         "dtype": "int32 (int8 x int8 matrix-core sums of 16-bit fixed-point inputs; fp32 scales)"
                  if args.kind != "valu" else "f32",
         "data": "synthetic",
-        "config": {"workload": "llama2-7b attention projection n_in=4096 n_out=4096 k=2048 (1.0 bpw), "
-                               "batch-%d decode GEMV, %d distinct layers per step" % (batch, R),
+        "config": {"workload": workload,
                    "kernel_variant": args.kind, "layers_per_step": R, "batch": batch},
         "us_per_layer_in_stream": round(ms_per_step * 1e3 / R, 4),
         "layer_products_per_s": round(R / (ms_per_step * 1e-3), 1),
@@ -194,6 +204,18 @@ def main():
         out["frac_of_read_ceiling"] = round(value / ceiling, 4)
         out["roofline"]["frac_of_read_ceiling"] = round(achieved / ceiling, 4)
 
+    stack.close()
+    for l in layers:
+        l.close()
+    del x_all, y_all
+
+    # ---- the 224-layer decoder stack (second decode workload) -----------------------------------
+    if args.workload == "config2" and not args.no_config5 and not args.stream_only:
+        try:
+            out["config5_stack"] = config5_bench(B, I, torch, np, batch, kind, stream)
+        except Exception as exc:  # reported, never hidden
+            out["config5_stack"] = {"error": repr(exc)}
+
     # ---- prefill (matrix-core path) ---------------------------------------------------------------
     if not args.no_prefill and not args.stream_only:
         try:
@@ -203,12 +225,57 @@ def main():
 
     # ---- the CPU oracle on this machine's cores (a baseline, not the target) ---------------------
     if not args.no_cpu_baseline and not args.stream_only:
-        out["cpu_baseline"] = cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer)
+        sp0 = specs[0]
+        out["cpu_baseline"] = cpu_baseline(I, np, sp0["n_in"], sp0["n_out"], sp0["k"], batch,
+                                           per_layer[0][0], cfg_no, R)
 
-    stack.close()
-    for l in layers:
-        l.close()
     print(json.dumps(out))
+
+
+def build_stream(B, I, torch, np, specs, cfg_no, batch):
+    """Packs one distinct random layer per spec, builds the stack and its input / output blocks
+    (x and y of the layers back to back, independent N(0,1) inputs per layer)."""
+    layers = []
+    for i, sp in enumerate(specs):
+        L = I.make_layer(sp["n_in"], sp["n_out"], sp["k"], seed=I.seed_for(cfg_no, i))
+        layers.append(B.dbf_pack_bits(sp["n_in"], sp["n_out"], sp["k"], L.A_bits, L.B_bits, L.a, L.m, L.b))
+    stack = B.dbf_stack_create(layers)
+    rng = np.random.default_rng(I.seed_for(cfg_no, 999))
+    n_x = sum(batch * sp["n_in"] for sp in specs)
+    n_y = sum(batch * sp["n_out"] for sp in specs)
+    x_host = I.random_activations_fp16(rng, 1, n_x)
+    x_all = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
+    y_all = torch.zeros(n_y, dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+    return layers, stack, x_all, y_all
+
+
+def config5_bench(B, I, torch, np, batch, kind, stream, steps=20, warmup=3):
+    """One decode pass over all 224 linear layers of the Llama-2-7B-shaped stack (1.21 GB of signs)."""
+    specs = I.llama2_7b_stack_shapes()
+    layers, stack, x_all, y_all = build_stream(B, I, torch, np, specs, 5, batch)
+    try:
+        for _ in range(warmup):
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        nbytes = float(sum(algorithmic_bytes(sp["n_in"], sp["n_out"], sp["k"], batch)[0] for sp in specs))
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        return {"layers": len(specs), "batch": batch, "ms_per_token_pass": round(ms, 5),
+                "token_passes_per_s": round(1e3 / ms, 1), "GBps": round(gbps, 2),
+                "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": nbytes, "steps": steps,
+                "note": "all linear layers of a 32-block decoder at 1.5 bits/weight, one stack call per pass, "
+                        "independent inputs per layer (no attention / norms between them)"}
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
 
 
 def isolated_latency(B, torch, np, layer, xs, ys, batch, stream, kind):
@@ -286,7 +353,7 @@ def prefill_bench(B, I, torch, np, stream):
     return res
 
 
-def cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer):
+def cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer, cfg_no=2, n_layers=256):
     """Times the oracle as it stands on a bounded sample: one layer of the stream, dense mode
     (decode signs, form W' in fp64, multiply), repeated a few times."""
     from oracle import dbf_oracle as O
@@ -298,8 +365,8 @@ def cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer):
                 threads = int(info.get("num_threads", threads))
     except Exception:
         pass
-    L = I.make_layer(n_in, n_out, k, seed=I.seed_for(2, 0))
-    X = I.make_activations(batch, n_in, I.seed_for(2, 0))
+    L = I.make_layer(n_in, n_out, k, seed=I.seed_for(cfg_no, 0))
+    X = I.make_activations(batch, n_in, I.seed_for(cfg_no, 0))
     times = []
     t_end = time.time() + 20.0
     while len(times) < 3 or (time.time() < t_end and len(times) < 8):
@@ -310,8 +377,9 @@ def cpu_baseline(I, np, n_in, n_out, k, batch, bytes_layer):
             break
     sec = float(np.median(times))
     return {"value": round(bytes_layer / sec / 1e9, 6), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "%d of the %s-layer stream: one 4096x4096 k=2048 layer, batch %d, dense fp64 oracle "
-                      "(decode signs, form W', multiply), median of %d runs" % (1, "256", batch, len(times)),
+            "sample": "1 of the %d-layer stream: one %dx%d k=%d layer, batch %d, dense fp64 oracle "
+                      "(decode signs, form W', multiply), median of %d runs" % (n_layers, n_in, n_out, k, batch,
+                                                                               len(times)),
             "seconds_per_layer": round(sec, 4), "layer_products_per_s": round(1.0 / sec, 4)}
 
 

@@ -20,7 +20,7 @@ Parity pins (tests/test_oracle_pins.py): k=1 rank-one closed form, brute-force
 sum of outer products on tiny shapes (exhaustive for <= 2x2x2), all-ones
 closed form, pure-Python fsum re-evaluation, invariances of the middle index,
 variance law for random signs, packing round trip, the bits-per-weight
-numbers the paper prints.  No function here is "parity unpinned".
+numbers the paper prints; the sampled-rows variant against the dense one.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -129,6 +129,27 @@ def forward_from_packed(X_f16_bits, layer, mode: str = "dense") -> np.ndarray:
     if mode == "staged":
         return forward_staged(X, a, A, m, B, b)
     raise ValueError("mode must be 'dense' or 'staged'")
+
+
+def forward_rows_from_packed(X_f16_bits, layer, rows) -> np.ndarray:
+    """Selected output columns Y[:, rows] of a packed layer, staged order, fp64.
+
+    For full-size layers where decoding all of A is the slow part: the middle
+    activations need every row of B, but output i only needs row i of A
+    (section 3, forward pass: y_i = a_i * sum_j A[i,j] m_j t_j).
+    Returns float64 (batch, len(rows)).
+    """
+    rows = np.asarray(rows, dtype=np.int64)
+    if rows.ndim != 1 or np.any(rows < 0) or np.any(rows >= layer.n_out):
+        raise ValueError("rows must be a 1-D list of output indices")
+    words_A = np.asarray(layer.A_bits, dtype=np.uint32).reshape(layer.n_out, -1)
+    A_sel = unpack_signs(words_A[rows], len(rows), layer.k)
+    B = unpack_signs(layer.B_bits, layer.k, layer.n_in)
+    a = f16_bits_to_f64(layer.a)[rows]
+    m = f16_bits_to_f64(layer.m)
+    b = f16_bits_to_f64(layer.b)
+    X = f16_bits_to_f64(X_f16_bits).reshape(-1, layer.n_in)
+    return forward_staged(X, a, A_sel, m, B, b)
 
 
 # ---------------------------------------------------------------------------

@@ -354,6 +354,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         asm volatile("s_waitcnt vmcnt(%1)" : "+v"(slot) : "n"(PF - 1) : "memory");
 #endif
     };
+    auto retire_ring = [](v4u (&ring)[PF]) {
+#if DBF_ASM_LOADS
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < PF; ++j) asm volatile("" : "+v"(ring[j]));
+#endif
+    };
 #pragma unroll
     for (int j = 0; j < PF; ++j) fetch(buf[j]);  // in flight during the wait and the prologue
 
@@ -453,6 +460,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                     fetch(buf[j]);
                 }
             }
+            // After the last row tile the ring holds PF placeholder loads that nobody will
+            // consume.  They must have landed before the compiler may reuse their registers
+            // (it considers them dead from here on): wait, with the slots as operands so that
+            // they stay allocated up to this point.  Nothing real is in flight any more, so
+            // the wait is short.
+            if (rtl + 1 == it.nrt) retire_ring(buf);
             if (!last_chunk) continue;  // (only with nrt == 1) keep accumulating over chunks
 
             // ---- combine the four wavefronts (integer adds: exact, order independent) -----

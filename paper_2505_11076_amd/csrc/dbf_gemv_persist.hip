@@ -460,6 +460,13 @@ void dbf_decode_persistent_kernel(const DbfItem* __restrict__ items, int n_items
                     fetch(buf[j]);
                 }
             }
+            // After the very last row tile the ring holds PF placeholder loads that nobody will
+            // consume; they must land before the compiler may reuse their registers.
+            if (!n_valid && rtl + 1 == nrt) {
+                drain();
+#pragma unroll
+                for (int j = 0; j < PF; ++j) asm volatile("" : "+v"(buf[j]));
+            }
             // The dependency poll issued before this row tile has landed (PF or more ring loads
             // were waited for since): start the input of an A item as early as its rows exist.
             if (n_valid && !input_issued) {

@@ -299,3 +299,35 @@ def test_forward_from_packed_against_hand_decoded_bits():
     for mode in ("dense", "staged"):
         got = O.forward_from_packed(X, L, mode)
         np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-18)
+
+
+def test_sampled_rows_equal_the_dense_product_and_the_brute_force():
+    """The sampled-rows entry point (used where decoding all of A at full size is too slow)
+    must return exactly the chosen columns of the dense result, in the order asked for,
+    repeated and unsorted indices included; a scalar-loop evaluation pins it independently."""
+    import struct
+
+    def h2f(u):
+        return struct.unpack("<e", struct.pack("<H", int(u)))[0]
+
+    L = I.make_layer(n_in=70, n_out=45, k=33, seed=123)
+    X = I.make_activations(3, 70, 124)
+    rows = [44, 0, 7, 7, 31, 12]
+    got = O.forward_rows_from_packed(X, L, rows)
+    full = O.forward_from_packed(X, L, "dense")
+    assert got.shape == (3, len(rows))
+    np.testing.assert_allclose(got, full[:, rows], rtol=1e-12, atol=1e-18)
+    # one entry by hand: y[t, i] = a_i * sum_j A[i,j] m_j * sum_l B[j,l] b_l x[t,l]
+    t, i = 2, 31
+    acc = []
+    for j in range(33):
+        Aij = 1.0 if (int(L.A_bits[i, j // 32]) >> (j % 32)) & 1 else -1.0
+        inner = math.fsum((1.0 if (int(L.B_bits[j, l // 32]) >> (l % 32)) & 1 else -1.0) * h2f(L.b[l]) * h2f(X[t, l])
+                          for l in range(70))
+        acc.append(Aij * h2f(L.m[j]) * inner)
+    want = h2f(L.a[i]) * math.fsum(acc)
+    assert got[t, rows.index(31)] == pytest.approx(want, rel=1e-12)
+    with pytest.raises(ValueError):
+        O.forward_rows_from_packed(X, L, [45])
+    with pytest.raises(ValueError):
+        O.forward_rows_from_packed(X, L, [-1])

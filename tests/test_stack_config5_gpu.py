@@ -1,0 +1,88 @@
+"""GPU parity at full size of the second decode workload: all 224 linear layers of a
+Llama-2-7B-shaped decoder at 1.5 bits/weight (4096x4096 k=3072, 4096x11008 and 11008x4096
+k=4477; 1.21 GB of sign bits), run as ONE stack call in the launch configuration the benchmark
+times (default kind, batch 1), plus batch 16.
+
+The fp64 oracle cannot decode 224 full layers in test time, so:
+  * the seven layers of the first decoder block are compared element by element (staged fp64);
+  * every eighth layer after that is compared on 64 sampled outputs per batch row, each
+    computed one by one by the oracle from all of B and the sampled rows of A;
+  * EVERY layer is checked against a property that holds at any size: for i.i.d. signs the
+    outputs have variance a_i^2 * sum_j m_j^2 * sum_l (b_l x_l)^2, so the measured rms over a
+    layer's outputs must match the predicted one (this catches a layer fed the wrong x block,
+    a wrong scale vector, or output written to the wrong place).
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as G
+from oracle import dbf_oracle as O
+from paper_2505_11076_amd import binding as B
+from paper_2505_11076_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def _predicted_rms(L, X):
+    a = O.f16_bits_to_f64(L.a)
+    m = O.f16_bits_to_f64(L.m)
+    b = O.f16_bits_to_f64(L.b)
+    x = O.f16_bits_to_f64(X).reshape(-1, L.n_in)
+    per_row = np.sum((x * b[None, :]) ** 2, axis=1) * np.sum(m ** 2)      # (batch,)
+    return np.sqrt(np.mean(a ** 2) * per_row)
+
+
+@pytest.mark.parametrize("batch", [1, 16])
+def test_config5_stack_full_size(batch):
+    specs = I.llama2_7b_stack_shapes()
+    assert len(specs) == 224
+    G.say("config5: generating and packing %d layers" % len(specs))
+    Ls, layers = [], []
+    for i, sp in enumerate(specs):
+        L = I.make_layer(sp["n_in"], sp["n_out"], sp["k"], seed=I.seed_for(5, i))
+        layers.append(G.pack(L))
+        full = i < 7
+        sampled = (not full) and i % 8 == 0
+        # keep the host copy of the bits only where the oracle will need them
+        Ls.append(L if (full or sampled) else I.LayerInputs(L.n_in, L.n_out, L.k, None, None, L.a, L.m, L.b))
+        if i % 32 == 31:
+            G.say("  packed %d" % (i + 1))
+    stack = B.dbf_stack_create(layers)
+    try:
+        rng = np.random.default_rng(I.seed_for(5, 9000 + batch))
+        Xs = [I.random_activations_fp16(rng, batch, sp["n_in"]) for sp in specs]
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        n_y = sum(batch * sp["n_out"] for sp in specs)
+        y_all = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+        G.say("config5: stack call, batch %d" % batch)
+        B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle())
+        torch.cuda.synchronize()
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+        y_host = y_all.cpu().view(torch.int16).numpy().view(np.uint16)
+        yo = 0
+        rows_rng = np.random.default_rng(I.seed_for(5, 7777))
+        for i, (sp, L) in enumerate(zip(specs, Ls)):
+            n_out = sp["n_out"]
+            y = O.f16_bits_to_f64(y_host[yo:yo + batch * n_out]).reshape(batch, n_out)
+            yo += batch * n_out
+            assert np.all(np.isfinite(y)), "layer %d has non-finite outputs" % i
+            rms = np.sqrt(np.mean(y ** 2, axis=1))
+            want = _predicted_rms(L, Xs[i])
+            # n_out >= 4096 samples per row: the sample rms is within a few percent of the law
+            assert np.all(np.abs(rms / want - 1.0) < 0.08), (i, rms, want)
+            if L.A_bits is None:
+                continue
+            if i < 7:
+                G.say("  layer %d: all outputs against the staged oracle" % i)
+                G.check(y, O.forward_from_packed(Xs[i], L, "staged"), "config5 layer %d" % i)
+            else:
+                G.say("  layer %d: 64 sampled outputs" % i)
+                rows = np.sort(rows_rng.choice(n_out, size=64, replace=False))
+                ref = O.forward_rows_from_packed(Xs[i], L, rows)
+                # (the gate's floor, the row rms, is estimated from the 64 sampled reference values)
+                G.check(y[:, rows], ref, "config5 layer %d sampled" % i)
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
