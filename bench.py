@@ -44,8 +44,10 @@ def algorithmic_bytes(n_in, n_out, k, batch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=300,
+                    help="untimed steps before the timed ones (a step is ~0.1 ms; the GPU clocks need a few "
+                         "tens of ms of load to settle after the idle set-up phase)")
     ap.add_argument("--layers", type=int, default=256, help="distinct layers in the stream")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split", "persist"], default="auto")
@@ -250,7 +252,7 @@ def build_stream(B, I, torch, np, specs, cfg_no, batch):
     return layers, stack, x_all, y_all
 
 
-def config5_bench(B, I, torch, np, batch, kind, stream, steps=20, warmup=3):
+def config5_bench(B, I, torch, np, batch, kind, stream, steps=60, warmup=60):
     """One decode pass over all 224 linear layers of the Llama-2-7B-shaped stack (1.21 GB of signs)."""
     specs = I.llama2_7b_stack_shapes()
     layers, stack, x_all, y_all = build_stream(B, I, torch, np, specs, 5, batch)

@@ -287,6 +287,40 @@ def test_persistent_kernel_walks_several_items(max_wg, span, monkeypatch):
             l.close()
 
 
+@pytest.mark.parametrize("batch", [12, 16])
+def test_more_workgroups_than_compute_units_at_large_batch(batch):
+    """Batches 9-16 use large LDS operands, so only two workgroups fit a compute unit; with more
+    than 256 A-stage workgroups some of them share one, and with k = 1024 every A-stage
+    workgroup walks two column chunks.  (Regression: placeholder loads of the tile prefetcher
+    that were still in flight at a chunk restart used to overwrite reused registers in exactly
+    this situation, which corrupted whole row tiles at random.)"""
+    shapes = [(256, 4096, 1024)] * 12
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 800 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 900 + i)) for i, L in enumerate(Ls)]
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        n_y = sum(batch * L.n_out for L in Ls)
+        refs = [O.forward_from_packed(Xs[i], L, "staged") for i, L in enumerate(Ls)]
+        for kind, name in ((B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split")):
+            for rep in range(3):
+                G.say("many workgroups, batch %d [%s] rep %d" % (batch, name, rep))
+                y_all = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle(), kind)
+                torch.cuda.synchronize()
+                yo = 0
+                for i, L in enumerate(Ls):
+                    y = G.dev_to_f64(y_all[yo:yo + batch * L.n_out]).reshape(batch, L.n_out)
+                    G.check(y, refs[i], "many-wg[%s] rep %d layer %d" % (name, rep, i))
+                    yo += batch * L.n_out
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
+
+
 def test_launch_errors_with_a_real_layer():
     L = I.make_layer(seed=I.seed_for(1, 74), **I.CONFIG1)
     layer = G.pack(L)
