@@ -49,8 +49,13 @@ struct GemmArgs {
     int x_vec_ok;               // X rows can be read with 16-byte loads
 };
 
-// (mask & a) | (~mask & b): one v_bfi_b32
-__device__ inline unsigned bfi(unsigned mask, unsigned a, unsigned b) { return (mask & a) | (~mask & b); }
+// (mask & a) | (~mask & b) as ONE v_bfi_b32.  Written as an instruction because with two constant
+// operands the compiler prefers an AND and an OR; all three operands are kept in registers.
+__device__ inline unsigned bfi(unsigned mask, unsigned a, unsigned b) {
+    unsigned d;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "v"(mask), "v"(a), "v"(b));
+    return d;
+}
 __device__ inline float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 __device__ inline unsigned pack2(float lo, float hi) {
     h2 v = {(_Float16)lo, (_Float16)hi};
@@ -143,6 +148,10 @@ __global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
 #pragma unroll
         for (int tb = 0; tb < 4; ++tb) acc[s][tb] = (v4f){0.f, 0.f, 0.f, 0.f};
 
+    // constants of the sign expansion, held in registers (see bfi)
+    unsigned sign_mask = 0x80008000u, one_one = 0x3C003C00u;
+    asm volatile("" : "+v"(sign_mask), "+v"(one_one));
+
     XRegs xr = load_x<HAS_COLSCALE>(a, token0 + s_tok, s_col);
     v4u bits_cur = tiles[0];
     store_x<HAS_COLSCALE>(a, xr, s_dst0, s_col);
@@ -156,7 +165,10 @@ __global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
             bits_next = tiles[(size_t)(kt + 1) * 64];
         }
         const unsigned char* xb = xs[kt & 1] + c * XROW_BYTES + 32 * g;
-        if (active) {
+        // (wavefronts beyond the matrix compute on row tile 0 and discard the result: a branch
+        // around the matrix instructions would make the compiler shuttle all 128 accumulators
+        // between the two register files on every iteration)
+        {
             const unsigned wd[4] = {bits_cur.x, bits_cur.y, bits_cur.z, bits_cur.w};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -168,10 +180,10 @@ __global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
                 for (int s = 0; s < 8; ++s) {
                     // two fp16 of magnitude 1 whose sign bits are bits (s, 16+s) resp. (8+s, 24+s)
                     v4u e;
-                    e.x = bfi(0x80008000u, wd[2 * h] << (15 - s), 0x3C003C00u);
-                    e.y = bfi(0x80008000u, wd[2 * h] << (7 - s), 0x3C003C00u);
-                    e.z = bfi(0x80008000u, wd[2 * h + 1] << (15 - s), 0x3C003C00u);
-                    e.w = bfi(0x80008000u, wd[2 * h + 1] << (7 - s), 0x3C003C00u);
+                    e.x = bfi(sign_mask, wd[2 * h] << (15 - s), one_one);
+                    e.y = bfi(sign_mask, s < 7 ? wd[2 * h] << (7 - s) : wd[2 * h], one_one);
+                    e.z = bfi(sign_mask, wd[2 * h + 1] << (15 - s), one_one);
+                    e.w = bfi(sign_mask, s < 7 ? wd[2 * h + 1] << (7 - s) : wd[2 * h + 1], one_one);
                     const v8h av = __builtin_bit_cast(v8h, e);
 #pragma unroll
                     for (int tb = 0; tb < 4; ++tb)
