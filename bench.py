@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--no-config5", action="store_true", help="skip the extra 224-layer stack measurement")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="only the prefill (matrix-core) measurement: what the prefill rocprofv3 summary is taken on")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -79,6 +81,9 @@ def main():
     B.lib()
     kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA,
             "mfma_split": B.GEMV_MFMA_SPLIT, "persist": B.GEMV_PERSIST}[args.kind]
+    if args.prefill_only:
+        print(json.dumps({"prefill": prefill_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
+        return
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
     batch = args.batch

@@ -20,9 +20,13 @@
 //   * b is folded into the X tile when it is staged (fp32 product rounded once to fp16),
 //     m and a are applied to the fp32 accumulators in the epilogues, mid is stored as fp16.
 //
-// Work split: a workgroup of 4 wavefronts computes 512 rows x 64 tokens; wavefront w owns the
-// 128-row tile w of the block (8 row groups x 4 token blocks = 32 accumulator tiles) and all
-// four share the 64-token X tile in LDS (double buffered, one barrier per 64 columns).
+// Work split: a workgroup of 8 wavefronts computes 512 rows x 64 tokens.  Wavefronts w and w + 4
+// share the 128-row tile w of the block and sit on the same SIMD: each expands only four of the
+// eight bit planes of the sign tile (64 of its rows; 4 row groups x 4 token blocks = 16
+// accumulator tiles), so that the vector-ALU sign expansion of one overlaps the matrix
+// instructions of the other -- a single wavefront issues in order and would do one after the
+// other.  All eight share the 64-token X tile in LDS (double buffered, one barrier per 64
+// columns); the first four stage it.
 #include "dbf_kernels.h"
 
 namespace {
@@ -33,8 +37,10 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
 constexpr int GM_TOKENS = 64;            // tokens per workgroup
-constexpr int GM_ROWTILES = 4;           // 128-row tiles per workgroup (one per wavefront)
+constexpr int GM_ROWTILES = 4;           // 128-row tiles per workgroup (one per pair of wavefronts)
+constexpr int GM_THREADS = 512;
 constexpr int XROW_BYTES = 64 * 2 + 16;  // one token's 64 fp16 columns + padding (LDS banks)
+constexpr int GM_DEPTH = 4;              // 64-column steps requested ahead of the one being computed
 
 struct GemmArgs {
     const uint8_t* bits;        // tiled sign matrix of the stage: n_rt x n_ct tiles
@@ -99,7 +105,11 @@ template <bool HAS_COLSCALE>
 __device__ inline void store_x(const GemmArgs& a, const XRegs& r, unsigned char* dst, int col0) {
     const unsigned in[8] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w, r.hi.x, r.hi.y, r.hi.z, r.hi.w};
     unsigned out[8];
-    if (HAS_COLSCALE) {
+    if (HAS_COLSCALE && col0 >= a.k_valid) {
+        // a step beyond the matrix: X is zero there and the scale vector has no such entries
+#pragma unroll
+        for (int q = 0; q < 8; ++q) out[q] = 0u;
+    } else if (HAS_COLSCALE) {
         const v4u* sp = reinterpret_cast<const v4u*>(a.col_scale + col0);
         const v4u s0 = sp[0], s1 = sp[1];
         const unsigned sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
@@ -126,14 +136,16 @@ __device__ inline void store_x(const GemmArgs& a, const XRegs& r, unsigned char*
 }
 
 template <bool HAS_COLSCALE>
-__global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
+__global__ __launch_bounds__(GM_THREADS) void dbf_gemm_stage_kernel(const GemmArgs a) {
     __shared__ __align__(16) unsigned char xs[2][GM_TOKENS * XROW_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
     const int token0 = blockIdx.y * GM_TOKENS;
-    const int rt = blockIdx.x * GM_ROWTILES + w;  // this wavefront's row tile
+    const int rt = blockIdx.x * GM_ROWTILES + (w & 3);  // this wavefront's row tile
+    const int sh = w >> 2;                              // ... and its half of the bit planes
+    const bool stager = w < 4;                          // stages X into LDS
     const bool active = rt < a.n_rt;              // wavefronts beyond the matrix only help staging X
     const v4u* tiles = reinterpret_cast<const v4u*>(a.bits) + (size_t)(active ? rt : 0) * a.n_ct * 64 + lane;
 
@@ -142,9 +154,9 @@ __global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
     unsigned char* s_dst0 = xs[0] + s_tok * XROW_BYTES + s_col * 2;
     unsigned char* s_dst1 = xs[1] + s_tok * XROW_BYTES + s_col * 2;
 
-    v4f acc[8][4];
+    v4f acc[4][4];
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int tb = 0; tb < 4; ++tb) acc[s][tb] = (v4f){0.f, 0.f, 0.f, 0.f};
 
@@ -152,24 +164,35 @@ __global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
     unsigned sign_mask = 0x80008000u, one_one = 0x3C003C00u;
     asm volatile("" : "+v"(sign_mask), "+v"(one_one));
 
-    XRegs xr = load_x<HAS_COLSCALE>(a, token0 + s_tok, s_col);
-    v4u bits_cur = tiles[0];
-    store_x<HAS_COLSCALE>(a, xr, s_dst0, s_col);
+    // Software pipeline over the 64-column steps.  With one wavefront per SIMD nothing else hides
+    // memory latency, so the X columns and the sign tile of step kt + GM_DEPTH are requested
+    // while step kt is computed; the loop is unrolled GM_DEPTH times so that every in-flight
+    // register has a fixed name.  Steps beyond the matrix (the count is rounded up to a
+    // multiple of GM_DEPTH) stage zeros for X and therefore add nothing.
+    XRegs xr[GM_DEPTH];
+    v4u bq[GM_DEPTH];
+    const int last_ct = a.n_ct - 1;
+#pragma unroll
+    for (int j = 0; j < GM_DEPTH; ++j) {
+        if (stager) xr[j] = load_x<HAS_COLSCALE>(a, token0 + s_tok, j * 64 + s_col);
+        bq[j] = tiles[(size_t)min(j, last_ct) * 64];
+    }
+    if (stager) store_x<HAS_COLSCALE>(a, xr[0], s_dst0, s_col);
     __syncthreads();
 
-    for (int kt = 0; kt < a.n_ct; ++kt) {
-        const bool more = kt + 1 < a.n_ct;
-        v4u bits_next = bits_cur;
-        if (more) {
-            xr = load_x<HAS_COLSCALE>(a, token0 + s_tok, (kt + 1) * 64 + s_col);
-            bits_next = tiles[(size_t)(kt + 1) * 64];
-        }
-        const unsigned char* xb = xs[kt & 1] + c * XROW_BYTES + 32 * g;
-        // (wavefronts beyond the matrix compute on row tile 0 and discard the result: a branch
-        // around the matrix instructions would make the compiler shuttle all 128 accumulators
-        // between the two register files on every iteration)
-        {
-            const unsigned wd[4] = {bits_cur.x, bits_cur.y, bits_cur.z, bits_cur.w};
+    for (int kt0 = 0; kt0 < a.n_ct; kt0 += GM_DEPTH) {
+#pragma unroll
+        for (int j = 0; j < GM_DEPTH; ++j) {
+            const int kt = kt0 + j;
+            // xr[j] held step kt, which was staged one step ago: reuse it for step kt + GM_DEPTH
+            if (stager) xr[j] = load_x<HAS_COLSCALE>(a, token0 + s_tok, (kt + GM_DEPTH) * 64 + s_col);
+            const unsigned char* xb = xs[j & 1] + c * XROW_BYTES + 32 * g;
+            // (wavefronts beyond the matrix compute on row tile 0 and discard the result: a
+            // branch around the matrix instructions would make the compiler shuttle all 128
+            // accumulators between the two register files on every iteration)
+            // this wavefront's bit planes 4*sh .. 4*sh+3, moved down to planes 0..3
+            const unsigned wd[4] = {bq[j].x >> (4 * sh), bq[j].y >> (4 * sh), bq[j].z >> (4 * sh),
+                                    bq[j].w >> (4 * sh)};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 v8h xf[4];
@@ -177,31 +200,33 @@ __global__ __launch_bounds__(256) void dbf_gemm_stage_kernel(const GemmArgs a) {
                 for (int tb = 0; tb < 4; ++tb)
                     xf[tb] = *reinterpret_cast<const v8h*>(xb + tb * 16 * XROW_BYTES + 16 * h);
 #pragma unroll
-                for (int s = 0; s < 8; ++s) {
+                for (int s = 0; s < 4; ++s) {
                     // two fp16 of magnitude 1 whose sign bits are bits (s, 16+s) resp. (8+s, 24+s)
                     v4u e;
                     e.x = bfi(sign_mask, wd[2 * h] << (15 - s), one_one);
-                    e.y = bfi(sign_mask, s < 7 ? wd[2 * h] << (7 - s) : wd[2 * h], one_one);
+                    e.y = bfi(sign_mask, wd[2 * h] << (7 - s), one_one);
                     e.z = bfi(sign_mask, wd[2 * h + 1] << (15 - s), one_one);
-                    e.w = bfi(sign_mask, s < 7 ? wd[2 * h + 1] << (7 - s) : wd[2 * h + 1], one_one);
+                    e.w = bfi(sign_mask, wd[2 * h + 1] << (7 - s), one_one);
                     const v8h av = __builtin_bit_cast(v8h, e);
 #pragma unroll
                     for (int tb = 0; tb < 4; ++tb)
                         acc[s][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[tb], acc[s][tb], 0, 0, 0);
                 }
             }
+            bq[j] = tiles[(size_t)min(kt + GM_DEPTH, last_ct) * 64];
+            // stage step kt + 1 (its columns were requested GM_DEPTH - 1 steps ago)
+            if (stager)
+                store_x<HAS_COLSCALE>(a, xr[(j + 1) % GM_DEPTH], (j & 1) ? s_dst0 : s_dst1, (kt + 1) * 64 + s_col);
+            __syncthreads();
         }
-        if (more) store_x<HAS_COLSCALE>(a, xr, (kt & 1) ? s_dst0 : s_dst1, (kt + 1) * 64 + s_col);
-        __syncthreads();
-        bits_cur = bits_next;
     }
 
     // ---- epilogue: acc[s][tb][i] of lane (g, c) is row 16*s + 4*g + i, token 16*tb + c --------
     if (!active) return;
     const bool vec_ok = (a.ldo & 3) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 7) == 0;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const int n0 = rt * DBF_TILE_ROWS + 16 * s + 4 * g;
+    for (int s = 0; s < 4; ++s) {
+        const int n0 = rt * DBF_TILE_ROWS + 16 * (4 * sh + s) + 4 * g;
         float rs[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) rs[i] = -h2f(a.row_scale[n0 + i]);  // operand was the negated signs
@@ -254,7 +279,7 @@ extern "C" int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int 
     s1.n_valid = ks;  // padded rows have m = 0 and are written as zeros: stage 2 reads them
     s1.x_vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
     hipLaunchKernelGGL(dbf_gemm_stage_kernel<true>,
-                       dim3((s1.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(256), 0, stream, s1);
+                       dim3((s1.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(GM_THREADS), 0, stream, s1);
     if (hipGetLastError() != hipSuccess) return DBF_EHIP;
 
     GemmArgs s2;
@@ -267,7 +292,7 @@ extern "C" int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int 
     s2.n_valid = L->n_out;
     s2.x_vec_ok = 1;
     hipLaunchKernelGGL(dbf_gemm_stage_kernel<false>,
-                       dim3((s2.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(256), 0, stream, s2);
+                       dim3((s2.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(GM_THREADS), 0, stream, s2);
     if (hipGetLastError() != hipSuccess) return DBF_EHIP;
     return DBF_OK;
 }
