@@ -70,7 +70,9 @@ __device__ inline unsigned pack2(float lo, float hi) {
 
 // Sixteen consecutive fp16 columns of one token, loaded from global memory.
 struct XRegs {
-    v4u lo, hi;  // columns 0..7 and 8..15 of the thread's 16-column block
+    v4u lo, hi;      // columns 0..7 and 8..15 of the thread's 16-column block
+    v4u slo, shi;    // stage 1: the same columns of the scale vector b (requested together with X,
+                     // so that staging never waits for them)
 };
 
 template <bool HAS_COLSCALE>
@@ -78,6 +80,13 @@ __device__ inline XRegs load_x(const GemmArgs& a, int token, int col0) {
     XRegs r;
     r.lo = (v4u){0, 0, 0, 0};
     r.hi = (v4u){0, 0, 0, 0};
+    r.slo = (v4u){0, 0, 0, 0};
+    r.shi = (v4u){0, 0, 0, 0};
+    if (HAS_COLSCALE && col0 < a.k_valid) {  // b is zero padded up to a multiple of 64 columns
+        const v4u* sp = reinterpret_cast<const v4u*>(a.col_scale + col0);
+        r.slo = sp[0];
+        r.shi = sp[1];
+    }
     if (token >= a.T) return r;
     const uint16_t* row = a.X + (size_t)token * a.ldx;
     if (a.x_vec_ok && col0 + 16 <= a.k_valid) {
@@ -105,13 +114,9 @@ template <bool HAS_COLSCALE>
 __device__ inline void store_x(const GemmArgs& a, const XRegs& r, unsigned char* dst, int col0) {
     const unsigned in[8] = {r.lo.x, r.lo.y, r.lo.z, r.lo.w, r.hi.x, r.hi.y, r.hi.z, r.hi.w};
     unsigned out[8];
-    if (HAS_COLSCALE && col0 >= a.k_valid) {
-        // a step beyond the matrix: X is zero there and the scale vector has no such entries
-#pragma unroll
-        for (int q = 0; q < 8; ++q) out[q] = 0u;
-    } else if (HAS_COLSCALE) {
-        const v4u* sp = reinterpret_cast<const v4u*>(a.col_scale + col0);
-        const v4u s0 = sp[0], s1 = sp[1];
+    if (HAS_COLSCALE) {
+        // (beyond the matrix both X and the scale registers are zero)
+        const v4u s0 = r.slo, s1 = r.shi;
         const unsigned sc[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {  // four columns 4q .. 4q+3
@@ -185,7 +190,14 @@ __global__ __launch_bounds__(GM_THREADS) void dbf_gemm_stage_kernel(const GemmAr
         for (int j = 0; j < GM_DEPTH; ++j) {
             const int kt = kt0 + j;
             // xr[j] held step kt, which was staged one step ago: reuse it for step kt + GM_DEPTH
-            if (stager) xr[j] = load_x<HAS_COLSCALE>(a, token0 + s_tok, (kt + GM_DEPTH) * 64 + s_col);
+            // Stage step kt + 1 first (its columns were requested GM_DEPTH - 1 steps ago; the
+            // buffer it goes to was last read in step kt - 1, which the barrier has closed), so
+            // that the staging wavefronts reach the barrier at the end of this step together
+            // with the others instead of keeping them waiting.
+            if (stager) {
+                store_x<HAS_COLSCALE>(a, xr[(j + 1) % GM_DEPTH], (j & 1) ? s_dst0 : s_dst1, (kt + 1) * 64 + s_col);
+                xr[j] = load_x<HAS_COLSCALE>(a, token0 + s_tok, (kt + GM_DEPTH) * 64 + s_col);
+            }
             const unsigned char* xb = xs[j & 1] + c * XROW_BYTES + 32 * g;
             // (wavefronts beyond the matrix compute on row tile 0 and discard the result: a
             // branch around the matrix instructions would make the compiler shuttle all 128
@@ -193,30 +205,49 @@ __global__ __launch_bounds__(GM_THREADS) void dbf_gemm_stage_kernel(const GemmAr
             // this wavefront's bit planes 4*sh .. 4*sh+3, moved down to planes 0..3
             const unsigned wd[4] = {bq[j].x >> (4 * sh), bq[j].y >> (4 * sh), bq[j].z >> (4 * sh),
                                     bq[j].w >> (4 * sh)};
+            // Eight (half, plane) rounds of four matrix instructions each.  A wavefront issues in
+            // order, so the expansion of the NEXT round's operand (four shift + insert pairs) is
+            // written, and pinned by scheduling barriers, between the matrix instructions of the
+            // current round: one pair after each of them keeps the matrix pipe fed.
+            auto expand = [&](int r, int part) -> unsigned {
+                // round r = 4*h + s; parts x, y, z, w hold the fp16 pairs whose sign bits are bits
+                // (s, 16+s) resp. (8+s, 24+s) of the two words of half h
+                const int h = r >> 2, s = r & 3;
+                const unsigned word = wd[2 * h + (part >> 1)];
+                return bfi(sign_mask, word << ((part & 1) ? 7 - s : 15 - s), one_one);
+            };
+            v8h xf[2][4];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                v8h xf[4];
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int tb = 0; tb < 4; ++tb)
-                    xf[tb] = *reinterpret_cast<const v8h*>(xb + tb * 16 * XROW_BYTES + 16 * h);
+                    xf[h][tb] = *reinterpret_cast<const v8h*>(xb + tb * 16 * XROW_BYTES + 16 * h);
+            v4u e_next;
+            e_next.x = expand(0, 0);
+            e_next.y = expand(0, 1);
+            e_next.z = expand(0, 2);
+            e_next.w = expand(0, 3);
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    // two fp16 of magnitude 1 whose sign bits are bits (s, 16+s) resp. (8+s, 24+s)
-                    v4u e;
-                    e.x = bfi(sign_mask, wd[2 * h] << (15 - s), one_one);
-                    e.y = bfi(sign_mask, wd[2 * h] << (7 - s), one_one);
-                    e.z = bfi(sign_mask, wd[2 * h + 1] << (15 - s), one_one);
-                    e.w = bfi(sign_mask, wd[2 * h + 1] << (7 - s), one_one);
-                    const v8h av = __builtin_bit_cast(v8h, e);
+            for (int r = 0; r < 8; ++r) {
+                const int h = r >> 2, s = r & 3;
+                const v8h av = __builtin_bit_cast(v8h, e_next);
+                const int rn = r < 7 ? r + 1 : 7;  // (the last round re-expands itself: unused)
+                acc[s][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[h][0], acc[s][0], 0, 0, 0);
+                const unsigned n0 = expand(rn, 0);
+                acc[s][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[h][1], acc[s][1], 0, 0, 0);
+                const unsigned n1 = expand(rn, 1);
+                acc[s][2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[h][2], acc[s][2], 0, 0, 0);
+                const unsigned n2 = expand(rn, 2);
+                acc[s][3] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[h][3], acc[s][3], 0, 0, 0);
+                const unsigned n3 = expand(rn, 3);
+                e_next = (v4u){n0, n1, n2, n3};
 #pragma unroll
-                    for (int tb = 0; tb < 4; ++tb)
-                        acc[s][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, xf[tb], acc[s][tb], 0, 0, 0);
+                for (int i = 0; i < 4; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one matrix instruction
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // two vector-ALU instructions
                 }
             }
             bq[j] = tiles[(size_t)min(kt + GM_DEPTH, last_ct) * 64];
-            // stage step kt + 1 (its columns were requested GM_DEPTH - 1 steps ago)
-            if (stager)
-                store_x<HAS_COLSCALE>(a, xr[(j + 1) % GM_DEPTH], (j & 1) ? s_dst0 : s_dst1, (kt + 1) * 64 + s_col);
             __syncthreads();
         }
     }
