@@ -58,7 +58,7 @@ void free_plan(DbfPlan& p) {
 
 // Builds and uploads the launch tables for `n` layers whose stages (with their x/y offsets
 // already set) are given in sB / sA.
-int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA, int span, DbfPlan* p) {
+int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA, int span, int span_a, DbfPlan* p) {
     const int n = (int)sB.size();
     std::vector<DbfWorkItem> wB1, wA1;
     std::vector<DbfItem> items_n, items_1;
@@ -72,12 +72,6 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, span);
     nBn = (int)items_n.size();
-    int span_a = span;  // experiment hook: a different span for the A stage
-    if (const char* e = std::getenv("DBF_STACK_SPAN_A")) {
-        span_a = std::atoi(e);
-        if (span_a < 1) span_a = 1;
-        if (span_a > DBF_MAX_SPAN) span_a = DBF_MAX_SPAN;
-    }
     for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span_a);
     for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, 1);
     nB1 = (int)items_1.size();
@@ -212,7 +206,7 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     if (e == hipSuccess) {
         // a single layer runs alone: one row tile per workgroup gives the most parallelism
         std::vector<DbfStage> vB(1, sb), vA(1, sa);
-        if (build_plan(vB, vA, 1, &L->plan) != DBF_OK) e = hipErrorOutOfMemory;
+        if (build_plan(vB, vA, 1, 1, &L->plan) != DBF_OK) e = hipErrorOutOfMemory;
     }
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -277,11 +271,14 @@ int read_timeouts(const DbfPlan& p, int* timeouts) {
     return DBF_OK;
 }
 
-int stack_span() {
-    // Row tiles per workgroup in stack launches: the input vector is quantised once per
-    // workgroup, so a larger span amortises that prologue; DBF_STACK_SPAN overrides (1..16).
-    const char* e = std::getenv("DBF_STACK_SPAN");
-    int v = e ? std::atoi(e) : 4;
+int stack_span(const char* env_name, int fallback) {
+    // Row tiles per workgroup in stack launches.  The input vector is quantised once per
+    // workgroup, so a larger span amortises that prologue, a smaller one balances the tail of
+    // the launch better.  Measured best on the 256-layer stream: 2 for the B stage (whose row
+    // tiles are twice as wide at these shapes), 4 for the A stage.  The environment variables
+    // DBF_STACK_SPAN / DBF_STACK_SPAN_A override (1..16; experiments and tests).
+    const char* e = std::getenv(env_name);
+    int v = e ? std::atoi(e) : fallback;
     if (v < 1) v = 1;
     if (v > DBF_MAX_SPAN) v = DBF_MAX_SPAN;
     return v;
@@ -401,7 +398,7 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
         S->h_x_prefix[i + 1] = S->h_x_prefix[i] + L->n_in;
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
     }
-    const int rc = build_plan(sB, sA, stack_span(), &S->plan);
+    const int rc = build_plan(sB, sA, stack_span("DBF_STACK_SPAN", 2), stack_span("DBF_STACK_SPAN_A", 4), &S->plan);
     if (rc != DBF_OK) {
         dbf_stack_free(S);
         return rc;

@@ -189,10 +189,28 @@ template <bool STAGE_A>
 __device__ inline void input_one_pass(const DbfItem& it, const Ctx& c) {
     InputVec<STAGE_A> iv[UNR];
     float mx = 0.f;
+    if (STAGE_A) {
+        // The middle activations may have been written by another compute die during this
+        // launch, so they are read with agent-scope loads -- as 16-byte loads, which the
+        // atomic-load builtin cannot express.  All lanes load (out-of-range vectors re-read the
+        // last one and are ignored below), so the assembly runs in straight-line code, and the
+        // single wait names every destination register: nothing can touch them while in flight.
 #pragma unroll
-    for (int j = 0; j < UNR; ++j) {
-        const int v = 256 * j + c.tid;
-        if (v < c.nvec) iv[j].load(it, c.x, 0, v, v < c.nvec_x);
+        for (int j = 0; j < UNR; ++j) {
+            const int v = min(256 * j + c.tid, c.nvec - 1);
+            const float* p = it.t + 8 * (size_t)v;
+            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(iv[j].r0) : "v"(p) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, off offset:16 sc1" : "=v"(iv[j].r1) : "v"(p) : "memory");
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(iv[j].r0), "+v"(iv[j].r1));
+    } else {
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int v = 256 * j + c.tid;
+            if (v < c.nvec) iv[j].load(it, c.x, 0, v, v < c.nvec_x);
+        }
     }
 #pragma unroll
     for (int j = 0; j < UNR; ++j)

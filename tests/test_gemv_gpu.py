@@ -261,6 +261,7 @@ def test_persistent_kernel_walks_several_items(max_wg, span, monkeypatch):
     layers = [G.pack(L) for L in Ls]
     monkeypatch.setenv("DBF_PERSIST_MAX_WG", str(max_wg))
     monkeypatch.setenv("DBF_STACK_SPAN", str(span))
+    monkeypatch.setenv("DBF_STACK_SPAN_A", str(span))
     stack = B.dbf_stack_create(layers)   # the hooks are read when the plan is built
     try:
         x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
