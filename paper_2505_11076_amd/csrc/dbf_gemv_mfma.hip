@@ -47,6 +47,9 @@
 #ifndef DBF_LOAD_BITS
 #define DBF_LOAD_BITS "nt"
 #endif
+#ifndef DBF_PROLOGUE_PRIO
+#define DBF_PROLOGUE_PRIO 0
+#endif
 #ifndef DBF_PF
 #define DBF_PF 4
 #endif
@@ -78,15 +81,32 @@ __device__ inline float half_bits_to_float(uint16_t h) {
 __device__ inline uint16_t float_to_half_bits(float f) {
     return __builtin_bit_cast(uint16_t, (_Float16)f);
 }
+// Wavefront reductions with data-parallel-primitive moves (register to register, a few cycles
+// each) instead of LDS-crossbar shuffles (~100 cycles each, six in a chain): butterflies inside
+// every row of 16 lanes, then the four row results through scalar registers.
+template <int CTRL>
+__device__ inline int dpp_move(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
 __device__ inline float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0xB1>(__builtin_bit_cast(int, v))));   // quad_perm [1,0,3,2]
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x4E>(__builtin_bit_cast(int, v))));   // quad_perm [2,3,0,1]
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x124>(__builtin_bit_cast(int, v))));  // row_ror:4
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x128>(__builtin_bit_cast(int, v))));  // row_ror:8
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 __device__ inline int wave_sum(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x124>(v);
+    v += dpp_move<0x128>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
 }
 
 // Fixed part of the LDS carve-up (the quantised operand and the reduction buffers follow).
@@ -183,34 +203,18 @@ struct Ctx {
     int nvec, nvec_x;   // vector items per row incl. padding / items backed by x
 };
 
-// The decode case in one pass: load the row once, reduce max|u|, quantise from registers.
+// The decode case in one pass: the row was loaded once into registers (by the kernel's
+// prologue, see there); reduce max|u| and quantise from the registers.
 // Contains one barrier; ends with the operand in LDS (not yet synchronised).
 template <bool STAGE_A>
-__device__ inline void input_one_pass(const DbfItem& it, const Ctx& c) {
+__device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const v4u (&r1)[UNR]) {
     InputVec<STAGE_A> iv[UNR];
     float mx = 0.f;
-    if (STAGE_A) {
-        // The middle activations may have been written by another compute die during this
-        // launch, so they are read with agent-scope loads -- as 16-byte loads, which the
-        // atomic-load builtin cannot express.  All lanes load (out-of-range vectors re-read the
-        // last one and are ignored below), so the assembly runs in straight-line code, and the
-        // single wait names every destination register: nothing can touch them while in flight.
 #pragma unroll
-        for (int j = 0; j < UNR; ++j) {
-            const int v = min(256 * j + c.tid, c.nvec - 1);
-            const float* p = it.t + 8 * (size_t)v;
-            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(iv[j].r0) : "v"(p) : "memory");
-            asm volatile("global_load_dwordx4 %0, %1, off offset:16 sc1" : "=v"(iv[j].r1) : "v"(p) : "memory");
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(iv[j].r0), "+v"(iv[j].r1));
-    } else {
-#pragma unroll
-        for (int j = 0; j < UNR; ++j) {
-            const int v = 256 * j + c.tid;
-            if (v < c.nvec) iv[j].load(it, c.x, 0, v, v < c.nvec_x);
-        }
+    for (int j = 0; j < UNR; ++j) {
+        const int v = 256 * j + c.tid;
+        iv[j].r0 = (STAGE_A || v < c.nvec_x) ? r0[j] : (v4u){0, 0, 0, 0};  // beyond x the product is zero
+        iv[j].r1 = r1[j];
     }
 #pragma unroll
     for (int j = 0; j < UNR; ++j)
@@ -319,6 +323,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
     int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + ((ncols * chs + 15) & ~15));  // [2][128][ncols]
 
+#if DBF_PROLOGUE_PRIO
+    // (experiment: wavefront priority raised for the prologue.  The arbiter favours older
+    // wavefronts, so the youngest workgroup's prologue is slow -- but what it gains the streaming
+    // neighbours lose; measured neutral, left off.)
+    __builtin_amdgcn_s_setprio(DBF_PROLOGUE_PRIO);
+#endif
     const DbfItem it = items[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -379,9 +389,6 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         for (int j = 0; j < PF; ++j) asm volatile("" : "+v"(ring[j]));
 #endif
     };
-#pragma unroll
-    for (int j = 0; j < PF; ++j) fetch(buf[j]);  // in flight during the wait and the prologue
-
     // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
     if (use_sync && stage_a) {
         if (tid == 0) {
@@ -404,14 +411,65 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     cx.nvec = it.n_ct * 8;
     cx.nvec_x = it.cols >> 3;
     cx.fast = stage_a || ((it.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
-    // row scales of this item's rows (zero padded in memory up to a full row tile)
-    for (int i = tid; i < it.nrt * DBF_TILE_ROWS; i += 256) misc->rscale[i] = it.row_scale[i];
+    const bool one_pass = cx.fast && batch == 1 && cx.nvec <= 256 * UNR && it.n_ct <= ch_tiles;
+
+    // Every load of the prologue is issued here, back to back and in order of urgency: the row
+    // scales and the input vector FIRST (the workgroup cannot start without them), then the first
+    // PF sign tiles.  Loads complete in issue order, so the small critical loads do not queue
+    // behind 4 KiB of tiles per wavefront, and one wait that leaves the PF youngest loads (the
+    // tiles) in flight covers them.  All of it is straight-line inline assembly with every
+    // destination named by the wait: addresses are clamped instead of branching, and whatever a
+    // lane loaded beyond its range is ignored later.  (The general path below does not use the
+    // input registers; for it the loads are merely harmless.)
+    constexpr int RS_WORDS = DBF_MAX_SPAN * DBF_TILE_ROWS / 2 / 256;
+    unsigned rs_reg[RS_WORDS];
+    v4u in0[UNR], in1[UNR];
+    {
+        const int rs_last = it.nrt * (DBF_TILE_ROWS / 2) - 1;
+#pragma unroll
+        for (int q = 0; q < RS_WORDS; ++q) {
+            const unsigned* p = reinterpret_cast<const unsigned*>(it.row_scale) + min(tid + 256 * q, rs_last);
+            asm volatile("global_load_dword %0, %1, off" : "=v"(rs_reg[q]) : "v"(p) : "memory");
+        }
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int v = min(256 * j + tid, cx.nvec - 1);
+            const int vx = max(min(v, cx.nvec_x - 1), 0);
+            // A stage: 8 fp32 of t (agent scope: maybe written by another compute die during this
+            // launch).  B stage: 8 fp16 of x and of b; if x cannot be read in 16-byte pieces
+            // the general path is taken and b stands in for it here.
+            const void* p0 = stage_a ? static_cast<const void*>(it.t + 8 * (size_t)v)
+                                     : (cx.fast ? static_cast<const void*>(x + 8 * (size_t)vx)
+                                                : static_cast<const void*>(it.in_scale + 8 * (size_t)v));
+            const void* p1 = stage_a ? static_cast<const void*>(it.t + 8 * (size_t)v + 4)
+                                     : static_cast<const void*>(it.in_scale + 8 * (size_t)v);
+            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(in0[j]) : "v"(p0) : "memory");
+            asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(in1[j]) : "v"(p1) : "memory");
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < PF; ++j) fetch(buf[j]);
+#if DBF_ASM_LOADS
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(PF) : "memory");
+#else
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+#pragma unroll
+    for (int q = 0; q < RS_WORDS; ++q) asm volatile("" : "+v"(rs_reg[q]));
+#pragma unroll
+    for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(in0[j]), "+v"(in1[j]));
+
     for (int i = tid; i < 2 * DBF_TILE_ROWS * ncols; i += 256) red[i] = 0;
     if (tid < DBF_MAX_BATCH) misc->sigma[tid] = 0;
+    // row scales: read by the epilogues, which come after several barriers
+#pragma unroll
+    for (int q = 0; q < RS_WORDS; ++q) {
+        const int idx = tid + 256 * q;
+        if (2 * idx < it.nrt * DBF_TILE_ROWS) reinterpret_cast<unsigned*>(misc->rscale)[idx] = rs_reg[q];
+    }
 
-    const bool one_pass = cx.fast && batch == 1 && cx.nvec <= 256 * UNR && it.n_ct <= ch_tiles;
     if (one_pass) {
-        if (stage_a) input_one_pass<true>(it, cx); else input_one_pass<false>(it, cx);
+        if (stage_a) input_one_pass<true>(cx, in0, in1); else input_one_pass<false>(cx, in0, in1);
     } else {
         if (stage_a) input_scales<true>(it, cx); else input_scales<false>(it, cx);
     }
@@ -430,6 +488,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     const int e_s = rho >> 4;
     int tile_no = 0;  // row tiles finished so far: selects the reduction buffer
 
+#if DBF_PROLOGUE_PRIO
+    __builtin_amdgcn_s_setprio(0);
+#endif
     for (;;) {  // chunks of columns (a single one unless the batch is large)
         if (!one_pass) {
             if (stage_a) input_quantise_chunk<true>(it, cx, c0, cend);
