@@ -5,10 +5,12 @@ Workload (the configuration the headline metric is quoted on): Llama-2-7B
 attention-projection shape n_in = n_out = 4096, k = 2048 (1.0 bit/weight), batch-1
 decode.  One layer holds only 2 MiB of sign bits -- less than a kernel launch
 costs and small enough to sit in cache -- so the sustained number is measured on
-a stream of 256 DISTINCT layers (512 MiB of signs, twice the 256 MB last-level
-cache) with independent inputs, run as one dbf_stack_gemv call.  One "step" is
-one pass of the whole path (x.b -> B stage -> .m -> A stage -> .a -> fp16 y) over
-all 256 layers.  Inputs are resident in HBM before timing starts.
+a stream of 512 DISTINCT layers (1 GiB of signs, four times the 256 MB last-level
+cache and about what one decode step of a 7B model streams) with independent
+inputs, run as one dbf_stack_gemv call.  One "step" is one pass of the whole path
+(x.b -> B stage -> .m -> A stage -> .a -> fp16 y) over all of them; the same stream
+at 256 and 1024 layers is reported next to it (the launch head and tail are fixed
+costs per step).  Inputs are resident in HBM before timing starts.
 
 Prints ONE JSON line.  `value` is the achieved rate on ALGORITHMIC bytes
 (sign bits + fp16 scale vectors + x + y; no padding, no scratch, no re-reads).
@@ -48,7 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=300,
                     help="untimed steps before the timed ones (a step is ~0.1 ms; the GPU clocks need a few "
                          "tens of ms of load to settle after the idle set-up phase)")
-    ap.add_argument("--layers", type=int, default=256, help="distinct layers in the stream")
+    ap.add_argument("--layers", type=int, default=512,
+                    help="distinct layers in the stream (config2); 512 layers = 1.07 GB of sign bits, about what "
+                         "one decode step of a 7B model streams; 256 and 1024 are reported next to it")
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split", "persist"], default="auto")
     ap.add_argument("--workload", choices=["config2", "config5"], default="config2",
@@ -164,7 +168,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath) and args.workload == "config2" and R == 256 and batch == 1:
+    if os.path.exists(tpath) and args.workload == "config2" and R == 512 and batch == 1:
         try:
             traffic = json.load(open(tpath)).get("bench_default_bytes_per_launch")
         except Exception:
@@ -211,6 +215,18 @@ def main():
         out["frac_of_read_ceiling"] = round(value / ceiling, 4)
         out["roofline"]["frac_of_read_ceiling"] = round(achieved / ceiling, 4)
 
+    # ---- the same stream at other lengths (launch head and tail are fixed costs per step) ------
+    if args.workload == "config2" and not args.stream_only:
+        by_len = {str(R): {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2)}}
+        for R2 in (256, 1024):
+            if R2 == R:
+                continue
+            try:
+                by_len[str(R2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R2, batch, kind, stream)
+            except Exception as exc:  # reported, never hidden
+                by_len[str(R2)] = {"error": repr(exc)}
+        out["by_stream_length"] = by_len
+
     stack.close()
     for l in layers:
         l.close()
@@ -255,6 +271,38 @@ def build_stream(B, I, torch, np, specs, cfg_no, batch):
     y_all = torch.zeros(n_y, dtype=torch.float16, device="cuda")
     torch.cuda.synchronize()
     return layers, stack, x_all, y_all
+
+
+def stream_length_bench(B, I, torch, np, layers, spec, R2, batch, kind, stream, steps=100, warmup=100):
+    """The config-2 stream with R2 distinct layers: reuses the packed layers of the main run (and
+    packs more if R2 is larger); returns the step time and the achieved rate."""
+    extra = []
+    for i in range(len(layers), R2):
+        L = I.make_layer(spec["n_in"], spec["n_out"], spec["k"], seed=I.seed_for(2, i))
+        extra.append(B.dbf_pack_bits(spec["n_in"], spec["n_out"], spec["k"], L.A_bits, L.B_bits, L.a, L.m, L.b))
+    use = (list(layers) + extra)[:R2]
+    stack = B.dbf_stack_create(use)
+    try:
+        rng = np.random.default_rng(I.seed_for(2, 998))
+        x_host = I.random_activations_fp16(rng, 1, R2 * batch * spec["n_in"])
+        x = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
+        y = torch.zeros(R2 * batch * spec["n_out"], dtype=torch.float16, device="cuda")
+        for _ in range(warmup):
+            B.dbf_stack_gemv(stack, x.data_ptr(), y.data_ptr(), batch, stream, kind)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            B.dbf_stack_gemv(stack, x.data_ptr(), y.data_ptr(), batch, stream, kind)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        nbytes = algorithmic_bytes(spec["n_in"], spec["n_out"], spec["k"], batch)[0] * R2
+        return {"ms_per_step": round(ms, 5), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 2)}
+    finally:
+        stack.close()
+        for l in extra:
+            l.close()
 
 
 def config5_bench(B, I, torch, np, batch, kind, stream, steps=60, warmup=60):

@@ -25,11 +25,13 @@ inline bool shape_ok(int n_in, int n_out, int k) {
         }                                  \
     } while (0)
 
-// Matrix-core items of one stage of one layer, at most `span` row tiles each.
+// Matrix-core items of one stage of one layer.  The number of row tiles per item follows
+// `pattern`, cyclically; `phase` carries the position in the pattern from layer to layer.
 void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool stage_a,
-                  int need, int span) {
-    const int peers = (st.n_rt + span - 1) / span;  // items this call appends
-    for (int rt = 0; rt < st.n_rt; rt += span) {
+                  int need, const std::vector<int>& pattern, int* phase) {
+    const size_t first = out.size();
+    for (int rt = 0; rt < st.n_rt;) {
+        const int span = pattern[(size_t)(*phase)++ % pattern.size()];
         DbfItem it;
         std::memset(&it, 0, sizeof(it));
         it.bits = st.bits + (size_t)rt * st.n_ct * DBF_TILE_BYTES;
@@ -46,9 +48,10 @@ void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool
         it.layer = layer;
         it.need = need;
         it.stage_a = stage_a ? 1 : 0;
-        it.peers = peers;
         out.push_back(it);
+        rt += it.nrt;
     }
+    for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);  // items of this call
 }
 
 void free_plan(DbfPlan& p) {
@@ -58,7 +61,8 @@ void free_plan(DbfPlan& p) {
 
 // Builds and uploads the launch tables for `n` layers whose stages (with their x/y offsets
 // already set) are given in sB / sA.
-int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA, int span, int span_a, DbfPlan* p) {
+int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA, const std::vector<int>& span_b,
+               const std::vector<int>& span_a, DbfPlan* p) {
     const int n = (int)sB.size();
     std::vector<DbfWorkItem> wB1, wA1;
     std::vector<DbfItem> items_n, items_1;
@@ -70,12 +74,16 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
         if (sB[i].cols > p->max_cols_B) p->max_cols_B = sB[i].cols;
         if (sA[i].cols > p->max_cols_A) p->max_cols_A = sA[i].cols;
     }
-    for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, span);
+    const std::vector<int> one(1, 1);
+    int phase = 0;
+    for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, span_b, &phase);
     nBn = (int)items_n.size();
-    for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span_a);
-    for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, 1);
+    phase = 0;
+    for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span_a, &phase);
+    phase = 0;
+    for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, one, &phase);
     nB1 = (int)items_1.size();
-    for (int i = 0; i < n; ++i) append_items(items_1, sA[i], i, true, sB[i].n_rt, 1);
+    for (int i = 0; i < n; ++i) append_items(items_1, sA[i], i, true, sB[i].n_rt, one, &phase);
 
     size_t off = 0;
     const size_t o_sB = off;  off = align_up(off + sizeof(DbfStage) * n, 256);
@@ -119,7 +127,9 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->nA1 = (int)items_1.size() - nB1;
     p->d_sync = reinterpret_cast<int*>(d + o_sy);
     p->d_psync = reinterpret_cast<unsigned*>(d + o_ps);
-    p->span = span > span_a ? span : span_a;
+    p->span = 1;
+    for (int v : span_b) p->span = v > p->span ? v : p->span;
+    for (int v : span_a) p->span = v > p->span ? v : p->span;
     p->persist_ok = p->span <= DBF_PERSIST_MAX_SPAN && p->max_cols_B <= DBF_PERSIST_MAX_COLS &&
                     p->max_cols_A <= DBF_PERSIST_MAX_COLS;
     for (int i = 0; i < n; ++i)
@@ -206,7 +216,7 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
     if (e == hipSuccess) {
         // a single layer runs alone: one row tile per workgroup gives the most parallelism
         std::vector<DbfStage> vB(1, sb), vA(1, sa);
-        if (build_plan(vB, vA, 1, 1, &L->plan) != DBF_OK) e = hipErrorOutOfMemory;
+        if (build_plan(vB, vA, std::vector<int>(1, 1), std::vector<int>(1, 1), &L->plan) != DBF_OK) e = hipErrorOutOfMemory;
     }
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -271,16 +281,27 @@ int read_timeouts(const DbfPlan& p, int* timeouts) {
     return DBF_OK;
 }
 
-int stack_span(const char* env_name, int fallback) {
-    // Row tiles per workgroup in stack launches.  The input vector is quantised once per
-    // workgroup, so a larger span amortises that prologue, a smaller one balances the tail of
-    // the launch better.  Measured best on the 256-layer stream: 2 for the B stage (whose row
-    // tiles are twice as wide at these shapes), 4 for the A stage.  The environment variables
-    // DBF_STACK_SPAN / DBF_STACK_SPAN_A override (1..16; experiments and tests).
+std::vector<int> stack_spans(const char* env_name, const char* fallback) {
+    // Row tiles per workgroup in stack launches, as a cyclic pattern ("3,2,1,2").  The input
+    // vector is quantised once per workgroup, so larger items amortise that prologue and smaller
+    // ones balance the end of the launch; UNEQUAL neighbours matter as much: workgroups that all
+    // start together on equal items also finish together, and the launch then alternates
+    // between "everybody in the prologue" and "everybody streaming" instead of keeping the
+    // memory system evenly busy.  The environment variables DBF_STACK_SPAN / DBF_STACK_SPAN_A
+    // override the patterns (values 1..16; experiments and tests).
     const char* e = std::getenv(env_name);
-    int v = e ? std::atoi(e) : fallback;
-    if (v < 1) v = 1;
-    if (v > DBF_MAX_SPAN) v = DBF_MAX_SPAN;
+    std::vector<int> v;
+    for (const char* q = e ? e : fallback; *q;) {
+        char* end = nullptr;
+        long x = std::strtol(q, &end, 10);
+        if (end == q) break;
+        if (x < 1) x = 1;
+        if (x > DBF_MAX_SPAN) x = DBF_MAX_SPAN;
+        v.push_back((int)x);
+        q = (*end == ',') ? end + 1 : end;
+        if (*end != ',' ) break;
+    }
+    if (v.empty()) v.push_back(1);
     return v;
 }
 
@@ -398,7 +419,7 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
         S->h_x_prefix[i + 1] = S->h_x_prefix[i] + L->n_in;
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
     }
-    const int rc = build_plan(sB, sA, stack_span("DBF_STACK_SPAN", 2), stack_span("DBF_STACK_SPAN_A", 4), &S->plan);
+    const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", "2"), stack_spans("DBF_STACK_SPAN_A", "4"), &S->plan);
     if (rc != DBF_OK) {
         dbf_stack_free(S);
         return rc;
