@@ -62,7 +62,8 @@ enum {
 
 /* Which decode kernel dbf_gemv_kind runs. */
 enum {
-    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses: the fastest variant for the shape             */
+    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses: DBF_GEMV_MFMA for a group of layers,
+                          DBF_GEMV_MFMA_SPLIT for a single layer (measured faster there)  */
     DBF_GEMV_VALU = 1, /* fp32 add/subtract per sign bit on the vector ALU (exact fp32 sums) */
     DBF_GEMV_MFMA = 2, /* sign bytes fed to the int8 matrix cores as the adder; the input
                           vector of each stage is rounded once to 16-bit fixed point.  Both

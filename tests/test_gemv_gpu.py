@@ -337,3 +337,46 @@ def test_launch_errors_with_a_real_layer():
         assert lib.dbf_gemv_kind(h, x.data_ptr(), y.data_ptr(), 1, 7, None) == B.DBF_EINVAL
     finally:
         layer.close()
+
+
+def test_stack_call_replayed_from_a_captured_graph():
+    """The launch entry points allocate nothing, synchronise nothing and keep all state on the
+    device (counters cleared by the last workgroup), so a stack call can be captured into a HIP
+    graph and replayed.  Every replay, with eager work and synchronisations in between, must
+    reproduce the eager result bit for bit."""
+    shapes = [(512, 512, 256), (1024, 384, 700), (256, 640, 1000), (512, 512, 256)]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 950 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(1, L.n_in, I.seed_for(5, 960 + i)) for i, L in enumerate(Ls)]
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        n_y = sum(L.n_out for L in Ls)
+        for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA_SPLIT, "mfma_split"), (B.GEMV_PERSIST, "persist")):
+            G.say("graph capture [%s]" % name)
+            y_eager = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_eager.data_ptr(), 1, G.stream_handle(), kind)
+            torch.cuda.synchronize()
+            want = y_eager.cpu().view(torch.int16).numpy().copy()
+            y_graph = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                graph.capture_begin()
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_graph.data_ptr(), 1, side.cuda_stream, kind)
+                graph.capture_end()
+            torch.cuda.current_stream().wait_stream(side)
+            for rep in range(4):
+                y_graph.fill_(float("nan"))          # eager work between the replays
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                got = y_graph.cpu().view(torch.int16).numpy()
+                assert np.array_equal(got, want), (name, rep)
+            del graph
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
