@@ -376,6 +376,9 @@ def read_ceiling(B, torch, stream):
 
 
 def prefill_bench(B, I, torch, np, stream):
+    """Both config-4 shapes at T = 2048, default variant (int8 matrix cores) and, next to it, the
+    fp16 variant.  TFLOP/s counts the factored work 2*T*k*(n_in+n_out) for either variant (the
+    int8 variant issues twice the multiply-adds, two int8 planes, at twice the rate)."""
     res = {}
     for cfg in I.CONFIG4:
         n_in, n_out, k, T = cfg["n_in"], cfg["n_out"], cfg["k"], cfg["T"]
@@ -389,21 +392,27 @@ def prefill_bench(B, I, torch, np, stream):
         x = torch.from_numpy(X.view(np.int16).copy()).cuda().view(torch.float16)
         y = torch.zeros((T, n_out), dtype=torch.float16, device="cuda")
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-        for _ in range(3):
-            B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        n = 10
-        e0.record()
-        for _ in range(n):
-            B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / n
         flops = 2.0 * T * k * (n_in + n_out)
-        tf = flops / (ms * 1e-3) / 1e12
-        res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)] = {
-            "ms": round(ms, 4), "tflops": round(tf, 2), "frac_of_f16_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
+        entry = {}
+        for name, kind in (("int8", B.GEMM_I8), ("f16", B.GEMM_F16)):
+            for _ in range(5):
+                B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream, kind)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = 20
+            e0.record()
+            for _ in range(n):
+                B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream, kind)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / n
+            tf = flops / (ms * 1e-3) / 1e12
+            entry[name] = {"ms": round(ms, 4), "tflops": round(tf, 2),
+                           "frac_of_f16_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
+        best = entry["int8"]  # the default variant
+        res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)] = {"ms": best["ms"], "tflops": best["tflops"],
+                                                       "frac_of_f16_mfma_peak": best["frac_of_f16_mfma_peak"],
+                                                       "variant": "int8 (default)", "by_variant": entry}
         layer.close()
     return res
 

@@ -152,18 +152,29 @@ int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
 
 /* ---- prefill: the same product for T tokens as two matrix-core contractions ------------
  * (The paper times batch 1 only, section 4.4; rows of X are independent, so the product is
- * defined for any T by the same expression.)  Sign tiles are expanded to +-scale fp16 in
- * registers and multiplied with fp16 X on the matrix cores with fp32 accumulation; the
- * middle activations are rounded once to fp16.
+ * defined for any T by the same expression, section 3.)  Two variants:
+ *   DBF_GEMM_I8  (what dbf_gemm uses): the int8 matrix cores as the adder.  X.b, and later
+ *                the middle activations, are rounded per token to 16-bit fixed point
+ *                (q = rint(u * 32512 / max|u|)) and split into two int8 planes; the masked
+ *                sign bytes are the other operand; the sums are exact integers; the middle
+ *                activations stay in fp32.
+ *   DBF_GEMM_F16 sign tiles expanded to +-1 fp16 in registers and multiplied with fp16 X.b on
+ *                the fp16 matrix cores with fp32 accumulation; the middle activations are
+ *                rounded once to fp16.
  *
- * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1.
- * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes,
- * 256-byte aligned, contents undefined on return.  Errors: DBF_EINVAL, DBF_EWORKSPACE,
- * DBF_EHIP.  dbf_gemm_workspace_bytes returns 0 for a NULL layer or T < 1.
+ * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1 (at most 65535 * 64).
+ * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes (enough
+ * for either variant), 256-byte aligned, contents undefined on return.  Asynchronous on the
+ * stream; allocates nothing.  Errors: DBF_EINVAL (NULL pointer, T < 1 or too large, unknown
+ * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_EHIP.
+ * dbf_gemm_workspace_bytes returns 0 for a NULL layer or T < 1.
  */
+enum { DBF_GEMM_AUTO = 0, DBF_GEMM_F16 = 1, DBF_GEMM_I8 = 2 };
 size_t dbf_gemm_workspace_bytes(const dbf_layer* layer, int T);
 int dbf_gemm(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
              void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
+                  void* workspace_dev, size_t workspace_bytes, int kind, void* hip_stream);
 
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a

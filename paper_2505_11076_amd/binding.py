@@ -19,12 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libdbf.so")
 
 DBF_OK, DBF_EINVAL, DBF_ESHAPE, DBF_ENOTSIGN, DBF_ENOMEM, DBF_EHIP, DBF_EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
 GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT, GEMV_PERSIST = 0, 1, 2, 3, 4
+GEMM_AUTO, GEMM_F16, GEMM_I8 = 0, 1, 2
 MAX_BATCH = 16
 
 EXPORTS = [
     "dbf_pack", "dbf_pack_bits", "dbf_unpack_bits", "dbf_dims", "dbf_free",
     "dbf_tiled_bytes", "dbf_signs_to_bits_host", "dbf_tile_host", "dbf_untile_host",
-    "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm",
+    "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
     "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
     "dbf_probe_read", "dbf_strerror",
@@ -68,6 +69,7 @@ def lib() -> C.CDLL:
     L.dbf_gemm_workspace_bytes.argtypes = [vp, i32]
     L.dbf_gemm_workspace_bytes.restype = sz
     L.dbf_gemm.argtypes = [vp, vp, vp, i32, vp, sz, vp]
+    L.dbf_gemm_kind.argtypes = [vp, vp, vp, i32, vp, sz, i32, vp]
     L.dbf_stack_create.argtypes = [pp, i32, pp]
     L.dbf_stack_offsets.argtypes = [vp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
     L.dbf_stack_gemv.argtypes = [vp, vp, vp, i32, i32, vp]
@@ -207,8 +209,9 @@ def dbf_gemm_workspace_bytes(layer: Layer, T: int) -> int:
 
 
 def dbf_gemm(layer: Layer, X_ptr: int, Y_ptr: int, T: int, workspace_ptr: int, workspace_bytes: int,
-             stream: int = 0) -> None:
-    _check(lib().dbf_gemm(layer.handle, X_ptr, Y_ptr, T, workspace_ptr, workspace_bytes, stream), "dbf_gemm")
+             stream: int = 0, kind: int = GEMM_AUTO) -> None:
+    _check(lib().dbf_gemm_kind(layer.handle, X_ptr, Y_ptr, T, workspace_ptr, workspace_bytes, kind, stream),
+           "dbf_gemm")
 
 
 # ---- stacks --------------------------------------------------------------------------------

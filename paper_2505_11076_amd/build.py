@@ -24,6 +24,7 @@ SOURCES = [
     "dbf_gemv_mfma.hip",
     "dbf_gemv_persist.hip",
     "dbf_gemm_mfma.hip",
+    "dbf_gemm_i8.hip",
     "dbf_probe.hip",
 ]
 

@@ -312,6 +312,36 @@ std::vector<int> stack_spans(const char* env_name, const char* fallback) {
 
 extern "C" {
 
+size_t dbf_gemm_workspace_bytes(const dbf_layer* L, int T) {
+    if (!L || T < 1) return 0;
+    const size_t a = dbf_gemm_f16_workspace_bytes(L, T), b = dbf_gemm_i8_workspace_bytes(L, T);
+    return a > b ? a : b;  // enough for either variant
+}
+
+int dbf_gemm_kind(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
+                  size_t workspace_bytes, int kind, void* hip_stream) {
+    if (!L || !X_dev || !Y_dev || T < 1) return DBF_EINVAL;
+    if (kind != DBF_GEMM_AUTO && kind != DBF_GEMM_F16 && kind != DBF_GEMM_I8) return DBF_EINVAL;
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) ||
+        workspace_bytes < dbf_gemm_workspace_bytes(L, T))
+        return DBF_EWORKSPACE;
+    if ((T + 63) / 64 > 65535) return DBF_EINVAL;  // token blocks are the grid's y dimension
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (kind == DBF_GEMM_AUTO) kind = DBF_GEMM_I8;
+    const hipError_t e = kind == DBF_GEMM_I8 ? dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, stream)
+                                             : dbf_gemm_f16_launch(L, X_dev, Y_dev, T, workspace_dev, stream);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return DBF_EHIP;
+    }
+    return DBF_OK;
+}
+
+int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
+             size_t workspace_bytes, void* hip_stream) {
+    return dbf_gemm_kind(L, X_dev, Y_dev, T, workspace_dev, workspace_bytes, DBF_GEMM_AUTO, hip_stream);
+}
+
 int dbf_pack_bits(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32_t* B_bits,
                   const uint16_t* a, const uint16_t* m, const uint16_t* b, dbf_layer** out) {
     if (out) *out = nullptr;

@@ -1,0 +1,399 @@
+// Prefill with the int8 matrix cores as the adder: the decode trick (dbf_gemv_mfma.hip) for T tokens.
+//
+//   quantise:  u = X . b per token, rounded once to 16-bit fixed point, split into two int8 planes
+//   stage 1:   mid = ((X . b) B^T) . m      (T x k, fp32)   contraction over n_in
+//   quantise:  mid per token -> two int8 planes
+//   stage 2:   Y   = (mid A^T) . a          (T x n_out, fp16) contraction over k
+//
+// (forward-pass expression of the paper, section 3; the paper times batch 1 only, so this design
+// is not taken from it).  Compared with the fp16 path (dbf_gemm_mfma.hip):
+//   * the A operand of v_mfma_i32_16x16x64_i8 is the masked sign bytes, one AND per register
+//     (0.25 vector-ALU operations per sign instead of 1), and one instruction covers 64 columns;
+//   * the sums are exact integers: acc_s = 2^s * sum over set bits of q, so
+//     sum(+-q) = 2 (acc_s >> s) - sum(q); the only roundings left are the two 16-bit
+//     quantisations (relative 2^-16 of the row maximum) and the fp16 output;
+//   * hi and lo planes are separate instructions with separate accumulators: twice the
+//     instructions at twice the int8 rate.
+//
+// Work split of a stage: workgroup = 256 rows x 64 tokens, 4 wavefronts; wavefront w owns row tile
+// (w & 1) and the token half (w >> 1): 128 rows x 32 tokens = 8 planes x 2 token blocks x
+// {hi, lo} = 32 accumulator tiles (128 registers).  Twice as many workgroups as compute units at
+// 4096 rows x 2048 tokens, i.e. two wavefronts per SIMD.  The 64-token slice of the quantised
+// operand (2 planes x 64 tokens x 64 bytes per step) is staged in LDS, double buffered; sign
+// tiles and operand columns of step kt + 4 are requested while step kt is computed.
+#include "dbf_kernels.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+
+constexpr float QMAX = 32512.f;     // 127*256: largest |q| so that hi and lo fit int8
+constexpr int QI_TOKENS = 64;       // tokens per workgroup
+constexpr int QI_ROWTILES = 2;      // 128-row tiles per workgroup
+constexpr int QI_TROW = 64 + 16;    // LDS bytes per (plane, token): 64 operand bytes + bank padding
+constexpr int QI_PLANE = QI_TOKENS * QI_TROW;
+constexpr int QI_DEPTH = 4;         // steps requested ahead
+
+template <int CTRL>
+__device__ inline int dpp_move(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+__device__ inline float wave_max(float v) {
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0xB1>(__builtin_bit_cast(int, v))));
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x4E>(__builtin_bit_cast(int, v))));
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x124>(__builtin_bit_cast(int, v))));
+    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x128>(__builtin_bit_cast(int, v))));
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ inline int wave_sum(int v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x124>(v);
+    v += dpp_move<0x128>(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Quantisation of one token row per workgroup: q = rint(u * 32512 / max|u|), hi/lo int8 planes.
+//   FROM_F32 = false: u = x (fp16) * col_scale (fp16, zero padded)      (input of stage 1)
+//   FROM_F32 = true:  u = src (fp32, leading dimension ld)               (input of stage 2)
+// Output layout ("step major"): byte ((kt * Tp + token) * 2 + plane) * 64 + j holds plane (0 = hi,
+// 1 = lo) of column 64 kt + j of `token`; Tp = T rounded up to 64.  The 64 tokens x 2 planes x 64
+// bytes a workgroup of the stage kernel stages per step are then 8 KiB of contiguous memory.
+// Zeros beyond `cols`; scale[token] = max|u| / 32512, sigma[token] = sum of q.
+// ---------------------------------------------------------------------------------------------
+struct QuantArgs {
+    const void* src;
+    const uint16_t* col_scale;
+    signed char* dst;
+    float* scale;
+    int* sigma;
+    int T, Tp, cols, kp;
+    long long ld;     // elements between token rows of src
+    int vec_ok;       // rows can be read in 16-byte (fp16) / 32-byte (fp32) pieces
+};
+
+template <bool FROM_F32>
+__device__ inline void load8(const QuantArgs& a, int token, int v, float (&u)[8]) {
+    // columns 8v .. 8v+7 (v < kp/8); zero beyond `cols`
+    const int c0 = 8 * v;
+    if (FROM_F32) {
+        const float* row = static_cast<const float*>(a.src) + (size_t)token * a.ld;
+        if (a.vec_ok && c0 + 8 <= a.cols) {
+            const v4f f0 = *reinterpret_cast<const v4f*>(row + c0), f1 = *reinterpret_cast<const v4f*>(row + c0 + 4);
+            u[0] = f0.x;  u[1] = f0.y;  u[2] = f0.z;  u[3] = f0.w;
+            u[4] = f1.x;  u[5] = f1.y;  u[6] = f1.z;  u[7] = f1.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) u[i] = c0 + i < a.cols ? row[c0 + i] : 0.f;
+        }
+    } else {
+        const uint16_t* row = static_cast<const uint16_t*>(a.src) + (size_t)token * a.ld;
+        if (a.vec_ok && c0 + 8 <= a.cols) {
+            const h8 xv = *reinterpret_cast<const h8*>(row + c0);
+            const h8 bv = *reinterpret_cast<const h8*>(a.col_scale + c0);
+            u[0] = (float)xv.s0 * (float)bv.s0;  u[1] = (float)xv.s1 * (float)bv.s1;
+            u[2] = (float)xv.s2 * (float)bv.s2;  u[3] = (float)xv.s3 * (float)bv.s3;
+            u[4] = (float)xv.s4 * (float)bv.s4;  u[5] = (float)xv.s5 * (float)bv.s5;
+            u[6] = (float)xv.s6 * (float)bv.s6;  u[7] = (float)xv.s7 * (float)bv.s7;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                u[i] = c0 + i < a.cols ? (float)__builtin_bit_cast(_Float16, row[c0 + i]) *
+                                             (float)__builtin_bit_cast(_Float16, a.col_scale[c0 + i])
+                                       : 0.f;
+        }
+    }
+}
+
+template <bool FROM_F32>
+__global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs a) {
+    __shared__ float wmax[4];
+    __shared__ int wsum[4];
+    const int token = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nvec = a.kp >> 3;
+    float mx = 0.f;
+    for (int v = tid; v < nvec; v += 256) {
+        float u[8];
+        load8<FROM_F32>(a, token, v, u);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[i]));
+    }
+    mx = wave_max(mx);
+    if (lane == 0) wmax[w] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const float inv = mx > 0.f ? QMAX / mx : 0.f;
+    int local = 0;
+    for (int v = tid; v < nvec; v += 256) {
+        float u[8];
+        load8<FROM_F32>(a, token, v, u);   // second read of the row: L2 resident
+        unsigned hi4[2] = {0, 0}, lo4[2] = {0, 0};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float f = rintf(u[i] * inv);
+            f = fminf(fmaxf(f, -QMAX), QMAX);
+            const int q = (int)f;
+            const int lo = ((q + 128) & 255) - 128;
+            const int hi = (q - lo) >> 8;
+            hi4[i >> 2] |= (unsigned)(hi & 255) << (8 * (i & 3));
+            lo4[i >> 2] |= (unsigned)(lo & 255) << (8 * (i & 3));
+            local += q;
+        }
+        signed char* d = a.dst + (((size_t)(v >> 3) * a.Tp + token) * 2) * 64 + 8 * (v & 7);
+        *reinterpret_cast<uint2*>(d) = make_uint2(hi4[0], hi4[1]);
+        *reinterpret_cast<uint2*>(d + 64) = make_uint2(lo4[0], lo4[1]);
+    }
+    local = wave_sum(local);
+    if (lane == 0) wsum[w] = local;
+    __syncthreads();
+    if (tid == 0) {
+        a.scale[token] = mx / QMAX;
+        a.sigma[token] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One stage: out[token][row] = rscale[row] * scale[token] * sum_col sign(row, col) * q[token][col]
+// ---------------------------------------------------------------------------------------------
+struct StageArgs {
+    const uint8_t* bits;        // tiled sign matrix: n_rt x n_ct tiles
+    const uint16_t* row_scale;  // fp16 [n_rt*128] (m or a, zero padded)
+    const signed char* xq;      // [n_ct][Tp][2][64] quantised operand (step major, see above)
+    const float* scale;         // [T]
+    const int* sigma;           // [T]
+    void* out;                  // OUT_F32: float [T][ldo]; else fp16 [T][ldo]
+    int n_rt, n_ct, T, Tp, ldo;
+    int n_valid;                // output rows to store
+};
+
+template <bool OUT_F32>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void dbf_gemm_i8_stage_kernel(const StageArgs a) {
+    __shared__ __align__(16) unsigned char xs[2][2 * QI_PLANE];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, c = lane & 15;
+    const int token0 = blockIdx.y * QI_TOKENS;
+    const int th = w >> 1;                                   // token half of this wavefront
+    int rt = blockIdx.x * QI_ROWTILES + (w & 1);             // its row tile
+    const bool active = rt < a.n_rt;                         // beyond the matrix: compute on tile 0, store nothing
+    if (!active) rt = 0;
+    const v4u* tiles = reinterpret_cast<const v4u*>(a.bits) + (size_t)rt * a.n_ct * 64 + lane;
+
+    // staging role: thread -> (token, plane, 32-byte half of the 64 operand bytes of a step)
+    const int s_tok = tid >> 2, s_plane = (tid >> 1) & 1, s_half = tid & 1;
+    // (tokens in [T, Tp) hold whatever the workspace held: they are computed and never stored)
+    const signed char* s_src = a.xq + (size_t)token0 * 128 + 32 * tid;
+    const size_t s_step = (size_t)a.Tp * 128;                // bytes between steps
+    unsigned char* s_dst0 = xs[0] + s_plane * QI_PLANE + s_tok * QI_TROW + 32 * s_half;
+    unsigned char* s_dst1 = xs[1] + s_plane * QI_PLANE + s_tok * QI_TROW + 32 * s_half;
+
+    v4i acc[8][2][2];  // [plane s][token block][hi, lo]
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            acc[s][tb][0] = (v4i){0, 0, 0, 0};
+            acc[s][tb][1] = (v4i){0, 0, 0, 0};
+        }
+
+    // software pipeline: sign tile and operand columns of step kt + QI_DEPTH are requested while
+    // step kt is computed; unrolled QI_DEPTH times so that every in-flight register has a fixed
+    // name.  Steps beyond the matrix (count rounded up) re-read the last step's data and are
+    // given a zero sign operand... they are simply not executed: see the guard in the loop.
+    v4u bq[QI_DEPTH], x0[QI_DEPTH], x1[QI_DEPTH];
+    const int last_ct = a.n_ct - 1;
+#pragma unroll
+    for (int j = 0; j < QI_DEPTH; ++j) {
+        const int kt = min(j, last_ct);
+        bq[j] = tiles[(size_t)kt * 64];
+        x0[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step);
+        x1[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step + 16);
+    }
+    *reinterpret_cast<v4u*>(s_dst0) = x0[0];
+    *reinterpret_cast<v4u*>(s_dst0 + 16) = x1[0];
+    __syncthreads();
+
+    // operand rows of this lane: token 32*th + 16*tb + c, k-group g
+    const unsigned char* xlane = xs[0] + (32 * th + c) * QI_TROW + 16 * g;
+
+    for (int kt0 = 0; kt0 < a.n_ct; kt0 += QI_DEPTH) {
+#pragma unroll
+        for (int j = 0; j < QI_DEPTH; ++j) {
+            const int kt = kt0 + j;
+            // stage step kt + 1 (requested QI_DEPTH - 1 steps ago) into the other buffer, then reuse
+            // the registers for step kt + QI_DEPTH
+            {
+                unsigned char* d = (j & 1) ? s_dst0 : s_dst1;
+                *reinterpret_cast<v4u*>(d) = x0[(j + 1) % QI_DEPTH];
+                *reinterpret_cast<v4u*>(d + 16) = x1[(j + 1) % QI_DEPTH];
+                const int kn = min(kt + QI_DEPTH, last_ct);
+                x0[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step);
+                x1[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step + 16);
+            }
+            // A step beyond the matrix contributes nothing if its sign operand is zero: masked
+            // bytes of an all-zero tile are zero.  (No branch around the matrix instructions.)
+            const unsigned live = kt < a.n_ct ? 0xFFFFFFFFu : 0u;
+            const v4u bits = {bq[j].x & live, bq[j].y & live, bq[j].z & live, bq[j].w & live};
+            const unsigned char* xb = xlane + (j & 1) * (2 * QI_PLANE);
+            v4i xop[2][2];
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                xop[tb][0] = *reinterpret_cast<const v4i*>(xb + tb * 16 * QI_TROW);
+                xop[tb][1] = *reinterpret_cast<const v4i*>(xb + tb * 16 * QI_TROW + QI_PLANE);
+            }
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const unsigned msk = 0x01010101u << s;
+                v4i av;
+                av.x = (int)(bits.x & msk);
+                av.y = (int)(bits.y & msk);
+                av.z = (int)(bits.z & msk);
+                av.w = (int)(bits.w & msk);
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    acc[s][tb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, xop[tb][0], acc[s][tb][0], 0, 0, 0);
+                    acc[s][tb][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, xop[tb][1], acc[s][tb][1], 0, 0, 0);
+                }
+            }
+            bq[j] = tiles[(size_t)min(kt + QI_DEPTH, last_ct) * 64];
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: acc[s][tb][p][i] of lane (g, c) is row 16*s + 4*g + i, token 32*th + 16*tb + c ----
+    if (!active) return;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const int token = token0 + 32 * th + 16 * tb + c;
+        if (token >= a.T) continue;
+        const float tscale = a.scale[token];
+        const int tsigma = a.sigma[token];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int n0 = rt * DBF_TILE_ROWS + 16 * s + 4 * g;
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int vh = acc[s][tb][0][i], vl = acc[s][tb][1][i];
+                if (s < 7) {
+                    vh >>= s;
+                    vl >>= s;
+                } else {  // the mask 0x80 is -128 as an int8
+                    vh = -(vh >> 7);
+                    vl = -(vl >> 7);
+                }
+                const int total = 2 * (vh * 256 + vl) - tsigma;
+                const float rs = (float)__builtin_bit_cast(_Float16, a.row_scale[n0 + i]);
+                v[i] = (float)total * tscale * rs;
+            }
+            if (OUT_F32) {
+                float* dst = static_cast<float*>(a.out) + (size_t)token * a.ldo + n0;
+                if (n0 + 4 <= a.n_valid) {
+                    *reinterpret_cast<v4f*>(dst) = (v4f){v[0], v[1], v[2], v[3]};
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (n0 + i < a.n_valid) dst[i] = v[i];
+                }
+            } else {
+                uint16_t* dst = static_cast<uint16_t*>(a.out) + (size_t)token * a.ldo + n0;
+                const bool vec_ok = (a.ldo & 3) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 7) == 0;
+                if (vec_ok && n0 + 4 <= a.n_valid) {
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    *reinterpret_cast<h4*>(dst) = (h4){(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (n0 + i < a.n_valid) dst[i] = __builtin_bit_cast(uint16_t, (_Float16)v[i]);
+                }
+            }
+        }
+    }
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// workspace carve-up (all sections 256-byte aligned)
+struct I8Workspace {
+    size_t xq1, sc1, sg1, mid, xq2, sc2, sg2, total;
+};
+inline I8Workspace i8_workspace(const dbf_layer* L, int T) {
+    const size_t kp1 = (size_t)dbf_col_tiles(L->n_in) * DBF_TILE_COLS;
+    const size_t kp2 = (size_t)dbf_col_tiles(L->k) * DBF_TILE_COLS;
+    const size_t ks = (size_t)dbf_row_tiles(L->k) * DBF_TILE_ROWS;
+    const size_t Tp = ((size_t)T + 63) & ~(size_t)63;
+    I8Workspace w;
+    size_t off = 0;
+    w.xq1 = off;  off = align256(off + Tp * 2 * kp1);
+    w.sc1 = off;  off = align256(off + (size_t)T * 4);
+    w.sg1 = off;  off = align256(off + (size_t)T * 4);
+    w.mid = off;  off = align256(off + (size_t)T * ks * 4);
+    w.xq2 = off;  off = align256(off + Tp * 2 * kp2);
+    w.sc2 = off;  off = align256(off + (size_t)T * 4);
+    w.sg2 = off;  off = align256(off + (size_t)T * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+size_t dbf_gemm_i8_workspace_bytes(const dbf_layer* L, int T) { return i8_workspace(L, T).total; }
+
+// Launches quantise -> stage 1 -> quantise -> stage 2 on `stream`.  Arguments are validated by
+// the caller (dbf_gemm); `ws` holds at least dbf_gemm_i8_workspace_bytes(L, T) bytes.
+hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* ws,
+                              hipStream_t stream) {
+    const I8Workspace w = i8_workspace(L, T);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    const int ks = dbf_row_tiles(L->k) * DBF_TILE_ROWS;
+    const int kp1 = dbf_col_tiles(L->n_in) * DBF_TILE_COLS, kp2 = dbf_col_tiles(L->k) * DBF_TILE_COLS;
+    const unsigned tok_blocks = (unsigned)((T + QI_TOKENS - 1) / QI_TOKENS);
+
+    QuantArgs q1;
+    q1.src = X_dev;  q1.col_scale = L->db;
+    q1.dst = reinterpret_cast<signed char*>(base + w.xq1);
+    q1.scale = reinterpret_cast<float*>(base + w.sc1);  q1.sigma = reinterpret_cast<int*>(base + w.sg1);
+    q1.T = T;  q1.Tp = (T + 63) & ~63;  q1.cols = L->n_in;  q1.kp = kp1;  q1.ld = L->n_in;
+    q1.vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(dbf_quantise_rows_kernel<false>, dim3(T), dim3(256), 0, stream, q1);
+
+    StageArgs s1;
+    s1.bits = L->dB;  s1.row_scale = L->dm;
+    s1.xq = q1.dst;  s1.scale = q1.scale;  s1.sigma = q1.sigma;
+    s1.out = base + w.mid;
+    s1.n_rt = dbf_row_tiles(L->k);  s1.n_ct = dbf_col_tiles(L->n_in);  s1.T = T;  s1.Tp = q1.Tp;  s1.ldo = ks;
+    s1.n_valid = ks;  // padded rows have m = 0 and are written as zeros: the second quantisation reads them
+    hipLaunchKernelGGL(dbf_gemm_i8_stage_kernel<true>,
+                       dim3((s1.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(256), 0, stream, s1);
+
+    QuantArgs q2;
+    q2.src = base + w.mid;  q2.col_scale = nullptr;
+    q2.dst = reinterpret_cast<signed char*>(base + w.xq2);
+    q2.scale = reinterpret_cast<float*>(base + w.sc2);  q2.sigma = reinterpret_cast<int*>(base + w.sg2);
+    q2.T = T;  q2.Tp = q1.Tp;  q2.cols = kp2 < ks ? kp2 : ks;  q2.kp = kp2;  q2.ld = ks;
+    q2.vec_ok = 1;
+    hipLaunchKernelGGL(dbf_quantise_rows_kernel<true>, dim3(T), dim3(256), 0, stream, q2);
+
+    StageArgs s2;
+    s2.bits = L->dA;  s2.row_scale = L->da;
+    s2.xq = q2.dst;  s2.scale = q2.scale;  s2.sigma = q2.sigma;
+    s2.out = Y_dev;
+    s2.n_rt = dbf_row_tiles(L->n_out);  s2.n_ct = dbf_col_tiles(L->k);  s2.T = T;  s2.Tp = q1.Tp;  s2.ldo = L->n_out;
+    s2.n_valid = L->n_out;
+    hipLaunchKernelGGL(dbf_gemm_i8_stage_kernel<false>,
+                       dim3((s2.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(256), 0, stream, s2);
+    return hipGetLastError();
+}

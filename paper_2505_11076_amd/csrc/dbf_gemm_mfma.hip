@@ -284,21 +284,16 @@ inline size_t mid_stride(const dbf_layer* L) { return (size_t)dbf_row_tiles(L->k
 
 }  // namespace
 
-extern "C" size_t dbf_gemm_workspace_bytes(const dbf_layer* L, int T) {
-    if (!L || T < 1) return 0;
+size_t dbf_gemm_f16_workspace_bytes(const dbf_layer* L, int T) {
     return ((size_t)T * mid_stride(L) * 2 + 255) & ~(size_t)255;
 }
 
-extern "C" int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int T,
-                        void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
-    if (!L || !X_dev || !Y_dev || T < 1) return DBF_EINVAL;
-    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) ||
-        workspace_bytes < dbf_gemm_workspace_bytes(L, T))
-        return DBF_EWORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+// Launches the two fp16 stages on `stream`.  Arguments are validated by the caller (dbf_gemm);
+// `workspace_dev` holds at least dbf_gemm_f16_workspace_bytes(L, T) bytes.
+hipError_t dbf_gemm_f16_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
+                               hipStream_t stream) {
     const int ks = (int)mid_stride(L);
     const unsigned tok_blocks = (unsigned)((T + GM_TOKENS - 1) / GM_TOKENS);
-    if (tok_blocks > 65535u) return DBF_EINVAL;
 
     GemmArgs s1;
     s1.bits = L->dB;  s1.col_scale = L->db;  s1.row_scale = L->dm;
@@ -311,7 +306,7 @@ extern "C" int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int 
     s1.x_vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
     hipLaunchKernelGGL(dbf_gemm_stage_kernel<true>,
                        dim3((s1.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(GM_THREADS), 0, stream, s1);
-    if (hipGetLastError() != hipSuccess) return DBF_EHIP;
+    if (hipGetLastError() != hipSuccess) return hipErrorUnknown;
 
     GemmArgs s2;
     s2.bits = L->dA;  s2.col_scale = nullptr;  s2.row_scale = L->da;
@@ -324,6 +319,5 @@ extern "C" int dbf_gemm(const dbf_layer* L, const void* X_dev, void* Y_dev, int 
     s2.x_vec_ok = 1;
     hipLaunchKernelGGL(dbf_gemm_stage_kernel<false>,
                        dim3((s2.n_rt + GM_ROWTILES - 1) / GM_ROWTILES, tok_blocks), dim3(GM_THREADS), 0, stream, s2);
-    if (hipGetLastError() != hipSuccess) return DBF_EHIP;
-    return DBF_OK;
+    return hipGetLastError();
 }

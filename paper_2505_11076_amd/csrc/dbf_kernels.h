@@ -35,4 +35,18 @@ hipError_t dbf_launch_persistent(const DbfItem* items, int n_items, unsigned* ps
                                  int n_layers, const void* x_base, void* y_base, int max_cols,
                                  int max_wg, hipStream_t stream);
 
+// Prefill (T tokens).  Both variants run two stages with the middle activations in the caller's
+// workspace; arguments are validated by dbf_gemm before these are called.
+//   f16: fp16 matrix cores, sign words expanded to +-1 in registers, middle activations in fp16.
+//   i8:  int8 matrix cores as the adder (masked sign bytes as one operand, the activations
+//        rounded per token to 16-bit fixed point and split into two int8 planes), exact integer
+//        sums, middle activations in fp32.
+struct dbf_layer;
+size_t dbf_gemm_f16_workspace_bytes(const dbf_layer* L, int T);
+hipError_t dbf_gemm_f16_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
+                               hipStream_t stream);
+size_t dbf_gemm_i8_workspace_bytes(const dbf_layer* L, int T);
+hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
+                              hipStream_t stream);
+
 #endif  // DBF_KERNELS_H

@@ -43,14 +43,15 @@ def run_gemv(layer: B.Layer, X_bits: np.ndarray, kind: int) -> np.ndarray:
     return dev_to_f64(y)
 
 
-def run_gemm(layer: B.Layer, X_bits: np.ndarray) -> np.ndarray:
+def run_gemm(layer: B.Layer, X_bits: np.ndarray, kind: int = B.GEMM_AUTO) -> np.ndarray:
     T = X_bits.shape[0]
     x = f16_to_dev(X_bits)
     y = torch.full((T, layer.n_out), float("nan"), dtype=torch.float16, device="cuda")
     ws_bytes = B.dbf_gemm_workspace_bytes(layer, T)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    # scratch pre-filled with a byte pattern: nothing may depend on its contents
+    ws = torch.full((max(ws_bytes, 256),), 0xA5, dtype=torch.uint8, device="cuda")
     assert ws.data_ptr() % 256 == 0
-    B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream_handle())
+    B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream_handle(), kind)
     torch.cuda.synchronize()
     return dev_to_f64(y)
 

@@ -1,6 +1,7 @@
 """GPU parity of the prefill path (dbf_gemm: two matrix-core contractions) against
-the fp64 dense-W' oracle on the same seeded inputs.  Gate as for decode: gated
-relative error <= 2e-3 (fp16 X.b, fp16 middle activations, fp32 accumulation).
+the fp64 dense-W' oracle on the same seeded inputs, for both variants: int8 matrix
+cores with 16-bit fixed-point activations (the default) and fp16 matrix cores.
+Gate as for decode: gated relative error <= 2e-3.
 """
 import numpy as np
 import pytest
@@ -15,20 +16,24 @@ import gpu_util as G
 pytestmark = pytest.mark.gpu
 
 
+KINDS = [(B.GEMM_I8, "i8"), (B.GEMM_F16, "f16")]
+
+
 def _case(n_in, n_out, k, T, seed, rows=None):
     L = I.make_layer(n_in, n_out, k, seed)
     X = I.make_activations(T, n_in, seed)
     layer = G.pack(L)
     try:
-        what = "gemm n_in=%d n_out=%d k=%d T=%d seed=%d" % (n_in, n_out, k, T, seed)
-        G.say("start " + what)
-        y = G.run_gemm(layer, X, )
-        if rows is None:
-            ref = O.forward_from_packed(X, L, "dense")
-            return G.check(y, ref, what)
-        # large case: the oracle evaluates a sample of token rows (each output row one by one)
-        ref = O.forward_from_packed(X[rows], L, "dense")
-        return G.check(y[rows], ref, what + " (sampled rows)")
+        ref = O.forward_from_packed(X if rows is None else X[rows], L, "dense")
+        for kind, name in KINDS:
+            what = "gemm[%s] n_in=%d n_out=%d k=%d T=%d seed=%d" % (name, n_in, n_out, k, T, seed)
+            G.say("start " + what)
+            y = G.run_gemm(layer, X, kind)
+            if rows is None:
+                G.check(y, ref, what)
+            else:
+                # large case: the oracle evaluates a sample of token rows (each output row one by one)
+                G.check(y[rows], ref, what + " (sampled rows)")
     finally:
         layer.close()
 
@@ -53,9 +58,12 @@ def test_gemm_agrees_with_gemv_rows():
     X = I.make_activations(16, 512, I.seed_for(4, 50))
     layer = G.pack(L)
     try:
-        yg = G.run_gemm(layer, X)
         yv = G.run_gemv(layer, X, B.GEMV_VALU)
-        G.check(yg, yv, "gemm vs gemv[valu]")
+        for kind, name in KINDS:
+            G.check(G.run_gemm(layer, X, kind), yv, "gemm[%s] vs gemv[valu]" % name)
+        # the int8 variant quantises exactly as the matrix-core decode kernel does: same integers,
+        # same scales, so the fp16 outputs are identical
+        assert np.array_equal(G.run_gemm(layer, X, B.GEMM_I8), G.run_gemv(layer, X, B.GEMV_MFMA_SPLIT))
     finally:
         layer.close()
 
