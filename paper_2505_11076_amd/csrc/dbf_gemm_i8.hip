@@ -32,10 +32,22 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
 constexpr float QMAX = 32512.f;     // 127*256: largest |q| so that hi and lo fit int8
 constexpr int QI_TOKENS = 64;       // tokens per workgroup
-constexpr int QI_ROWTILES = 2;      // 128-row tiles per workgroup
+#ifndef DBF_QI_ROWTILES
+#define DBF_QI_ROWTILES 2
+#endif
+constexpr int QI_ROWTILES = DBF_QI_ROWTILES;  // 128-row tiles per workgroup
 constexpr int QI_TROW = 64 + 16;    // LDS bytes per (plane, token): 64 operand bytes + bank padding
 constexpr int QI_PLANE = QI_TOKENS * QI_TROW;
 constexpr int QI_DEPTH = 4;         // steps requested ahead
+#ifndef DBF_QI_TB
+#define DBF_QI_TB 2
+#endif
+constexpr int QI_TB = DBF_QI_TB;    // 16-token blocks per wavefront (2: 128 accumulator registers, 1: 64)
+constexpr int QI_TSPLIT = QI_TOKENS / (16 * QI_TB);       // wavefronts that share a row tile
+constexpr int QI_WAVES = QI_ROWTILES * QI_TSPLIT;
+constexpr int QI_THREADS = 64 * QI_WAVES;
+constexpr int QI_STAGE_BYTES = 2 * QI_TOKENS * 64 / QI_THREADS;  // operand bytes a thread stages per step
+static_assert(QI_STAGE_BYTES == 32 || QI_STAGE_BYTES == 16, "staging is one or two 16-byte pieces per thread");
 
 template <int CTRL>
 __device__ inline int dpp_move(int v) {
@@ -63,7 +75,7 @@ __device__ inline int wave_sum(int v) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Quantisation of one token row per workgroup: q = rint(u * 32512 / max|u|), hi/lo int8 planes.
+// Quantisation of token rows: q = rint(u * 32512 / max|u|), hi/lo int8 planes.
 //   FROM_F32 = false: u = x (fp16) * col_scale (fp16, zero padded)      (input of stage 1)
 //   FROM_F32 = true:  u = src (fp32, leading dimension ld)               (input of stage 2)
 // Output layout ("step major"): byte ((kt * Tp + token) * 2 + plane) * 64 + j holds plane (0 = hi,
@@ -115,8 +127,82 @@ __device__ inline void load8(const QuantArgs& a, int token, int v, float (&u)[8]
     }
 }
 
+// Quantises eight values and stores their two planes; returns the sum of the q.
+__device__ inline int quantise_store(const QuantArgs& a, int token, int v, const float (&u)[8], float inv) {
+    unsigned hi4[2] = {0, 0}, lo4[2] = {0, 0};
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float f = rintf(u[i] * inv);
+        f = fminf(fmaxf(f, -QMAX), QMAX);
+        const int q = (int)f;
+        const int lo = ((q + 128) & 255) - 128;
+        const int hi = (q - lo) >> 8;
+        hi4[i >> 2] |= (unsigned)(hi & 255) << (8 * (i & 3));
+        lo4[i >> 2] |= (unsigned)(lo & 255) << (8 * (i & 3));
+        sum += q;
+    }
+    signed char* d = a.dst + (((size_t)(v >> 3) * a.Tp + token) * 2) * 64 + 8 * (v & 7);
+    *reinterpret_cast<uint2*>(d) = make_uint2(hi4[0], hi4[1]);
+    *reinterpret_cast<uint2*>(d + 64) = make_uint2(lo4[0], lo4[1]);
+    return sum;
+}
+
+// One wavefront per token (four tokens per workgroup, no LDS, no barriers).  Rows of up to 4096
+// columns are held in registers between the max pass and the quantisation; longer rows are read
+// twice (the second read hits in L2).
 template <bool FROM_F32>
 __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs a) {
+    constexpr int HOLD = 8;  // vectors of 8 columns a lane can hold
+    const int lane = threadIdx.x & 63;
+    const int token = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (token >= a.T) return;
+    const int nvec = a.kp >> 3;
+    float mx = 0.f;
+    int local = 0;
+    if (nvec <= 64 * HOLD) {
+        float u[HOLD][8];
+#pragma unroll
+        for (int r = 0; r < HOLD; ++r) {
+            const int v = lane + 64 * r;
+            if (v < nvec) {
+                load8<FROM_F32>(a, token, v, u[r]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[r][i]));
+            }
+        }
+        mx = wave_max(mx);
+        const float inv = mx > 0.f ? QMAX / mx : 0.f;
+#pragma unroll
+        for (int r = 0; r < HOLD; ++r) {
+            const int v = lane + 64 * r;
+            if (v < nvec) local += quantise_store(a, token, v, u[r], inv);
+        }
+    } else {
+        for (int v = lane; v < nvec; v += 64) {
+            float u[8];
+            load8<FROM_F32>(a, token, v, u);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[i]));
+        }
+        mx = wave_max(mx);
+        const float inv = mx > 0.f ? QMAX / mx : 0.f;
+        for (int v = lane; v < nvec; v += 64) {
+            float u[8];
+            load8<FROM_F32>(a, token, v, u);
+            local += quantise_store(a, token, v, u, inv);
+        }
+    }
+    local = wave_sum(local);
+    if (lane == 0) {
+        a.scale[token] = mx / QMAX;
+        a.sigma[token] = local;
+    }
+}
+
+// One workgroup per token: for rows too long to hold in a wavefront's registers.
+template <bool FROM_F32>
+__global__ __launch_bounds__(256) void dbf_quantise_rows_block_kernel(const QuantArgs a) {
     __shared__ float wmax[4];
     __shared__ int wsum[4];
     const int token = blockIdx.x;
@@ -178,7 +264,7 @@ struct StageArgs {
 };
 
 template <bool OUT_F32>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(QI_THREADS) __attribute__((amdgpu_waves_per_eu(QI_TB == 2 ? 2 : 4, QI_TB == 2 ? 2 : 4)))
 void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     __shared__ __align__(16) unsigned char xs[2][2 * QI_PLANE];
 
@@ -186,25 +272,27 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
     const int token0 = blockIdx.y * QI_TOKENS;
-    const int th = w >> 1;                                   // token half of this wavefront
-    int rt = blockIdx.x * QI_ROWTILES + (w & 1);             // its row tile
+    const int th = w / QI_ROWTILES;                          // token slice of this wavefront
+    int rt = blockIdx.x * QI_ROWTILES + (w % QI_ROWTILES);   // its row tile
     const bool active = rt < a.n_rt;                         // beyond the matrix: compute on tile 0, store nothing
     if (!active) rt = 0;
     const v4u* tiles = reinterpret_cast<const v4u*>(a.bits) + (size_t)rt * a.n_ct * 64 + lane;
 
     // staging role: thread -> (token, plane, 32-byte half of the 64 operand bytes of a step)
-    const int s_tok = tid >> 2, s_plane = (tid >> 1) & 1, s_half = tid & 1;
+    // (the 8 KiB of a step are contiguous in memory: thread t takes bytes [SB*t, SB*t + SB))
+    constexpr int SB = QI_STAGE_BYTES;
+    const int s_tok = (tid * SB) >> 7, s_plane = ((tid * SB) >> 6) & 1, s_half = (tid * SB) & 63;
     // (tokens in [T, Tp) hold whatever the workspace held: they are computed and never stored)
-    const signed char* s_src = a.xq + (size_t)token0 * 128 + 32 * tid;
+    const signed char* s_src = a.xq + (size_t)token0 * 128 + SB * tid;
     const size_t s_step = (size_t)a.Tp * 128;                // bytes between steps
-    unsigned char* s_dst0 = xs[0] + s_plane * QI_PLANE + s_tok * QI_TROW + 32 * s_half;
-    unsigned char* s_dst1 = xs[1] + s_plane * QI_PLANE + s_tok * QI_TROW + 32 * s_half;
+    unsigned char* s_dst0 = xs[0] + s_plane * QI_PLANE + s_tok * QI_TROW + s_half;
+    unsigned char* s_dst1 = xs[1] + s_plane * QI_PLANE + s_tok * QI_TROW + s_half;
 
-    v4i acc[8][2][2];  // [plane s][token block][hi, lo]
+    v4i acc[8][QI_TB][2];  // [plane s][token block][hi, lo]
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
+        for (int tb = 0; tb < QI_TB; ++tb) {
             acc[s][tb][0] = (v4i){0, 0, 0, 0};
             acc[s][tb][1] = (v4i){0, 0, 0, 0};
         }
@@ -220,37 +308,42 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
         const int kt = min(j, last_ct);
         bq[j] = tiles[(size_t)kt * 64];
         x0[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step);
-        x1[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step + 16);
+        if (SB == 32) x1[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step + 16);
     }
     *reinterpret_cast<v4u*>(s_dst0) = x0[0];
-    *reinterpret_cast<v4u*>(s_dst0 + 16) = x1[0];
+    if (SB == 32) *reinterpret_cast<v4u*>(s_dst0 + 16) = x1[0];
     __syncthreads();
 
     // operand rows of this lane: token 32*th + 16*tb + c, k-group g
-    const unsigned char* xlane = xs[0] + (32 * th + c) * QI_TROW + 16 * g;
+    const unsigned char* xlane = xs[0] + (16 * QI_TB * th + c) * QI_TROW + 16 * g;
 
     for (int kt0 = 0; kt0 < a.n_ct; kt0 += QI_DEPTH) {
 #pragma unroll
         for (int j = 0; j < QI_DEPTH; ++j) {
             const int kt = kt0 + j;
+            v4u bq_next;
             // stage step kt + 1 (requested QI_DEPTH - 1 steps ago) into the other buffer, then reuse
             // the registers for step kt + QI_DEPTH
             {
                 unsigned char* d = (j & 1) ? s_dst0 : s_dst1;
                 *reinterpret_cast<v4u*>(d) = x0[(j + 1) % QI_DEPTH];
-                *reinterpret_cast<v4u*>(d + 16) = x1[(j + 1) % QI_DEPTH];
+                if (SB == 32) *reinterpret_cast<v4u*>(d + 16) = x1[(j + 1) % QI_DEPTH];
                 const int kn = min(kt + QI_DEPTH, last_ct);
                 x0[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step);
-                x1[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step + 16);
+                if (SB == 32) x1[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step + 16);
+                bq_next = tiles[(size_t)kn * 64];
+                // keep the three requests here, at the top of the step: the scheduler otherwise
+                // sinks them below the matrix instructions and shortens the prefetch distance
+                __builtin_amdgcn_sched_barrier(0);
             }
             // A step beyond the matrix contributes nothing if its sign operand is zero: masked
             // bytes of an all-zero tile are zero.  (No branch around the matrix instructions.)
             const unsigned live = kt < a.n_ct ? 0xFFFFFFFFu : 0u;
             const v4u bits = {bq[j].x & live, bq[j].y & live, bq[j].z & live, bq[j].w & live};
             const unsigned char* xb = xlane + (j & 1) * (2 * QI_PLANE);
-            v4i xop[2][2];
+            v4i xop[QI_TB][2];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
+            for (int tb = 0; tb < QI_TB; ++tb) {
                 xop[tb][0] = *reinterpret_cast<const v4i*>(xb + tb * 16 * QI_TROW);
                 xop[tb][1] = *reinterpret_cast<const v4i*>(xb + tb * 16 * QI_TROW + QI_PLANE);
             }
@@ -263,12 +356,12 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
                 av.z = (int)(bits.z & msk);
                 av.w = (int)(bits.w & msk);
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
+                for (int tb = 0; tb < QI_TB; ++tb) {
                     acc[s][tb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, xop[tb][0], acc[s][tb][0], 0, 0, 0);
                     acc[s][tb][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, xop[tb][1], acc[s][tb][1], 0, 0, 0);
                 }
             }
-            bq[j] = tiles[(size_t)min(kt + QI_DEPTH, last_ct) * 64];
+            bq[j] = bq_next;
             __syncthreads();
         }
     }
@@ -276,8 +369,8 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     // ---- epilogue: acc[s][tb][p][i] of lane (g, c) is row 16*s + 4*g + i, token 32*th + 16*tb + c ----
     if (!active) return;
 #pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-        const int token = token0 + 32 * th + 16 * tb + c;
+    for (int tb = 0; tb < QI_TB; ++tb) {
+        const int token = token0 + 16 * QI_TB * th + 16 * tb + c;
         if (token >= a.T) continue;
         const float tscale = a.scale[token];
         const int tsigma = a.sigma[token];
@@ -368,7 +461,8 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     q1.scale = reinterpret_cast<float*>(base + w.sc1);  q1.sigma = reinterpret_cast<int*>(base + w.sg1);
     q1.T = T;  q1.Tp = (T + 63) & ~63;  q1.cols = L->n_in;  q1.kp = kp1;  q1.ld = L->n_in;
     q1.vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(dbf_quantise_rows_kernel<false>, dim3(T), dim3(256), 0, stream, q1);
+    if (kp1 <= 4096) hipLaunchKernelGGL(dbf_quantise_rows_kernel<false>, dim3((T + 3) / 4), dim3(256), 0, stream, q1);
+    else hipLaunchKernelGGL(dbf_quantise_rows_block_kernel<false>, dim3(T), dim3(256), 0, stream, q1);
 
     StageArgs s1;
     s1.bits = L->dB;  s1.row_scale = L->dm;
@@ -377,7 +471,7 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     s1.n_rt = dbf_row_tiles(L->k);  s1.n_ct = dbf_col_tiles(L->n_in);  s1.T = T;  s1.Tp = q1.Tp;  s1.ldo = ks;
     s1.n_valid = ks;  // padded rows have m = 0 and are written as zeros: the second quantisation reads them
     hipLaunchKernelGGL(dbf_gemm_i8_stage_kernel<true>,
-                       dim3((s1.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(256), 0, stream, s1);
+                       dim3((s1.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(QI_THREADS), 0, stream, s1);
 
     QuantArgs q2;
     q2.src = base + w.mid;  q2.col_scale = nullptr;
@@ -385,7 +479,8 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     q2.scale = reinterpret_cast<float*>(base + w.sc2);  q2.sigma = reinterpret_cast<int*>(base + w.sg2);
     q2.T = T;  q2.Tp = q1.Tp;  q2.cols = kp2 < ks ? kp2 : ks;  q2.kp = kp2;  q2.ld = ks;
     q2.vec_ok = 1;
-    hipLaunchKernelGGL(dbf_quantise_rows_kernel<true>, dim3(T), dim3(256), 0, stream, q2);
+    if (kp2 <= 4096) hipLaunchKernelGGL(dbf_quantise_rows_kernel<true>, dim3((T + 3) / 4), dim3(256), 0, stream, q2);
+    else hipLaunchKernelGGL(dbf_quantise_rows_block_kernel<true>, dim3(T), dim3(256), 0, stream, q2);
 
     StageArgs s2;
     s2.bits = L->dA;  s2.row_scale = L->da;
@@ -394,6 +489,6 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     s2.n_rt = dbf_row_tiles(L->n_out);  s2.n_ct = dbf_col_tiles(L->k);  s2.T = T;  s2.Tp = q1.Tp;  s2.ldo = L->n_out;
     s2.n_valid = L->n_out;
     hipLaunchKernelGGL(dbf_gemm_i8_stage_kernel<false>,
-                       dim3((s2.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(256), 0, stream, s2);
+                       dim3((s2.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(QI_THREADS), 0, stream, s2);
     return hipGetLastError();
 }
