@@ -31,6 +31,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix-core peak
+MFMA_I8_PEAK_TOPS = 5000.0     # dense int8 matrix-core peak
 
 
 def algorithmic_bytes(n_in, n_out, k, batch):
@@ -86,7 +87,8 @@ def main():
     kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA,
             "mfma_split": B.GEMV_MFMA_SPLIT, "persist": B.GEMV_PERSIST}[args.kind]
     if args.prefill_only:
-        print(json.dumps({"prefill": prefill_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
+        st = torch.cuda.current_stream().cuda_stream
+        print(json.dumps({"prefill": prefill_bench(B, I, torch, np, st), "mfma_probe": mfma_probe(B, torch, st)}))
         return
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
@@ -243,6 +245,7 @@ def main():
     if not args.no_prefill and not args.stream_only:
         try:
             out["prefill"] = prefill_bench(B, I, torch, np, stream)
+            out["mfma_probe"] = mfma_probe(B, torch, stream)
         except Exception as exc:  # reported, never hidden
             out["prefill"] = {"error": repr(exc)}
 
@@ -414,6 +417,24 @@ def prefill_bench(B, I, torch, np, stream):
                                                        "frac_of_f16_mfma_peak": best["frac_of_f16_mfma_peak"],
                                                        "variant": "int8 (default)", "by_variant": entry}
         layer.close()
+    return res
+
+
+def mfma_probe(B, torch, stream):
+    """What the int8 matrix pipe sustains (fraction of the 5.0 POP/s data-sheet peak) at two wavefronts
+    per SIMD, for the prefill kernel's instruction (16x16x64) and the 8-pass one (32x32x32), bare and
+    with the ANDs that make the sign operand: the ceiling the prefill stage kernel is compared with."""
+    res = {"unit": "fraction of %.0f TOP/s" % MFMA_I8_PEAK_TOPS, "wavefronts_per_simd": 2}
+    iters = 2000
+    for name, wide, ands in (("i8_16x16x64", False, False), ("i8_16x16x64_sign_ands", False, True),
+                             ("i8_32x32x32", True, False), ("i8_32x32x32_sign_ands", True, True)):
+        B.dbf_probe_mfma(wide, ands, 2, iters, 0, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ops = B.dbf_probe_mfma(wide, ands, 2, iters, 0, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e12 / MFMA_I8_PEAK_TOPS, 4)
     return res
 
 

@@ -212,6 +212,19 @@ int dbf_stack_gemv_timed(const dbf_stack* stack, const void* x_dev, void* y_dev,
  * Asynchronous.  Errors: DBF_EINVAL, DBF_EHIP. */
 int dbf_probe_read(const void* src_dev, size_t bytes, void* sink_dev, void* hip_stream);
 
+/* Measurement aid: launches a kernel on `hip_stream` that issues int8 matrix instructions on
+ * independent accumulators and nothing else: `iters` iterations of 128 accumulator registers'
+ * worth of instructions (2^19 multiply-adds for wide = 0, 2^18 for wide = 1) per wavefront,
+ * wavefronts_per_simd (1..4) wavefronts on every SIMD of the current device.
+ *   wide = 0: v_mfma_i32_16x16x64_i8 (the prefill stage kernel's instruction); 1: v_mfma_i32_32x32x32_i8.
+ *   with_ands != 0: the sign operand is remade by 4 ANDs for every group of matrix instructions that
+ *     the prefill kernel feeds from one masked operand (4 for wide = 0, 2 for wide = 1).
+ * Timing it gives what the matrix pipe sustains for that instruction mix, next to the data-sheet
+ * peak.  *ops (host, may be NULL) receives the integer operations of the launch (2 per
+ * multiply-add).  sink_dev: device, 4 bytes, or NULL.  Asynchronous.  Errors: DBF_EINVAL, DBF_EHIP. */
+int dbf_probe_mfma(int wide, int with_ands, int wavefronts_per_simd, int iters, void* sink_dev,
+                   void* hip_stream, double* ops);
+
 const char* dbf_strerror(int code);
 
 #ifdef __cplusplus

@@ -28,7 +28,7 @@ EXPORTS = [
     "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
     "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
-    "dbf_probe_read", "dbf_strerror",
+    "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
 ]
 
 _lib = None
@@ -77,6 +77,7 @@ def lib() -> C.CDLL:
     L.dbf_stack_free.argtypes = [vp]
     L.dbf_stack_free.restype = None
     L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
+    L.dbf_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp, C.POINTER(C.c_double)]
     L.dbf_strerror.argtypes = [i32]
     L.dbf_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -263,6 +264,15 @@ def dbf_stack_gemv_timed(stack: Stack, x_ptr: int, y_ptr: int, batch: int, strea
 
 def dbf_probe_read(src_ptr: int, nbytes: int, sink_ptr: int = 0, stream: int = 0) -> None:
     _check(lib().dbf_probe_read(src_ptr, nbytes, sink_ptr, stream), "dbf_probe_read")
+
+
+def dbf_probe_mfma(wide: bool, with_ands: bool, wavefronts_per_simd: int, iters: int, sink_ptr: int = 0,
+                   stream: int = 0) -> float:
+    """Launches the matrix-pipe probe; returns the integer operations of the launch."""
+    ops = C.c_double(0)
+    _check(lib().dbf_probe_mfma(int(wide), int(with_ands), wavefronts_per_simd, iters, sink_ptr, stream,
+                                C.byref(ops)), "dbf_probe_mfma")
+    return float(ops.value)
 
 
 def dbf_sync_timeouts(layer: Layer) -> int:
