@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--prefill-only", action="store_true",
                     help="only the prefill (matrix-core) measurement: what the prefill rocprofv3 summary is taken on")
+    ap.add_argument("--table4", action="store_true",
+                    help="only the second workload: the layer sizes of the paper's matrix-vector timing table "
+                         "(Llama-3 shapes, 1 / 1.5 / 2 / 2.3 bits per weight), isolated latency and streamed rate")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -89,6 +92,10 @@ def main():
     if args.prefill_only:
         st = torch.cuda.current_stream().cuda_stream
         print(json.dumps({"prefill": prefill_bench(B, I, torch, np, st), "mfma_probe": mfma_probe(B, torch, st)}))
+        return
+    if args.table4:
+        print(json.dumps({"table4": table4_bench(B, I, torch, np, args.batch, kind,
+                                                 torch.cuda.current_stream().cuda_stream)}))
         return
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
@@ -334,6 +341,59 @@ def config5_bench(B, I, torch, np, batch, kind, stream, steps=60, warmup=60):
         stack.close()
         for l in layers:
             l.close()
+
+
+# The paper's Table 4 (RTX 4090, fp16 activations, batch 1), microseconds per matrix-vector product, by
+# (n_out, n_in) and bits per weight; printed next to this machine's numbers as context only.
+PAPER_TABLE4_US = {
+    (4096, 4096): {2.3: 29, 2.0: 27, 1.5: 24, 1.0: 20},
+    (4096, 14336): {2.3: 56, 2.0: 51, 1.5: 43, 1.0: 37},
+    (8192, 8192): {2.3: 64, 2.0: 58, 1.5: 51, 1.0: 38},
+    (8192, 28672): {2.3: 167, 2.0: 149, 1.5: 115, 1.0: 84},
+}
+
+
+def table4_bench(B, I, torch, np, batch, kind, stream):
+    """Every (shape, bits per weight) of the second workload: the isolated call (cache warm) and a
+    stream of distinct copies of the layer (at least 512 MB of signs, at most 256 copies) in one
+    stack call per step."""
+    rows = []
+    for ci, cfg in enumerate(I.table4_configs()):
+        n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
+        nbytes = algorithmic_bytes(n_in, n_out, k, batch)[0]
+        R = int(min(256, max(2, -(-(512 << 20) // nbytes))))
+        specs = [dict(n_in=n_in, n_out=n_out, k=k)] * R
+        layers, stack, x_all, y_all = build_stream(B, I, torch, np, specs, 6, batch)
+        try:
+            xs = x_all[: batch * n_in]
+            ys = y_all[: batch * n_out]
+            iso = isolated_latency(B, torch, np, layers[0], xs, ys, batch, stream, kind)
+            steps = max(20, min(200, int(0.05 / (nbytes * R / 5e12))))
+            for _ in range(steps):
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / steps
+            gbps = nbytes * R / (ms * 1e-3) / 1e9
+            rows.append({"n_out": n_out, "n_in": n_in, "bits": cfg["bits"], "k": k,
+                         "isolated_us_p50": iso["p50"], "back_to_back_us": iso["back_to_back_us"],
+                         "stream_layers": R, "stream_us_per_layer": round(ms * 1e3 / R, 3),
+                         "stream_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                         "paper_rtx4090_us": PAPER_TABLE4_US.get((n_out, n_in), {}).get(cfg["bits"])})
+        finally:
+            stack.close()
+            for l in layers:
+                l.close()
+            del x_all, y_all
+    return {"batch": batch, "rows": rows,
+            "note": "isolated = one dbf_gemv call, cache warm (p50 of 200 event pairs); stream = distinct copies of "
+                    "the layer in one dbf_stack_gemv call per step, signs read from HBM; paper column: its Table 4 "
+                    "on an RTX 4090, another machine, context only"}
 
 
 def isolated_latency(B, torch, np, layer, xs, ys, batch, stream, kind):

@@ -1,6 +1,7 @@
 // C ABI of libdbf: argument checks, the layer / stack objects and kernel dispatch.
 // Every operation of the layer product itself runs in the HIP kernels; this file only
 // validates, allocates at pack time, and launches.
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -48,10 +49,79 @@ void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool
         it.layer = layer;
         it.need = need;
         it.stage_a = stage_a ? 1 : 0;
+        it.ct0 = 0;
+        it.ct_n = st.n_ct;
+        it.pieces = 1;
         out.push_back(it);
         rt += it.nrt;
     }
     for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);  // items of this call
+}
+
+// Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
+// the whole input row for the quantisation scale) and the last piece an extra epilogue, which at 4096
+// columns costs more than the added parallelism gains (measured 17 vs 14 us for a 4096 x 4096 layer
+// alone).  So rows of up to PIECE_NEVER_TILES column tiles are never cut, pieces hold at least
+// PIECE_MIN_TILES tiles, and a stage is cut until it offers about PIECE_TARGET_ITEMS workgroups.
+// Environment overrides (experiments and tests): DBF_COL_PIECES = 0 never cut / N cut into N where it
+// fits; DBF_PIECE_TARGET, DBF_PIECE_MIN_TILES, DBF_PIECE_NEVER_TILES.
+constexpr int PIECE_MIN_TILES = 24;
+constexpr int PIECE_NEVER_TILES = 64;
+constexpr int PIECE_TARGET_ITEMS = 256;
+constexpr int PIECE_MAX_ROW_TILES = 1024;  // plans with more row tiles than this per stage are never cut
+
+int env_int(const char* name, int fallback) {
+    const char* e = std::getenv(name);
+    return e ? std::atoi(e) : fallback;
+}
+
+// Pieces per row tile of a stage with n_ct column tiles when the launch holds stage_row_tiles row
+// tiles of that stage.
+int pieces_for(int n_ct, int stage_row_tiles) {
+    const int forced = env_int("DBF_COL_PIECES", -1);
+    if (forced == 0) return 1;
+    const int min_tiles = std::max(1, env_int("DBF_PIECE_MIN_TILES", PIECE_MIN_TILES));
+    if (forced < 0 && n_ct <= env_int("DBF_PIECE_NEVER_TILES", PIECE_NEVER_TILES)) return 1;
+    const int target = env_int("DBF_PIECE_TARGET", PIECE_TARGET_ITEMS);
+    int want = forced > 0 ? forced : (target + stage_row_tiles - 1) / stage_row_tiles;
+    const int fit = n_ct / (forced > 0 ? 8 : min_tiles);
+    if (want > fit) want = fit;
+    return want < 1 ? 1 : want;
+}
+
+// Items of one stage of one layer with every row tile cut into `pieces` column pieces of (almost)
+// equal size.  acc / cnt: this stage's accumulators (row 0) and arrival counters (row tile 0).
+void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool stage_a, int need,
+                        int pieces, int* acc, int acc_stride, int* cnt) {
+    const size_t first = out.size();
+    for (int rt = 0; rt < st.n_rt; ++rt) {
+        for (int pc = 0; pc < pieces; ++pc) {
+            DbfItem it;
+            std::memset(&it, 0, sizeof(it));
+            it.bits = st.bits + (size_t)rt * st.n_ct * DBF_TILE_BYTES;
+            it.in_scale = st.in_scale;
+            it.row_scale = st.row_scale + (size_t)rt * DBF_TILE_ROWS;
+            it.t = st.t;
+            it.io_off = stage_a ? st.y_off : st.x_off;
+            it.n_ct = st.n_ct;
+            it.nrt = 1;
+            it.row0 = rt * DBF_TILE_ROWS;
+            it.rows = st.rows;
+            it.cols = st.cols;
+            it.t_stride = st.t_stride;
+            it.layer = layer;
+            it.need = need;
+            it.stage_a = stage_a ? 1 : 0;
+            it.ct0 = (int)((long long)st.n_ct * pc / pieces);
+            it.ct_n = (int)((long long)st.n_ct * (pc + 1) / pieces) - it.ct0;
+            it.pieces = pieces;
+            it.acc_stride = acc_stride;
+            it.acc = acc + (size_t)rt * DBF_TILE_ROWS;
+            it.cnt = cnt + rt;
+            out.push_back(it);
+        }
+    }
+    for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);
 }
 
 void free_plan(DbfPlan& p) {
@@ -85,6 +155,26 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     nB1 = (int)items_1.size();
     for (int i = 0; i < n; ++i) append_items(items_1, sA[i], i, true, sB[i].n_rt, one, &phase);
 
+    // Column pieces for launches with few row tiles.  Accumulators: int32 [DBF_PIECES_MAX_BATCH][rows of
+    // the stage, padded to whole tiles] per layer and stage; counters: one per row tile.  Both start at
+    // zero and are returned to zero by the workgroup that finishes a row tile.
+    long long rtB = 0, rtA = 0;
+    for (int i = 0; i < n; ++i) {
+        rtB += sB[i].n_rt;
+        rtA += sA[i].n_rt;
+    }
+    std::vector<int> pcB(n, 1), pcA(n, 1);
+    bool cut = false;
+    if (rtB <= PIECE_MAX_ROW_TILES && rtA <= PIECE_MAX_ROW_TILES) {
+        for (int i = 0; i < n; ++i) {
+            pcB[i] = pieces_for(sB[i].n_ct, (int)rtB);
+            pcA[i] = pieces_for(sA[i].n_ct, (int)rtA);
+            cut = cut || pcB[i] > 1 || pcA[i] > 1;
+        }
+    }
+    const size_t acc_ints = cut ? (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * (size_t)(rtB + rtA) : 0;
+    const size_t cnt_ints = cut ? (size_t)(rtB + rtA) : 0;
+
     size_t off = 0;
     const size_t o_sB = off;  off = align_up(off + sizeof(DbfStage) * n, 256);
     const size_t o_sA = off;  off = align_up(off + sizeof(DbfStage) * n, 256);
@@ -94,6 +184,33 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     const size_t o_i1 = off;  off = align_up(off + sizeof(DbfItem) * items_1.size(), 256);
     const size_t o_sy = off;  off = align_up(off + sizeof(int) * (2 * (size_t)n + 1), 256);
     const size_t o_ps = off;  off = align_up(off + sizeof(unsigned) * ((size_t)n + 3), 256);
+    const size_t o_ac = off;  off = align_up(off + sizeof(int) * acc_ints, 256);
+    const size_t o_cn = off;  off = align_up(off + sizeof(int) * cnt_ints, 256);
+    std::vector<DbfItem> items_p;
+    int nBp = 0;
+    if (cut) {
+        // device addresses are offsets from the block's base, known only after the allocation:
+        // build with a null base here and rebase below
+        int* acc0 = reinterpret_cast<int*>(o_ac);
+        int* cnt0 = reinterpret_cast<int*>(o_cn);
+        size_t row_tiles_before = 0;
+        for (int i = 0; i < n; ++i) {
+            const int stride = sB[i].n_rt * DBF_TILE_ROWS;
+            append_piece_items(items_p, sB[i], i, false, 0, pcB[i],
+                               acc0 + (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * row_tiles_before, stride,
+                               cnt0 + row_tiles_before);
+            row_tiles_before += sB[i].n_rt;
+        }
+        nBp = (int)items_p.size();
+        for (int i = 0; i < n; ++i) {
+            const int stride = sA[i].n_rt * DBF_TILE_ROWS;
+            append_piece_items(items_p, sA[i], i, true, sB[i].n_rt, pcA[i],
+                               acc0 + (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * row_tiles_before, stride,
+                               cnt0 + row_tiles_before);
+            row_tiles_before += sA[i].n_rt;
+        }
+    }
+    const size_t o_ip = off;  off = align_up(off + sizeof(DbfItem) * items_p.size(), 256);
     std::vector<uint8_t> image(off, 0);
     std::memcpy(image.data() + o_sB, sB.data(), sizeof(DbfStage) * n);
     std::memcpy(image.data() + o_sA, sA.data(), sizeof(DbfStage) * n);
@@ -103,6 +220,13 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     std::memcpy(image.data() + o_i1, items_1.data(), sizeof(DbfItem) * items_1.size());
     void* dev = nullptr;
     hipError_t e = hipMalloc(&dev, off);
+    if (e == hipSuccess) {
+        for (DbfItem& it : items_p) {  // rebase the accumulator and counter addresses
+            it.acc = reinterpret_cast<int*>(static_cast<uint8_t*>(dev) + reinterpret_cast<size_t>(it.acc));
+            it.cnt = reinterpret_cast<int*>(static_cast<uint8_t*>(dev) + reinterpret_cast<size_t>(it.cnt));
+        }
+        std::memcpy(image.data() + o_ip, items_p.data(), sizeof(DbfItem) * items_p.size());
+    }
     if (e == hipSuccess) e = hipMemcpy(dev, image.data(), off, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
@@ -127,6 +251,9 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->nA1 = (int)items_1.size() - nB1;
     p->d_sync = reinterpret_cast<int*>(d + o_sy);
     p->d_psync = reinterpret_cast<unsigned*>(d + o_ps);
+    p->d_items_p = cut ? reinterpret_cast<DbfItem*>(d + o_ip) : nullptr;
+    p->nBp = nBp;
+    p->nAp = (int)items_p.size() - nBp;
     p->span = 1;
     for (int v : span_b) p->span = v > p->span ? v : p->span;
     for (int v : span_a) p->span = v > p->span ? v : p->span;
@@ -245,6 +372,7 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     // AUTO: a group of layers runs as one fused launch; a single layer is faster as two launches
     // (measured 14.3 vs 15.5 us at 4096 x 4096, k = 2048: the second launch's set-up overlaps the
     // first kernel instead of its workgroups polling).  The persistent kernel is opt-in.
+    const bool pieces_ok = kind == DBF_GEMV_AUTO;  // the named kinds keep their one-workgroup-per-row-tile lists
     if (kind == DBF_GEMV_AUTO) kind = p.n_layers > 1 ? DBF_GEMV_MFMA : DBF_GEMV_MFMA_SPLIT;
     if (kind == DBF_GEMV_PERSIST && !persist_eligible(p, x, batch)) kind = DBF_GEMV_MFMA;
     if (kind == DBF_GEMV_PERSIST) {
@@ -264,15 +392,22 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
     const bool span = dbf_mfma_chunk_tiles(batch, max_cols) >= dbf_col_tiles(max_cols);
     const DbfItem* items = span ? p.d_items_n : p.d_items_1;
-    const int nB = span ? p.nBn : p.nB1, nA = span ? p.nAn : p.nA1;
+    int nB = span ? p.nBn : p.nB1, nA = span ? p.nAn : p.nA1;
+    int pieces = 0;
+    if (pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH) {  // few row tiles: cut them into column pieces
+        items = p.d_items_p;
+        nB = p.nBp;
+        nA = p.nAp;
+        pieces = 1;
+    }
     if (kind == DBF_GEMV_MFMA) {
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         return DBF_OK;
     }
-    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, stream));
     if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, stream));
     return DBF_OK;
 }
 

@@ -70,6 +70,7 @@ typedef unsigned short us8 __attribute__((ext_vector_type(8)));
 
 constexpr int PF = DBF_PF;         // tiles of sign bits kept in flight per wavefront
 constexpr int UNR = DBF_UNR;       // independent 16-byte loads per thread in the prologue
+constexpr int WIDE = 3;            // the same in the input passes of the kernel variant for wide rows and column pieces
 constexpr float QMAX = 32512.f;    // 127*256: largest |q| so that hi and lo fit int8
 constexpr int XQ_PAD = 16;         // bytes of padding per operand row (LDS bank spread)
 constexpr unsigned OOB = 0x80000000u;  // buffer offset that is out of range for any span
@@ -116,7 +117,10 @@ struct Misc {
     int sigma[DBF_MAX_BATCH];      // sum over all columns of q
     float wmax[4][DBF_MAX_BATCH];  // per-wavefront max|u|
     uint16_t rscale[DBF_MAX_SPAN * DBF_TILE_ROWS];  // fp16 row scales of this workgroup's rows
+    int last;                      // column pieces: this workgroup was the last of its row tile to arrive
+    int pad_[3];
 };
+static_assert(sizeof(Misc) % 16 == 0, "the operand rows behind it are read in 16-byte pieces");
 
 // Eight consecutive input values u[8*v .. 8*v+7] of batch row bi (vector item v).
 // B stage: x (fp16) times b (fp16), exact in fp32.  A stage: the fp32 middle activations.
@@ -236,20 +240,22 @@ __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const 
 }
 
 // General case, first pass: max|u| of every batch row -> scale / inv.  Two barriers.
-template <bool STAGE_A>
+template <bool STAGE_A, int W>
 __device__ inline void input_scales(const DbfItem& it, const Ctx& c) {
     for (int bi = 0; bi < c.batch; ++bi) {
         float mx = 0.f;
         if (c.fast) {
-            for (int base = 0; base < c.nvec; base += 256 * UNR) {
-                InputVec<STAGE_A> iv[UNR];
+            // (W vector items per thread and round: all their loads are in flight together, so a
+            // wide row costs a few memory latencies, not one per 256*W*8 columns)
+            for (int base = 0; base < c.nvec; base += 256 * W) {
+                InputVec<STAGE_A> iv[W];
 #pragma unroll
-                for (int j = 0; j < UNR; ++j) {
+                for (int j = 0; j < W; ++j) {
                     const int v = base + 256 * j + c.tid;
                     if (v < c.nvec) iv[j].load(it, c.x, bi, v, v < c.nvec_x);
                 }
 #pragma unroll
-                for (int j = 0; j < UNR; ++j)
+                for (int j = 0; j < W; ++j)
                     if (base + 256 * j + c.tid < c.nvec) mx = fmaxf(mx, iv[j].absmax());
             }
         } else {
@@ -269,7 +275,7 @@ __device__ inline void input_scales(const DbfItem& it, const Ctx& c) {
 }
 
 // General case, second pass: quantise columns [64*c0, 64*cend) of every batch row into LDS.
-template <bool STAGE_A>
+template <bool STAGE_A, int W>
 __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int c0, int cend) {
     for (int bi = 0; bi < c.batch; ++bi) {
         const float inv = c.misc->inv[bi];
@@ -278,15 +284,15 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
         signed char* lo_row = c.xq + (2 * bi + 1) * c.chs;
         if (c.fast) {
             const int v0 = c0 * 8, v1 = cend * 8;
-            for (int base = v0; base < v1; base += 256 * UNR) {
-                InputVec<STAGE_A> iv[UNR];
+            for (int base = v0; base < v1; base += 256 * W) {
+                InputVec<STAGE_A> iv[W];
 #pragma unroll
-                for (int j = 0; j < UNR; ++j) {
+                for (int j = 0; j < W; ++j) {
                     const int v = base + 256 * j + c.tid;
                     if (v < v1) iv[j].load(it, c.x, bi, v, v < c.nvec_x);
                 }
 #pragma unroll
-                for (int j = 0; j < UNR; ++j) {
+                for (int j = 0; j < W; ++j) {
                     const int v = base + 256 * j + c.tid;
                     if (v < v1) local += iv[j].quantise_to(hi_row + (v - v0) * 8, lo_row + (v - v0) * 8, inv);
                 }
@@ -311,7 +317,11 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
     }
 }
 
-template <int NCG>
+// PIECES: the variant for lists whose items may be column pieces of a row tile (few row tiles) or
+// have rows too wide for the one-pass prologue; its input passes keep more loads in flight.  The
+// other instantiation is the hot one (long streams of layers of up to 4096 columns at batch 1)
+// and carries none of that code.
+template <int NCG, bool PIECES>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
@@ -329,7 +339,14 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     // neighbours lose; measured neutral, left off.)
     __builtin_amdgcn_s_setprio(DBF_PROLOGUE_PRIO);
 #endif
+    constexpr int IN_W = PIECES ? WIDE : UNR;
     const DbfItem it = items[blockIdx.x];
+    // Fields only the epilogue of a column piece needs are read again there instead of living in scalar
+    // registers through the whole kernel (the volatile asm keeps the compiler from merging the reads).
+    auto late = [&]() { const DbfItem* q = items + blockIdx.x; asm volatile("" : "+s"(q)); return q; };
+    auto piece_acc = [&]() { return late()->acc; };
+    auto piece_cnt = [&]() { return late()->cnt; };
+    auto piece_acc_stride = [&]() { return late()->acc_stride; };
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
@@ -355,8 +372,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     // top of the loop.  Loads complete in issue order; when slot j is consumed exactly PF-1
     // younger tile loads are outstanding, so vmcnt(PF-1) is the exact wait.  Any other memory
     // operation the compiler issues in between only makes that wait more conservative.
-    int c0 = 0;
-    int cend = min(it.n_ct, ch_tiles);
+    // (An item covers column tiles [ct0, ct_end) of its row tiles: all of them, unless the row tile is
+    // cut into column pieces.)
+    const int ct_first = PIECES ? it.ct0 : 0;
+    const int ct_end = PIECES ? it.ct0 + it.ct_n : it.n_ct;
+    const int n_pieces = PIECES ? it.pieces : 1;
+    int c0 = ct_first;
+    int cend = min(ct_end, c0 + ch_tiles);
     int steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
     int p_rt = 0, p_i = 0;
     v4u buf[PF];
@@ -471,7 +493,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     if (one_pass) {
         if (stage_a) input_one_pass<true>(cx, in0, in1); else input_one_pass<false>(cx, in0, in1);
     } else {
-        if (stage_a) input_scales<true>(it, cx); else input_scales<false>(it, cx);
+        if (stage_a) input_scales<true, IN_W>(it, cx); else input_scales<false, IN_W>(it, cx);
     }
 
     v4i acc[NCG][8];
@@ -483,6 +505,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         xrow[gi] = (col < ncols ? col : col % ncols) * chs + 16 * g;
     }
     const int xo_max = (ch_tiles - 1) * 64;  // padded steps read a valid (ignored) operand
+    // one pass: the whole row is in LDS at its own column offsets; otherwise LDS holds the current chunk
+    const int xo_base = one_pass ? ct_first * 64 : 0;
     // epilogue coordinates: thread -> (row rho of the tile, batch rows bi = tid>>7, +2, ...)
     const int rho = tid & 127;
     const int e_s = rho >> 4;
@@ -493,14 +517,14 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
 #endif
     for (;;) {  // chunks of columns (a single one unless the batch is large)
         if (!one_pass) {
-            if (stage_a) input_quantise_chunk<true>(it, cx, c0, cend);
-            else input_quantise_chunk<false>(it, cx, c0, cend);
+            if (stage_a) input_quantise_chunk<true, IN_W>(it, cx, c0, cend);
+            else input_quantise_chunk<false, IN_W>(it, cx, c0, cend);
         }
         __syncthreads();
-        const bool last_chunk = cend >= it.n_ct;
+        const bool last_chunk = cend >= ct_end;
 
         for (int rtl = 0; rtl < it.nrt; ++rtl) {
-            if (c0 == 0) {
+            if (c0 == ct_first) {
 #pragma unroll
                 for (int gi = 0; gi < NCG; ++gi)
 #pragma unroll
@@ -513,11 +537,11 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             v4i xop[NCG], xnext[NCG];
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi)
-                xnext[gi] = *reinterpret_cast<const v4i*>(xq + xrow[gi] + min(w * 64, xo_max));
+                xnext[gi] = *reinterpret_cast<const v4i*>(xq + xrow[gi] + min(xo_base + w * 64, xo_max));
             for (int i0 = 0; i0 < steps; i0 += PF) {
 #pragma unroll
                 for (int j = 0; j < PF; ++j) {
-                    const int xo = (w + 4 * (i0 + j + 1)) * 64;  // operand offset of the next step
+                    const int xo = xo_base + (w + 4 * (i0 + j + 1)) * 64;  // operand offset of the next step
 #pragma unroll
                     for (int gi = 0; gi < NCG; ++gi) {
                         xop[gi] = xnext[gi];
@@ -579,7 +603,15 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                     vh = -(vh >> 7);
                     vl = -(vl >> 7);
                 }
-                const int total = 2 * (vh * 256 + vl) - misc->sigma[bi];
+                // (sigma covers the columns this workgroup quantised: its own piece, or, in the one-pass
+                // case, the whole row -- then only the first piece subtracts it)
+                const int sig = (one_pass && ct_first != 0) ? 0 : misc->sigma[bi];
+                const int total = 2 * (vh * 256 + vl) - sig;
+                if (n_pieces > 1) {  // a column piece: add the exact integer sum; the last piece to arrive finishes the row
+                    __hip_atomic_fetch_add(piece_acc() + (size_t)bi * piece_acc_stride() + rho, total, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    continue;
+                }
                 const float val = (float)total * misc->scale[bi] * rscale;
                 if (stage_a) {
                     if (row < it.rows) y[(size_t)bi * it.rows + row] = float_to_half_bits(val);
@@ -591,11 +623,43 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 }
             }
         }
-        if (last_chunk) break;
+        if (last_chunk) {
+            if (n_pieces > 1) {
+                // ---- column pieces: count this piece in; the last one reads the row tile's sums (and
+                // clears them and the counter for the next launch), scales and stores them.  Integer
+                // adds are exact, so the result does not depend on the order of arrival.
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's adds have been performed ...
+                __syncthreads();                                  // ... and so have the workgroup's
+                if (tid == 0) {
+                    int* cnt = piece_cnt();
+                    const int before = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    misc->last = before == n_pieces - 1;
+                    if (misc->last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __syncthreads();
+                if (misc->last) {
+                    const int row = it.row0 + rho;
+                    const float rscale = half_bits_to_float(misc->rscale[rho]);
+                    for (int bi = tid >> 7; bi < batch; bi += 2) {
+                        const int total = __hip_atomic_exchange(piece_acc() + (size_t)bi * piece_acc_stride() + rho, 0,
+                                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const float val = (float)total * misc->scale[bi] * rscale;
+                        if (stage_a) {
+                            if (row < it.rows) y[(size_t)bi * it.rows + row] = float_to_half_bits(val);
+                        } else {
+                            __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + (size_t)bi * it.t_stride + row,
+                                               __builtin_bit_cast(unsigned, val), __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                    }
+                }
+            }
+            break;
+        }
         // next chunk (reached only with nrt == 1): restart the tile cursor there
         __syncthreads();  // every wavefront is done reading this chunk's operand
         c0 = cend;
-        cend = min(it.n_ct, c0 + ch_tiles);
+        cend = min(ct_end, c0 + ch_tiles);
         steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
         p_rt = 0;
         p_i = 0;
@@ -612,7 +676,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             // this wavefront's write-through stores of t have been acknowledged by memory ...
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();  // ... and so have those of the whole workgroup
-            if (tid == 0)
+            // (of the pieces of a row tile only the one that stored the result publishes it)
+            if (tid == 0 && (n_pieces == 1 || misc->last))
                 __hip_atomic_fetch_add(&sync[it.layer], it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else if (tid == 0) {
             const int fin = __hip_atomic_fetch_add(&sync[n_layers + it.layer], 1, __ATOMIC_RELAXED,
@@ -645,17 +710,21 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols) {
 
 hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, hipStream_t stream) {
+                                 int max_cols, int pieces, hipStream_t stream) {
     if (n_items <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols);
     const size_t smem = mfma_smem_bytes(batch, ch_tiles);
-    if (batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1>), dim3(n_items), dim3(256), smem, stream, items, sync,
+    // column pieces (small batches only), or rows the one-pass prologue cannot take (it holds 256*UNR*8 columns)
+    if (pieces || (batch <= 8 && max_cols > 256 * UNR * 8))
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else if (batch <= 8)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     return hipGetLastError();
 }

@@ -10,6 +10,7 @@
 #define DBF_MAX_SPAN 16  /* most row tiles one workgroup takes */
 #define DBF_PERSIST_MAX_SPAN 4  /* most row tiles per item the persistent decode kernel accepts */
 #define DBF_PERSIST_MAX_COLS 12288  /* most columns of a stage it accepts (LDS staging) */
+#define DBF_PIECES_MAX_BATCH 2  /* largest batch for which row tiles may be cut into column pieces */
 
 static inline int dbf_row_tiles(int rows) { return (rows + DBF_TILE_ROWS - 1) / DBF_TILE_ROWS; }
 static inline int dbf_col_tiles(int cols) { return (cols + DBF_TILE_COLS - 1) / DBF_TILE_COLS; }
@@ -61,7 +62,14 @@ struct DbfItem {
     int need;                   // A stage: B-stage row tiles of the layer that must be done
     int stage_a;                // 0: B stage, 1: A stage
     int peers;                  // A stage: number of A-stage items of this layer in the list
-    int pad_[2];
+    // Column pieces (lists with pieces > 1 hold one row tile per item): the item covers column tiles
+    // [ct0, ct0 + ct_n) of its row tile; the pieces of a row tile add their exact integer sums into
+    // acc and the last one to arrive (cnt) scales and stores the result, and clears both.
+    int ct0, ct_n;              // column tiles of this item (0, n_ct if the row tile is not cut)
+    int pieces;                 // items that share this row tile (1: not cut)
+    int acc_stride;             // elements between batch rows of acc
+    int* acc;                   // int32 [DBF_PIECES_MAX_BATCH][acc_stride], this row tile's first row
+    int* cnt;                   // arrival counter of this row tile
 };
 
 // Device-side state of one launch plan: everything a decode call of a layer or a stack needs.
@@ -77,6 +85,8 @@ struct DbfPlan {
     int nBn, nAn;
     DbfItem* d_items_1;         // the same with one row tile per item (used when the columns of
     int nB1, nA1;               // a stage do not fit one LDS chunk at the requested batch)
+    DbfItem* d_items_p;         // one row tile per item, row tiles cut into column pieces: built for plans
+    int nBp, nAp;               // with few row tiles (a layer alone, a short stack); NULL otherwise
     int* d_sync;                // [n_layers] B-row-tile counters, [n_layers] finished A items, [1] time-outs
     unsigned* d_psync;          // persistent kernel: [n_layers] ever-growing B-row-tile counters,
                                 // then {exited workgroups, epoch}

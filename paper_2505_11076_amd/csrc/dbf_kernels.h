@@ -20,9 +20,11 @@ hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfW
 //   use_sync == 0: no waiting and no counters (the caller orders the stages by launches).
 // Items with nrt > 1 are allowed only if every item's columns fit one LDS chunk, i.e.
 // dbf_mfma_chunk_tiles(batch, max_cols) >= dbf_col_tiles(max_cols).
+//   pieces != 0: the list may hold column pieces of row tiles (DbfItem::pieces > 1; one row tile per
+//   item, batch <= DBF_PIECES_MAX_BATCH); pieces == 0: every item covers all columns of its row tiles.
 hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, hipStream_t stream);
+                                 int max_cols, int pieces, hipStream_t stream);
 int dbf_mfma_chunk_tiles(int batch, int max_cols);
 
 // Batch-1 decode of items[0..n_items) (B items first, then A items) in one persistent launch

@@ -106,6 +106,25 @@ CONFIG4 = [                                                      # prefill shape
 ]
 
 
+# Second workload: the layer sizes of the paper's matrix-vector timing table (Table 4: Llama-3
+# shapes, printed as rows x columns of W = n_out x n_in) plus the grouped-query k/v projection
+# 4096 -> 1024, each at the table's four sizes in bits per weight.  The middle size follows the
+# storage formula k = floor(bits * n*m / (n+m)) (section 3, "Middle dimension size").
+TABLE4_SHAPES = [                                                # (n_out, n_in)
+    (4096, 4096), (4096, 14336), (8192, 8192), (8192, 28672), (1024, 4096),
+]
+TABLE4_BITS = [1.0, 1.5, 2.0, 2.3]
+
+
+def middle_size(bits: float, n_out: int, n_in: int) -> int:
+    return int(np.floor(bits * n_out * n_in / (n_out + n_in)))
+
+
+def table4_configs() -> list[dict]:
+    return [dict(n_in=n_in, n_out=n_out, k=middle_size(bits, n_out, n_in), bits=bits)
+            for (n_out, n_in) in TABLE4_SHAPES for bits in TABLE4_BITS]
+
+
 def llama2_7b_stack_shapes(n_blocks: int = 32) -> list[dict]:
     """Linear layers of a Llama-2-7B-shaped decoder at 1.5 bits per weight.
 

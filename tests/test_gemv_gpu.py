@@ -380,3 +380,59 @@ def test_stack_call_replayed_from_a_captured_graph():
         stack.close()
         for l in layers:
             l.close()
+
+
+@pytest.mark.parametrize("batch", [1, 2])
+def test_column_pieces_equal_whole_rows_bit_for_bit(batch, monkeypatch):
+    """Launches with few row tiles cut long rows into column pieces that add exact integer sums into
+    per-row accumulators; the last piece scales and stores.  Every piece quantises with the scale of
+    the whole row, so the result must equal the uncut launch bit for bit -- for a layer alone (two
+    launches), for a short stack (one launch, the finishing piece publishes the row tile), with
+    pieces forced onto short rows, and on repeated calls (accumulators and counters are left at zero)."""
+    shapes = [(6000, 300, 520), (520, 700, 6000), (4100, 260, 4500)]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 970 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 980 + i)) for i, L in enumerate(Ls)]
+
+    def run(env):
+        for name in ("DBF_COL_PIECES", "DBF_PIECE_NEVER_TILES", "DBF_PIECE_MIN_TILES", "DBF_PIECE_TARGET"):
+            monkeypatch.delenv(name, raising=False)
+        for name, val in env.items():
+            monkeypatch.setenv(name, val)
+        layers = [G.pack(L) for L in Ls]       # the plans are built here, under this environment
+        stack = B.dbf_stack_create(layers)
+        outs = []
+        try:
+            for rep in range(2):
+                for L, X, layer in zip(Ls, Xs, layers):
+                    y = torch.full((batch, L.n_out), float("nan"), dtype=torch.float16, device="cuda")
+                    B.dbf_gemv(layer, G.f16_to_dev(X).data_ptr(), y.data_ptr(), batch, G.stream_handle())
+                    torch.cuda.synchronize()
+                    outs.append(y.cpu().view(torch.int16).numpy().copy())
+                x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+                y_all = torch.full((sum(batch * L.n_out for L in Ls),), float("nan"), dtype=torch.float16, device="cuda")
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle())
+                torch.cuda.synchronize()
+                outs.append(y_all.cpu().view(torch.int16).numpy().copy())
+            assert B.dbf_stack_sync_timeouts(stack) == 0
+            for layer in layers:
+                assert B.dbf_sync_timeouts(layer) == 0
+        finally:
+            stack.close()
+            for l in layers:
+                l.close()
+        return outs
+
+    G.say("column pieces: whole rows")
+    whole = run({"DBF_COL_PIECES": "0"})
+    for label, env in (("default rule", {}), ("3 pieces everywhere", {"DBF_COL_PIECES": "3"}),
+                       ("many small pieces", {"DBF_PIECE_NEVER_TILES": "0", "DBF_PIECE_MIN_TILES": "2",
+                                              "DBF_PIECE_TARGET": "4096"})):
+        G.say("column pieces: " + label)
+        got = run(env)
+        assert len(got) == len(whole)
+        for i, (g, w) in enumerate(zip(got, whole)):
+            assert np.array_equal(g, w), (label, i)
+    # and the whole-row result is the oracle's, within the gate
+    for L, X, y_bits in zip(Ls, Xs, whole[:3]):
+        G.check(O.f16_bits_to_f64(y_bits.view(np.uint16)).reshape(batch, L.n_out), O.forward_from_packed(X, L, "staged"),
+                "whole rows %dx%d" % (L.n_out, L.n_in))

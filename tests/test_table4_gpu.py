@@ -1,0 +1,60 @@
+"""GPU parity on the second decode workload: the layer sizes of the paper's matrix-vector timing
+table (Table 4: 4096x4096, 4096x14336, 8192x8192, 8192x28672 as rows x columns of W) and the
+grouped-query projection 4096 -> 1024, at the smallest and the largest of the table's sizes in
+bits per weight (1 and 2.3; the middle size follows k = floor(bits n m / (n + m)), section 3).
+
+These layers are too large for the dense fp64 oracle in test time (W' of 8192x28672 alone is
+1.9 GB, forming it 3e12 multiply-adds), so, in the launch configuration the benchmark times
+(default kind; batch 1, and batch 4 for one shape):
+  * 96 sampled outputs per batch row are compared with the oracle, which computes each one from
+    all of B and the sampled rows of A (staged order, fp64);
+  * all outputs are checked against the variance law of i.i.d. signs,
+    var(y_i) = a_i^2 * sum_j m_j^2 * sum_l (b_l x_l)^2, which catches a wrong scale vector, a
+    wrong input block or outputs written to the wrong place.
+Inputs wider than one LDS chunk (14336 and 28672 columns) take the kernel's chunked path.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as G
+from oracle import dbf_oracle as O
+from paper_2505_11076_amd import binding as B
+from paper_2505_11076_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+CASES = [(n_out, n_in, bits, 1) for (n_out, n_in) in I.TABLE4_SHAPES for bits in (1.0, 2.3)]
+CASES.append((4096, 14336, 1.5, 4))
+
+
+@pytest.mark.parametrize("n_out,n_in,bits,batch", CASES)
+def test_table4_layer(n_out, n_in, bits, batch):
+    k = I.middle_size(bits, n_out, n_in)
+    what = "table4 n_out=%d n_in=%d bits=%.1f k=%d batch=%d" % (n_out, n_in, bits, k, batch)
+    G.say("start " + what)
+    seed = I.seed_for(6, n_out + n_in + int(10 * bits))
+    L = I.make_layer(n_in, n_out, k, seed)
+    X = I.make_activations(batch, n_in, seed)
+    layer = G.pack(L)
+    try:
+        x = G.f16_to_dev(X)
+        y = torch.full((batch, n_out), float("nan"), dtype=torch.float16, device="cuda")
+        B.dbf_gemv(layer, x.data_ptr(), y.data_ptr(), batch, G.stream_handle())
+        torch.cuda.synchronize()
+        assert B.dbf_sync_timeouts(layer) == 0
+        got = O.f16_bits_to_f64(y.cpu().view(torch.int16).numpy().view(np.uint16)).reshape(batch, n_out)
+        assert np.all(np.isfinite(got)), what
+        a = O.f16_bits_to_f64(L.a)
+        m = O.f16_bits_to_f64(L.m)
+        b = O.f16_bits_to_f64(L.b)
+        xf = O.f16_bits_to_f64(X).reshape(batch, n_in)
+        want_rms = np.sqrt(np.mean(a ** 2) * np.sum((xf * b[None, :]) ** 2, axis=1) * np.sum(m ** 2))
+        rms = np.sqrt(np.mean(got ** 2, axis=1))
+        assert np.all(np.abs(rms / want_rms - 1.0) < 0.12), (what, rms, want_rms)
+        rows = np.sort(np.random.default_rng(seed + 1).choice(n_out, size=96, replace=False))
+        G.say("  oracle on 96 sampled outputs")
+        ref = O.forward_rows_from_packed(X, L, rows)
+        G.check(got[:, rows], ref, what + " sampled")
+    finally:
+        layer.close()
