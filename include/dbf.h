@@ -188,8 +188,18 @@ int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
  * y_dev the concatenation of fp16 [batch][n_out_i] blocks; layer i's blocks start at
  * element offsets batch * (sum of n_in_j, j<i) and batch * (sum of n_out_j, j<i), which
  * dbf_stack_offsets also reports.
+ *
+ * dbf_stack_create_grouped: the same with groups of consecutive layers that read ONE input
+ * block (the projections of one activation vector: q, k, v; gate, up -- section 3 defines the
+ * product per layer, the grouping only says which x a layer is given).  group_sizes[0..n_groups)
+ * are positive and sum to n_layers; the layers of a group must have equal n_in (DBF_ESHAPE).
+ * x_dev then holds one fp16 [batch][n_in] block per GROUP, in group order; dbf_stack_offsets
+ * reports the same x offset for every layer of a group (and, at layer_index == n_layers, the
+ * total), y offsets as before.  group_sizes == NULL: every layer its own group.
  */
 int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** out);
+int dbf_stack_create_grouped(const dbf_layer* const* layers, int n_layers, const int* group_sizes,
+                             int n_groups, dbf_stack** out);
 int dbf_stack_offsets(const dbf_stack* stack, int layer_index, int batch,
                       size_t* x_offset_elems, size_t* y_offset_elems);
 int dbf_stack_gemv(const dbf_stack* stack, const void* x_dev, void* y_dev, int batch, int kind,

@@ -26,7 +26,7 @@ EXPORTS = [
     "dbf_pack", "dbf_pack_bits", "dbf_unpack_bits", "dbf_dims", "dbf_free",
     "dbf_tiled_bytes", "dbf_signs_to_bits_host", "dbf_tile_host", "dbf_untile_host",
     "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
-    "dbf_stack_create", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
+    "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
     "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
 ]
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
     L.dbf_gemm.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     L.dbf_gemm_kind.argtypes = [vp, vp, vp, i32, vp, sz, i32, vp]
     L.dbf_stack_create.argtypes = [pp, i32, pp]
+    L.dbf_stack_create_grouped.argtypes = [pp, i32, C.POINTER(C.c_int), i32, pp]
     L.dbf_stack_offsets.argtypes = [vp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
     L.dbf_stack_gemv.argtypes = [vp, vp, vp, i32, i32, vp]
     L.dbf_stack_gemv_timed.argtypes = [vp, vp, vp, i32, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
@@ -246,6 +247,25 @@ def dbf_stack_create(layers) -> Stack:
     h = C.c_void_p(0)
     _check(lib().dbf_stack_create(arr, len(layers), C.byref(h)), "dbf_stack_create")
     return Stack(h.value, layers)
+
+
+def dbf_stack_create_grouped(layers, group_sizes) -> Stack:
+    """Stack whose consecutive groups of layers (sizes in group_sizes) each read one shared x block."""
+    layers = list(layers)
+    sizes = [int(v) for v in group_sizes]
+    arr = (C.c_void_p * max(1, len(layers)))(*[l.handle for l in layers])
+    gs = (C.c_int * max(1, len(sizes)))(*sizes)
+    h = C.c_void_p(0)
+    _check(lib().dbf_stack_create_grouped(arr, len(layers), gs, len(sizes), C.byref(h)), "dbf_stack_create_grouped")
+    return Stack(h.value, layers)
+
+
+def dbf_stack_offsets(stack: Stack, layer_index: int, batch: int):
+    """Element offsets (x, y) of a layer's blocks in the stack's x and y buffers; layer_index == number of
+    layers gives the totals."""
+    xo, yo = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().dbf_stack_offsets(stack.handle, layer_index, batch, C.byref(xo), C.byref(yo)), "dbf_stack_offsets")
+    return int(xo.value), int(yo.value)
 
 
 def dbf_stack_gemv(stack: Stack, x_ptr: int, y_ptr: int, batch: int, stream: int = 0,

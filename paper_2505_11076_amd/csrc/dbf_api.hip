@@ -558,13 +558,31 @@ int dbf_sync_timeouts(const dbf_layer* L, int* timeouts) {
 
 // ---- stacks ---------------------------------------------------------------------------------
 
-int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** out) {
+int dbf_stack_create_grouped(const dbf_layer* const* layers, int n_layers, const int* group_sizes, int n_groups,
+                             dbf_stack** out) {
     if (out) *out = nullptr;
     if (!layers || !out || n_layers < 1) return DBF_EINVAL;
     for (int i = 0; i < n_layers; ++i)
         if (!layers[i]) return DBF_EINVAL;
     for (int i = 1; i < n_layers; ++i)
         if (layers[i]->device != layers[0]->device) return DBF_EINVAL;
+    // group of every layer: consecutive layers that read one input block
+    std::vector<int> first_of(n_layers);
+    if (group_sizes) {
+        if (n_groups < 1) return DBF_EINVAL;
+        int at = 0;
+        for (int g = 0; g < n_groups; ++g) {
+            if (group_sizes[g] < 1 || group_sizes[g] > n_layers - at) return DBF_EINVAL;
+            for (int j = 0; j < group_sizes[g]; ++j) {
+                if (layers[at + j]->n_in != layers[at]->n_in) return DBF_ESHAPE;
+                first_of[at + j] = at;
+            }
+            at += group_sizes[g];
+        }
+        if (at != n_layers) return DBF_EINVAL;
+    } else {
+        for (int i = 0; i < n_layers; ++i) first_of[i] = i;
+    }
 
     dbf_stack* S = new (std::nothrow) dbf_stack();
     if (!S) return DBF_ENOMEM;
@@ -578,15 +596,22 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
     S->n_layers = n_layers;
     S->device = layers[0]->device;
     S->h_x_prefix[0] = S->h_y_prefix[0] = 0;
+    long long x_end = 0;  // elements of x (per unit of batch) used so far
     for (int i = 0; i < n_layers; ++i) {
         const dbf_layer* L = layers[i];
+        if (first_of[i] == i) {
+            S->h_x_prefix[i] = x_end;
+            x_end += L->n_in;
+        } else {
+            S->h_x_prefix[i] = S->h_x_prefix[first_of[i]];
+        }
         sB[i] = L->h_stages[0];
         sA[i] = L->h_stages[1];
         sB[i].x_off = sA[i].x_off = S->h_x_prefix[i];
         sB[i].y_off = sA[i].y_off = S->h_y_prefix[i];
-        S->h_x_prefix[i + 1] = S->h_x_prefix[i] + L->n_in;
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
     }
+    S->h_x_prefix[n_layers] = x_end;
     const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", "2"), stack_spans("DBF_STACK_SPAN_A", "4"), &S->plan);
     if (rc != DBF_OK) {
         dbf_stack_free(S);
@@ -594,6 +619,10 @@ int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** o
     }
     *out = S;
     return DBF_OK;
+}
+
+int dbf_stack_create(const dbf_layer* const* layers, int n_layers, dbf_stack** out) {
+    return dbf_stack_create_grouped(layers, n_layers, nullptr, 0, out);
 }
 
 int dbf_stack_offsets(const dbf_stack* S, int layer_index, int batch, size_t* x_off, size_t* y_off) {

@@ -436,3 +436,56 @@ def test_column_pieces_equal_whole_rows_bit_for_bit(batch, monkeypatch):
     for L, X, y_bits in zip(Ls, Xs, whole[:3]):
         G.check(O.f16_bits_to_f64(y_bits.view(np.uint16)).reshape(batch, L.n_out), O.forward_from_packed(X, L, "staged"),
                 "whole rows %dx%d" % (L.n_out, L.n_in))
+
+
+@pytest.mark.parametrize("batch", [1, 3])
+def test_groups_of_layers_sharing_one_input(batch):
+    """q, k, v read one activation vector, gate and up another: a grouped stack takes one x block
+    per group.  Every layer's output must equal, bit for bit, its own dbf_gemv on that block, and
+    the oracle's within the gate; the reported offsets follow the groups."""
+    shapes = [(512, 512, 256), (512, 128, 200), (512, 128, 130),      # q, k, v
+              (384, 1000, 300), (384, 1000, 310),                      # gate, up
+              (1000, 384, 300)]                                        # down, alone
+    groups = [3, 2, 1]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 990 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    group_x = [I.make_activations(batch, n_in, I.seed_for(5, 996 + g)) for g, n_in in enumerate((512, 384, 1000))]
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create_grouped(layers, groups)
+    try:
+        owner = [0, 0, 0, 1, 1, 2]
+        x_starts = [0, batch * 512, batch * (512 + 384)]
+        yo = 0
+        for i, L in enumerate(Ls):
+            assert B.dbf_stack_offsets(stack, i, batch) == (x_starts[owner[i]], yo)
+            yo += batch * L.n_out
+        assert B.dbf_stack_offsets(stack, len(Ls), batch) == (batch * (512 + 384 + 1000), yo)
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in group_x])
+        for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA_SPLIT, "mfma_split"), (B.GEMV_VALU, "valu")):
+            G.say("grouped stack [%s] batch %d" % (name, batch))
+            y_all = torch.full((yo,), float("nan"), dtype=torch.float16, device="cuda")
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle(), kind)
+            torch.cuda.synchronize()
+            got_all = y_all.cpu().view(torch.int16).numpy().view(np.uint16)
+            at = 0
+            for i, (L, layer) in enumerate(zip(Ls, layers)):
+                got = got_all[at:at + batch * L.n_out]
+                at += batch * L.n_out
+                X = group_x[owner[i]]
+                y1 = torch.full((batch, L.n_out), float("nan"), dtype=torch.float16, device="cuda")
+                B.dbf_gemv(layer, G.f16_to_dev(X).data_ptr(), y1.data_ptr(), batch, G.stream_handle(), kind)
+                torch.cuda.synchronize()
+                assert np.array_equal(got, y1.cpu().view(torch.int16).numpy().view(np.uint16).reshape(-1)), (name, i)
+                G.check(O.f16_bits_to_f64(got).reshape(batch, L.n_out), O.forward_from_packed(X, L, "dense"),
+                        "grouped[%s] layer %d" % (name, i))
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+        # groups must be consistent
+        with pytest.raises(B.DbfError):
+            B.dbf_stack_create_grouped(layers, [2, 4])        # q and gate do not share n_in
+        with pytest.raises(B.DbfError):
+            B.dbf_stack_create_grouped(layers, [3, 2])        # sizes do not cover the layers
+        with pytest.raises(B.DbfError):
+            B.dbf_stack_create_grouped(layers, [3, 0, 3])
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()
