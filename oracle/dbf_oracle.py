@@ -20,7 +20,9 @@ Parity pins (tests/test_oracle_pins.py): k=1 rank-one closed form, brute-force
 sum of outer products on tiny shapes (exhaustive for <= 2x2x2), all-ones
 closed form, pure-Python fsum re-evaluation, invariances of the middle index,
 variance law for random signs, packing round trip, the bits-per-weight
-numbers the paper prints; the sampled-rows variant against the dense one.  No function here is "parity unpinned".
+numbers the paper prints; the sampled-rows variant against the dense one; pruning of middle
+channels against zeroing their scales and against a per-entry loop.  No function here is
+"parity unpinned".
 """
 from __future__ import annotations
 
@@ -150,6 +152,28 @@ def forward_rows_from_packed(X_f16_bits, layer, rows) -> np.ndarray:
     b = f16_bits_to_f64(layer.b)
     X = f16_bits_to_f64(X_f16_bits).reshape(-1, layer.n_in)
     return forward_staged(X, a, A_sel, m, B, b)
+
+
+# ---------------------------------------------------------------------------
+# Middle-channel pruning (section 3.5, "Nonuniform layer compression ratios")
+# ---------------------------------------------------------------------------
+
+
+def prune_middle(A_words, B_words, m_f16_bits, n_out: int, k: int, n_in: int, keep):
+    """Keeps the middle channels listed in `keep` (strictly increasing indices < k), in order.
+
+    The paper treats the middle dimension as channels and keeps those with the highest scores
+    (section 3.5); how the scores are obtained needs gradients and is not part of this.  The
+    structural step written out: decode the signs, take columns `keep` of A, rows `keep` of B and
+    entries `keep` of m, encode again.  Returns (A_words', B_words', m_bits', k').
+    """
+    keep = np.asarray(keep, dtype=np.int64)
+    if keep.ndim != 1 or keep.size < 1 or np.any(keep < 0) or np.any(keep >= k) or np.any(np.diff(keep) <= 0):
+        raise ValueError("keep must be a non-empty strictly increasing list of middle indices")
+    A = unpack_signs(A_words, n_out, k)
+    B = unpack_signs(B_words, k, n_in)
+    m = np.ascontiguousarray(m_f16_bits, dtype=np.uint16).reshape(-1)
+    return pack_signs(A[:, keep]), pack_signs(B[keep, :]), m[keep].copy(), int(keep.size)
 
 
 # ---------------------------------------------------------------------------

@@ -331,3 +331,58 @@ def test_sampled_rows_equal_the_dense_product_and_the_brute_force():
         O.forward_rows_from_packed(X, L, [45])
     with pytest.raises(ValueError):
         O.forward_rows_from_packed(X, L, [-1])
+
+
+# ---------------------------------------------------------------------------
+# Middle-channel pruning (section 3.5)
+# ---------------------------------------------------------------------------
+
+
+@pytest.mark.parametrize("shape", [(7, 5, 9), (33, 40, 70), (64, 31, 129)])
+def test_pruning_equals_zeroing_the_dropped_scales(shape):
+    """W' = sum_j m_j A[:,j] B[j,:]: dropping channel j removes exactly the term that m_j = 0
+    removes.  The pruned layer's dense weight must equal the original's with those scales zeroed
+    (independent of how prune_middle re-encodes anything)."""
+    n_in, n_out, k = shape
+    L = I.make_layer(n_in, n_out, k, seed=4242 + k)
+    rng = np.random.default_rng(99 + k)
+    keep = np.sort(rng.choice(k, size=max(1, (2 * k) // 3), replace=False))
+    A2, B2, m2, k2 = O.prune_middle(L.A_bits, L.B_bits, L.m, n_out, k, n_in, keep)
+    assert k2 == keep.size
+    a, m, b = O.f16_bits_to_f64(L.a), O.f16_bits_to_f64(L.m), O.f16_bits_to_f64(L.b)
+    m_zeroed = np.zeros_like(m)
+    m_zeroed[keep] = m[keep]
+    W_ref = O.dense_weight(a, O.unpack_signs(L.A_bits, n_out, k), m_zeroed, O.unpack_signs(L.B_bits, k, n_in), b)
+    W_new = O.dense_weight(a, O.unpack_signs(A2, n_out, k2), O.f16_bits_to_f64(m2), O.unpack_signs(B2, k2, n_in), b)
+    assert np.max(np.abs(W_new - W_ref)) <= 1e-15 * max(1.0, np.max(np.abs(W_ref))) * k
+
+
+def test_pruning_moves_every_entry_to_its_new_place():
+    """Entry by entry, with the bit positions of the canonical format computed by hand: sign
+    (i, j') of the new A is sign (i, keep[j']) of the old one, row j' of the new B is row keep[j']
+    of the old B, and the tail bits of the last word of a row are zero."""
+    n_in, n_out, k = 37, 29, 70
+    L = I.make_layer(n_in, n_out, k, seed=777)
+    keep = np.array([0, 3, 4, 31, 32, 33, 63, 64, 69])
+    A2, B2, m2, k2 = O.prune_middle(L.A_bits, L.B_bits, L.m, n_out, k, n_in, keep)
+    Aw = np.asarray(L.A_bits, dtype=np.uint32).reshape(n_out, -1)
+    Bw = np.asarray(L.B_bits, dtype=np.uint32).reshape(k, -1)
+    assert A2.shape == (n_out, 1) and B2.shape == (k2, 2) and k2 == 9
+    for i in range(n_out):
+        for jn, jo in enumerate(keep):
+            assert (int(A2[i, jn // 32]) >> (jn % 32)) & 1 == (int(Aw[i, jo // 32]) >> (jo % 32)) & 1
+        assert int(A2[i, 0]) >> 9 == 0
+    for jn, jo in enumerate(keep):
+        assert np.array_equal(B2[jn], Bw[jo])
+    assert np.array_equal(m2, np.asarray(L.m, dtype=np.uint16)[keep])
+
+
+def test_pruning_identity_and_argument_errors():
+    n_in, n_out, k = 20, 10, 40
+    L = I.make_layer(n_in, n_out, k, seed=31)
+    A2, B2, m2, k2 = O.prune_middle(L.A_bits, L.B_bits, L.m, n_out, k, n_in, np.arange(k))
+    assert k2 == k and np.array_equal(A2, np.asarray(L.A_bits).reshape(n_out, -1))
+    assert np.array_equal(B2, np.asarray(L.B_bits).reshape(k, -1)) and np.array_equal(m2, L.m)
+    for bad in ([], [3, 3], [5, 2], [-1, 2], [0, 40]):
+        with pytest.raises(ValueError):
+            O.prune_middle(L.A_bits, L.B_bits, L.m, n_out, k, n_in, bad)
