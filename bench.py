@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--table4", action="store_true",
                     help="only the second workload: the layer sizes of the paper's matrix-vector timing table "
                          "(Llama-3 shapes, 1 / 1.5 / 2 / 2.3 bits per weight), isolated latency and streamed rate")
+    ap.add_argument("--prune", action="store_true",
+                    help="only the middle-channel pruning measurement (dbf_prune_middle on two config-4 shaped layers)")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -92,6 +94,9 @@ def main():
     if args.prefill_only:
         st = torch.cuda.current_stream().cuda_stream
         print(json.dumps({"prefill": prefill_bench(B, I, torch, np, st), "mfma_probe": mfma_probe(B, torch, st)}))
+        return
+    if args.prune:
+        print(json.dumps({"prune_middle": prune_bench(B, I, torch, np)}))
         return
     if args.table4:
         print(json.dumps({"table4": table4_bench(B, I, torch, np, args.batch, kind,
@@ -394,6 +399,33 @@ def table4_bench(B, I, torch, np, batch, kind, stream):
             "note": "isolated = one dbf_gemv call, cache warm (p50 of 200 event pairs); stream = distinct copies of "
                     "the layer in one dbf_stack_gemv call per step, signs read from HBM; paper column: its Table 4 "
                     "on an RTX 4090, another machine, context only"}
+
+
+def prune_bench(B, I, torch, np):
+    """dbf_prune_middle from 2 to 1.5 bits per weight on the two prefill-shaped layers: the whole call
+    (allocation of the new layer, three gather kernels, its launch plan; synchronous) and the sign
+    bytes it has to move (kept signs read once, new signs written once)."""
+    res = {}
+    for cfg in I.CONFIG4:
+        n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
+        k2 = I.middle_size(1.5, n_out, n_in)
+        L = I.make_layer(n_in, n_out, k, seed=I.seed_for(4, n_in))
+        layer = B.dbf_pack_bits(n_in, n_out, k, L.A_bits, L.B_bits, L.a, L.m, L.b)
+        keep = np.sort(np.random.default_rng(I.seed_for(4, 77)).choice(k, size=k2, replace=False)).astype(np.int32)
+        times = []
+        for _ in range(7):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            pruned = B.dbf_prune_middle(layer, keep)
+            times.append(time.perf_counter() - t0)
+            pruned.close()
+        layer.close()
+        moved = 2.0 * k2 * (n_in + n_out) / 8.0
+        ms = float(np.median(times)) * 1e3
+        res["%dx%d_k%d_to_%d" % (n_in, n_out, k, k2)] = {
+            "ms_per_call": round(ms, 3), "sign_bytes_moved": moved, "GBps_whole_call": round(moved / (ms * 1e-3) / 1e9, 1),
+            "note": "whole synchronous call incl. device allocation and plan upload; kernel times: profiles/prune_middle.txt"}
+    return res
 
 
 def isolated_latency(B, torch, np, layer, xs, ys, batch, stream, kind):

@@ -176,6 +176,19 @@ int dbf_gemm(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
 int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
                   void* workspace_dev, size_t workspace_bytes, int kind, void* hip_stream);
 
+/* ---- middle-channel pruning (paper, section 3.5 "Nonuniform layer compression ratios") ------
+ * The paper treats the middle dimension as channels and keeps those with the highest scores
+ * (the scores need gradients and are the caller's business).  dbf_prune_middle makes the new,
+ * smaller layer on the device, in the packed tile layout, without unpacking:
+ *     A' = A[:, keep],  B' = B[keep, :],  m' = m[keep],  a' = a,  b' = b,   k' = n_keep,
+ * i.e. W'_new = sum over kept j of m_j A[:,j] B[j,:] (the old W' with the dropped m_j set to 0).
+ * keep: HOST array of n_keep middle indices, strictly increasing, each in [0, k); 1 <= n_keep <= k.
+ * The current device must be the layer's.  *out is a new, independent layer (free it with
+ * dbf_free; the old layer is untouched).  Synchronous: allocates, runs the gather kernels and
+ * returns when they have finished.  Errors: DBF_EINVAL (null, bad or unsorted indices, wrong
+ * device), DBF_ENOMEM, DBF_EHIP. */
+int dbf_prune_middle(const dbf_layer* layer, const int32_t* keep, int n_keep, dbf_layer** out);
+
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
  * benchmark stream of layers): the B and A stages of all layers run in one launch (two for

@@ -28,7 +28,7 @@ EXPORTS = [
     "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
     "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
-    "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
+    "dbf_prune_middle", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
 ]
 
 _lib = None
@@ -77,6 +77,7 @@ def lib() -> C.CDLL:
     L.dbf_stack_gemv_timed.argtypes = [vp, vp, vp, i32, i32, vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]
     L.dbf_stack_free.argtypes = [vp]
     L.dbf_stack_free.restype = None
+    L.dbf_prune_middle.argtypes = [vp, vp, i32, pp]
     L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
     L.dbf_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp, C.POINTER(C.c_double)]
     L.dbf_strerror.argtypes = [i32]
@@ -184,6 +185,14 @@ def dbf_pack_bits(n_in: int, n_out: int, k: int, A_bits, B_bits, a, m, b) -> Lay
     _check(lib().dbf_pack_bits(n_in, n_out, k, _ptr(A), _ptr(B), _ptr(a), _ptr(m), _ptr(b), C.byref(h)),
            "dbf_pack_bits")
     return Layer(h.value, n_in, n_out, k)
+
+
+def dbf_prune_middle(layer: Layer, keep) -> Layer:
+    """New layer that keeps the middle channels `keep` (strictly increasing indices) of `layer`."""
+    idx = _host(keep, np.int32).reshape(-1)
+    h = C.c_void_p(0)
+    _check(lib().dbf_prune_middle(layer.handle, _ptr(idx), int(idx.size), C.byref(h)), "dbf_prune_middle")
+    return Layer(h.value, layer.n_in, layer.n_out, int(idx.size))
 
 
 def dbf_unpack_bits(layer: Layer):

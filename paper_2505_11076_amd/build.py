@@ -26,6 +26,7 @@ SOURCES = [
     "dbf_gemm_mfma.hip",
     "dbf_gemm_i8.hip",
     "dbf_probe.hip",
+    "dbf_prune.hip",
 ]
 
 FLAGS = [

@@ -268,87 +268,112 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     return DBF_OK;
 }
 
-// Builds the device image of a layer from canonical words and uploads it.
-int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32_t* B_bits,
-                const uint16_t* a, const uint16_t* m, const uint16_t* b, dbf_layer** out) {
-    const size_t bytesA = dbf_tiled_bytes(n_out, k), bytesB = dbf_tiled_bytes(k, n_in);
-    const int rtA = dbf_row_tiles(n_out), rtB = dbf_row_tiles(k);
-    const int a_len = rtA * DBF_TILE_ROWS;
-    const int m_len = rtB * DBF_TILE_ROWS;
-    const int b_len = dbf_col_tiles(n_in) * DBF_TILE_COLS;
-    const int t_stride = m_len;  // >= col_tiles(k)*64, so the A stage may read its padded columns
-
-    // offsets inside the single device block (256-byte aligned sections)
+// Section offsets of a layer's single device block (256-byte aligned sections).
+struct LayerOffsets {
+    size_t A, B, a, m, b, image_bytes, t, total;
+    int a_len, m_len, b_len, t_stride;
+};
+LayerOffsets layer_offsets(int n_in, int n_out, int k) {
+    LayerOffsets o;
+    o.a_len = dbf_row_tiles(n_out) * DBF_TILE_ROWS;
+    o.m_len = dbf_row_tiles(k) * DBF_TILE_ROWS;
+    o.b_len = dbf_col_tiles(n_in) * DBF_TILE_COLS;
+    o.t_stride = o.m_len;  // >= col_tiles(k)*64, so the A stage may read its padded columns
     size_t off = 0;
-    const size_t offA = off;  off = align_up(off + bytesA, 256);
-    const size_t offB = off;  off = align_up(off + bytesB, 256);
-    const size_t offa = off;  off = align_up(off + 2 * (size_t)a_len, 256);
-    const size_t offm = off;  off = align_up(off + 2 * (size_t)m_len, 256);
-    const size_t offb = off;  off = align_up(off + 2 * (size_t)b_len, 256);
-    const size_t image_bytes = off;  // everything up to here is uploaded
-    const size_t offt = off;  off = align_up(off + 4 * (size_t)DBF_MAX_BATCH * t_stride, 256);
-    const size_t total = off;
+    o.A = off;  off = align_up(off + dbf_tiled_bytes(n_out, k), 256);
+    o.B = off;  off = align_up(off + dbf_tiled_bytes(k, n_in), 256);
+    o.a = off;  off = align_up(off + 2 * (size_t)o.a_len, 256);
+    o.m = off;  off = align_up(off + 2 * (size_t)o.m_len, 256);
+    o.b = off;  off = align_up(off + 2 * (size_t)o.b_len, 256);
+    o.image_bytes = off;  // signs and vectors; the scratch follows
+    o.t = off;  off = align_up(off + 4 * (size_t)DBF_MAX_BATCH * o.t_stride, 256);
+    o.total = off;
+    return o;
+}
 
-    uint8_t* image = static_cast<uint8_t*>(std::calloc(image_bytes, 1));
+// Allocates the device block of a layer of the given shape on the current device and describes it
+// (pointers, stages); the contents are left to the caller except the scratch, which is zeroed.
+int create_layer(int n_in, int n_out, int k, const LayerOffsets& o, dbf_layer** out) {
     dbf_layer* L = new (std::nothrow) dbf_layer();
-    if (!image || !L) {
-        std::free(image);
-        delete L;
-        return DBF_ENOMEM;
-    }
-    int rc = dbf_tile_host(n_out, k, A_bits, image + offA);
-    if (rc == DBF_OK) rc = dbf_tile_host(k, n_in, B_bits, image + offB);
-    if (rc != DBF_OK) {
-        std::free(image);
-        delete L;
-        return rc;
-    }
-    std::memcpy(image + offa, a, 2 * (size_t)n_out);
-    std::memcpy(image + offm, m, 2 * (size_t)k);
-    std::memcpy(image + offb, b, 2 * (size_t)n_in);
-
+    if (!L) return DBF_ENOMEM;
     void* dev = nullptr;
     int device = 0;
-    if (hipGetDevice(&device) != hipSuccess || hipMalloc(&dev, total) != hipSuccess) {
+    if (hipGetDevice(&device) != hipSuccess || hipMalloc(&dev, o.total) != hipSuccess) {
         (void)hipGetLastError();
-        std::free(image);
+        delete L;
+        return DBF_EHIP;
+    }
+    if (hipMemset(static_cast<uint8_t*>(dev) + o.t, 0, o.total - o.t) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(dev);
         delete L;
         return DBF_EHIP;
     }
     uint8_t* d = static_cast<uint8_t*>(dev);
     L->n_in = n_in;  L->n_out = n_out;  L->k = k;  L->device = device;
-    L->dev_block = dev;  L->device_bytes = total;
-    L->dA = d + offA;  L->dB = d + offB;
-    L->da = reinterpret_cast<uint16_t*>(d + offa);
-    L->dm = reinterpret_cast<uint16_t*>(d + offm);
-    L->db = reinterpret_cast<uint16_t*>(d + offb);
-    L->dt = reinterpret_cast<float*>(d + offt);
-    L->t_stride = t_stride;
+    L->dev_block = dev;  L->device_bytes = o.total;
+    L->dA = d + o.A;  L->dB = d + o.B;
+    L->da = reinterpret_cast<uint16_t*>(d + o.a);
+    L->dm = reinterpret_cast<uint16_t*>(d + o.m);
+    L->db = reinterpret_cast<uint16_t*>(d + o.b);
+    L->dt = reinterpret_cast<float*>(d + o.t);
+    L->t_stride = o.t_stride;
 
     DbfStage& sb = L->h_stages[0];
     sb.bits = L->dB;  sb.in_scale = L->db;  sb.row_scale = L->dm;  sb.t = L->dt;
     sb.x_off = 0;  sb.y_off = 0;
-    sb.n_rt = rtB;  sb.n_ct = dbf_col_tiles(n_in);
-    sb.rows = k;  sb.cols = n_in;  sb.t_stride = t_stride;  sb.pad_ = 0;
+    sb.n_rt = dbf_row_tiles(k);  sb.n_ct = dbf_col_tiles(n_in);
+    sb.rows = k;  sb.cols = n_in;  sb.t_stride = o.t_stride;  sb.pad_ = 0;
     DbfStage& sa = L->h_stages[1];
     sa.bits = L->dA;  sa.in_scale = nullptr;  sa.row_scale = L->da;  sa.t = L->dt;
     sa.x_off = 0;  sa.y_off = 0;
-    sa.n_rt = rtA;  sa.n_ct = dbf_col_tiles(k);
-    sa.rows = n_out;  sa.cols = k;  sa.t_stride = t_stride;  sa.pad_ = 0;
+    sa.n_rt = dbf_row_tiles(n_out);  sa.n_ct = dbf_col_tiles(k);
+    sa.rows = n_out;  sa.cols = k;  sa.t_stride = o.t_stride;  sa.pad_ = 0;
+    *out = L;
+    return DBF_OK;
+}
 
-    hipError_t e = hipMemcpy(dev, image, image_bytes, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemset(d + offt, 0, total - offt);
+// The launch plan of a layer alone: one row tile per workgroup gives the most parallelism.
+int finish_layer(dbf_layer* L) {
+    std::vector<DbfStage> vB(1, L->h_stages[0]), vA(1, L->h_stages[1]);
+    return build_plan(vB, vA, std::vector<int>(1, 1), std::vector<int>(1, 1), &L->plan);
+}
+
+void destroy_layer(dbf_layer* L) {
+    if (!L) return;
+    free_plan(L->plan);
+    if (L->dev_block) (void)hipFree(L->dev_block);
+    delete L;
+}
+
+// Builds the device image of a layer from canonical words and uploads it.
+int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32_t* B_bits,
+                const uint16_t* a, const uint16_t* m, const uint16_t* b, dbf_layer** out) {
+    const LayerOffsets o = layer_offsets(n_in, n_out, k);
+    uint8_t* image = static_cast<uint8_t*>(std::calloc(o.image_bytes, 1));
+    if (!image) return DBF_ENOMEM;
+    int rc = dbf_tile_host(n_out, k, A_bits, image + o.A);
+    if (rc == DBF_OK) rc = dbf_tile_host(k, n_in, B_bits, image + o.B);
+    if (rc != DBF_OK) {
+        std::free(image);
+        return rc;
+    }
+    std::memcpy(image + o.a, a, 2 * (size_t)n_out);
+    std::memcpy(image + o.m, m, 2 * (size_t)k);
+    std::memcpy(image + o.b, b, 2 * (size_t)n_in);
+
+    dbf_layer* L = nullptr;
+    rc = create_layer(n_in, n_out, k, o, &L);
+    if (rc != DBF_OK) {
+        std::free(image);
+        return rc;
+    }
+    hipError_t e = hipMemcpy(L->dev_block, image, o.image_bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     std::free(image);
-    if (e == hipSuccess) {
-        // a single layer runs alone: one row tile per workgroup gives the most parallelism
-        std::vector<DbfStage> vB(1, sb), vA(1, sa);
-        if (build_plan(vB, vA, std::vector<int>(1, 1), std::vector<int>(1, 1), &L->plan) != DBF_OK) e = hipErrorOutOfMemory;
-    }
-    if (e != hipSuccess) {
+    if (e != hipSuccess || finish_layer(L) != DBF_OK) {
         (void)hipGetLastError();
-        (void)hipFree(dev);
-        delete L;
+        destroy_layer(L);
         return DBF_EHIP;
     }
     *out = L;
@@ -533,11 +558,37 @@ int dbf_dims(const dbf_layer* L, int* n_in, int* n_out, int* k, size_t* device_b
     return DBF_OK;
 }
 
-void dbf_free(dbf_layer* L) {
-    if (!L) return;
-    free_plan(L->plan);
-    if (L->dev_block) (void)hipFree(L->dev_block);
-    delete L;
+void dbf_free(dbf_layer* L) { destroy_layer(L); }
+
+int dbf_prune_middle(const dbf_layer* L, const int32_t* keep, int n_keep, dbf_layer** out) {
+    if (out) *out = nullptr;
+    if (!L || !keep || !out || n_keep < 1 || n_keep > L->k) return DBF_EINVAL;
+    for (int i = 0; i < n_keep; ++i)
+        if (keep[i] < 0 || keep[i] >= L->k || (i > 0 && keep[i] <= keep[i - 1])) return DBF_EINVAL;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) {
+        (void)hipGetLastError();
+        return DBF_EHIP;
+    }
+    if (device != L->device) return DBF_EINVAL;  // the new layer lives where the old one does
+
+    dbf_layer* N = nullptr;
+    const LayerOffsets o = layer_offsets(L->n_in, L->n_out, n_keep);
+    int rc = create_layer(L->n_in, L->n_out, n_keep, o, &N);
+    if (rc != DBF_OK) return rc;
+    int* keep_dev = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&keep_dev), sizeof(int) * (size_t)n_keep);
+    if (e == hipSuccess) e = hipMemcpy(keep_dev, keep, sizeof(int) * (size_t)n_keep, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = dbf_prune_launch(L, N, keep_dev, n_keep, nullptr);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (keep_dev) (void)hipFree(keep_dev);
+    if (e != hipSuccess || finish_layer(N) != DBF_OK) {
+        (void)hipGetLastError();
+        destroy_layer(N);
+        return DBF_EHIP;
+    }
+    *out = N;
+    return DBF_OK;
 }
 
 int dbf_gemv_kind(const dbf_layer* L, const void* x_dev, void* y_dev, int batch, int kind,

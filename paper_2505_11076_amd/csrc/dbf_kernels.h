@@ -51,4 +51,9 @@ size_t dbf_gemm_i8_workspace_bytes(const dbf_layer* L, int T);
 hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
                               hipStream_t stream);
 
+// Middle-channel pruning: fills the sign tiles and vectors of `dst` (a freshly created layer with
+// k = n_keep on the same device) from `src` and the kept middle indices keep_dev (device, increasing,
+// each < src->k).  Queued on `stream`.
+hipError_t dbf_prune_launch(const dbf_layer* src, dbf_layer* dst, const int* keep_dev, int n_keep, hipStream_t stream);
+
 #endif  // DBF_KERNELS_H

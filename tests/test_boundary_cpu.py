@@ -177,6 +177,7 @@ def test_launch_argument_errors():
     assert lib.dbf_stack_create(arr, 1, C.byref(h)) == B.DBF_EINVAL
     assert lib.dbf_stack_create(arr, 0, C.byref(h)) == B.DBF_EINVAL
     assert lib.dbf_stack_create_grouped(None, 1, None, 0, C.byref(h)) == B.DBF_EINVAL
+    assert lib.dbf_prune_middle(None, None, 1, C.byref(h)) == B.DBF_EINVAL
     assert lib.dbf_stack_create_grouped(arr, 1, None, 0, C.byref(h)) == B.DBF_EINVAL
     assert lib.dbf_stack_gemv(None, 1, 1, 1, 0, None) == B.DBF_EINVAL
     assert lib.dbf_stack_offsets(None, 0, 1, None, None) == B.DBF_EINVAL
