@@ -21,8 +21,9 @@ sum of outer products on tiny shapes (exhaustive for <= 2x2x2), all-ones
 closed form, pure-Python fsum re-evaluation, invariances of the middle index,
 variance law for random signs, packing round trip, the bits-per-weight
 numbers the paper prints; the sampled-rows variant against the dense one; pruning of middle
-channels against zeroing their scales and against a per-entry loop.  No function here is
-"parity unpinned".
+channels against zeroing their scales and against a per-entry loop; the SVID projection
+against the singular value decomposition it converges to, exact rank-one inputs and its
+fixed point.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -174,6 +175,41 @@ def prune_middle(A_words, B_words, m_f16_bits, n_out: int, k: int, n_in: int, ke
     B = unpack_signs(B_words, k, n_in)
     m = np.ascontiguousarray(m_f16_bits, dtype=np.uint16).reshape(-1)
     return pack_signs(A[:, keep]), pack_signs(B[keep, :]), m[keep].copy(), int(keep.size)
+
+
+# ---------------------------------------------------------------------------
+# SVID projection (section 3.2, "Computing Double Binary Factorization")
+# ---------------------------------------------------------------------------
+
+
+def svid(Z, iters: int):
+    """SVID(Z) = a . Sign(Z) . m^T with a m^T the rank-1 decomposition of |Z| by power iteration.
+
+    The paper's steps, in its order: Z_pm1 = Sign(Z); rank-1 decomposition of |Z| "using power
+    iteration"; SVID(Z) = a . Z_pm1 . m^T.  What the paper leaves open, and the reading taken:
+      * Sign(0) = +1 (a sign matrix has entries from {-1, +1} only);
+      * the iteration starts from the constant unit vector v = 1/sqrt(cols) and runs `iters` rounds of
+        u <- |Z| v / ||.||,  v <- |Z|^T u,  sigma <- ||v||,  v <- v / sigma;
+      * the singular value goes to the left factor: a = sigma u, m = v (only the product a m^T matters).
+    Returns (S, a, m): S float64 matrix of +-1, a (rows,), m (cols,), all fp64.
+    """
+    Z = np.asarray(Z, dtype=np.float64)
+    if Z.ndim != 2 or iters < 1:
+        raise ValueError("Z must be a matrix and iters >= 1")
+    S = np.where(Z >= 0.0, 1.0, -1.0)
+    M = np.abs(Z)
+    rows, cols = M.shape
+    v = np.full(cols, 1.0 / np.sqrt(cols))
+    u = np.zeros(rows)
+    sigma = 0.0
+    for _ in range(iters):
+        u = M @ v
+        nu = np.sqrt(np.sum(u * u))
+        u = u / nu if nu > 0.0 else u
+        v = M.T @ u
+        sigma = np.sqrt(np.sum(v * v))
+        v = v / sigma if sigma > 0.0 else v
+    return S, sigma * u, v
 
 
 # ---------------------------------------------------------------------------

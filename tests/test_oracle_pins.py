@@ -386,3 +386,59 @@ def test_pruning_identity_and_argument_errors():
     for bad in ([], [3, 3], [5, 2], [-1, 2], [0, 40]):
         with pytest.raises(ValueError):
             O.prune_middle(L.A_bits, L.B_bits, L.m, n_out, k, n_in, bad)
+
+
+# ---------------------------------------------------------------------------
+# SVID projection (section 3.2)
+# ---------------------------------------------------------------------------
+
+
+def test_svid_converges_to_the_top_singular_triple_of_abs_z():
+    """Power iteration on |Z| (all entries positive: a simple, positive top singular pair) must reach
+    what a dense SVD gives: sigma_1 u_1 v_1^T, the best rank-one approximation of |Z|."""
+    rng = np.random.default_rng(5)
+    Z = rng.standard_normal((37, 23))
+    S, a, m = O.svid(Z, iters=60)
+    U, sv, Vt = np.linalg.svd(np.abs(Z))
+    u1, v1 = np.abs(U[:, 0]), np.abs(Vt[0])          # the sign of a singular pair is free; positive here
+    assert np.allclose(np.outer(a, m), sv[0] * np.outer(u1, v1), rtol=0, atol=1e-10 * sv[0])
+    assert abs(np.linalg.norm(m) - 1.0) < 1e-14 and abs(np.linalg.norm(a) - sv[0]) < 1e-10 * sv[0]
+    assert np.array_equal(S, np.where(Z >= 0, 1.0, -1.0))
+    # and it is the best rank-one fit: no nearby rank-one matrix is closer to |Z|
+    best = np.linalg.norm(np.abs(Z) - np.outer(a, m))
+    for _ in range(20):
+        a2 = a * (1 + 0.05 * rng.standard_normal(a.shape))
+        m2 = m * (1 + 0.05 * rng.standard_normal(m.shape))
+        assert np.linalg.norm(np.abs(Z) - np.outer(a2, m2)) >= best
+
+
+def test_svid_is_exact_on_matrices_of_its_own_form():
+    """If Z = p . S . q^T with p, q > 0, then |Z| = p q^T has rank one: one round already gives
+    a m^T = p q^T, and SVID(Z) = Z (the projection keeps the members of its set)."""
+    rng = np.random.default_rng(6)
+    p, q = rng.uniform(0.5, 2.0, 19), rng.uniform(0.5, 2.0, 31)
+    S0 = np.where(rng.random((19, 31)) < 0.5, 1.0, -1.0)
+    Z = p[:, None] * S0 * q[None, :]
+    for iters in (1, 2, 7):
+        S, a, m = O.svid(Z, iters)
+        assert np.array_equal(S, S0)
+        assert np.allclose(np.outer(a, m), np.outer(p, q), rtol=1e-13, atol=0)
+        assert np.allclose(a[:, None] * S * m[None, :], Z, rtol=1e-13, atol=0)
+
+
+def test_svid_first_round_by_hand_and_the_sign_of_zero():
+    """One round written out with scalar loops: v0 = 1/sqrt(cols); u = |Z| v0 normalised; v = |Z|^T u;
+    sigma = |v|.  Zero entries get the sign +1."""
+    Z = np.array([[1.0, -2.0, 0.0], [-3.0, 4.0, -0.0]])
+    S, a, m = O.svid(Z, 1)
+    assert np.array_equal(S, np.array([[1.0, -1.0, 1.0], [-1.0, 1.0, 1.0]]))
+    v0 = 1.0 / math.sqrt(3.0)
+    u = [(1.0 + 2.0 + 0.0) * v0, (3.0 + 4.0 + 0.0) * v0]
+    nu = math.sqrt(u[0] ** 2 + u[1] ** 2)
+    u = [u[0] / nu, u[1] / nu]
+    v = [1.0 * u[0] + 3.0 * u[1], 2.0 * u[0] + 4.0 * u[1], 0.0]
+    sigma = math.sqrt(sum(x * x for x in v))
+    assert np.allclose(a, [sigma * u[0], sigma * u[1]], rtol=1e-15)
+    assert np.allclose(m, [x / sigma for x in v], rtol=1e-15)
+    with pytest.raises(ValueError):
+        O.svid(Z, 0)
