@@ -69,6 +69,8 @@ def main():
                          "(Llama-3 shapes, 1 / 1.5 / 2 / 2.3 bits per weight), isolated latency and streamed rate")
     ap.add_argument("--prune", action="store_true",
                     help="only the middle-channel pruning measurement (dbf_prune_middle on two config-4 shaped layers)")
+    ap.add_argument("--svid", action="store_true",
+                    help="only the SVID projection measurement (dbf_svid on a 4096 x 4096 and an 11008 x 4096 matrix)")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -97,6 +99,9 @@ def main():
         return
     if args.prune:
         print(json.dumps({"prune_middle": prune_bench(B, I, torch, np)}))
+        return
+    if args.svid:
+        print(json.dumps({"svid": svid_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
         return
     if args.table4:
         print(json.dumps({"table4": table4_bench(B, I, torch, np, args.batch, kind,
@@ -425,6 +430,43 @@ def prune_bench(B, I, torch, np):
         res["%dx%d_k%d_to_%d" % (n_in, n_out, k, k2)] = {
             "ms_per_call": round(ms, 3), "sign_bytes_moved": moved, "GBps_whole_call": round(moved / (ms * 1e-3) / 1e9, 1),
             "note": "whole synchronous call incl. device allocation and plan upload; kernel times: profiles/prune_middle.txt"}
+    return res
+
+
+def svid_bench(B, I, torch, np, stream, iters=8):
+    """dbf_svid (signs + `iters` rounds of power iteration) on two factor-sized fp32 matrices.  Bytes:
+    Z is read once for the signs and twice per round (row dots, column dots); the packed signs and
+    the vectors are negligible next to it."""
+    res = {}
+    for rows, cols in ((4096, 4096), (11008, 4096)):
+        Z = I.make_svid_matrix(rows, cols, I.seed_for(8, rows))
+        z = torch.from_numpy(Z).cuda()
+        a = torch.zeros(rows, dtype=torch.float32, device="cuda")
+        m = torch.zeros(cols, dtype=torch.float32, device="cuda")
+        bits = torch.zeros(B.dbf_tiled_bytes(rows, cols), dtype=torch.uint8, device="cuda")
+        wsb = B.dbf_svid_workspace_bytes(rows, cols)
+        ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+        args = (z.data_ptr(), rows, cols, iters, a.data_ptr(), m.data_ptr(), bits.data_ptr(), ws.data_ptr(), wsb, stream)
+        for _ in range(5):
+            B.dbf_svid(*args)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 20
+        e0.record()
+        for _ in range(n):
+            B.dbf_svid(*args)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        nbytes = (2.0 * iters + 1.0) * rows * cols * 4.0
+        t0 = time.time()
+        from oracle import dbf_oracle as O
+        O.svid(Z.astype(np.float64), iters)
+        cpu_s = time.time() - t0
+        res["%dx%d_iters%d" % (rows, cols, iters)] = {
+            "ms_per_call": round(ms, 4), "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "cpu_oracle_s": round(cpu_s, 3)}
     return res
 
 

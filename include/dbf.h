@@ -189,6 +189,24 @@ int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
  * device), DBF_ENOMEM, DBF_EHIP. */
 int dbf_prune_middle(const dbf_layer* layer, const int32_t* keep, int n_keep, dbf_layer** out);
 
+/* ---- SVID projection (paper, section 3.2 "Computing Double Binary Factorization") ------------
+ * SVID(Z) = a . Sign(Z) . m^T, with a m^T the rank-one decomposition of |Z| by power iteration:
+ * the projection step of the ADMM iteration that computes the factorisation.  Readings where the
+ * paper is silent: Sign(0) = +1; the iteration starts from the constant unit vector and runs
+ * `iters` (>= 1) rounds of  u <- |Z| v / ||.||,  v <- |Z|^T u,  sigma <- ||v||,  v <- v / sigma;
+ * a = sigma u, m = v (so ||m|| = 1).
+ *   Z_dev:    device, fp32 [rows][cols] row major (read only); NaNs are not supported.
+ *   a_dev:    device, fp32 [rows] out;   m_dev: device, fp32 [cols] out (also used as the iterate).
+ *   bits_dev: device, dbf_tiled_bytes(rows, cols) bytes out: Sign(Z) in the tile layout of this
+ *             library (dbf_untile_host turns a host copy into canonical words), padding bits zero.
+ *   workspace_dev: device, 256-byte aligned, >= dbf_svid_workspace_bytes(rows, cols) bytes.
+ * Asynchronous on hip_stream, allocates nothing; all reductions have a fixed order (results do not
+ * depend on scheduling).  Errors: DBF_EINVAL (null / misaligned pointers, sizes out of range,
+ * iters < 1), DBF_EWORKSPACE, DBF_EHIP. */
+size_t dbf_svid_workspace_bytes(int rows, int cols); /* 0 if the sizes are out of range */
+int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* a_dev, void* m_dev, void* bits_dev,
+             void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
  * benchmark stream of layers): the B and A stages of all layers run in one launch (two for

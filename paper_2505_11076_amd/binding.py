@@ -28,7 +28,7 @@ EXPORTS = [
     "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
     "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
-    "dbf_prune_middle", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
+    "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
 ]
 
 _lib = None
@@ -78,6 +78,9 @@ def lib() -> C.CDLL:
     L.dbf_stack_free.argtypes = [vp]
     L.dbf_stack_free.restype = None
     L.dbf_prune_middle.argtypes = [vp, vp, i32, pp]
+    L.dbf_svid_workspace_bytes.argtypes = [i32, i32]
+    L.dbf_svid_workspace_bytes.restype = sz
+    L.dbf_svid.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
     L.dbf_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp, C.POINTER(C.c_double)]
     L.dbf_strerror.argtypes = [i32]
@@ -193,6 +196,15 @@ def dbf_prune_middle(layer: Layer, keep) -> Layer:
     h = C.c_void_p(0)
     _check(lib().dbf_prune_middle(layer.handle, _ptr(idx), int(idx.size), C.byref(h)), "dbf_prune_middle")
     return Layer(h.value, layer.n_in, layer.n_out, int(idx.size))
+
+
+def dbf_svid_workspace_bytes(rows: int, cols: int) -> int:
+    return int(lib().dbf_svid_workspace_bytes(rows, cols))
+
+
+def dbf_svid(z_ptr: int, rows: int, cols: int, iters: int, a_ptr: int, m_ptr: int, bits_ptr: int, ws_ptr: int,
+             ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().dbf_svid(z_ptr, rows, cols, iters, a_ptr, m_ptr, bits_ptr, ws_ptr, ws_bytes, stream), "dbf_svid")
 
 
 def dbf_unpack_bits(layer: Layer):

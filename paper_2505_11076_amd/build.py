@@ -27,6 +27,7 @@ SOURCES = [
     "dbf_gemm_i8.hip",
     "dbf_probe.hip",
     "dbf_prune.hip",
+    "dbf_svid.hip",
 ]
 
 FLAGS = [

@@ -1,0 +1,234 @@
+// SVID projection (paper, section 3.2): SVID(Z) = a . Sign(Z) . m^T, where a m^T is the rank-one
+// decomposition of |Z| obtained by power iteration.  It is the projection step of the ADMM iteration
+// that computes the factorisation; here it produces the sign matrix directly in the packed device
+// tile layout of this library (what a layer stores), and the two scale vectors in fp32.
+//
+// Readings of what the paper leaves open (the same as the CPU oracle's): Sign(0) = +1; the iteration
+// starts from the constant unit vector and runs `iters` rounds of
+//     u <- |Z| v / ||.||,   v <- |Z|^T u,   sigma <- ||v||,   v <- v / sigma;      a = sigma u,  m = v.
+//
+// Everything is bound by reading Z (fp32, rows x cols, row major): two passes per round (row dots,
+// column dots) and one for the signs.  All reductions have a fixed order, so the result does not
+// depend on scheduling:
+//   row dots     one wavefront per row, 16-byte loads, butterfly reduction;
+//   column dots  workgroup = 256 columns x 64 rows (4 row lanes x 16 rows, combined in LDS in lane
+//                order), partial sums per 64-row chunk, then summed over the chunks in a fixed order;
+//   norms        one workgroup, strided partial sums combined in a fixed tree;
+//   signs        one workgroup per 128 x 64 tile, a thread per four bytes of the tile.
+#include "dbf_kernels.h"
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int COL_CHUNK_ROWS = 64;   // rows per partial sum of the column pass
+constexpr int COL_BLOCK = 256;       // columns per workgroup of the column pass
+
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// u[i] = sum_j |Z[i][j]| v[j]
+__global__ __launch_bounds__(256) void dbf_svid_row_dots_kernel(const float* __restrict__ Z, int rows, int cols,
+                                                               const float* __restrict__ v, float* __restrict__ u,
+                                                               int vec_ok) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float* z = Z + (size_t)row * cols;
+    float s = 0.f;
+    if (vec_ok) {
+        for (int c = 4 * lane; c < cols; c += 256) {
+            const v4f a = *reinterpret_cast<const v4f*>(z + c), b = *reinterpret_cast<const v4f*>(v + c);
+            s += fabsf(a.x) * b.x + fabsf(a.y) * b.y + fabsf(a.z) * b.z + fabsf(a.w) * b.w;
+        }
+    } else {
+        for (int c = lane; c < cols; c += 64) s += fabsf(z[c]) * v[c];
+    }
+    s = wave_sum_f(s);
+    if (lane == 0) u[row] = s;
+}
+
+// partial[chunk][j] = sum over the chunk's rows i of |Z[i][j]| u[i]
+__global__ __launch_bounds__(256) void dbf_svid_col_dots_kernel(const float* __restrict__ Z, int rows, int cols,
+                                                               const float* __restrict__ u,
+                                                               float* __restrict__ partial) {
+    __shared__ float part[4][COL_BLOCK];
+    const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;       // column quad, row lane
+    const int col = blockIdx.x * COL_BLOCK + 4 * cl;
+    const int row0 = blockIdx.y * COL_CHUNK_ROWS;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    const bool vec = (cols & 3) == 0 && col + 4 <= cols;
+    if (vec) {
+        // rows beyond the matrix are read as the last row with weight zero: no branch in the loop, so
+        // the loads of several rounds are in flight together
+#pragma unroll
+        for (int i = rl; i < COL_CHUNK_ROWS; i += 4) {
+            const int row = row0 + i;
+            const int rc = min(row, rows - 1);
+            const float w = row < rows ? u[rc] : 0.f;
+            const v4f a = *reinterpret_cast<const v4f*>(Z + (size_t)rc * cols + col);
+            s[0] += fabsf(a.x) * w;  s[1] += fabsf(a.y) * w;  s[2] += fabsf(a.z) * w;  s[3] += fabsf(a.w) * w;
+        }
+    } else {
+        for (int i = rl; i < COL_CHUNK_ROWS; i += 4) {
+            const int row = row0 + i;
+            if (row >= rows) break;
+            const float w = u[row];
+            const float* z = Z + (size_t)row * cols + col;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (col + q < cols) s[q] += fabsf(z[q]) * w;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) part[rl][4 * cl + q] = s[q];
+    __syncthreads();
+    const int c = threadIdx.x;
+    if (blockIdx.x * COL_BLOCK + c < cols)
+        partial[(size_t)blockIdx.y * cols + blockIdx.x * COL_BLOCK + c] = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+}
+
+// v[j] = sum over chunks of partial[chunk][j]: four interleaved running sums (chunks c = 0, 4, 8, ... in the
+// first, and so on; the loads of a round are independent), combined as ((s0 + s1) + s2) + s3.
+// 64 threads per workgroup, so that even 4096 columns spread over 64 compute units.
+__global__ __launch_bounds__(64) void dbf_svid_col_reduce_kernel(const float* __restrict__ partial, int chunks, int cols,
+                                                              float* __restrict__ v) {
+    const int j = blockIdx.x * 64 + threadIdx.x;
+    if (j >= cols) return;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int c = 0;
+    for (; c + 4 <= chunks; c += 4) {
+        s0 += partial[(size_t)(c + 0) * cols + j];
+        s1 += partial[(size_t)(c + 1) * cols + j];
+        s2 += partial[(size_t)(c + 2) * cols + j];
+        s3 += partial[(size_t)(c + 3) * cols + j];
+    }
+    if (c + 0 < chunks) s0 += partial[(size_t)(c + 0) * cols + j];
+    if (c + 1 < chunks) s1 += partial[(size_t)(c + 1) * cols + j];
+    if (c + 2 < chunks) s2 += partial[(size_t)(c + 2) * cols + j];
+    v[j] = ((s0 + s1) + s2) + s3;
+}
+
+// x <- x / ||x||, *norm = ||x|| (x unchanged if the norm is zero).  One workgroup of 1024 threads.
+__global__ __launch_bounds__(1024) void dbf_svid_normalise_kernel(float* __restrict__ x, int len, float* __restrict__ norm) {
+    __shared__ float part[1024];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < len; i += 1024) s += x[i] * x[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 512; w >= 1; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    const float nrm = sqrtf(part[0]);
+    if (threadIdx.x == 0) *norm = nrm;
+    if (nrm > 0.f)
+        for (int i = threadIdx.x; i < len; i += 1024) x[i] = x[i] / nrm;
+}
+
+__global__ void dbf_svid_fill_kernel(float* __restrict__ x, int len, float value) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < len) x[i] = value;
+}
+
+// a[i] = sigma u[i]
+__global__ void dbf_svid_scale_kernel(const float* __restrict__ u, const float* __restrict__ sigma, int len, float* __restrict__ a) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < len) a[i] = *sigma * u[i];
+}
+
+// Sign(Z) into the tile layout: tile = 128 rows x 64 columns, byte 256 g + 16 r + j, bit s = sign of
+// (row 16 s + r, column 16 g + j), a set bit meaning +1.  Thread t makes bytes 4t .. 4t+3.
+__global__ __launch_bounds__(256) void dbf_svid_signs_kernel(const float* __restrict__ Z, int rows, int cols, int n_ct,
+                                                            uint8_t* __restrict__ bits) {
+    const int t = threadIdx.x;
+    const int g = t >> 6, r = (t >> 2) & 15, j0 = 4 * (t & 3);
+    const int col = blockIdx.x * DBF_TILE_COLS + 16 * g + j0;
+    const bool vec = (cols & 3) == 0 && col + 4 <= cols;
+    unsigned out = 0;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int row = blockIdx.y * DBF_TILE_ROWS + 16 * s + r;
+        if (row >= rows) continue;
+        const float* z = Z + (size_t)row * cols + col;
+        if (vec) {
+            const v4f a = *reinterpret_cast<const v4f*>(z);
+            out |= (unsigned)(a.x >= 0.f) << s;
+            out |= (unsigned)(a.y >= 0.f) << (8 + s);
+            out |= (unsigned)(a.z >= 0.f) << (16 + s);
+            out |= (unsigned)(a.w >= 0.f) << (24 + s);
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (col + q < cols) out |= (unsigned)(z[q] >= 0.f) << (8 * q + s);
+        }
+    }
+    reinterpret_cast<unsigned*>(bits + ((size_t)blockIdx.y * n_ct + blockIdx.x) * DBF_TILE_BYTES)[t] = out;
+}
+
+inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+struct SvidWorkspace {
+    size_t u, v, partial, scalars, total;
+};
+inline SvidWorkspace svid_workspace(int rows, int cols) {
+    SvidWorkspace w;
+    const size_t chunks = ((size_t)rows + COL_CHUNK_ROWS - 1) / COL_CHUNK_ROWS;
+    size_t off = 0;
+    w.u = off;        off = up256(off + 4 * (size_t)rows);
+    w.v = off;        off = up256(off + 4 * (size_t)cols);
+    w.partial = off;  off = up256(off + 4 * chunks * (size_t)cols);
+    w.scalars = off;  off = up256(off + 16);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" size_t dbf_svid_workspace_bytes(int rows, int cols) {
+    if (rows < 1 || cols < 1 || rows > DBF_MAX_DIM || cols > DBF_MAX_DIM) return 0;
+    return svid_workspace(rows, cols).total;
+}
+
+extern "C" int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* a_dev, void* m_dev, void* bits_dev,
+                        void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    if (!Z_dev || !a_dev || !m_dev || !bits_dev || rows < 1 || cols < 1 || iters < 1) return DBF_EINVAL;
+    if (rows > DBF_MAX_DIM || cols > DBF_MAX_DIM) return DBF_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(Z_dev) & 3) || (reinterpret_cast<uintptr_t>(a_dev) & 3) ||
+        (reinterpret_cast<uintptr_t>(m_dev) & 3) || (reinterpret_cast<uintptr_t>(bits_dev) & 3))
+        return DBF_EINVAL;
+    const SvidWorkspace w = svid_workspace(rows, cols);
+    if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) || workspace_bytes < w.total)
+        return DBF_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const float* Z = static_cast<const float*>(Z_dev);
+    uint8_t* base = static_cast<uint8_t*>(workspace_dev);
+    float* u = reinterpret_cast<float*>(base + w.u);
+    float* v = static_cast<float*>(m_dev);   // the right factor is iterated in place in the caller's buffer
+    float* partial = reinterpret_cast<float*>(base + w.partial);
+    float* nrm_u = reinterpret_cast<float*>(base + w.scalars);
+    float* sigma = nrm_u + 1;
+    const int vec_ok = ((cols & 3) == 0 && (reinterpret_cast<uintptr_t>(Z_dev) & 15) == 0 &&
+                        (reinterpret_cast<uintptr_t>(m_dev) & 15) == 0) ? 1 : 0;
+    const int chunks = (rows + COL_CHUNK_ROWS - 1) / COL_CHUNK_ROWS;
+    const int n_rt = dbf_row_tiles(rows), n_ct = dbf_col_tiles(cols);
+
+    hipLaunchKernelGGL(dbf_svid_signs_kernel, dim3(n_ct, n_rt), dim3(256), 0, st, Z, rows, cols, n_ct,
+                       static_cast<uint8_t*>(bits_dev));
+    hipLaunchKernelGGL(dbf_svid_fill_kernel, dim3((cols + 255) / 256), dim3(256), 0, st, v, cols,
+                       1.0f / sqrtf((float)cols));
+    for (int it = 0; it < iters; ++it) {
+        hipLaunchKernelGGL(dbf_svid_row_dots_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, Z, rows, cols, v, u, vec_ok);
+        hipLaunchKernelGGL(dbf_svid_normalise_kernel, dim3(1), dim3(1024), 0, st, u, rows, nrm_u);
+        hipLaunchKernelGGL(dbf_svid_col_dots_kernel, dim3((cols + COL_BLOCK - 1) / COL_BLOCK, chunks), dim3(256), 0, st,
+                           Z, rows, cols, u, partial);
+        hipLaunchKernelGGL(dbf_svid_col_reduce_kernel, dim3((cols + 63) / 64), dim3(64), 0, st, partial, chunks, cols, v);
+        hipLaunchKernelGGL(dbf_svid_normalise_kernel, dim3(1), dim3(1024), 0, st, v, cols, sigma);
+    }
+    hipLaunchKernelGGL(dbf_svid_scale_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, u, sigma, rows,
+                       static_cast<float*>(a_dev));
+    if (hipGetLastError() != hipSuccess) return DBF_EHIP;
+    return DBF_OK;
+}

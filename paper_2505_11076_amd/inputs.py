@@ -106,6 +106,20 @@ CONFIG4 = [                                                      # prefill shape
 ]
 
 
+def make_svid_matrix(rows: int, cols: int, seed: int) -> np.ndarray:
+    """Input of the SVID projection: an unconstrained fp32 matrix as the ADMM iteration produces them
+    (sum of a least-squares solution and a dual variable): i.i.d. N(0, 1), with a sprinkling of exact
+    +0.0 and -0.0 entries so that the sign of zero is exercised."""
+    rng = np.random.default_rng(seed + 700)
+    Z = rng.standard_normal((rows, cols)).astype(np.float32)
+    n_zero = max(2, (rows * cols) // 997)
+    idx = rng.choice(rows * cols, size=n_zero, replace=False)
+    flat = Z.reshape(-1)
+    flat[idx[: n_zero // 2]] = 0.0
+    flat[idx[n_zero // 2:]] = -0.0
+    return Z
+
+
 # Second workload: the layer sizes of the paper's matrix-vector timing table (Table 4: Llama-3
 # shapes, printed as rows x columns of W = n_out x n_in) plus the grouped-query k/v projection
 # 4096 -> 1024, each at the table's four sizes in bits per weight.  The middle size follows the

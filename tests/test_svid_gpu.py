@@ -1,0 +1,79 @@
+"""GPU parity of the SVID projection (section 3.2; dbf_svid) against the oracle's svid() on the same
+seeded matrices: Sign(Z) in the packed tile layout must be bit-exact (including +0.0 and -0.0 -> +1 and
+zero padding bits), and the two fp32 factors of the rank-one decomposition of |Z| must agree with the
+fp64 power iteration after the same number of rounds.
+
+Tolerance: every entry of a and m is a sum of up to 4096 non-negative fp32 products followed by a
+normalisation; sequential fp32 summation of n positive terms has relative error at most n * 2^-24
+(2.4e-4 at n = 4096), the tree-shaped parts far less, and the errors of one round enter the next
+through well-conditioned positive sums.  The gate is 2e-4 of the largest entry of each vector."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as G
+from oracle import dbf_oracle as O
+from paper_2505_11076_amd import binding as B
+from paper_2505_11076_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-4
+
+
+def _run(Z, iters):
+    rows, cols = Z.shape
+    z = torch.from_numpy(Z.copy()).cuda()
+    a = torch.full((rows,), float("nan"), dtype=torch.float32, device="cuda")
+    m = torch.full((cols,), float("nan"), dtype=torch.float32, device="cuda")
+    nb = B.dbf_tiled_bytes(rows, cols)
+    bits = torch.full((nb,), 0xA5, dtype=torch.uint8, device="cuda")
+    wsb = B.dbf_svid_workspace_bytes(rows, cols)
+    ws = torch.full((wsb,), 0xA5, dtype=torch.uint8, device="cuda")
+    B.dbf_svid(z.data_ptr(), rows, cols, iters, a.data_ptr(), m.data_ptr(), bits.data_ptr(), ws.data_ptr(), wsb,
+               G.stream_handle())
+    torch.cuda.synchronize()
+    words = B.dbf_untile_host(rows, cols, bits.cpu().numpy())
+    return a.cpu().numpy().astype(np.float64), m.cpu().numpy().astype(np.float64), words
+
+
+@pytest.mark.parametrize("shape", [(512, 256), (100, 77), (130, 1000), (1000, 129), (4096, 2048), (3, 5)])
+@pytest.mark.parametrize("iters", [1, 4])
+def test_svid_matches_the_oracle(shape, iters):
+    rows, cols = shape
+    G.say("start svid %dx%d iters=%d" % (rows, cols, iters))
+    Z = I.make_svid_matrix(rows, cols, I.seed_for(8, rows + cols))
+    S, a_ref, m_ref = O.svid(Z.astype(np.float64), iters)
+    a, m, words = _run(Z, iters)
+    assert np.array_equal(words, O.pack_signs(S)), "sign bits differ"
+    ea = np.max(np.abs(a - a_ref)) / np.max(np.abs(a_ref))
+    em = np.max(np.abs(m - m_ref)) / np.max(np.abs(m_ref))
+    G.say("  rel err a %.2e m %.2e (tol %.0e)" % (ea, em, TOL))
+    assert ea <= TOL and em <= TOL
+    assert abs(np.linalg.norm(m) - 1.0) <= 1e-5
+
+
+def test_svid_reproduces_a_matrix_of_its_own_form():
+    rng = np.random.default_rng(66)
+    p, q = rng.uniform(0.5, 2.0, 300).astype(np.float32), rng.uniform(0.5, 2.0, 520).astype(np.float32)
+    S0 = np.where(rng.random((300, 520)) < 0.5, 1.0, -1.0).astype(np.float32)
+    Z = (p[:, None] * S0 * q[None, :]).astype(np.float32)
+    a, m, words = _run(Z, 2)
+    assert np.array_equal(words, O.pack_signs(S0.astype(np.float64)))
+    back = a[:, None] * S0.astype(np.float64) * m[None, :]
+    assert np.max(np.abs(back - Z.astype(np.float64))) <= 1e-5 * np.max(np.abs(Z))
+
+
+def test_svid_argument_errors():
+    z = torch.zeros((4, 4), dtype=torch.float32, device="cuda")
+    a = torch.zeros(4, dtype=torch.float32, device="cuda")
+    bits = torch.zeros(B.dbf_tiled_bytes(4, 4), dtype=torch.uint8, device="cuda")
+    wsb = B.dbf_svid_workspace_bytes(4, 4)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    assert B.dbf_svid_workspace_bytes(0, 4) == 0
+    ok = (z.data_ptr(), 4, 4, 1, a.data_ptr(), a.data_ptr(), bits.data_ptr(), ws.data_ptr(), wsb, 0)
+    for pos, val in ((0, 0), (1, 0), (3, 0), (4, 0), (6, 0), (7, 0), (8, wsb - 1), (7, ws.data_ptr() + 4)):
+        bad = list(ok)
+        bad[pos] = val
+        with pytest.raises(B.DbfError):
+            B.dbf_svid(*bad)
