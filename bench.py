@@ -175,7 +175,7 @@ def main():
         # One launch does both stages of every layer, so a step IS one kernel: its average
         # duration is taken from the HIP events around the back-to-back timed steps (the
         # per-launch events of the timed entry point add a few microseconds of launch latency).
-        dom, dom_ms, dom_bytes = "dbf_items_mfma_kernel<%d> (B and A stages fused)" % ncg, ms_per_step, bytes_layer * R
+        dom, dom_ms, dom_bytes = "dbf_items_mfma_kernel<%d, false> (B and A stages fused)" % ncg, ms_per_step, bytes_layer * R
     elif msB_avg >= msA_avg:
         dom, dom_ms, dom_bytes = "B-stage launch", msB_avg, bytes_b * R
     else:
@@ -183,7 +183,7 @@ def main():
     if args.kind == "valu":
         dom += " of dbf_stage_valu_kernel"
     elif args.kind == "mfma_split":
-        dom += " of dbf_items_mfma_kernel<%d>" % ncg
+        dom += " of dbf_items_mfma_kernel<%d, false>" % ncg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
