@@ -215,3 +215,15 @@ def test_second_workload_middle_sizes_follow_the_storage_formula():
         n, m, k = cfg["n_out"], cfg["n_in"], cfg["k"]
         assert k == O.middle_dim_for_bits(cfg["bits"], n, m)
         assert O.bits_per_weight(n, m, k) <= cfg["bits"] < O.bits_per_weight(n, m, k + 1)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path uses no collectives: bench.py --gpus N with N > 1 must exit with a message, before it
+    touches a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode == 2
+    assert "one GPU" in res.stderr and res.stdout.strip() == ""
