@@ -663,7 +663,7 @@ int dbf_stack_create_grouped(const dbf_layer* const* layers, int n_layers, const
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
     }
     S->h_x_prefix[n_layers] = x_end;
-    const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", "2"), stack_spans("DBF_STACK_SPAN_A", "4"), &S->plan);
+    const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", "4"), stack_spans("DBF_STACK_SPAN_A", "4"), &S->plan);
     if (rc != DBF_OK) {
         dbf_stack_free(S);
         return rc;

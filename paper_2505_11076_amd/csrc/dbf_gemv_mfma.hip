@@ -65,7 +65,6 @@
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -324,17 +323,7 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // have rows too wide for the one-pass prologue; its input passes keep more loads in flight.  The
 // other instantiation is the hot one (long streams of layers of up to 4096 columns at batch 1)
 // and carries none of that code.
-//
-// W32: the variant on v_mfma_i32_32x32x32_i8.  A vector instruction between two 4-pass matrix
-// instructions costs about ten cycles of matrix-pipe time, and with 32 ANDs and 8 matrix instructions per
-// tile the 16x16x64 kernel is bound by instruction issue, not by HBM (vector ALU 60 % + matrix pipe 31 %
-// busy at 5.7 TB/s); behind the 8-pass instruction the ANDs are hidden.  One instruction takes 32 rows
-// = bit planes 2p and 2p+1 of the 16 tile rows (lane-dependent mask) x 32 columns of a tile, and its 32
-// operand columns hold all 16 batch rows (no second column group).  Lanes c and c^16 of the sign operand
-// need the same 16 bytes, so the tiles do not stay in registers: they are loaded straight into a
-// per-wavefront ring in LDS (global_load_lds_dwordx4, counted by vmcnt like the register ring) and read
-// from there with the duplicated addresses.
-template <int NCG, bool PIECES, bool W32 = false>
+template <int NCG, bool PIECES>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
@@ -345,8 +334,6 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     Misc* misc = reinterpret_cast<Misc*>(smem);
     signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
     int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + ((ncols * chs + 15) & ~15));  // [2][128][ncols]
-    // W32: [4 wavefronts][PF] tiles of sign bits in flight, 1 KiB aligned
-    unsigned char* ring = smem + ((sizeof(Misc) + ((ncols * chs + 15) & ~15) + 2 * DBF_TILE_ROWS * ncols * sizeof(int) + 1023) & ~(size_t)1023);
 
 #if DBF_PROLOGUE_PRIO
     // (experiment: wavefront priority raised for the prologue.  The arbiter favours older
@@ -396,24 +383,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     int cend = min(ct_end, c0 + ch_tiles);
     int steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
     int p_rt = 0, p_i = 0;
-    v4u buf[W32 ? 1 : PF];
-    // W32: slot `slot` of this wavefront's LDS ring <- the tile (a placeholder beyond the item's tiles reads
-    // the item's first tile; its step is multiplied with zero masks)
-    const unsigned ring_lds = (unsigned)reinterpret_cast<size_t>((__attribute__((address_space(3))) unsigned char*)ring) +
-                              (unsigned)(w * PF) * DBF_TILE_BYTES;
-    auto fetch32 = [&](int slot) {
-        const int ct = c0 + w + 4 * p_i;
-        const int ok = (int)(p_rt < it.nrt) & (int)(ct < cend);
-        const uint8_t* src = it.bits + (ok ? (size_t)(p_rt * it.n_ct + ct) * DBF_TILE_BYTES : (size_t)0);
-        const unsigned dst = ring_lds + (unsigned)slot * DBF_TILE_BYTES;
-        unsigned save;
-        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 " DBF_LOAD_BITS
-                     "\n\ts_mov_b32 m0, %0"
-                     : "=&s"(save) : "s"(dst), "v"(lane_off), "s"(src) : "memory");
-        const int wrap = (int)(p_i + 1 == steps);
-        p_i = wrap ? 0 : p_i + 1;
-        p_rt += wrap;
-    };
+    v4u buf[PF];
     // (the load itself, for a tile at byte offset `off` of the item's span; !ok: a placeholder that returns zeros)
     auto fetch_at = [&](v4u& dst, unsigned off, int ok) {
         const unsigned voff = lane_off + (ok ? off : OOB);
@@ -448,11 +418,11 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         asm volatile("s_waitcnt vmcnt(%1)" : "+v"(slot) : "n"(PF - 1) : "memory");
 #endif
     };
-    auto retire_ring = [](v4u (&rg)[W32 ? 1 : PF]) {
+    auto retire_ring = [](v4u (&rg)[PF]) {
 #if DBF_ASM_LOADS
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < (W32 ? 1 : PF); ++j) asm volatile("" : "+v"(rg[j]));
+        for (int j = 0; j < PF; ++j) asm volatile("" : "+v"(rg[j]));
 #endif
     };
     // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
@@ -514,9 +484,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         }
     }
 #pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        if constexpr (W32) fetch32(j); else fetch(buf[j]);
-    }
+    for (int j = 0; j < PF; ++j) fetch(buf[j]);
 #if DBF_ASM_LOADS
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(PF) : "memory");
 #else
@@ -543,15 +511,6 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     }
 
     v4i acc[NCG][8];
-    // W32: accumulators of the four plane pairs (32 rows x 32 operand columns each), this lane's masks
-    // (bit plane 2p or 2p+1 by lane), its operand row and its 16 bytes of a tile in the ring
-    v16i acc32[4];
-    const int h32 = lane >> 5, c32 = lane & 31;
-    unsigned pm[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) pm[p] = 0x01010101u << (2 * p + ((lane >> 4) & 1));
-    const int xrow32 = (c32 < ncols ? c32 : c32 % ncols) * chs + 16 * h32;
-    const unsigned char* tile32 = ring + (size_t)(w * PF) * DBF_TILE_BYTES + 256 * h32 + 16 * (lane & 15);
     // operand row this lane feeds to the matrix instruction (unused columns alias a valid row)
     int xrow[NCG];
 #pragma unroll
@@ -584,63 +543,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 for (int gi = 0; gi < NCG; ++gi)
 #pragma unroll
                     for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
-#pragma unroll
-                for (int p = 0; p < 4; ++p)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc32[p][v] = 0;
             }
-            if constexpr (W32) {
-                // ---- stream this wavefront's tiles of (row tile, chunk) through the LDS ring ----
-                v4i x0, x1, xn0, xn1;
-                {
-                    const int o = min(xo_base + w * 64, xo_max);
-                    xn0 = *reinterpret_cast<const v4i*>(xq + xrow32 + o);
-                    xn1 = *reinterpret_cast<const v4i*>(xq + xrow32 + o + 32);
-                }
-                for (int i0 = 0; i0 < steps; i0 += PF) {
-#pragma unroll
-                    for (int j = 0; j < PF; ++j) {
-                        const int o = min(xo_base + (w + 4 * (i0 + j + 1)) * 64, xo_max);  // operand of the next step
-                        x0 = xn0;
-                        x1 = xn1;
-                        xn0 = *reinterpret_cast<const v4i*>(xq + xrow32 + o);
-                        xn1 = *reinterpret_cast<const v4i*>(xq + xrow32 + o + 32);
-                        const bool live = c0 + w + 4 * (i0 + j) < cend;  // else a placeholder step: zero masks
-                        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(PF - 1) : "memory");
-                        const v4u b0 = *reinterpret_cast<const v4u*>(tile32 + j * DBF_TILE_BYTES);
-                        const v4u b1 = *reinterpret_cast<const v4u*>(tile32 + j * DBF_TILE_BYTES + 512);
-                        unsigned mk[4];
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) mk[p] = live ? pm[p] : 0u;
-                        // (column half outermost: four independent accumulators between two uses of one)
-#pragma unroll
-                        for (int kh = 0; kh < 2; ++kh) {
-                            const v4u b = kh ? b1 : b0;
-                            const v4i xo = kh ? x1 : x0;
-#pragma unroll
-                            for (int p = 0; p < 4; ++p) {
-                                v4i a;
-                                a.x = (int)(b.x & mk[p]);  a.y = (int)(b.y & mk[p]);  a.z = (int)(b.z & mk[p]);  a.w = (int)(b.w & mk[p]);
-                                acc32[p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, xo, acc32[p], 0, 0, 0);
-                            }
-                        }
-                        // the slot is rewritten only after its reads have returned
-                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                        fetch32(j);
-                    }
-                }
-                if (rtl + 1 == it.nrt) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the placeholders in flight
-                if (!last_chunk) continue;
-                int* rb = red + (tile_no & 1) * DBF_TILE_ROWS * ncols;
-                if (c32 < ncols) {
-#pragma unroll
-                    for (int p = 0; p < 4; ++p)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            atomicAdd(&rb[(16 * (2 * p + (v >> 3)) + 8 * ((v >> 2) & 1) + 4 * h32 + (v & 3)) * ncols + c32],
-                                      acc32[p][v]);
-                }
-            } else {
             // ---- stream this wavefront's tiles of (row tile, chunk) -----------------------
             // Slot j is consumed and then refilled in place, so PF-1 loads stay in flight and
             // no register copies are needed; the operand of the next step is read from LDS
@@ -712,8 +615,6 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                             atomicAdd(&rb[(16 * s + 4 * g + i) * ncols + col], acc[gi][s][i]);
                 }
             }
-            }  // 16x16x64 / 32x32x32
-            int* rb = red + (tile_no & 1) * DBF_TILE_ROWS * ncols;
             ++tile_no;
             __syncthreads();
             const int row = it.row0 + rtl * DBF_TILE_ROWS + rho;
@@ -791,9 +692,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         p_rt = 0;
         p_i = 0;
 #pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            if constexpr (W32) fetch32(j); else fetch(buf[j]);
-        }
+        for (int j = 0; j < PF; ++j) fetch(buf[j]);
     }
 
     // ---- fused launch: a B-stage item publishes its rows of t.  The counters are per layer
@@ -819,12 +718,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     }
 }
 
-size_t mfma_smem_bytes(int batch, int ch_tiles, bool w32) {
+size_t mfma_smem_bytes(int batch, int ch_tiles) {
     const int ncols = 2 * batch;
     const size_t xq = ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
-    const size_t base = sizeof(Misc) + xq + 2 * (size_t)DBF_TILE_ROWS * ncols * sizeof(int);
-    if (!w32) return base;
-    return ((base + 1023) & ~(size_t)1023) + 4 * (size_t)PF * DBF_TILE_BYTES;  // + the sign-tile ring
+    return sizeof(Misc) + xq + 2 * (size_t)DBF_TILE_ROWS * ncols * sizeof(int);
 }
 
 }  // namespace
@@ -846,16 +743,7 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols);
-    // (experiment switch, read once: DBF_MFMA32=1 takes the 32x32x32 variant where it applies)
-    static const bool want32 = [] { const char* e = std::getenv("DBF_MFMA32"); return e && e[0] == '1'; }();
-    const bool general = pieces || (batch <= 8 && max_cols > 256 * UNR * 8);
-    const bool w32 = want32 && !general && batch <= 8;
-    const size_t smem = mfma_smem_bytes(batch, ch_tiles, w32);
-    if (w32) {
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
-        return hipGetLastError();
-    }
+    const size_t smem = mfma_smem_bytes(batch, ch_tiles);
     // column pieces (small batches only), or rows the one-pass prologue cannot take (it holds 256*UNR*8 columns)
     if (pieces || (batch <= 8 && max_cols > 256 * UNR * 8))
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
