@@ -333,7 +333,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
     Misc* misc = reinterpret_cast<Misc*>(smem);
     signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
-    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + ((ncols * chs + 15) & ~15));  // [2][128][ncols]
+    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + ((ncols * chs + 15) & ~15));  // [2][ncols][128]
 
 #if DBF_PROLOGUE_PRIO
     // (experiment: wavefront priority raised for the prologue.  The arbiter favours older
@@ -612,7 +612,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                     for (int s = 0; s < 8; ++s)
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            atomicAdd(&rb[(16 * s + 4 * g + i) * ncols + col], acc[gi][s][i]);
+                            atomicAdd(&rb[col * DBF_TILE_ROWS + 4 * g + (16 * s + i)], acc[gi][s][i]);
                 }
             }
             ++tile_no;
@@ -620,10 +620,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             const int row = it.row0 + rtl * DBF_TILE_ROWS + rho;
             const float rscale = half_bits_to_float(misc->rscale[rtl * DBF_TILE_ROWS + rho]);
             for (int bi = tid >> 7; bi < batch; bi += 2) {
-                int* ph = &rb[rho * ncols + 2 * bi];
-                int vh = ph[0], vl = ph[1];
+                int* ph = &rb[(2 * bi) * DBF_TILE_ROWS + rho];  // column-major: [operand column][row of the tile]
+                int vh = ph[0], vl = ph[DBF_TILE_ROWS];
                 ph[0] = 0;
-                ph[1] = 0;
+                ph[DBF_TILE_ROWS] = 0;
                 if (e_s < 7) {
                     vh >>= e_s;
                     vl >>= e_s;
