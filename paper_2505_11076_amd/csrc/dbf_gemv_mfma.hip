@@ -167,21 +167,27 @@ struct InputVec {
         return m;
     }
     // Quantises the eight values, stores the two int8 planes, returns the sum of the q.
+    // q = 256 hi + lo with lo in [-128, 127]: with t = q + 128, hi is byte 1 of t (t >> 8, sign included,
+    // |q| <= 32512) and lo is byte 0 of t with its top bit flipped (t mod 256 - 128).  The bytes of the
+    // eight t are gathered with byte permutes: one for two values, then one per plane for four.
     __device__ inline int quantise_to(signed char* hi_dst, signed char* lo_dst, float inv) const {
         float u[8];
         get(u);
-        unsigned hi4[2] = {0, 0}, lo4[2] = {0, 0};
+        unsigned pair[4];
         int sum = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float f = rintf(u[i] * inv);
-            f = fminf(fmaxf(f, -QMAX), QMAX);
-            const int q = (int)f;
-            const int lo = ((q + 128) & 255) - 128;
-            const int hi = (q - lo) >> 8;
-            hi4[i >> 2] |= (unsigned)(hi & 255) << (8 * (i & 3));
-            lo4[i >> 2] |= (unsigned)(lo & 255) << (8 * (i & 3));
-            sum += q;
+        for (int i = 0; i < 8; i += 2) {
+            const int q0 = (int)__builtin_amdgcn_fmed3f(rintf(u[i] * inv), -QMAX, QMAX);
+            const int q1 = (int)__builtin_amdgcn_fmed3f(rintf(u[i + 1] * inv), -QMAX, QMAX);
+            sum += q0 + q1;
+            // bytes (t0.b0, t1.b0, t0.b1, t1.b1); selector bytes 0-3 pick from the second source, 4-7 from the first
+            pair[i >> 1] = __builtin_amdgcn_perm((unsigned)(q1 + 128), (unsigned)(q0 + 128), 0x05010400u);
+        }
+        unsigned hi4[2], lo4[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            lo4[h] = __builtin_amdgcn_perm(pair[2 * h + 1], pair[2 * h], 0x05040100u) ^ 0x80808080u;
+            hi4[h] = __builtin_amdgcn_perm(pair[2 * h + 1], pair[2 * h], 0x07060302u);
         }
         *reinterpret_cast<uint2*>(hi_dst) = make_uint2(hi4[0], hi4[1]);
         *reinterpret_cast<uint2*>(lo_dst) = make_uint2(lo4[0], lo4[1]);
