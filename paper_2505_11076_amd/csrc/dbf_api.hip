@@ -124,6 +124,25 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
     for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);
 }
 
+// Row tiles per workgroup for one stage of one layer in a launch whose stage holds `stage_tiles` tiles
+// (1 KiB each) in all.  The input row is quantised once per workgroup, so longer items amortise that
+// prologue; shorter ones leave more items to balance the end of the launch.  Measured on streams of
+// 0.25-1 GB of signs: items of 128-256 KiB with about 2000 of them per stage do best (4096 x 4096 layers,
+// k = 2048: 5.7 TB/s at 2 and 4 row tiles for the two stages against 5.4 at 1 and 1; k = 4096: 5.7 TB/s at
+// 2 and 2 against 4.8 at 4 and 4), and rows too wide for the one-pass prologue, which read the input twice,
+// always want the longest items (8192 x 8192, k = 8192: 3.9 TB/s at 4 against 3.0 at 1).
+int auto_span(const DbfStage& st, long long stage_tiles) {
+    constexpr long long WANT_ITEMS = 2048;
+    constexpr int MAX_AUTO_SPAN = 4;
+    if (st.cols > dbf_mfma_one_pass_cols()) return MAX_AUTO_SPAN;
+    long long item_tiles = stage_tiles / WANT_ITEMS;
+    if (item_tiles > 256) item_tiles = 256;
+    int span = (int)((2 * item_tiles + st.n_ct) / (2 * st.n_ct));  // item_tiles / n_ct, rounded to nearest
+    if (span < 1) span = 1;
+    if (span > MAX_AUTO_SPAN) span = MAX_AUTO_SPAN;
+    return span;
+}
+
 void free_plan(DbfPlan& p) {
     if (p.dev_block) (void)hipFree(p.dev_block);
     p.dev_block = nullptr;
@@ -145,11 +164,24 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
         if (sA[i].cols > p->max_cols_A) p->max_cols_A = sA[i].cols;
     }
     const std::vector<int> one(1, 1);
+    // row tiles per item: the given pattern, or (empty pattern) chosen per layer from the size of the launch
+    long long tiles_B = 0, tiles_A = 0;
+    for (int i = 0; i < n; ++i) {
+        tiles_B += (long long)sB[i].n_rt * sB[i].n_ct;
+        tiles_A += (long long)sA[i].n_rt * sA[i].n_ct;
+    }
+    int max_span = 1;
+    auto pattern_for = [&](const std::vector<int>& given, const DbfStage& st, long long stage_tiles) {
+        std::vector<int> v = given.empty() ? std::vector<int>(1, auto_span(st, stage_tiles)) : given;
+        for (int x : v) max_span = x > max_span ? x : max_span;
+        return v;
+    };
     int phase = 0;
-    for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, span_b, &phase);
+    for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, pattern_for(span_b, sB[i], tiles_B), &phase);
     nBn = (int)items_n.size();
     phase = 0;
-    for (int i = 0; i < n; ++i) append_items(items_n, sA[i], i, true, sB[i].n_rt, span_a, &phase);
+    for (int i = 0; i < n; ++i)
+        append_items(items_n, sA[i], i, true, sB[i].n_rt, pattern_for(span_a, sA[i], tiles_A), &phase);
     phase = 0;
     for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, one, &phase);
     nB1 = (int)items_1.size();
@@ -254,9 +286,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->d_items_p = cut ? reinterpret_cast<DbfItem*>(d + o_ip) : nullptr;
     p->nBp = nBp;
     p->nAp = (int)items_p.size() - nBp;
-    p->span = 1;
-    for (int v : span_b) p->span = v > p->span ? v : p->span;
-    for (int v : span_a) p->span = v > p->span ? v : p->span;
+    p->span = max_span;
     p->persist_ok = p->span <= DBF_PERSIST_MAX_SPAN && p->max_cols_B <= DBF_PERSIST_MAX_COLS &&
                     p->max_cols_A <= DBF_PERSIST_MAX_COLS;
     for (int i = 0; i < n; ++i)
@@ -451,9 +481,11 @@ std::vector<int> stack_spans(const char* env_name, const char* fallback) {
     // start together on equal items also finish together, and the launch then alternates
     // between "everybody in the prologue" and "everybody streaming" instead of keeping the
     // memory system evenly busy.  The environment variables DBF_STACK_SPAN / DBF_STACK_SPAN_A
-    // override the patterns (values 1..16; experiments and tests).
+    // give the patterns (values 1..16; experiments and tests); without them the pattern is empty
+    // and build_plan chooses per layer (auto_span).
     const char* e = std::getenv(env_name);
     std::vector<int> v;
+    if (!e && !*fallback) return v;
     for (const char* q = e ? e : fallback; *q;) {
         char* end = nullptr;
         long x = std::strtol(q, &end, 10);
@@ -663,7 +695,7 @@ int dbf_stack_create_grouped(const dbf_layer* const* layers, int n_layers, const
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
     }
     S->h_x_prefix[n_layers] = x_end;
-    const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", "4"), stack_spans("DBF_STACK_SPAN_A", "4"), &S->plan);
+    const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", ""), stack_spans("DBF_STACK_SPAN_A", ""), &S->plan);
     if (rc != DBF_OK) {
         dbf_stack_free(S);
         return rc;

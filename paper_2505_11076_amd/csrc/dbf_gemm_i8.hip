@@ -20,7 +20,8 @@
 // {hi, lo} = 32 accumulator tiles (128 registers).  Twice as many workgroups as compute units at
 // 4096 rows x 2048 tokens, i.e. two wavefronts per SIMD.  The 64-token slice of the quantised
 // operand (2 planes x 64 tokens x 64 bytes per step) is staged in LDS, double buffered; sign
-// tiles and operand columns of step kt + 4 are requested while step kt is computed.
+// tiles and operand columns of step kt + 4 are requested while step kt is computed, by loads
+// issued and waited for by hand (see the stage kernel).
 #include "dbf_kernels.h"
 
 namespace {
@@ -32,22 +33,21 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
 constexpr float QMAX = 32512.f;     // 127*256: largest |q| so that hi and lo fit int8
 constexpr int QI_TOKENS = 64;       // tokens per workgroup
-#ifndef DBF_QI_ROWTILES
-#define DBF_QI_ROWTILES 2
-#endif
-constexpr int QI_ROWTILES = DBF_QI_ROWTILES;  // 128-row tiles per workgroup
+constexpr int QI_ROWTILES = 2;      // 128-row tiles per workgroup
 constexpr int QI_TROW = 64 + 16;    // LDS bytes per (plane, token): 64 operand bytes + bank padding
 constexpr int QI_PLANE = QI_TOKENS * QI_TROW;
 constexpr int QI_DEPTH = 4;         // steps requested ahead
-#ifndef DBF_QI_TB
-#define DBF_QI_TB 2
+constexpr int QI_TB = 2;            // 16-token blocks per wavefront: 8 planes x 2 x {hi, lo} = 128 accumulator registers
+constexpr int QI_TSPLIT = QI_TOKENS / (16 * QI_TB);       // token slices of a row tile
+// 1: workgroups that read the same operand slice are renumbered onto one compute die (one L2); 0: launch order
+#ifndef DBF_QI_XCD_REMAP
+#define DBF_QI_XCD_REMAP 1
 #endif
-constexpr int QI_TB = DBF_QI_TB;    // 16-token blocks per wavefront (2: 128 accumulator registers, 1: 64)
-constexpr int QI_TSPLIT = QI_TOKENS / (16 * QI_TB);       // wavefronts that share a row tile
 constexpr int QI_WAVES = QI_ROWTILES * QI_TSPLIT;
+constexpr int QI_OCC = 2;           // wavefronts per SIMD (the accumulators leave room for no more)
 constexpr int QI_THREADS = 64 * QI_WAVES;
 constexpr int QI_STAGE_BYTES = 2 * QI_TOKENS * 64 / QI_THREADS;  // operand bytes a thread stages per step
-static_assert(QI_STAGE_BYTES == 32 || QI_STAGE_BYTES == 16, "staging is one or two 16-byte pieces per thread");
+static_assert(QI_STAGE_BYTES == 32, "staging is two 16-byte pieces per thread");
 
 template <int CTRL>
 __device__ inline int dpp_move(int v) {
@@ -264,26 +264,35 @@ struct StageArgs {
 };
 
 template <bool OUT_F32>
-__global__ __launch_bounds__(QI_THREADS) __attribute__((amdgpu_waves_per_eu(QI_TB == 2 ? 2 : 4, QI_TB == 2 ? 2 : 4)))
+__global__ __launch_bounds__(QI_THREADS) __attribute__((amdgpu_waves_per_eu(QI_OCC, QI_OCC)))
 void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     __shared__ __align__(16) unsigned char xs[2][2 * QI_PLANE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, c = lane & 15;
-    const int token0 = blockIdx.y * QI_TOKENS;
+    // Workgroups are handed to the 8 compute dies in turn (linear id modulo 8) and each die has its own L2.
+    // All workgroups of a token block read the same operand slice, so they are renumbered to share a die:
+    // die d takes a contiguous range of the (token block, row group) pairs, row group fastest.
+#if DBF_QI_XCD_REMAP
+    const unsigned n_wg = gridDim.x * gridDim.y, lin = blockIdx.x + gridDim.x * blockIdx.y;
+    const unsigned die = lin & 7, slot = lin >> 3, per = n_wg >> 3, extra = n_wg & 7;
+    const unsigned vid = die * per + (die < extra ? die : extra) + slot;
+    const int bx = (int)(vid % gridDim.x), by = (int)(vid / gridDim.x);
+#else
+    const int bx = blockIdx.x, by = blockIdx.y;
+#endif
+    const int token0 = by * QI_TOKENS;
     const int th = w / QI_ROWTILES;                          // token slice of this wavefront
-    int rt = blockIdx.x * QI_ROWTILES + (w % QI_ROWTILES);   // its row tile
+    int rt = bx * QI_ROWTILES + (w % QI_ROWTILES);           // its row tile
     const bool active = rt < a.n_rt;                         // beyond the matrix: compute on tile 0, store nothing
     if (!active) rt = 0;
-    const v4u* tiles = reinterpret_cast<const v4u*>(a.bits) + (size_t)rt * a.n_ct * 64 + lane;
 
     // staging role: thread -> (token, plane, 32-byte half of the 64 operand bytes of a step)
     // (the 8 KiB of a step are contiguous in memory: thread t takes bytes [SB*t, SB*t + SB))
     constexpr int SB = QI_STAGE_BYTES;
     const int s_tok = (tid * SB) >> 7, s_plane = ((tid * SB) >> 6) & 1, s_half = (tid * SB) & 63;
     // (tokens in [T, Tp) hold whatever the workspace held: they are computed and never stored)
-    const signed char* s_src = a.xq + (size_t)token0 * 128 + SB * tid;
     const size_t s_step = (size_t)a.Tp * 128;                // bytes between steps
     unsigned char* s_dst0 = xs[0] + s_plane * QI_PLANE + s_tok * QI_TROW + s_half;
     unsigned char* s_dst1 = xs[1] + s_plane * QI_PLANE + s_tok * QI_TROW + s_half;
@@ -297,49 +306,50 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
             acc[s][tb][1] = (v4i){0, 0, 0, 0};
         }
 
-    // software pipeline: sign tile and operand columns of step kt + QI_DEPTH are requested while
-    // step kt is computed; unrolled QI_DEPTH times so that every in-flight register has a fixed
-    // name.  Steps beyond the matrix (count rounded up) re-read the last step's data and are
-    // given a zero sign operand... they are simply not executed: see the guard in the loop.
+    // Software pipeline with hand-issued loads.  The sign tile and the operand bytes of step kt + QI_DEPTH are
+    // requested at the end of step kt by inline assembly and waited for by hand: the compiler does not see
+    // these loads, so it cannot drain the whole pipeline with a vmcnt(0) wait at the loop's back edge (which
+    // it does for loads it tracks: once per QI_DEPTH steps every wavefront then sits out a full memory
+    // latency).  Loads complete in issue order.  A step's group is issued as (x0, x1, bq); at the top of step
+    // kt the groups of steps kt+1 .. kt+3 are in flight behind bq of step kt, and the step needs bq(kt),
+    // x0(kt+1), x1(kt+1): bq(kt+1) and the two younger groups may stay outstanding = 1 + 3 + 3 loads.
+    static_assert(QI_DEPTH == 4 && QI_STAGE_BYTES == 32, "the wait counts below are written for this pipeline");
     v4u bq[QI_DEPTH], x0[QI_DEPTH], x1[QI_DEPTH];
     const int last_ct = a.n_ct - 1;
+    const unsigned x_voff = (unsigned)(SB * tid), t_voff = (unsigned)(lane * 16);
+    const signed char* x_base = a.xq + (size_t)token0 * 128;
+    const uint8_t* t_base = a.bits + (size_t)rt * a.n_ct * DBF_TILE_BYTES;
+    auto request = [&](int j, int kt) {  // kt is the same for all lanes: the step's part of the address is scalar
+        const signed char* xs_ = x_base + (size_t)kt * s_step;
+        const uint8_t* ts_ = t_base + (size_t)kt * DBF_TILE_BYTES;
+        asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(x0[j]) : "v"(x_voff), "s"(xs_) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, %2 offset:16" : "=v"(x1[j]) : "v"(x_voff), "s"(xs_) : "memory");
+        asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(bq[j]) : "v"(t_voff), "s"(ts_) : "memory");
+    };
 #pragma unroll
-    for (int j = 0; j < QI_DEPTH; ++j) {
-        const int kt = min(j, last_ct);
-        bq[j] = tiles[(size_t)kt * 64];
-        x0[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step);
-        if (SB == 32) x1[j] = *reinterpret_cast<const v4u*>(s_src + kt * s_step + 16);
-    }
+    for (int j = 0; j < QI_DEPTH; ++j) request(j, min(j, last_ct));
+    asm volatile("s_waitcnt vmcnt(10)" : "+v"(x0[0]), "+v"(x1[0]) : : "memory");
     *reinterpret_cast<v4u*>(s_dst0) = x0[0];
-    if (SB == 32) *reinterpret_cast<v4u*>(s_dst0 + 16) = x1[0];
+    *reinterpret_cast<v4u*>(s_dst0 + 16) = x1[0];
     __syncthreads();
 
-    // operand rows of this lane: token 32*th + 16*tb + c, k-group g
     const unsigned char* xlane = xs[0] + (16 * QI_TB * th + c) * QI_TROW + 16 * g;
 
     for (int kt0 = 0; kt0 < a.n_ct; kt0 += QI_DEPTH) {
 #pragma unroll
         for (int j = 0; j < QI_DEPTH; ++j) {
             const int kt = kt0 + j;
-            v4u bq_next;
-            // stage step kt + 1 (requested QI_DEPTH - 1 steps ago) into the other buffer, then reuse
-            // the registers for step kt + QI_DEPTH
+            const int jn = (j + 1) % QI_DEPTH;
+            asm volatile("s_waitcnt vmcnt(7)" : "+v"(x0[jn]), "+v"(x1[jn]), "+v"(bq[j]) : : "memory");
+            // stage step kt + 1 into the other buffer
             {
                 unsigned char* d = (j & 1) ? s_dst0 : s_dst1;
-                *reinterpret_cast<v4u*>(d) = x0[(j + 1) % QI_DEPTH];
-                if (SB == 32) *reinterpret_cast<v4u*>(d + 16) = x1[(j + 1) % QI_DEPTH];
-                const int kn = min(kt + QI_DEPTH, last_ct);
-                x0[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step);
-                if (SB == 32) x1[j] = *reinterpret_cast<const v4u*>(s_src + kn * s_step + 16);
-                bq_next = tiles[(size_t)kn * 64];
-                // keep the three requests here, at the top of the step: the scheduler otherwise
-                // sinks them below the matrix instructions and shortens the prefetch distance
-                __builtin_amdgcn_sched_barrier(0);
+                *reinterpret_cast<v4u*>(d) = x0[jn];
+                *reinterpret_cast<v4u*>(d + 16) = x1[jn];
             }
-            // A step beyond the matrix contributes nothing if its sign operand is zero: masked
-            // bytes of an all-zero tile are zero.  (No branch around the matrix instructions.)
+            // A step beyond the matrix contributes nothing if its sign operand is zero (no branch around
+            // the matrix instructions); `live` is the same for all lanes and is folded into the plane masks.
             const unsigned live = kt < a.n_ct ? 0xFFFFFFFFu : 0u;
-            const v4u bits = {bq[j].x & live, bq[j].y & live, bq[j].z & live, bq[j].w & live};
             const unsigned char* xb = xlane + (j & 1) * (2 * QI_PLANE);
             v4i xop[QI_TB][2];
 #pragma unroll
@@ -347,24 +357,32 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
                 xop[tb][0] = *reinterpret_cast<const v4i*>(xb + tb * 16 * QI_TROW);
                 xop[tb][1] = *reinterpret_cast<const v4i*>(xb + tb * 16 * QI_TROW + QI_PLANE);
             }
+            v4i av[8];
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
-                const unsigned msk = 0x01010101u << s;
-                v4i av;
-                av.x = (int)(bits.x & msk);
-                av.y = (int)(bits.y & msk);
-                av.z = (int)(bits.z & msk);
-                av.w = (int)(bits.w & msk);
+                const unsigned msk = (0x01010101u << s) & live;
+                av[s].x = (int)(bq[j].x & msk);
+                av[s].y = (int)(bq[j].y & msk);
+                av[s].z = (int)(bq[j].z & msk);
+                av[s].w = (int)(bq[j].w & msk);
+                if (s == 7) {
+                    // every register of slot j has been read: request step kt + QI_DEPTH into it
+                    asm volatile("" : "+v"(av[s]), "+v"(bq[j]), "+v"(x0[j]), "+v"(x1[j]));
+                    request(j, min(kt + QI_DEPTH, last_ct));
+                }
 #pragma unroll
                 for (int tb = 0; tb < QI_TB; ++tb) {
-                    acc[s][tb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, xop[tb][0], acc[s][tb][0], 0, 0, 0);
-                    acc[s][tb][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, xop[tb][1], acc[s][tb][1], 0, 0, 0);
+                    acc[s][tb][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], xop[tb][0], acc[s][tb][0], 0, 0, 0);
+                    acc[s][tb][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], xop[tb][1], acc[s][tb][1], 0, 0, 0);
                 }
             }
-            bq[j] = bq_next;
             __syncthreads();
         }
     }
+    // the requests of the last QI_DEPTH steps are still in flight: let them land before their registers are reused
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < QI_DEPTH; ++j) asm volatile("" : "+v"(bq[j]), "+v"(x0[j]), "+v"(x1[j]));
 
     // ---- epilogue: acc[s][tb][p][i] of lane (g, c) is row 16*s + 4*g + i, token 32*th + 16*tb + c ----
     if (!active) return;
@@ -380,13 +398,10 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
             float v[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                int vh = acc[s][tb][0][i], vl = acc[s][tb][1][i];
-                if (s < 7) {
-                    vh >>= s;
-                    vl >>= s;
-                } else {  // the mask 0x80 is -128 as an int8
-                    vh = -(vh >> 7);
-                    vl = -(vl >> 7);
+                int vh = acc[s][tb][0][i] >> s, vl = acc[s][tb][1][i] >> s;
+                if (s == 7) {  // the mask 0x80 is -128 as an int8
+                    vh = -vh;
+                    vl = -vl;
                 }
                 const int total = 2 * (vh * 256 + vl) - tsigma;
                 const float rs = (float)__builtin_bit_cast(_Float16, a.row_scale[n0 + i]);

@@ -56,7 +56,7 @@
 #define DBF_PF 4
 #endif
 #ifndef DBF_UNR
-#define DBF_UNR 2
+#define DBF_UNR 3
 #endif
 #ifndef DBF_WAVES_PER_EU
 #define DBF_WAVES_PER_EU 4
@@ -732,6 +732,8 @@ size_t mfma_smem_bytes(int batch, int ch_tiles) {
 
 }  // namespace
 
+int dbf_mfma_one_pass_cols() { return 256 * UNR * 8; }
+
 int dbf_mfma_chunk_tiles(int batch, int max_cols) {
     const int ncols = 2 * batch;
     const int budget = batch > 8 ? 32768 : 28672;  // LDS bytes for the quantised operand
@@ -750,8 +752,8 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
     uint16_t* y = static_cast<uint16_t*>(y_base);
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols);
     const size_t smem = mfma_smem_bytes(batch, ch_tiles);
-    // column pieces (small batches only), or rows the one-pass prologue cannot take (it holds 256*UNR*8 columns)
-    if (pieces || (batch <= 8 && max_cols > 256 * UNR * 8))
+    // column pieces (small batches only)
+    if (pieces)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (batch <= 8)

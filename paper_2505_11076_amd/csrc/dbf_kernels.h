@@ -26,6 +26,9 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
                                  int use_sync, const void* x_base, void* y_base, int batch,
                                  int max_cols, int pieces, hipStream_t stream);
 int dbf_mfma_chunk_tiles(int batch, int max_cols);
+// Widest input row (columns) the matrix-core kernel's one-pass prologue takes at batch 1: such rows are
+// read once and quantised from registers; wider ones are read twice (scale, then quantisation).
+int dbf_mfma_one_pass_cols();
 
 // Batch-1 decode of items[0..n_items) (B items first, then A items) in one persistent launch
 // whose workgroups prefetch their next item while streaming the current one.  Requirements
