@@ -23,7 +23,9 @@ variance law for random signs, packing round trip, the bits-per-weight
 numbers the paper prints; the sampled-rows variant against the dense one; pruning of middle
 channels against zeroing their scales and against a per-entry loop; the SVID projection
 against the singular value decomposition it converges to, exact rank-one inputs and its
-fixed point.  No function here is "parity unpinned".
+fixed point; the ADMM update against the normal equations of its least-squares step, an augmented
+least-squares solve by a library routine, its fixed point at an exactly factorisable W and the scalar
+closed form.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -210,6 +212,59 @@ def svid(Z, iters: int):
         sigma = np.sqrt(np.sum(v * v))
         v = v / sigma if sigma > 0.0 else v
     return S, sigma * u, v
+
+
+# ---------------------------------------------------------------------------
+# One ADMM update (section 3.2, the three-line ADMM update after the SVID definition)
+# ---------------------------------------------------------------------------
+
+
+def admm_step_from(Minv, C, rho: float, S, a, m, U, svid_iters: int):
+    """The ADMM update with its two constant matrices already formed:
+    Minv = (B^T B + rho I)^-1 and C = B^T W do not change while B and W are fixed, so an implementation
+    forms them once per outer iteration and repeats only what is written here.
+
+        A     = a . S . m^T                       (the current iterate, in SVID form)
+        W_hat = Minv^T (C + rho (A - U))          (Minv is symmetric in exact arithmetic; it is applied
+                                                   transposed so that the result is defined for any input)
+        Z     = W_hat + U
+        (S', a', m') = SVID(Z);   A' = a' . S' . m'^T
+        U'    = U + W_hat - A'
+    Returns (S', a', m', U', W_hat), all fp64.
+    """
+    Minv = np.asarray(Minv, dtype=np.float64)
+    C = np.asarray(C, dtype=np.float64)
+    S = np.asarray(S, dtype=np.float64)
+    a = np.asarray(a, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    q, r = C.shape
+    if Minv.shape != (q, q) or S.shape != (q, r) or U.shape != (q, r) or a.shape != (q,) or m.shape != (r,):
+        raise ValueError("shape mismatch")
+    A = a[:, None] * S * m[None, :]
+    W_hat = Minv.T @ (C + rho * (A - U))
+    S2, a2, m2 = svid(W_hat + U, svid_iters)
+    A2 = a2[:, None] * S2 * m2[None, :]
+    return S2, a2, m2, U + W_hat - A2, W_hat
+
+
+def admm_step(B, W, rho: float, S, a, m, U, svid_iters: int):
+    """One ADMM update as the paper prints it, for the least-squares form min_X ||B X - W|| with X
+    constrained to the SVID form:
+
+        W_hat = (B^T B + rho I)^-1 (B^T W + rho (A - U)),  A' = SVID(W_hat + U),  U' = U + W_hat - A'.
+
+    B is (p x q), W (p x r), the iterate A = a . S . m^T and the scaled dual U are (q x r).  (The
+    subproblem of the alternating minimisation, min_A ||A B - W||, has this form after transposition.)
+    Returns (S', a', m', U', W_hat), all fp64.
+    """
+    B = np.asarray(B, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    if B.ndim != 2 or W.ndim != 2 or B.shape[0] != W.shape[0] or rho <= 0.0:
+        raise ValueError("B (p x q), W (p x r), rho > 0")
+    q = B.shape[1]
+    G = B.T @ B + rho * np.eye(q)
+    return admm_step_from(np.linalg.inv(G), B.T @ W, rho, S, a, m, U, svid_iters)
 
 
 # ---------------------------------------------------------------------------

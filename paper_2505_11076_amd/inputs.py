@@ -154,3 +154,19 @@ def llama2_7b_stack_shapes(n_blocks: int = 32) -> list[dict]:
             out.append(dict(n_in=4096, n_out=11008, k=4477))
         out.append(dict(n_in=11008, n_out=4096, k=4477))
     return out
+
+
+def make_admm_problem(p: int, q: int, r: int, seed: int):
+    """Operands of one ADMM update of the factorisation (section 3.2) in the least-squares form
+    min_X ||B X - W||: the fixed factor B (p x q, i.i.d. N(0, 1/p): rows of comparable norm, as after the
+    paper's row normalisation), the target W (p x r, N(0, 1)), the current iterate in SVID form (signs S
+    (q x r, +-1 as int8), a (q), m (r), positive) and the scaled dual variable U (q x r, N(0, 0.3^2)).
+    fp32 throughout, as an fp32 implementation of the compression would hold them."""
+    rng = np.random.default_rng(seed + 900)
+    B = (rng.standard_normal((p, q)) / np.sqrt(p)).astype(np.float32)
+    W = rng.standard_normal((p, r)).astype(np.float32)
+    S = np.where(rng.random((q, r)) < 0.5, 1, -1).astype(np.int8)
+    a = rng.uniform(0.2, 1.5, q).astype(np.float32)
+    m = rng.uniform(0.2, 1.5, r).astype(np.float32)
+    U = (0.3 * rng.standard_normal((q, r))).astype(np.float32)
+    return B, W, S, a, m, U

@@ -442,3 +442,103 @@ def test_svid_first_round_by_hand_and_the_sign_of_zero():
     assert np.allclose(m, [x / sigma for x in v], rtol=1e-15)
     with pytest.raises(ValueError):
         O.svid(Z, 0)
+
+
+# ---------------------------------------------------------------------------
+# ADMM update (section 3.2)
+# ---------------------------------------------------------------------------
+
+
+def _admm_case(p, q, r, seed):
+    rng = np.random.default_rng(seed)
+    B = rng.standard_normal((p, q)) / math.sqrt(p)
+    W = rng.standard_normal((p, r))
+    S = np.where(rng.random((q, r)) < 0.5, 1.0, -1.0)
+    a, m = rng.uniform(0.2, 1.5, q), rng.uniform(0.2, 1.5, r)
+    U = 0.3 * rng.standard_normal((q, r))
+    return B, W, S, a, m, U
+
+
+def test_admm_w_hat_satisfies_the_normal_equations_and_minimises_its_objective():
+    """W_hat is the minimiser over X of f(X) = 1/2 ||B X - W||^2 + rho/2 ||X - A + U||^2 (the first line of
+    the generic ADMM iteration with f the least-squares error and z = A), so the gradient
+    B^T (B X - W) + rho (X - A + U) vanishes there and every other X does worse."""
+    for (p, q, r, rho) in ((13, 7, 9, 1.0), (6, 11, 5, 0.25), (20, 20, 3, 4.0)):
+        B, W, S, a, m, U = _admm_case(p, q, r, 40 + p)
+        A = a[:, None] * S * m[None, :]
+        W_hat = O.admm_step(B, W, rho, S, a, m, U, 3)[4]
+        grad = B.T @ (B @ W_hat - W) + rho * (W_hat - A + U)
+        assert np.max(np.abs(grad)) < 1e-11 * (1.0 + np.max(np.abs(W)))
+        f = lambda X: 0.5 * np.sum((B @ X - W) ** 2) + 0.5 * rho * np.sum((X - A + U) ** 2)
+        rng = np.random.default_rng(p)
+        for _ in range(10):
+            assert f(W_hat + 1e-3 * rng.standard_normal(W_hat.shape)) > f(W_hat)
+
+
+def test_admm_w_hat_equals_an_augmented_least_squares_solve():
+    """The same minimiser from a library routine that never forms B^T B: stack sqrt(rho) I under B and
+    sqrt(rho) (A - U) under W and solve the tall least-squares problem."""
+    B, W, S, a, m, U = _admm_case(17, 8, 6, 77)
+    rho = 0.7
+    A = a[:, None] * S * m[None, :]
+    tall = np.vstack([B, math.sqrt(rho) * np.eye(8)])
+    rhs = np.vstack([W, math.sqrt(rho) * (A - U)])
+    X = np.linalg.lstsq(tall, rhs, rcond=None)[0]
+    assert np.allclose(O.admm_step(B, W, rho, S, a, m, U, 2)[4], X, rtol=0, atol=1e-12)
+
+
+def test_admm_fixed_point_when_w_is_exactly_factorisable():
+    """If W = B A* with A* of the SVID form, then A = A*, U = 0 is a fixed point of the update:
+    W_hat = (B^T B + rho I)^-1 (B^T B A* + rho A*) = A*, SVID(A*) = A*, U stays 0."""
+    B, _, S, a, m, _ = _admm_case(15, 6, 10, 5)
+    A_star = a[:, None] * S * m[None, :]
+    S2, a2, m2, U2, W_hat = O.admm_step(B, B @ A_star, 1.0, S, a, m, np.zeros((6, 10)), 1)
+    assert np.allclose(W_hat, A_star, rtol=0, atol=1e-12)
+    assert np.array_equal(S2, S)
+    assert np.allclose(np.outer(a2, m2), np.outer(a, m), rtol=1e-11, atol=0)
+    assert np.max(np.abs(U2)) < 1e-11
+
+
+def test_admm_scalar_closed_form_and_the_dual_update():
+    """p = q = r = 1: W_hat = (b w + rho (A - u)) / (b^2 + rho); SVID of a scalar z is z itself
+    (sign(z) * |z| * 1), so A' = W_hat + u and u' = u + W_hat - A' = 0.  Checked for both signs of z."""
+    for (b, w, s, a, m, u, rho) in ((2.0, 3.0, 1.0, 0.5, 1.0, 0.25, 1.0), (1.5, -4.0, -1.0, 2.0, 1.0, -0.5, 2.0)):
+        S2, a2, m2, U2, W_hat = O.admm_step([[b]], [[w]], rho, [[s]], [a], [m], [[u]], 2)
+        want = (b * w + rho * (s * a * m - u)) / (b * b + rho)
+        assert abs(W_hat[0, 0] - want) < 1e-15
+        z = want + u
+        assert S2[0, 0] == (1.0 if z >= 0 else -1.0)
+        assert abs(a2[0] * m2[0] - abs(z)) < 1e-15 and abs(U2[0, 0]) < 1e-15
+
+
+def test_admm_large_penalty_limit_and_conservation():
+    """rho -> infinity pins X to A - U: W_hat -> A - U.  And for any rho the three outputs are tied by
+    U' + A' = U + W_hat (the dual update), whatever SVID returns."""
+    B, W, S, a, m, U = _admm_case(9, 5, 7, 3)
+    A = a[:, None] * S * m[None, :]
+    W_hat = O.admm_step(B, W, 1e12, S, a, m, U, 1)[4]
+    assert np.allclose(W_hat, A - U, rtol=0, atol=1e-9)
+    S2, a2, m2, U2, W_hat = O.admm_step(B, W, 1.0, S, a, m, U, 4)
+    assert np.allclose(U2 + a2[:, None] * S2 * m2[None, :], U + W_hat, rtol=0, atol=1e-13)
+    S3, a3, m3 = O.svid(W_hat + U, 4)
+    assert np.array_equal(S2, S3) and np.array_equal(a2, a3) and np.array_equal(m2, m3)
+
+
+def test_admm_precomputed_form_matches_and_rejects_bad_shapes():
+    B, W, S, a, m, U = _admm_case(12, 6, 8, 11)
+    rho = 1.0
+    Minv = np.linalg.inv(B.T @ B + rho * np.eye(6))
+    full = O.admm_step(B, W, rho, S, a, m, U, 3)
+    pre = O.admm_step_from(Minv, B.T @ W, rho, S, a, m, U, 3)
+    for x, y in zip(full, pre):
+        assert np.array_equal(x, y)
+    # a non-symmetric "inverse" is applied transposed (the documented convention)
+    M2 = Minv + np.triu(np.ones((6, 6)), 1) * 0.01
+    A = a[:, None] * S * m[None, :]
+    assert np.allclose(O.admm_step_from(M2, B.T @ W, rho, S, a, m, U, 1)[4], M2.T @ (B.T @ W + rho * (A - U)))
+    with pytest.raises(ValueError):
+        O.admm_step_from(Minv[:5], B.T @ W, rho, S, a, m, U, 1)
+    with pytest.raises(ValueError):
+        O.admm_step(B, W[:5], rho, S, a, m, U, 1)
+    with pytest.raises(ValueError):
+        O.admm_step(B, W, 0.0, S, a, m, U, 1)
