@@ -207,6 +207,31 @@ size_t dbf_svid_workspace_bytes(int rows, int cols); /* 0 if the sizes are out o
 int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* a_dev, void* m_dev, void* bits_dev,
              void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/* ---- one ADMM update (paper, section 3.2, the three-line update that follows the SVID definition) ----
+ * The compression solves min ||B X - W|| with X constrained to the SVID form a . S . m^T by ADMM (the
+ * alternating minimisation's subproblem min_A ||A B - W|| has this form after transposition):
+ *     W_hat = (B^T B + rho I)^-1 (B^T W + rho (A - U)),   A' = SVID(W_hat + U),   U' = U + W_hat - A'.
+ * B and W do not change during the inner iterations, so the caller forms the two constant matrices once
+ *     Minv = (B^T B + rho I)^-1   (q x q),      C = B^T W   (q x r)
+ * and this call does what is repeated, on the device, with the iterate kept in its factored form:
+ *     Z = Minv^T (C + rho (a . S . m^T - U)) + U;   (S, a, m) <- SVID(Z);   U <- Z - a . S . m^T.
+ * (Minv is symmetric in exact arithmetic; it is applied transposed, i.e. read by rows of the summation
+ * index, so the result is defined for whatever the caller's inverse holds.)
+ *   Minv_dev: device, fp32 [q][q] row major (read only).    C_dev: device, fp32 [q][r] row major (read only).
+ *   rho: penalty factor, > 0 (the paper uses 1).   svid_iters: rounds of the power iteration, >= 1.
+ *   a_dev: device, fp32 [q];  m_dev: device, fp32 [r];  bits_dev: device, dbf_tiled_bytes(q, r) bytes, the
+ *          signs S in the tile layout (as dbf_svid writes them);  U_dev: device, fp32 [q][r].
+ *          All four are read as the current iterate and overwritten with the next one.
+ *   workspace_dev: device, 256-byte aligned, >= dbf_admm_workspace_bytes(q, r) bytes (two q x r fp32
+ *          matrices and the SVID workspace).
+ * Asynchronous on hip_stream, allocates nothing; results do not depend on scheduling.  NaNs unsupported.
+ * Errors: DBF_EINVAL (null or misaligned pointers, sizes out of range, rho <= 0 or not finite,
+ * svid_iters < 1), DBF_EWORKSPACE, DBF_EHIP. */
+size_t dbf_admm_workspace_bytes(int q, int r); /* 0 if the sizes are out of range */
+int dbf_admm_step(const void* Minv_dev, const void* C_dev, int q, int r, float rho, int svid_iters,
+                  void* a_dev, void* m_dev, void* bits_dev, void* U_dev, void* workspace_dev,
+                  size_t workspace_bytes, void* hip_stream);
+
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
  * benchmark stream of layers): the B and A stages of all layers run in one launch (two for

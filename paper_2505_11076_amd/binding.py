@@ -28,7 +28,7 @@ EXPORTS = [
     "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
     "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
-    "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
+    "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_admm_workspace_bytes", "dbf_admm_step", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
 ]
 
 _lib = None
@@ -81,6 +81,9 @@ def lib() -> C.CDLL:
     L.dbf_svid_workspace_bytes.argtypes = [i32, i32]
     L.dbf_svid_workspace_bytes.restype = sz
     L.dbf_svid.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.dbf_admm_workspace_bytes.argtypes = [i32, i32]
+    L.dbf_admm_workspace_bytes.restype = sz
+    L.dbf_admm_step.argtypes = [vp, vp, i32, i32, C.c_float, i32, vp, vp, vp, vp, vp, sz, vp]
     L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
     L.dbf_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp, C.POINTER(C.c_double)]
     L.dbf_strerror.argtypes = [i32]
@@ -205,6 +208,16 @@ def dbf_svid_workspace_bytes(rows: int, cols: int) -> int:
 def dbf_svid(z_ptr: int, rows: int, cols: int, iters: int, a_ptr: int, m_ptr: int, bits_ptr: int, ws_ptr: int,
              ws_bytes: int, stream: int = 0) -> None:
     _check(lib().dbf_svid(z_ptr, rows, cols, iters, a_ptr, m_ptr, bits_ptr, ws_ptr, ws_bytes, stream), "dbf_svid")
+
+
+def dbf_admm_workspace_bytes(q: int, r: int) -> int:
+    return int(lib().dbf_admm_workspace_bytes(q, r))
+
+
+def dbf_admm_step(minv_ptr: int, c_ptr: int, q: int, r: int, rho: float, svid_iters: int, a_ptr: int, m_ptr: int,
+                  bits_ptr: int, u_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
+    _check(lib().dbf_admm_step(minv_ptr, c_ptr, q, r, float(rho), svid_iters, a_ptr, m_ptr, bits_ptr, u_ptr,
+                               ws_ptr, ws_bytes, stream), "dbf_admm_step")
 
 
 def dbf_unpack_bits(layer: Layer):

@@ -28,6 +28,7 @@ SOURCES = [
     "dbf_probe.hip",
     "dbf_prune.hip",
     "dbf_svid.hip",
+    "dbf_admm.hip",
 ]
 
 FLAGS = [

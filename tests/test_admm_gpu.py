@@ -1,0 +1,152 @@
+"""GPU parity of one ADMM update (section 3.2; dbf_admm_step) against the oracle's admm_step_from() on
+the same seeded operands.  The two constant matrices Minv = (B^T B + rho I)^-1 and C = B^T W are formed
+here with numpy in fp64 and rounded to fp32; both sides start from those fp32 values.
+
+What is compared, and why these gates:
+  * Z = W_hat + U is not an output, but the outputs determine it: U' + a' . S' . m'^T = Z up to fp32
+    rounding of the last subtraction.  That sum is compared with the oracle's Z.  Each entry of Z is an
+    fp32 sum of q <= 2048 products on the matrix cores: error bound q * 2^-24 * sum|terms|, typically
+    sqrt(q) * 2^-24 of the row's scale, i.e. 1e-6 .. 1e-5 of rms(Z).  Gate: 1e-4 of rms(Z).
+  * the signs S' are those of the oracle's Z wherever |Z| exceeds that gate (closer to zero either sign
+    is right: the decision is taken on a value that differs by rounding; the first check covers them);
+  * a', m' as in the SVID test: 2e-4 of the largest entry, plus the gate on Z;
+  * U' against the oracle where the signs are decided: U' = Z - a' m' s, so 5e-4 of max(a') max(m').
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_util as G
+from oracle import dbf_oracle as O
+from paper_2505_11076_amd import binding as B
+from paper_2505_11076_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+Z_GATE = 1e-4
+VEC_TOL = 2e-4 + Z_GATE
+U_TOL = 5e-4
+
+
+def _constants(Bm, W, rho):
+    B64, W64 = Bm.astype(np.float64), W.astype(np.float64)
+    Minv = np.linalg.inv(B64.T @ B64 + rho * np.eye(B64.shape[1]))
+    return Minv.astype(np.float32), (B64.T @ W64).astype(np.float32)
+
+
+class DeviceState:
+    """The iterate (a, m, packed S, U) on the device, plus the constants and the workspace."""
+
+    def __init__(self, Minv, C, S, a, m, U):
+        self.q, self.r = C.shape
+        self.Minv = torch.from_numpy(Minv.copy()).cuda()
+        self.C = torch.from_numpy(C.copy()).cuda()
+        self.a = torch.from_numpy(a.copy()).cuda()
+        self.m = torch.from_numpy(m.copy()).cuda()
+        self.U = torch.from_numpy(U.copy()).cuda()
+        tiled = B.dbf_tile_host(self.q, self.r, O.pack_signs(S.astype(np.float64)))
+        self.bits = torch.from_numpy(tiled.copy()).cuda()
+        self.wsb = B.dbf_admm_workspace_bytes(self.q, self.r)
+        self.ws = torch.full((self.wsb,), 0xA5, dtype=torch.uint8, device="cuda")
+
+    def step(self, rho, iters):
+        B.dbf_admm_step(self.Minv.data_ptr(), self.C.data_ptr(), self.q, self.r, rho, iters, self.a.data_ptr(),
+                        self.m.data_ptr(), self.bits.data_ptr(), self.U.data_ptr(), self.ws.data_ptr(), self.wsb,
+                        G.stream_handle())
+        torch.cuda.synchronize()
+
+    def host(self):
+        words = B.dbf_untile_host(self.q, self.r, self.bits.cpu().numpy())
+        S = O.unpack_signs(words, self.q, self.r)
+        return S, self.a.cpu().numpy().astype(np.float64), self.m.cpu().numpy().astype(np.float64), \
+            self.U.cpu().numpy().astype(np.float64)
+
+
+def _check_step(what, before, after, Minv, C, rho, iters):
+    S0, a0, m0, U0 = before
+    S1, a1, m1, U1 = after
+    S_ref, a_ref, m_ref, U_ref, W_hat = O.admm_step_from(Minv.astype(np.float64), C.astype(np.float64), rho, S0, a0,
+                                                         m0, U0, iters)
+    Z_ref = W_hat + U0
+    rms = np.sqrt(np.mean(Z_ref ** 2))
+    assert np.all(np.isfinite(U1)) and np.all(np.isfinite(a1)) and np.all(np.isfinite(m1)), what
+    Z_gpu = U1 + a1[:, None] * S1 * m1[None, :]
+    ez = np.max(np.abs(Z_gpu - Z_ref)) / rms
+    decided = np.abs(Z_ref) > Z_GATE * rms
+    ea = np.max(np.abs(a1 - a_ref)) / np.max(np.abs(a_ref))
+    em = np.max(np.abs(m1 - m_ref)) / np.max(np.abs(m_ref))
+    eu = np.max(np.abs(U1 - U_ref)[decided]) / (np.max(a_ref) * np.max(m_ref))
+    G.say("  %s: Z err %.2e of rms (gate %.0e), undecided signs %d of %d, a %.2e m %.2e (tol %.1e), U %.2e (tol %.0e)"
+          % (what, ez, Z_GATE, int(np.sum(~decided)), decided.size, ea, em, VEC_TOL, eu, U_TOL))
+    assert ez <= Z_GATE, what
+    assert np.array_equal(S1[decided], S_ref[decided]), what + ": sign bits differ"
+    assert np.sum(~decided) <= max(4, decided.size // 1000), what
+    assert ea <= VEC_TOL and em <= VEC_TOL, what
+    assert eu <= U_TOL, what
+
+
+@pytest.mark.parametrize("shape", [(96, 64, 80), (300, 200, 333), (520, 260, 516), (40, 3, 5), (700, 513, 1030)])
+@pytest.mark.parametrize("rho,iters", [(1.0, 1), (0.5, 3)])
+def test_admm_step_matches_the_oracle(shape, rho, iters):
+    p, q, r = shape
+    G.say("start admm p=%d q=%d r=%d rho=%g iters=%d" % (p, q, r, rho, iters))
+    Bm, W, S, a, m, U = I.make_admm_problem(p, q, r, I.seed_for(9, p + q + r))
+    Minv, C = _constants(Bm, W, rho)
+    dev = DeviceState(Minv, C, S, a, m, U)
+    state0 = dev.host()
+    dev.step(rho, iters)
+    state1 = dev.host()
+    _check_step("step 1", state0, state1, Minv, C, rho, iters)
+    # a second update from the device's own state (each update is checked from the inputs it was given)
+    dev.step(rho, iters)
+    _check_step("step 2", state1, dev.host(), Minv, C, rho, iters)
+
+
+def test_admm_step_at_full_size():
+    """The size bench.py times: a 4096 x 4096 weight at 1 bit per weight, i.e. q = k = 2048 middle channels,
+    r = 4096; the oracle still takes only seconds there, so everything is compared."""
+    p, q, r, rho, iters = 4096, 2048, 4096, 1.0, 2
+    G.say("start admm full size p=%d q=%d r=%d" % (p, q, r))
+    Bm, W, S, a, m, U = I.make_admm_problem(p, q, r, I.seed_for(9, 1))
+    Minv, C = _constants(Bm, W, rho)
+    G.say("  constants formed")
+    dev = DeviceState(Minv, C, S, a, m, U)
+    state0 = dev.host()
+    dev.step(rho, iters)
+    _check_step("full size", state0, dev.host(), Minv, C, rho, iters)
+
+
+def test_admm_fixed_point_on_an_exactly_factorisable_target():
+    """W = B A* with A* of the SVID form and U = 0: the update must give A* back and leave U at zero
+    (to fp32 accuracy)."""
+    p, q, r = 300, 128, 192
+    Bm, _, S, a, m, _ = I.make_admm_problem(p, q, r, 5)
+    A_star = a[:, None].astype(np.float64) * S * m[None, :]
+    W = (Bm.astype(np.float64) @ A_star).astype(np.float32)
+    Minv, C = _constants(Bm, W, 1.0)
+    dev = DeviceState(Minv, C, S, a, m, np.zeros((q, r), dtype=np.float32))
+    dev.step(1.0, 2)
+    S1, a1, m1, U1 = dev.host()
+    assert np.array_equal(S1, S.astype(np.float64))
+    assert np.max(np.abs(np.outer(a1, m1) - np.outer(a, m))) <= 1e-4 * np.max(np.outer(a, m))
+    assert np.max(np.abs(U1)) <= 1e-4 * np.max(np.abs(A_star))
+
+
+def test_admm_argument_errors():
+    q, r = 8, 8
+    f = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda")
+    Minv, C, a, m, U = f(q, q), f(q, r), f(q), f(r), f(q, r)
+    bits = torch.zeros(B.dbf_tiled_bytes(q, r), dtype=torch.uint8, device="cuda")
+    wsb = B.dbf_admm_workspace_bytes(q, r)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    assert B.dbf_admm_workspace_bytes(0, 4) == 0 and wsb >= 2 * 4 * q * r
+    ok = (Minv.data_ptr(), C.data_ptr(), q, r, 1.0, 1, a.data_ptr(), m.data_ptr(), bits.data_ptr(), U.data_ptr(),
+          ws.data_ptr(), wsb, 0)
+    B.dbf_admm_step(*ok)
+    torch.cuda.synchronize()
+    for pos, val in ((0, 0), (1, 0), (2, 0), (3, 0), (4, 0.0), (4, -1.0), (4, float("inf")), (5, 0), (6, 0), (7, 0),
+                     (8, 0), (9, 0), (10, 0), (11, wsb - 1), (10, ws.data_ptr() + 4), (9, U.data_ptr() + 2)):
+        bad = list(ok)
+        bad[pos] = val
+        with pytest.raises(B.DbfError):
+            B.dbf_admm_step(*bad)

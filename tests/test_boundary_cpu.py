@@ -180,6 +180,8 @@ def test_launch_argument_errors():
     assert lib.dbf_prune_middle(None, None, 1, C.byref(h)) == B.DBF_EINVAL
     assert lib.dbf_svid(None, 4, 4, 1, None, None, None, None, 0, None) == B.DBF_EINVAL
     assert lib.dbf_svid_workspace_bytes(0, 4) == 0 and lib.dbf_svid_workspace_bytes(64, 64) > 0
+    assert lib.dbf_admm_step(None, None, 4, 4, 1.0, 1, None, None, None, None, None, 0, None) == B.DBF_EINVAL
+    assert lib.dbf_admm_workspace_bytes(0, 4) == 0 and lib.dbf_admm_workspace_bytes(64, 64) >= 2 * 4 * 64 * 64
     assert lib.dbf_stack_create_grouped(arr, 1, None, 0, C.byref(h)) == B.DBF_EINVAL
     assert lib.dbf_stack_gemv(None, 1, 1, 1, 0, None) == B.DBF_EINVAL
     assert lib.dbf_stack_offsets(None, 0, 1, None, None) == B.DBF_EINVAL
