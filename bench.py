@@ -32,6 +32,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 matrix-core peak
 MFMA_I8_PEAK_TOPS = 5000.0     # dense int8 matrix-core peak
+MFMA_F32_PEAK_TFLOPS = 157.3   # dense fp32 matrix-core peak
 
 
 def algorithmic_bytes(n_in, n_out, k, batch):
@@ -71,6 +72,8 @@ def main():
                     help="only the middle-channel pruning measurement (dbf_prune_middle on two config-4 shaped layers)")
     ap.add_argument("--svid", action="store_true",
                     help="only the SVID projection measurement (dbf_svid on a 4096 x 4096 and an 11008 x 4096 matrix)")
+    ap.add_argument("--admm", action="store_true",
+                    help="only the ADMM update measurement (dbf_admm_step for a 4096 x 4096 weight at 1 and 2 bits)")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -102,6 +105,9 @@ def main():
         return
     if args.svid:
         print(json.dumps({"svid": svid_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
+        return
+    if args.admm:
+        print(json.dumps({"admm": admm_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
         return
     if args.table4:
         print(json.dumps({"table4": table4_bench(B, I, torch, np, args.batch, kind,
@@ -467,6 +473,52 @@ def svid_bench(B, I, torch, np, stream, iters=8):
             "ms_per_call": round(ms, 4), "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "cpu_oracle_s": round(cpu_s, 3)}
+    return res
+
+
+def admm_bench(B, I, torch, np, stream, svid_iters=2, rho=1.0):
+    """dbf_admm_step for the factor of a 4096 x 4096 weight with q = 2048 and q = 4096 middle channels (1 and 2
+    bits per weight): the q x q x r fp32 contraction dominates (2 q^2 r flops, priced against the fp32
+    matrix-core peak); around it the step reads or writes a q x r fp32 matrix 7 + 2 * svid_iters times
+    (C, U in, R out; R in; U in, Z out; Z in for the signs and twice per round; Z in, U out).
+    The constant matrices are formed with numpy beforehand (not timed: once per outer iteration)."""
+    res = {}
+    for p, q, r in ((4096, 2048, 4096), (4096, 4096, 4096)):
+        Bm, W, S, a, m, U = I.make_admm_problem(p, q, r, I.seed_for(9, q))
+        B64 = Bm.astype(np.float64)
+        Minv = np.linalg.inv(B64.T @ B64 + rho * np.eye(q)).astype(np.float32)
+        Cm = (B64.T @ W.astype(np.float64)).astype(np.float32)
+        words = B.dbf_signs_to_bits_host(S)
+        d = {"Minv": torch.from_numpy(Minv).cuda(), "C": torch.from_numpy(Cm).cuda(), "a": torch.from_numpy(a).cuda(),
+             "m": torch.from_numpy(m).cuda(), "U": torch.from_numpy(U).cuda(),
+             "bits": torch.from_numpy(B.dbf_tile_host(q, r, words)).cuda()}
+        wsb = B.dbf_admm_workspace_bytes(q, r)
+        ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+        args = (d["Minv"].data_ptr(), d["C"].data_ptr(), q, r, rho, svid_iters, d["a"].data_ptr(), d["m"].data_ptr(),
+                d["bits"].data_ptr(), d["U"].data_ptr(), ws.data_ptr(), wsb, stream)
+        for _ in range(3):
+            B.dbf_admm_step(*args)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 20
+        e0.record()
+        for _ in range(n):
+            B.dbf_admm_step(*args)   # every call is the next ADMM iteration on the updated iterate
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        flops = 2.0 * q * q * r
+        nbytes = (7.0 + 2.0 * svid_iters) * q * r * 4.0 + 4.0 * q * q
+        t0 = time.time()
+        from oracle import dbf_oracle as O
+        O.admm_step_from(Minv.astype(np.float64), Cm.astype(np.float64), rho, S.astype(np.float64),
+                         a.astype(np.float64), m.astype(np.float64), U.astype(np.float64), svid_iters)
+        cpu_s = time.time() - t0
+        res["q%d_r%d_svid%d" % (q, r, svid_iters)] = {
+            "ms_per_step": round(ms, 4), "contraction_flops": flops,
+            "tflops_whole_step": round(flops / (ms * 1e-3) / 1e12, 2),
+            "frac_of_f32_mfma_peak_whole_step": round(flops / (ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+            "elementwise_bytes": nbytes, "cpu_oracle_s": round(cpu_s, 3)}
     return res
 
 

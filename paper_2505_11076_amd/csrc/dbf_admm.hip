@@ -105,7 +105,10 @@ __global__ __launch_bounds__(256) void dbf_admm_elementwise_kernel(const float* 
 // blocks: the R tiles it needs stay in its own L2.
 // ---------------------------------------------------------------------------------------------
 constexpr int GT = 128;         // outputs per workgroup side
-constexpr int GK = 16;          // values of k per step
+#ifndef DBF_ADMM_GK
+#define DBF_ADMM_GK 16
+#endif
+constexpr int GK = DBF_ADMM_GK; // values of k per step
 constexpr int GLD = GT + 32;    // LDS row length in floats
 
 struct GemmArgs {
@@ -142,19 +145,20 @@ __global__ __launch_bounds__(256) void dbf_admm_gemm_kernel(const GemmArgs g) {
     const int wi = (w & 1) * 64, wj = (w >> 1) * 64;  // this wavefront's 64 x 64 corner in the tile
     const int l32 = lane & 31, h = lane >> 5;
 
-    // staging role: two 16-byte pieces of each tile per thread: rows k = tid / 32 and + 8, columns 4 (tid % 32)
+    // staging role: GK / 8 16-byte pieces of each tile per thread: rows k = tid / 32 (+ 8, ...), columns 4 (tid % 32)
+    constexpr int NP = GK / 8;
     const int sk = tid >> 5, sc = 4 * (tid & 31);
-    v4f ra[2], rb[2];
+    v4f ra[NP], rb[NP];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
+        for (int e = 0; e < NP; ++e) {
             ra[e] = load_row4(g.Mt, (size_t)g.M, k0 + sk + 8 * e, g.K, i0 + sc, g.M, g.vec_m);
             rb[e] = load_row4(g.R, (size_t)g.N, k0 + sk + 8 * e, g.K, j0 + sc, g.N, g.vec_n);
         }
     };
     auto stage = [&](int buf) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
+        for (int e = 0; e < NP; ++e) {
             *reinterpret_cast<v4f*>(&As[buf][sk + 8 * e][sc]) = ra[e];
             *reinterpret_cast<v4f*>(&Bs[buf][sk + 8 * e][sc]) = rb[e];
         }
@@ -168,24 +172,63 @@ __global__ __launch_bounds__(256) void dbf_admm_gemm_kernel(const GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[bi][bj][v] = 0.f;
 
-    fetch(0);
-    stage(0);
-    __syncthreads();
     const int steps = (g.K + GK - 1) / GK;
-    for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < steps) fetch((s + 1) * GK);
+    // (the operand values of k pair kk + 1 are read from LDS before the matrix instructions of pair kk are
+    // issued, into the other of two register sets: the LDS latency then hides behind 256 cycles of matrix work)
+    auto multiply = [&](int buf) {
+        float fa[2][2], fb[2][2];
+        auto read_pair = [&](int kk, int set) {
+            fa[set][0] = As[buf][2 * kk + h][wi + l32];
+            fa[set][1] = As[buf][2 * kk + h][wi + 32 + l32];
+            fb[set][0] = Bs[buf][2 * kk + h][wj + l32];
+            fb[set][1] = Bs[buf][2 * kk + h][wj + 32 + l32];
+        };
+        read_pair(0, 0);
 #pragma unroll
         for (int kk = 0; kk < GK / 2; ++kk) {
-            const float a0 = As[buf][2 * kk + h][wi + l32], a1 = As[buf][2 * kk + h][wi + 32 + l32];
-            const float b0 = Bs[buf][2 * kk + h][wj + l32], b1 = Bs[buf][2 * kk + h][wj + 32 + l32];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            const int set = kk & 1;
+            if (kk + 1 < GK / 2) read_pair(kk + 1, set ^ 1);
+            __builtin_amdgcn_sched_barrier(0);  // (keeps the reads above the matrix instructions)
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0], fb[set][0], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0], fb[set][1], acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][1], fb[set][0], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][1], fb[set][1], acc[1][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (s + 1 < steps) stage(buf ^ 1);
+    };
+    // A workgroup whose tiles lie wholly inside both operands (and whose rows can be read in 16-byte pieces)
+    // takes a loop without a single branch: guarded loads put a wait for memory between the request and the
+    // matrix instructions of every step.  The last step requests its own tiles once more instead of none.
+    const bool inside = g.vec_m && g.vec_n && i0 + GT <= g.M && j0 + GT <= g.N && g.K % GK == 0;
+    if (inside) {
+        const float* pa = g.Mt + (size_t)sk * g.M + i0 + sc;
+        const float* pb = g.R + (size_t)sk * g.N + j0 + sc;
+        auto fetch_inside = [&](int k0) {
+#pragma unroll
+            for (int e = 0; e < NP; ++e) {
+                ra[e] = *reinterpret_cast<const v4f*>(pa + (size_t)(k0 + 8 * e) * g.M);
+                rb[e] = *reinterpret_cast<const v4f*>(pb + (size_t)(k0 + 8 * e) * g.N);
+            }
+        };
+        fetch_inside(0);
+        stage(0);
         __syncthreads();
+        for (int s = 0; s < steps; ++s) {
+            fetch_inside(min(s + 1, steps - 1) * GK);
+            multiply(s & 1);
+            stage((s & 1) ^ 1);
+            __syncthreads();
+        }
+    } else {
+        fetch(0);
+        stage(0);
+        __syncthreads();
+        for (int s = 0; s < steps; ++s) {
+            if (s + 1 < steps) fetch((s + 1) * GK);
+            multiply(s & 1);
+            if (s + 1 < steps) stage((s & 1) ^ 1);
+            __syncthreads();
+        }
     }
 
     // epilogue: register v of lane l of a 32 x 32 block is row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
