@@ -194,7 +194,8 @@ int dbf_prune_middle(const dbf_layer* layer, const int32_t* keep, int n_keep, db
  * the projection step of the ADMM iteration that computes the factorisation.  Readings where the
  * paper is silent: Sign(0) = +1; the iteration starts from the constant unit vector and runs
  * `iters` (>= 1) rounds of  u <- |Z| v / ||.||,  v <- |Z|^T u,  sigma <- ||v||,  v <- v / sigma;
- * a = sigma u, m = v (so ||m|| = 1).
+ * a = sigma u, m = v (so ||m|| = 1).  (The kernels keep the iterate unnormalised between the passes
+ * and divide at the end: the same values up to fp32 rounding.)
  *   Z_dev:    device, fp32 [rows][cols] row major (read only); NaNs are not supported.
  *   a_dev:    device, fp32 [rows] out;   m_dev: device, fp32 [cols] out (also used as the iterate).
  *   bits_dev: device, dbf_tiled_bytes(rows, cols) bytes out: Sign(Z) in the tile layout of this

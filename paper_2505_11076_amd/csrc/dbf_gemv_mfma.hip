@@ -524,7 +524,6 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         const int col = 16 * gi + c;
         xrow[gi] = (col < ncols ? col : col % ncols) * chs + 16 * g;
     }
-    const int xo_max = (ch_tiles - 1) * 64;  // padded steps read a valid (ignored) operand
     // one pass: the whole row is in LDS at its own column offsets; otherwise LDS holds the current chunk
     const int xo_base = one_pass ? ct_first * 64 : 0;
     // epilogue coordinates: thread -> (row rho of the tile, batch rows bi = tid>>7, +2, ...)

@@ -8,12 +8,16 @@
 //     u <- |Z| v / ||.||,   v <- |Z|^T u,   sigma <- ||v||,   v <- v / sigma;      a = sigma u,  m = v.
 //
 // Everything is bound by reading Z (fp32, rows x cols, row major): two passes per round (row dots,
-// column dots) and one for the signs.  All reductions have a fixed order, so the result does not
-// depend on scheduling:
+// column dots) and one for the signs.  A round is three launches: the normalisations are not passes of
+// their own.  The iterate is kept unnormalised (u_raw = |Z| v, v_raw = |Z|^T u_raw; the length of u
+// cancels in v / ||v||), the column reduction leaves the squared length of v_raw as one partial sum per
+// workgroup, and the next row pass scales by 1 / ||v_raw|| on the fly; the last kernel forms
+// m = v_raw / ||v_raw|| and a = sigma u = u_raw ||v_raw|| / ||u_raw||^2.  All reductions have a fixed
+// order, so the result does not depend on scheduling:
 //   row dots     one wavefront per row, 16-byte loads, butterfly reduction;
 //   column dots  workgroup = 256 columns x 64 rows (4 row lanes x 16 rows, combined in LDS in lane
 //                order), partial sums per 64-row chunk, then summed over the chunks in a fixed order;
-//   norms        one workgroup, strided partial sums combined in a fixed tree;
+//   norms        partial sums of squares per 64 columns (v) or per thread stride (u), combined in a fixed tree;
 //   signs        one workgroup per 128 x 64 tile, a thread per four bytes of the tile.
 #include "dbf_kernels.h"
 
@@ -30,10 +34,20 @@ __device__ inline float wave_sum_f(float v) {
     return v;
 }
 
-// u[i] = sum_j |Z[i][j]| v[j]
+// Sum of n partial sums in a fixed order (lane-strided, then butterfly); every lane gets the result.
+__device__ inline float wave_total(const float* __restrict__ part, int n, int lane) {
+    float s = 0.f;
+    for (int i = lane; i < n; i += 64) s += part[i];
+    return wave_sum_f(s);
+}
+
+// u_raw[i] = (sum_j |Z[i][j]| v_raw[j]) / ||v_raw||, with ||v_raw||^2 = sum of ss_part[0 .. n_ss).
+// FIRST: the start vector, v = 1 / sqrt(cols) everywhere (v_raw and ss_part are not read).
+template <bool FIRST>
 __global__ __launch_bounds__(256) void dbf_svid_row_dots_kernel(const float* __restrict__ Z, int rows, int cols,
-                                                               const float* __restrict__ v, float* __restrict__ u,
-                                                               int vec_ok) {
+                                                               const float* __restrict__ v,
+                                                               const float* __restrict__ ss_part, int n_ss,
+                                                               float* __restrict__ u, int vec_ok) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
@@ -41,14 +55,26 @@ __global__ __launch_bounds__(256) void dbf_svid_row_dots_kernel(const float* __r
     float s = 0.f;
     if (vec_ok) {
         for (int c = 4 * lane; c < cols; c += 256) {
-            const v4f a = *reinterpret_cast<const v4f*>(z + c), b = *reinterpret_cast<const v4f*>(v + c);
-            s += fabsf(a.x) * b.x + fabsf(a.y) * b.y + fabsf(a.z) * b.z + fabsf(a.w) * b.w;
+            const v4f a = *reinterpret_cast<const v4f*>(z + c);
+            if (FIRST) {
+                s += (fabsf(a.x) + fabsf(a.y)) + (fabsf(a.z) + fabsf(a.w));
+            } else {
+                const v4f b = *reinterpret_cast<const v4f*>(v + c);
+                s += fabsf(a.x) * b.x + fabsf(a.y) * b.y + fabsf(a.z) * b.z + fabsf(a.w) * b.w;
+            }
         }
     } else {
-        for (int c = lane; c < cols; c += 64) s += fabsf(z[c]) * v[c];
+        for (int c = lane; c < cols; c += 64) s += FIRST ? fabsf(z[c]) : fabsf(z[c]) * v[c];
     }
     s = wave_sum_f(s);
-    if (lane == 0) u[row] = s;
+    float inv;
+    if (FIRST) {
+        inv = 1.0f / sqrtf((float)cols);
+    } else {
+        const float nrm = sqrtf(wave_total(ss_part, n_ss, lane));
+        inv = nrm > 0.f ? 1.0f / nrm : 0.f;
+    }
+    if (lane == 0) u[row] = s * inv;
 }
 
 // partial[chunk][j] = sum over the chunk's rows i of |Z[i][j]| u[i]
@@ -91,53 +117,52 @@ __global__ __launch_bounds__(256) void dbf_svid_col_dots_kernel(const float* __r
         partial[(size_t)blockIdx.y * cols + blockIdx.x * COL_BLOCK + c] = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
 }
 
-// v[j] = sum over chunks of partial[chunk][j]: four interleaved running sums (chunks c = 0, 4, 8, ... in the
-// first, and so on; the loads of a round are independent), combined as ((s0 + s1) + s2) + s3.
+// v_raw[j] = sum over chunks of partial[chunk][j]: four interleaved running sums (chunks c = 0, 4, 8, ... in the
+// first, and so on; the loads of a round are independent), combined as ((s0 + s1) + s2) + s3; and
+// ss_part[workgroup] = sum of v_raw[j]^2 over the workgroup's 64 columns (butterfly order).
 // 64 threads per workgroup, so that even 4096 columns spread over 64 compute units.
 __global__ __launch_bounds__(64) void dbf_svid_col_reduce_kernel(const float* __restrict__ partial, int chunks, int cols,
-                                                              float* __restrict__ v) {
+                                                              float* __restrict__ v, float* __restrict__ ss_part) {
     const int j = blockIdx.x * 64 + threadIdx.x;
-    if (j >= cols) return;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    int c = 0;
-    for (; c + 4 <= chunks; c += 4) {
-        s0 += partial[(size_t)(c + 0) * cols + j];
-        s1 += partial[(size_t)(c + 1) * cols + j];
-        s2 += partial[(size_t)(c + 2) * cols + j];
-        s3 += partial[(size_t)(c + 3) * cols + j];
+    if (j < cols) {
+        int c = 0;
+        for (; c + 4 <= chunks; c += 4) {
+            s0 += partial[(size_t)(c + 0) * cols + j];
+            s1 += partial[(size_t)(c + 1) * cols + j];
+            s2 += partial[(size_t)(c + 2) * cols + j];
+            s3 += partial[(size_t)(c + 3) * cols + j];
+        }
+        if (c + 0 < chunks) s0 += partial[(size_t)(c + 0) * cols + j];
+        if (c + 1 < chunks) s1 += partial[(size_t)(c + 1) * cols + j];
+        if (c + 2 < chunks) s2 += partial[(size_t)(c + 2) * cols + j];
     }
-    if (c + 0 < chunks) s0 += partial[(size_t)(c + 0) * cols + j];
-    if (c + 1 < chunks) s1 += partial[(size_t)(c + 1) * cols + j];
-    if (c + 2 < chunks) s2 += partial[(size_t)(c + 2) * cols + j];
-    v[j] = ((s0 + s1) + s2) + s3;
+    const float vj = ((s0 + s1) + s2) + s3;
+    if (j < cols) v[j] = vj;
+    const float ss = wave_sum_f(vj * vj);
+    if (threadIdx.x == 0) ss_part[blockIdx.x] = ss;
 }
 
-// x <- x / ||x||, *norm = ||x|| (x unchanged if the norm is zero).  One workgroup of 1024 threads.
-__global__ __launch_bounds__(1024) void dbf_svid_normalise_kernel(float* __restrict__ x, int len, float* __restrict__ norm) {
-    __shared__ float part[1024];
+// The two factors from the unnormalised iterate: m = v_raw / ||v_raw|| (in place) and
+// a = sigma u = u_raw ||v_raw|| / ||u_raw||^2 (sigma = ||v_raw|| / ||u_raw||, u = u_raw / ||u_raw||).
+// Every workgroup forms both lengths itself, in the same fixed order, and then writes its 256 entries of each.
+__global__ __launch_bounds__(256) void dbf_svid_finish_kernel(const float* __restrict__ u_raw, int rows,
+                                                             const float* __restrict__ ss_part, int n_ss,
+                                                             float* __restrict__ m, int cols, float* __restrict__ a) {
+    __shared__ float part[256];
     float s = 0.f;
-    for (int i = threadIdx.x; i < len; i += 1024) s += x[i] * x[i];
+    for (int i = threadIdx.x; i < rows; i += 256) s += u_raw[i] * u_raw[i];
     part[threadIdx.x] = s;
     __syncthreads();
-    for (int w = 512; w >= 1; w >>= 1) {
+    for (int w = 128; w >= 1; w >>= 1) {
         if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
         __syncthreads();
     }
-    const float nrm = sqrtf(part[0]);
-    if (threadIdx.x == 0) *norm = nrm;
-    if (nrm > 0.f)
-        for (int i = threadIdx.x; i < len; i += 1024) x[i] = x[i] / nrm;
-}
-
-__global__ void dbf_svid_fill_kernel(float* __restrict__ x, int len, float value) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < len) x[i] = value;
-}
-
-// a[i] = sigma u[i]
-__global__ void dbf_svid_scale_kernel(const float* __restrict__ u, const float* __restrict__ sigma, int len, float* __restrict__ a) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < len) a[i] = *sigma * u[i];
+    const float ssu = part[0];
+    const float nv = sqrtf(wave_total(ss_part, n_ss, threadIdx.x & 63));
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < rows) a[i] = ssu > 0.f ? u_raw[i] * (nv / ssu) : 0.f;
+    if (i < cols && nv > 0.f) m[i] = m[i] / nv;
 }
 
 // Sign(Z) into the tile layout: tile = 128 rows x 64 columns, byte 256 g + 16 r + j, bit s = sign of
@@ -180,7 +205,7 @@ inline SvidWorkspace svid_workspace(int rows, int cols) {
     w.u = off;        off = up256(off + 4 * (size_t)rows);
     w.v = off;        off = up256(off + 4 * (size_t)cols);
     w.partial = off;  off = up256(off + 4 * chunks * (size_t)cols);
-    w.scalars = off;  off = up256(off + 16);
+    w.scalars = off;  off = up256(off + 4 * (((size_t)cols + 63) / 64));   // squared length of v_raw per 64 columns
     w.total = off;
     return w;
 }
@@ -208,27 +233,29 @@ extern "C" int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* 
     float* u = reinterpret_cast<float*>(base + w.u);
     float* v = static_cast<float*>(m_dev);   // the right factor is iterated in place in the caller's buffer
     float* partial = reinterpret_cast<float*>(base + w.partial);
-    float* nrm_u = reinterpret_cast<float*>(base + w.scalars);
-    float* sigma = nrm_u + 1;
+    float* ss_part = reinterpret_cast<float*>(base + w.scalars);
     const int vec_ok = ((cols & 3) == 0 && (reinterpret_cast<uintptr_t>(Z_dev) & 15) == 0 &&
                         (reinterpret_cast<uintptr_t>(m_dev) & 15) == 0) ? 1 : 0;
     const int chunks = (rows + COL_CHUNK_ROWS - 1) / COL_CHUNK_ROWS;
     const int n_rt = dbf_row_tiles(rows), n_ct = dbf_col_tiles(cols);
+    const int n_ss = (cols + 63) / 64;
 
     hipLaunchKernelGGL(dbf_svid_signs_kernel, dim3(n_ct, n_rt), dim3(256), 0, st, Z, rows, cols, n_ct,
                        static_cast<uint8_t*>(bits_dev));
-    hipLaunchKernelGGL(dbf_svid_fill_kernel, dim3((cols + 255) / 256), dim3(256), 0, st, v, cols,
-                       1.0f / sqrtf((float)cols));
     for (int it = 0; it < iters; ++it) {
-        hipLaunchKernelGGL(dbf_svid_row_dots_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, Z, rows, cols, v, u, vec_ok);
-        hipLaunchKernelGGL(dbf_svid_normalise_kernel, dim3(1), dim3(1024), 0, st, u, rows, nrm_u);
+        if (it == 0)
+            hipLaunchKernelGGL(dbf_svid_row_dots_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, st, Z, rows, cols, v,
+                               ss_part, n_ss, u, vec_ok);
+        else
+            hipLaunchKernelGGL(dbf_svid_row_dots_kernel<false>, dim3((rows + 3) / 4), dim3(256), 0, st, Z, rows, cols, v,
+                               ss_part, n_ss, u, vec_ok);
         hipLaunchKernelGGL(dbf_svid_col_dots_kernel, dim3((cols + COL_BLOCK - 1) / COL_BLOCK, chunks), dim3(256), 0, st,
                            Z, rows, cols, u, partial);
-        hipLaunchKernelGGL(dbf_svid_col_reduce_kernel, dim3((cols + 63) / 64), dim3(64), 0, st, partial, chunks, cols, v);
-        hipLaunchKernelGGL(dbf_svid_normalise_kernel, dim3(1), dim3(1024), 0, st, v, cols, sigma);
+        hipLaunchKernelGGL(dbf_svid_col_reduce_kernel, dim3(n_ss), dim3(64), 0, st, partial, chunks, cols, v, ss_part);
     }
-    hipLaunchKernelGGL(dbf_svid_scale_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, u, sigma, rows,
-                       static_cast<float*>(a_dev));
+    const int longest = rows > cols ? rows : cols;
+    hipLaunchKernelGGL(dbf_svid_finish_kernel, dim3((longest + 255) / 256), dim3(256), 0, st, u, rows, ss_part, n_ss, v,
+                       cols, static_cast<float*>(a_dev));
     if (hipGetLastError() != hipSuccess) return DBF_EHIP;
     return DBF_OK;
 }
