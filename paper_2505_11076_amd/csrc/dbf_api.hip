@@ -64,7 +64,7 @@ void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool
 // alone).  So rows of up to PIECE_NEVER_TILES column tiles are never cut, pieces hold at least
 // PIECE_MIN_TILES tiles, and a stage is cut until it offers about PIECE_TARGET_ITEMS workgroups.
 // Environment overrides (experiments and tests): DBF_COL_PIECES = 0 never cut / N cut into N where it
-// fits; DBF_PIECE_TARGET, DBF_PIECE_MIN_TILES, DBF_PIECE_NEVER_TILES.
+// fits; DBF_PIECE_TARGET, DBF_PIECE_MIN_TILES, DBF_PIECE_NEVER_TILES, DBF_PIECE_MAX_ROW_TILES.
 constexpr int PIECE_MIN_TILES = 24;
 constexpr int PIECE_NEVER_TILES = 64;
 constexpr int PIECE_TARGET_ITEMS = 256;
@@ -201,7 +201,8 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     std::vector<int> pcB(n, 1), pcA(n, 1);
     bool cut = false;
-    if (rtB <= PIECE_MAX_ROW_TILES && rtA <= PIECE_MAX_ROW_TILES) {
+    const int max_rt = env_int("DBF_PIECE_MAX_ROW_TILES", PIECE_MAX_ROW_TILES);
+    if (rtB <= max_rt && rtA <= max_rt) {
         for (int i = 0; i < n; ++i) {
             pcB[i] = pieces_for(sB[i].n_ct, (int)rtB);
             pcA[i] = pieces_for(sA[i].n_ct, (int)rtA);
