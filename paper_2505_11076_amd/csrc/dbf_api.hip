@@ -52,6 +52,7 @@ void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool
         it.ct0 = 0;
         it.ct_n = st.n_ct;
         it.pieces = 1;
+        it.q_in = st.q_in;
         out.push_back(it);
         rt += it.nrt;
     }
@@ -122,6 +123,7 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
             it.acc_stride = acc_stride;
             it.acc = acc + (size_t)rt * DBF_TILE_ROWS;
             it.cnt = cnt + rt;
+            it.q_in = st.q_in;
             out.push_back(it);
         }
     }
@@ -305,7 +307,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
 
 // Section offsets of a layer's single device block (256-byte aligned sections).
 struct LayerOffsets {
-    size_t A, B, a, m, b, image_bytes, t, total;
+    size_t A, B, a, m, b, image_bytes, t, qB, qA, total;
     int a_len, m_len, b_len, t_stride;
 };
 LayerOffsets layer_offsets(int n_in, int n_out, int k) {
@@ -322,6 +324,8 @@ LayerOffsets layer_offsets(int n_in, int n_out, int k) {
     o.b = off;  off = align_up(off + 2 * (size_t)o.b_len, 256);
     o.image_bytes = off;  // signs and vectors; the scratch follows
     o.t = off;  off = align_up(off + 4 * (size_t)DBF_MAX_BATCH * o.t_stride, 256);
+    o.qB = off;  off = align_up(off + DBF_QIN_HEADER + 2 * (size_t)DBF_MAX_BATCH * o.b_len, 256);
+    o.qA = off;  off = align_up(off + DBF_QIN_HEADER + 2 * (size_t)DBF_MAX_BATCH * dbf_col_tiles(k) * DBF_TILE_COLS, 256);
     o.total = off;
     return o;
 }
@@ -353,17 +357,19 @@ int create_layer(int n_in, int n_out, int k, const LayerOffsets& o, dbf_layer** 
     L->db = reinterpret_cast<uint16_t*>(d + o.b);
     L->dt = reinterpret_cast<float*>(d + o.t);
     L->t_stride = o.t_stride;
+    L->dqB = d + o.qB;
+    L->dqA = d + o.qA;
 
     DbfStage& sb = L->h_stages[0];
     sb.bits = L->dB;  sb.in_scale = L->db;  sb.row_scale = L->dm;  sb.t = L->dt;
     sb.x_off = 0;  sb.y_off = 0;
     sb.n_rt = dbf_row_tiles(k);  sb.n_ct = dbf_col_tiles(n_in);
-    sb.rows = k;  sb.cols = n_in;  sb.t_stride = o.t_stride;  sb.pad_ = 0;
+    sb.rows = k;  sb.cols = n_in;  sb.t_stride = o.t_stride;  sb.pad_ = 0;  sb.q_in = L->dqB;
     DbfStage& sa = L->h_stages[1];
     sa.bits = L->dA;  sa.in_scale = nullptr;  sa.row_scale = L->da;  sa.t = L->dt;
     sa.x_off = 0;  sa.y_off = 0;
     sa.n_rt = dbf_row_tiles(n_out);  sa.n_ct = dbf_col_tiles(k);
-    sa.rows = n_out;  sa.cols = k;  sa.t_stride = o.t_stride;  sa.pad_ = 0;
+    sa.rows = n_out;  sa.cols = k;  sa.t_stride = o.t_stride;  sa.pad_ = 0;  sa.q_in = L->dqA;
     *out = L;
     return DBF_OK;
 }
@@ -450,24 +456,36 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     }
     // several row tiles per workgroup only if all columns of both stages fit one LDS chunk
     const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
-    const bool span = dbf_mfma_chunk_tiles(batch, max_cols) >= dbf_col_tiles(max_cols);
+    const bool use_pieces = pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH;
+    const bool shared_q = pieces_ok && !use_pieces && batch >= 2 && env_int("DBF_SHARED_Q", 1) != 0;
+    const bool span = dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols);
     const DbfItem* items = span ? p.d_items_n : p.d_items_1;
     int nB = span ? p.nBn : p.nB1, nA = span ? p.nAn : p.nA1;
     int pieces = 0;
-    if (pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH) {  // few row tiles: cut them into column pieces
+    if (use_pieces) {  // few row tiles: cut them into column pieces
         items = p.d_items_p;
         nB = p.nBp;
         nA = p.nAp;
         pieces = 1;
     }
+    if (shared_q) {
+        // Batches of 2 and more: every stage input is quantised once per call, then the items copy it.
+        // Four launches: quantise x, B items, quantise t, A items.
+        DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesB, p.n_layers, 0, x, batch, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, 1, stream));
+        if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
+        DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesA, p.n_layers, 1, x, batch, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, 1, stream));
+        return DBF_OK;
+    }
     if (kind == DBF_GEMV_MFMA) {
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, 0, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         return DBF_OK;
     }
-    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, stream));
     if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, stream));
     return DBF_OK;
 }
 

@@ -329,7 +329,10 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // have rows too wide for the one-pass prologue; its input passes keep more loads in flight.  The
 // other instantiation is the hot one (long streams of layers of up to 4096 columns at batch 1)
 // and carries none of that code.
-template <int NCG, bool PIECES>
+// SHARED: the stage input was quantised once for the whole launch by dbf_quantise_inputs_kernel (batches of
+// 2 and more, where every item quantising all batch rows itself would cost more than streaming its tiles):
+// the prologue takes scales and sums from there and copies the int8 planes of its columns into LDS.
+template <int NCG, bool PIECES, bool SHARED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
@@ -453,7 +456,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     cx.nvec = it.n_ct * 8;
     cx.nvec_x = it.cols >> 3;
     cx.fast = stage_a || ((it.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
-    const bool one_pass = cx.fast && batch == 1 && cx.nvec <= 256 * UNR && it.n_ct <= ch_tiles;
+    const bool one_pass = !SHARED && cx.fast && batch == 1 && cx.nvec <= 256 * UNR && it.n_ct <= ch_tiles;
 
     // Every load of the prologue is issued here, back to back and in order of urgency: the row
     // scales and the input vector FIRST (the workgroup cannot start without them), then the first
@@ -510,7 +513,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         if (2 * idx < it.nrt * DBF_TILE_ROWS) reinterpret_cast<unsigned*>(misc->rscale)[idx] = rs_reg[q];
     }
 
-    if (one_pass) {
+    if (SHARED) {
+        if (tid < batch) {  // (the same threads that cleared sigma above)
+            misc->scale[tid] = reinterpret_cast<const float*>(it.q_in)[tid];
+            misc->sigma[tid] = reinterpret_cast<const int*>(it.q_in + 64)[tid];
+        }
+    } else if (one_pass) {
         if (stage_a) input_one_pass<true>(cx, in0, in1); else input_one_pass<false>(cx, in0, in1);
     } else {
         if (stage_a) input_scales<true, IN_W>(it, cx); else input_scales<false, IN_W>(it, cx);
@@ -535,7 +543,16 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     __builtin_amdgcn_s_setprio(0);
 #endif
     for (;;) {  // chunks of columns (a single one unless the batch is large)
-        if (!one_pass) {
+        if (SHARED) {
+            // columns [64 c0, 64 cend) of the 2 * batch planes, 16 bytes per thread and round
+            const unsigned char* planes = it.q_in + DBF_QIN_HEADER + (size_t)c0 * DBF_TILE_COLS;
+            const int per_row = (cend - c0) * (DBF_TILE_COLS / 16);
+            const size_t q_stride = (size_t)it.n_ct * DBF_TILE_COLS;
+            for (int r = 0; r < ncols; ++r)
+                for (int i = tid; i < per_row; i += 256)
+                    *reinterpret_cast<v4u*>(xq + r * chs + 16 * i) =
+                        *reinterpret_cast<const v4u*>(planes + r * q_stride + 16 * (size_t)i);
+        } else if (!one_pass) {
             if (stage_a) input_quantise_chunk<true, IN_W>(it, cx, c0, cend);
             else input_quantise_chunk<false, IN_W>(it, cx, c0, cend);
         }
@@ -723,6 +740,45 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     }
 }
 
+// The input of one stage of every layer of a launch, quantised once: block (layer, batch row) reads the row
+// (x times b, or the fp32 middle activations), finds max|u| and writes q = rint(u * 32512 / max|u|) as two
+// int8 planes, with the scale and the sum of the q in front (DbfStage::q_in).  The arithmetic is that of the
+// items' own prologue (the same functions), so a launch that takes its input from here gives the same bits.
+template <bool STAGE_A>
+__global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage* __restrict__ stages,
+                                                                 const uint16_t* __restrict__ x_base, int batch) {
+    __shared__ Misc misc;
+    const DbfStage st = stages[blockIdx.x];
+    const int bi = blockIdx.y;
+    DbfItem it;
+    it.t = st.t + (size_t)bi * st.t_stride;
+    it.t_stride = st.t_stride;
+    it.in_scale = st.in_scale;
+    it.cols = st.cols;
+    it.n_ct = st.n_ct;
+    const uint16_t* x = x_base + st.x_off * batch;
+    const size_t q_stride = (size_t)st.n_ct * DBF_TILE_COLS;
+    Ctx cx;
+    cx.misc = &misc;
+    cx.xq = reinterpret_cast<signed char*>(st.q_in + DBF_QIN_HEADER + (size_t)(2 * bi) * q_stride);
+    cx.x = x + (size_t)bi * st.cols;
+    cx.chs = (int)q_stride;
+    cx.tid = threadIdx.x;  cx.lane = threadIdx.x & 63;  cx.w = threadIdx.x >> 6;
+    cx.batch = 1;   // this block's row is "batch row 0" of the helpers
+    cx.nvec = st.n_ct * 8;
+    cx.nvec_x = st.cols >> 3;
+    cx.fast = STAGE_A || ((st.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
+    if (threadIdx.x == 0) misc.sigma[0] = 0;
+    __syncthreads();
+    input_scales<STAGE_A, WIDE>(it, cx);
+    input_quantise_chunk<STAGE_A, WIDE>(it, cx, 0, st.n_ct);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        reinterpret_cast<float*>(st.q_in)[bi] = misc.scale[0];
+        reinterpret_cast<int*>(st.q_in + 64)[bi] = misc.sigma[0];
+    }
+}
+
 size_t mfma_smem_bytes(int batch, int ch_tiles) {
     const int ncols = 2 * batch;
     const size_t xq = ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
@@ -733,9 +789,18 @@ size_t mfma_smem_bytes(int batch, int ch_tiles) {
 
 int dbf_mfma_one_pass_cols() { return 256 * UNR * 8; }
 
-int dbf_mfma_chunk_tiles(int batch, int max_cols) {
+int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q) {
     const int ncols = 2 * batch;
-    const int budget = batch > 8 ? 32768 : 28672;  // LDS bytes for the quantised operand
+    // LDS bytes for the quantised operand.  Items that quantise their input themselves keep four workgroups
+    // per compute unit; items that copy a shared quantised input (batches of 2 and more) settle for three
+    // (52 KiB each, of which the reduction buffers take 1 KiB per operand row) if that lets a whole row stay
+    // in LDS, so that an item can take several row tiles.
+    int budget = batch > 8 ? 32768 : 28672;
+    if (shared_q) {
+        const int env = []() { const char* e = std::getenv("DBF_SHARED_LDS_KB"); return e ? std::atoi(e) : 52; }();
+        const int roomy = env * 1024 - (int)sizeof(Misc) - 1024 * ncols;
+        if (roomy > budget) budget = roomy;
+    }
     int ch_tiles = ((budget / ncols - XQ_PAD) / DBF_TILE_COLS) & ~3;
     const int need = (dbf_col_tiles(max_cols) + 3) & ~3;
     if (ch_tiles > need) ch_tiles = need;
@@ -743,23 +808,40 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols) {
     return ch_tiles;
 }
 
+hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, int stage_a, const void* x_base,
+                                      int batch, hipStream_t stream) {
+    if (n_layers <= 0) return hipSuccess;
+    const uint16_t* x = static_cast<const uint16_t*>(x_base);
+    if (stage_a)
+        hipLaunchKernelGGL(dbf_quantise_inputs_kernel<true>, dim3(n_layers, batch), dim3(256), 0, stream, d_stages, x, batch);
+    else
+        hipLaunchKernelGGL(dbf_quantise_inputs_kernel<false>, dim3(n_layers, batch), dim3(256), 0, stream, d_stages, x, batch);
+    return hipGetLastError();
+}
+
 hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, int pieces, hipStream_t stream) {
+                                 int max_cols, int pieces, int shared_q, hipStream_t stream) {
     if (n_items <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
-    const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols);
+    const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols, shared_q);
     const size_t smem = mfma_smem_bytes(batch, ch_tiles);
     // column pieces (small batches only)
-    if (pieces)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
+    if (shared_q && batch <= 8)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else if (shared_q)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else if (pieces)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     return hipGetLastError();
 }

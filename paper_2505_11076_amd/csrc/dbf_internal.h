@@ -31,6 +31,9 @@ struct DbfStage {
     int rows, cols;             // valid rows / cols
     int t_stride;               // elements between batch rows of t
     int pad_;
+    unsigned char* q_in;        // the stage's input quantised once per call (batches of 2 and more):
+                                // float scale[16], int sigma[16], then int8 [2 * 16][n_ct * 64] planes
+                                // (row 2 bi = high bytes, 2 bi + 1 = low bytes of batch row bi)
 };
 
 // Work item of the vector-ALU kernel: one 128-row tile of one layer.
@@ -70,7 +73,9 @@ struct DbfItem {
     int acc_stride;             // elements between batch rows of acc
     int* acc;                   // int32 [DBF_PIECES_MAX_BATCH][acc_stride], this row tile's first row
     int* cnt;                   // arrival counter of this row tile
+    const unsigned char* q_in;  // the stage's quantised input (see DbfStage)
 };
+#define DBF_QIN_HEADER 128      /* bytes of scale[16] + sigma[16] in front of the planes */
 
 // Device-side state of one launch plan: everything a decode call of a layer or a stack needs.
 struct DbfPlan {
@@ -108,6 +113,8 @@ struct dbf_layer {
     uint16_t* db;           // fp16 [col_tiles(n_in)*64]
     float* dt;              // fp32 [DBF_MAX_BATCH][t_stride]
     int t_stride;
+    unsigned char* dqB;     // quantised input of the B stage (DbfStage::q_in)
+    unsigned char* dqA;     // quantised input of the A stage
     DbfStage h_stages[2];   // {B stage, A stage} with offsets 0
     DbfPlan plan;           // launch plan of this layer alone
 };

@@ -19,13 +19,20 @@ hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfW
 //   their rows there; the last workgroup to finish clears the counters for the next launch.
 //   use_sync == 0: no waiting and no counters (the caller orders the stages by launches).
 // Items with nrt > 1 are allowed only if every item's columns fit one LDS chunk, i.e.
-// dbf_mfma_chunk_tiles(batch, max_cols) >= dbf_col_tiles(max_cols).
+// dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols).
 //   pieces != 0: the list may hold column pieces of row tiles (DbfItem::pieces > 1; one row tile per
 //   item, batch <= DBF_PIECES_MAX_BATCH); pieces == 0: every item covers all columns of its row tiles.
+//   shared_q != 0: the input of the items' stage has been quantised for the whole launch by
+//   dbf_launch_quantise_inputs (same stream, earlier); the items copy it instead of quantising it themselves.
+//   Only with use_sync == 0 and pieces == 0.
 hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, int pieces, hipStream_t stream);
-int dbf_mfma_chunk_tiles(int batch, int max_cols);
+                                 int max_cols, int pieces, int shared_q, hipStream_t stream);
+// Quantises the input of one stage (stage_a = 0: x times b of every layer, 1: the middle activations) of the
+// n_layers stages in d_stages for `batch` rows into the stages' q_in buffers.
+hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, int stage_a, const void* x_base,
+                                      int batch, hipStream_t stream);
+int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q);
 // Widest input row (columns) the matrix-core kernel's one-pass prologue takes at batch 1: such rows are
 // read once and quantised from registers; wider ones are read twice (scale, then quantisation).
 int dbf_mfma_one_pass_cols();
