@@ -457,7 +457,14 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     // several row tiles per workgroup only if all columns of both stages fit one LDS chunk
     const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
     const bool use_pieces = pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH;
-    const bool shared_q = pieces_ok && !use_pieces && batch >= 2 && env_int("DBF_SHARED_Q", 1) != 0;
+    // Batches of 2 and more: every stage input is quantised once per call; the items copy it into LDS (1)
+    // or, if a whole row does not fit there at this batch, read it from memory tile by tile (2).
+    int shared_q = 0;
+    if (pieces_ok && !use_pieces && batch >= 2) {
+        shared_q = dbf_mfma_chunk_tiles(batch, max_cols, 1) >= dbf_col_tiles(max_cols) ? 1 : 2;
+        shared_q = env_int("DBF_SHARED_Q", shared_q);
+        if (shared_q < 0 || shared_q > 2) shared_q = 0;
+    }
     const bool span = dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols);
     const DbfItem* items = span ? p.d_items_n : p.d_items_1;
     int nB = span ? p.nBn : p.nB1, nA = span ? p.nAn : p.nA1;
@@ -469,13 +476,12 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
         pieces = 1;
     }
     if (shared_q) {
-        // Batches of 2 and more: every stage input is quantised once per call, then the items copy it.
         // Four launches: quantise x, B items, quantise t, A items.
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesB, p.n_layers, 0, x, batch, stream));
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, 1, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesA, p.n_layers, 1, x, batch, stream));
-        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, 1, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, stream));
         return DBF_OK;
     }
     if (kind == DBF_GEMV_MFMA) {

@@ -329,10 +329,13 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // have rows too wide for the one-pass prologue; its input passes keep more loads in flight.  The
 // other instantiation is the hot one (long streams of layers of up to 4096 columns at batch 1)
 // and carries none of that code.
-// SHARED: the stage input was quantised once for the whole launch by dbf_quantise_inputs_kernel (batches of
-// 2 and more, where every item quantising all batch rows itself would cost more than streaming its tiles):
-// the prologue takes scales and sums from there and copies the int8 planes of its columns into LDS.
-template <int NCG, bool PIECES, bool SHARED>
+// SHARED != 0: the stage input was quantised once for the whole launch by dbf_quantise_inputs_kernel (batches
+// of 2 and more, where every item quantising all batch rows itself would cost more than streaming its tiles):
+// the prologue takes scales and sums from there.  SHARED == 1: the int8 planes of the item's columns are copied
+// into LDS and read from there as at batch 1.  SHARED == 2 (rows that do not fit the LDS of a workgroup at this
+// batch): no operand in LDS at all; the 16 operand bytes a lane needs for a tile are requested from memory (the
+// planes are L2 resident: every item of the layer reads them) together with the tile, in the same ring.
+template <int NCG, bool PIECES, int SHARED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
@@ -342,7 +345,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
     Misc* misc = reinterpret_cast<Misc*>(smem);
     signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
-    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + ((ncols * chs + 15) & ~15));  // [2][ncols][128]
+    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + (SHARED == 2 ? 0 : ((ncols * chs + 15) & ~15)));  // [2][ncols][128]
 
 #if DBF_PROLOGUE_PRIO
     // (experiment: wavefront priority raised for the prologue.  The arbiter favours older
@@ -393,8 +396,38 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     int steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
     int p_rt = 0, p_i = 0;
     v4u buf[PF];
+    // SHARED == 2: the operand ring.  A second buffer resource covers the 2 * batch planes of the stage; lane
+    // (g, c) of column group gi reads bytes 16 g .. 16 g + 15 of the tile's 64 columns of plane row 16 gi + c
+    // (unused operand columns alias a valid row).  A slot's loads are issued as (tile, operand[0], operand[1]).
+    constexpr int XB_N = SHARED == 2 ? NCG : 1;
+    constexpr int SLOT_LOADS = SHARED == 2 ? 1 + NCG : 1;
+    v4i xb[PF][XB_N];
+    v4u xrsrc = {0, 0, 0, 0};
+    unsigned x_lane_off[XB_N] = {};
+    if (SHARED == 2) {
+        const uint64_t pa = reinterpret_cast<uint64_t>(it.q_in + DBF_QIN_HEADER);
+        xrsrc.x = __builtin_amdgcn_readfirstlane((unsigned)pa);
+        xrsrc.y = __builtin_amdgcn_readfirstlane((unsigned)(pa >> 32) & 0xFFFFu);
+        xrsrc.z = __builtin_amdgcn_readfirstlane((unsigned)(ncols * it.n_ct * DBF_TILE_COLS));
+        xrsrc.w = 0x00020000u;
+#pragma unroll
+        for (int gi = 0; gi < XB_N; ++gi) {
+            const int col = 16 * gi + c;
+            x_lane_off[gi] = (unsigned)((col < ncols ? col : col % ncols) * it.n_ct * DBF_TILE_COLS + 16 * g);
+        }
+    }
+    auto fetch_operand = [&](int j, int ct, int ok) {
+        if (SHARED == 2) {
+#pragma unroll
+            for (int gi = 0; gi < XB_N; ++gi) {
+                const unsigned voff = ok ? x_lane_off[gi] + (unsigned)ct * DBF_TILE_COLS : OOB;
+                asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(xb[j][gi]) : "v"(voff), "s"(xrsrc) : "memory");
+            }
+        }
+    };
     // (the load itself, for a tile at byte offset `off` of the item's span; !ok: a placeholder that returns zeros)
-    auto fetch_at = [&](v4u& dst, unsigned off, int ok) {
+    auto fetch_at = [&](int j, unsigned off, int ct, int ok) {
+        v4u& dst = buf[j];
         const unsigned voff = lane_off + (ok ? off : OOB);
 #if DBF_ASM_LOADS
         asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen " DBF_LOAD_BITS
@@ -404,8 +437,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(it.bits), 0, (int)rsrc.z, 0x00020000),
             voff, 0, 0);
 #endif
+        fetch_operand(j, ct, ok);
     };
-    auto fetch = [&](v4u& dst) {
+    auto fetch = [&](int j) {
+        v4u& dst = buf[j];
         const int ct = c0 + w + 4 * p_i;
         const int ok = (int)(p_rt < it.nrt) & (int)(ct < cend);
         const unsigned off = (unsigned)(p_rt * it.n_ct + ct) * DBF_TILE_BYTES;
@@ -418,20 +453,32 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(it.bits), 0, (int)rsrc.z, 0x00020000),
             voff, 0, 0);
 #endif
+        fetch_operand(j, ct, ok);
         const int wrap = (int)(p_i + 1 == steps);
         p_i = wrap ? 0 : p_i + 1;
         p_rt += wrap;
     };
-    auto wait_slot = [](v4u& slot) {
+    auto wait_slot = [&](int j) {
 #if DBF_ASM_LOADS
-        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(slot) : "n"(PF - 1) : "memory");
+        if (SHARED == 2 && NCG == 2)
+            asm volatile("s_waitcnt vmcnt(%3)" : "+v"(buf[j]), "+v"(xb[j][0]), "+v"(xb[j][XB_N - 1]) : "n"((PF - 1) * SLOT_LOADS) : "memory");
+        else if (SHARED == 2)
+            asm volatile("s_waitcnt vmcnt(%2)" : "+v"(buf[j]), "+v"(xb[j][0]) : "n"((PF - 1) * SLOT_LOADS) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(%1)" : "+v"(buf[j]) : "n"(PF - 1) : "memory");
 #endif
     };
-    auto retire_ring = [](v4u (&rg)[PF]) {
+    auto retire_ring = [&]() {
 #if DBF_ASM_LOADS
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < PF; ++j) asm volatile("" : "+v"(rg[j]));
+        for (int j = 0; j < PF; ++j) {
+            asm volatile("" : "+v"(buf[j]));
+            if (SHARED == 2) {
+#pragma unroll
+                for (int gi = 0; gi < XB_N; ++gi) asm volatile("" : "+v"(xb[j][gi]));
+            }
+        }
 #endif
     };
     // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
@@ -493,9 +540,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         }
     }
 #pragma unroll
-    for (int j = 0; j < PF; ++j) fetch(buf[j]);
+    for (int j = 0; j < PF; ++j) fetch(j);
 #if DBF_ASM_LOADS
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(PF) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(PF * SLOT_LOADS) : "memory");
 #else
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif
@@ -543,7 +590,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
     __builtin_amdgcn_s_setprio(0);
 #endif
     for (;;) {  // chunks of columns (a single one unless the batch is large)
-        if (SHARED) {
+        if (SHARED == 1) {
             // columns [64 c0, 64 cend) of the 2 * batch planes, 16 bytes per thread and round
             const unsigned char* planes = it.q_in + DBF_QIN_HEADER + (size_t)c0 * DBF_TILE_COLS;
             const int per_row = (cend - c0) * (DBF_TILE_COLS / 16);
@@ -552,7 +599,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 for (int i = tid; i < per_row; i += 256)
                     *reinterpret_cast<v4u*>(xq + r * chs + 16 * i) =
                         *reinterpret_cast<const v4u*>(planes + r * q_stride + 16 * (size_t)i);
-        } else if (!one_pass) {
+        } else if (SHARED == 0 && !one_pass) {
             if (stage_a) input_quantise_chunk<true, IN_W>(it, cx, c0, cend);
             else input_quantise_chunk<false, IN_W>(it, cx, c0, cend);
         }
@@ -581,7 +628,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi) {
                 xp[gi] = xq + xrow[gi] + xo_base + w * 64;
-                xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
+                if (SHARED != 2) xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
             }
             for (int i0 = 0; i0 < steps; i0 += PF) {
                 const int g_ok = (int)(p_rt < it.nrt);
@@ -591,8 +638,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 for (int j = 0; j < PF; ++j) {
 #pragma unroll
                     for (int gi = 0; gi < NCG; ++gi)
-                        xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * 4 * DBF_TILE_COLS);
-                    wait_slot(buf[j]);
+                        if (SHARED != 2) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * 4 * DBF_TILE_COLS);
+                    wait_slot(j);
 #pragma unroll
                     for (int s = 0; s < 8; ++s) {
                         const uint32_t msk = 0x01010101u << s;
@@ -603,9 +650,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                         a.w = (int)(buf[j].w & msk);
 #pragma unroll
                         for (int gi = 0; gi < NCG; ++gi)
-                            acc[gi][s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, xr[j & 1][gi], acc[gi][s], 0, 0, 0);
+                            acc[gi][s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, SHARED == 2 ? xb[j][gi % XB_N] : xr[j & 1][gi],
+                                                                               acc[gi][s], 0, 0, 0);
                     }
-                    fetch_at(buf[j], g_off + (unsigned)j * 4u * DBF_TILE_BYTES, g_ok & (int)(g_ct + 4 * j < cend));
+                    fetch_at(j, g_off + (unsigned)j * 4u * DBF_TILE_BYTES, g_ct + 4 * j, g_ok & (int)(g_ct + 4 * j < cend));
                 }
 #pragma unroll
                 for (int gi = 0; gi < NCG; ++gi) xp[gi] += PF * 4 * DBF_TILE_COLS;
@@ -618,7 +666,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             // (it considers them dead from here on): wait, with the slots as operands so that
             // they stay allocated up to this point.  Nothing real is in flight any more, so
             // the wait is short.
-            if (rtl + 1 == it.nrt) retire_ring(buf);
+            if (rtl + 1 == it.nrt) retire_ring();
             if (!last_chunk) continue;  // (only with nrt == 1) keep accumulating over chunks
 
             // ---- combine the four wavefronts (integer adds: exact, order independent) -----
@@ -714,7 +762,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         p_rt = 0;
         p_i = 0;
 #pragma unroll
-        for (int j = 0; j < PF; ++j) fetch(buf[j]);
+        for (int j = 0; j < PF; ++j) fetch(j);
     }
 
     // ---- fused launch: a B-stage item publishes its rows of t.  The counters are per layer
@@ -779,9 +827,9 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
     }
 }
 
-size_t mfma_smem_bytes(int batch, int ch_tiles) {
+size_t mfma_smem_bytes(int batch, int ch_tiles, int shared_q) {
     const int ncols = 2 * batch;
-    const size_t xq = ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
+    const size_t xq = shared_q == 2 ? 0 : ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
     return sizeof(Misc) + xq + 2 * (size_t)DBF_TILE_ROWS * ncols * sizeof(int);
 }
 
@@ -796,6 +844,10 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q) {
     // (52 KiB each, of which the reduction buffers take 1 KiB per operand row) if that lets a whole row stay
     // in LDS, so that an item can take several row tiles.
     int budget = batch > 8 ? 32768 : 28672;
+    if (shared_q == 2) {  // no operand in LDS: the whole row is one "chunk"
+        const int all = (dbf_col_tiles(max_cols) + 3) & ~3;
+        return all < 4 ? 4 : all;
+    }
     if (shared_q) {
         const int env = []() { const char* e = std::getenv("DBF_SHARED_LDS_KB"); return e ? std::atoi(e) : 52; }();
         const int roomy = env * 1024 - (int)sizeof(Misc) - 1024 * ncols;
@@ -826,22 +878,28 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols, shared_q);
-    const size_t smem = mfma_smem_bytes(batch, ch_tiles);
+    const size_t smem = mfma_smem_bytes(batch, ch_tiles, shared_q);
     // column pieces (small batches only)
-    if (shared_q && batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
+    if (shared_q == 2 && batch <= 8)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 2>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else if (shared_q == 2)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 2>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else if (shared_q && batch <= 8)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 1>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (shared_q)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 1>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (pieces)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, 0>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 0>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     return hipGetLastError();
 }
