@@ -75,6 +75,13 @@ constexpr int UNR = DBF_UNR;       // independent 16-byte loads per thread in th
 constexpr int WIDE = 3;            // the same in the input passes of the kernel variant for wide rows and column pieces
 constexpr float QMAX = 32512.f;    // 127*256: largest |q| so that hi and lo fit int8
 constexpr int XQ_PAD = 16;         // bytes of padding per operand row (LDS bank spread)
+#ifndef DBF_RB_STRIDE
+#define DBF_RB_STRIDE 129
+#endif
+// Elements between operand columns of a reduction buffer: one more than the 128 rows of a tile, so that the
+// lanes of a half wavefront (16 operand columns x 2 row groups) add into different LDS banks; with 128 all
+// operand columns share a bank, which at 16 live columns (batch 8) made the reduction as long as the streaming.
+constexpr int RB_STRIDE = DBF_RB_STRIDE;
 constexpr unsigned OOB = 0x80000000u;  // buffer offset that is out of range for any span
 constexpr int SPIN_LIMIT = 1 << 18;    // polls of a producer counter before giving up (~0.5 s)
 
@@ -551,7 +558,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
 #pragma unroll
     for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(in0[j]), "+v"(in1[j]));
 
-    for (int i = tid; i < 2 * DBF_TILE_ROWS * ncols; i += 256) red[i] = 0;
+    for (int i = tid; i < 2 * RB_STRIDE * ncols; i += 256) red[i] = 0;
     if (tid < DBF_MAX_BATCH) misc->sigma[tid] = 0;
     // row scales: read by the epilogues, which come after several barriers
 #pragma unroll
@@ -673,7 +680,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             // acc[gi][s][i] of lane (g, c) is row 16*s + 4*g + i, column 16*gi + c.  The two
             // reduction buffers alternate, so one barrier per row tile is enough: a buffer is
             // cleared by its readers one barrier before anybody adds to it again.
-            int* rb = red + (tile_no & 1) * DBF_TILE_ROWS * ncols;
+            int* rb = red + (tile_no & 1) * RB_STRIDE * ncols;
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi) {
                 const int col = 16 * gi + c;
@@ -682,7 +689,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                     for (int s = 0; s < 8; ++s)
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            atomicAdd(&rb[col * DBF_TILE_ROWS + 4 * g + (16 * s + i)], acc[gi][s][i]);
+                            atomicAdd(&rb[col * RB_STRIDE + 4 * g + (16 * s + i)], acc[gi][s][i]);
                 }
             }
             ++tile_no;
@@ -690,10 +697,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             const int row = it.row0 + rtl * DBF_TILE_ROWS + rho;
             const float rscale = half_bits_to_float(misc->rscale[rtl * DBF_TILE_ROWS + rho]);
             for (int bi = tid >> 7; bi < batch; bi += 2) {
-                int* ph = &rb[(2 * bi) * DBF_TILE_ROWS + rho];  // column-major: [operand column][row of the tile]
-                int vh = ph[0], vl = ph[DBF_TILE_ROWS];
+                int* ph = &rb[(2 * bi) * RB_STRIDE + rho];  // column-major: [operand column][row of the tile]
+                int vh = ph[0], vl = ph[RB_STRIDE];
                 ph[0] = 0;
-                ph[DBF_TILE_ROWS] = 0;
+                ph[RB_STRIDE] = 0;
                 if (e_s < 7) {
                     vh >>= e_s;
                     vl >>= e_s;
@@ -830,7 +837,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
 size_t mfma_smem_bytes(int batch, int ch_tiles, int shared_q) {
     const int ncols = 2 * batch;
     const size_t xq = shared_q == 2 ? 0 : ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
-    return sizeof(Misc) + xq + 2 * (size_t)DBF_TILE_ROWS * ncols * sizeof(int);
+    return sizeof(Misc) + xq + 2 * (size_t)RB_STRIDE * ncols * sizeof(int);
 }
 
 }  // namespace
@@ -850,7 +857,7 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q) {
     }
     if (shared_q) {
         const int env = []() { const char* e = std::getenv("DBF_SHARED_LDS_KB"); return e ? std::atoi(e) : 52; }();
-        const int roomy = env * 1024 - (int)sizeof(Misc) - 1024 * ncols;
+        const int roomy = env * 1024 - (int)sizeof(Misc) - 2 * RB_STRIDE * 4 * ncols;
         if (roomy > budget) budget = roomy;
     }
     int ch_tiles = ((budget / ncols - XQ_PAD) / DBF_TILE_COLS) & ~3;
