@@ -825,8 +825,27 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
     cx.fast = STAGE_A || ((st.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
     if (threadIdx.x == 0) misc.sigma[0] = 0;
     __syncthreads();
-    input_scales<STAGE_A, WIDE>(it, cx);
-    input_quantise_chunk<STAGE_A, WIDE>(it, cx, 0, st.n_ct);
+    if (cx.fast && cx.nvec <= 256 * UNR) {
+        // the row fits the registers of the workgroup: read once (plain loads: the middle activations were
+        // written by an earlier launch), reduce, quantise from the registers
+        v4u r0[UNR], r1[UNR];
+#pragma unroll
+        for (int j = 0; j < UNR; ++j) {
+            const int v = min(256 * j + cx.tid, cx.nvec - 1);
+            if (STAGE_A) {
+                r0[j] = *reinterpret_cast<const v4u*>(it.t + 8 * (size_t)v);
+                r1[j] = *reinterpret_cast<const v4u*>(it.t + 8 * (size_t)v + 4);
+            } else {
+                const int vx = max(min(v, cx.nvec_x - 1), 0);
+                r0[j] = *reinterpret_cast<const v4u*>(cx.x + 8 * (size_t)vx);
+                r1[j] = *reinterpret_cast<const v4u*>(it.in_scale + 8 * (size_t)v);
+            }
+        }
+        input_one_pass<STAGE_A>(cx, r0, r1);
+    } else {
+        input_scales<STAGE_A, WIDE>(it, cx);
+        input_quantise_chunk<STAGE_A, WIDE>(it, cx, 0, st.n_ct);
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         reinterpret_cast<float*>(st.q_in)[bi] = misc.scale[0];
