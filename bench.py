@@ -181,7 +181,12 @@ def main():
         # One launch does both stages of every layer, so a step IS one kernel: its average
         # duration is taken from the HIP events around the back-to-back timed steps (the
         # per-launch events of the timed entry point add a few microseconds of launch latency).
-        dom, dom_ms, dom_bytes = "dbf_items_mfma_kernel<%d, false> (B and A stages fused)" % ncg, ms_per_step, bytes_layer * R
+        if batch == 1 or args.kind != "auto":
+            dom, dom_ms, dom_bytes = "dbf_items_mfma_kernel<%d, false, 0> (B and A stages fused)" % ncg, ms_per_step, bytes_layer * R
+        elif msB_avg >= msA_avg:  # batches of 2 and more: input quantiser + items, per stage
+            dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2>)" % ncg, msB_avg, bytes_b * R
+        else:
+            dom, dom_ms, dom_bytes = "A-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2>)" % ncg, msA_avg, bytes_a * R
     elif msB_avg >= msA_avg:
         dom, dom_ms, dom_bytes = "B-stage launch", msB_avg, bytes_b * R
     else:
@@ -189,7 +194,7 @@ def main():
     if args.kind == "valu":
         dom += " of dbf_stage_valu_kernel"
     elif args.kind == "mfma_split":
-        dom += " of dbf_items_mfma_kernel<%d, false>" % ncg
+        dom += " of dbf_items_mfma_kernel<%d, false, 0>" % ncg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -251,6 +256,16 @@ def main():
             except Exception as exc:  # reported, never hidden
                 by_len[str(R2)] = {"error": repr(exc)}
         out["by_stream_length"] = by_len
+        if batch == 1:
+            # the same stream at the other batch sizes of the workload (configuration 2: batch 4 and 16)
+            by_batch = {"1": {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2)}}
+            for b2 in (4, 16):
+                try:
+                    by_batch[str(b2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R, b2, kind, stream,
+                                                            steps=40, warmup=20)
+                except Exception as exc:  # reported, never hidden
+                    by_batch[str(b2)] = {"error": repr(exc)}
+            out["by_batch"] = by_batch
 
     stack.close()
     for l in layers:
@@ -348,11 +363,32 @@ def config5_bench(B, I, torch, np, batch, kind, stream, steps=60, warmup=60):
         ms = e0.elapsed_time(e1) / steps
         nbytes = float(sum(algorithmic_bytes(sp["n_in"], sp["n_out"], sp["k"], batch)[0] for sp in specs))
         gbps = nbytes / (ms * 1e-3) / 1e9
-        return {"layers": len(specs), "batch": batch, "ms_per_token_pass": round(ms, 5),
-                "token_passes_per_s": round(1e3 / ms, 1), "GBps": round(gbps, 2),
-                "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": nbytes, "steps": steps,
-                "note": "all linear layers of a 32-block decoder at 1.5 bits/weight, one stack call per pass, "
-                        "independent inputs per layer (no attention / norms between them)"}
+        res = {"layers": len(specs), "batch": batch, "ms_per_token_pass": round(ms, 5),
+               "token_passes_per_s": round(1e3 / ms, 1), "GBps": round(gbps, 2),
+               "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": nbytes, "steps": steps,
+               "note": "all linear layers of a 32-block decoder at 1.5 bits/weight, one stack call per pass, "
+                       "independent inputs per layer (no attention / norms between them)"}
+        if batch == 1:  # the workload's other batch size: 16 tokens per pass through the same stack
+            b2 = 16
+            del x_all, y_all
+            rng = np.random.default_rng(I.seed_for(5, 997))
+            x_host = I.random_activations_fp16(rng, 1, sum(b2 * sp["n_in"] for sp in specs))
+            x2 = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
+            y2 = torch.zeros(sum(b2 * sp["n_out"] for sp in specs), dtype=torch.float16, device="cuda")
+            for _ in range(10):
+                B.dbf_stack_gemv(stack, x2.data_ptr(), y2.data_ptr(), b2, stream, kind)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                B.dbf_stack_gemv(stack, x2.data_ptr(), y2.data_ptr(), b2, stream, kind)
+            e1.record()
+            torch.cuda.synchronize()
+            ms2 = e0.elapsed_time(e1) / 20
+            nb2 = float(sum(algorithmic_bytes(sp["n_in"], sp["n_out"], sp["k"], b2)[0] for sp in specs))
+            res["batch16"] = {"ms_per_pass": round(ms2, 5), "tokens_per_s": round(b2 * 1e3 / ms2, 1),
+                              "GBps": round(nb2 / (ms2 * 1e-3) / 1e9, 2)}
+        return res
     finally:
         stack.close()
         for l in layers:
