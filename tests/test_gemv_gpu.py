@@ -489,3 +489,68 @@ def test_groups_of_layers_sharing_one_input(batch):
         stack.close()
         for l in layers:
             l.close()
+
+
+# ---- batches of 2 and more: input quantised once per call ---------------------------------------
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("shape,batch", [((700, 260, 390), 2), ((700, 260, 390), 7), ((1000, 50, 130), 3),
+                                         ((3000, 200, 1500), 16), ((101, 77, 33), 9), ((4096, 512, 700), 4)])
+def test_shared_quantised_input_equals_the_items_own_bit_for_bit(mode, shape, batch, monkeypatch):
+    """DBF_GEMV_AUTO at batch >= 2 quantises each stage input once per call and lets the items copy it into LDS
+    (mode 1, here also with rows that need several LDS chunks) or read it from memory tile by tile (mode 2).
+    The quantiser uses the arithmetic of the items' own prologue and the integer sums are exact, so the result
+    must equal, bit for bit, the kind in which every item quantises for itself (checked against the oracle
+    here too).  Shapes with columns that are no multiple of 8 take the scalar input path."""
+    n_in, n_out, k = shape
+    seed = I.seed_for(1, 70 + batch)
+    L = I.make_layer(n_in, n_out, k, seed)
+    X = I.make_activations(batch, n_in, seed)
+    ref = O.forward_from_packed(X, L, "dense")
+    layer = G.pack(L)
+    try:
+        what = "shared-q mode %d n_in=%d n_out=%d k=%d batch=%d" % (mode, n_in, n_out, k, batch)
+        G.say("start " + what)
+        own = G.run_gemv(layer, X, B.GEMV_MFMA_SPLIT)
+        monkeypatch.setenv("DBF_SHARED_Q", str(mode))
+        monkeypatch.setenv("DBF_COL_PIECES", "0")   # (batch 2 would otherwise take the column-piece list)
+        l2 = G.pack(L)                               # the piece list is decided when the plan is built
+        try:
+            shared = G.run_gemv(l2, X, B.GEMV_AUTO)
+            again = G.run_gemv(l2, X, B.GEMV_AUTO)   # the per-layer buffers are reused from call to call
+        finally:
+            l2.close()
+        G.check(shared, ref, what)
+        assert np.array_equal(shared, own), what
+        assert np.array_equal(again, own), what + " (second call)"
+    finally:
+        layer.close()
+
+
+@pytest.mark.parametrize("batch", [4, 16])
+def test_stack_at_larger_batches_equals_per_layer_calls(batch):
+    """A stack call at batch 4 and 16 (one quantiser launch per stage for all layers) against per-layer calls of
+    the kind in which every item quantises for itself."""
+    shapes = [(512, 384, 200), (1000, 130, 77), (512, 512, 256), (4096, 256, 300)]
+    Ls = [I.make_layer(n_in, n_out, k, I.seed_for(1, 90 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        G.say("start stack batch=%d" % batch)
+        Xs = [I.make_activations(batch, L.n_in, 300 + i) for i, L in enumerate(Ls)]
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        y_all = torch.full((sum(batch * L.n_out for L in Ls),), float("nan"), dtype=torch.float16, device="cuda")
+        B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle(), B.GEMV_AUTO)
+        torch.cuda.synchronize()
+        got = G.dev_to_f64(y_all)
+        at = 0
+        for L, layer, X in zip(Ls, layers, Xs):
+            want = G.run_gemv(layer, X, B.GEMV_MFMA_SPLIT)
+            n = batch * L.n_out
+            assert np.array_equal(got[at:at + n].reshape(batch, L.n_out), want), (L.n_in, L.n_out, L.k)
+            at += n
+    finally:
+        stack.close()
+        for layer in layers:
+            layer.close()
