@@ -460,7 +460,7 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     // Batches of 2 and more: every stage input is quantised once per call; the items copy it into LDS (1)
     // or, if a whole row does not fit there at this batch, read it from memory tile by tile (2).
     int shared_q = 0;
-    if (pieces_ok && !use_pieces && batch >= 2) {
+    if (pieces_ok && !use_pieces && batch >= env_int("DBF_SHARED_MIN_BATCH", 2)) {
         shared_q = dbf_mfma_chunk_tiles(batch, max_cols, 1) >= dbf_col_tiles(max_cols) ? 1 : 2;
         shared_q = env_int("DBF_SHARED_Q", shared_q);
         if (shared_q < 0 || shared_q > 2) shared_q = 0;
