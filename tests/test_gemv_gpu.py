@@ -339,23 +339,24 @@ def test_launch_errors_with_a_real_layer():
         layer.close()
 
 
-def test_stack_call_replayed_from_a_captured_graph():
+@pytest.mark.parametrize("batch", [1, 4])
+def test_stack_call_replayed_from_a_captured_graph(batch):
     """The launch entry points allocate nothing, synchronise nothing and keep all state on the
     device (counters cleared by the last workgroup), so a stack call can be captured into a HIP
     graph and replayed.  Every replay, with eager work and synchronisations in between, must
-    reproduce the eager result bit for bit."""
+    reproduce the eager result bit for bit.  (Batch 4 takes the four-launch path with the input quantisers.)"""
     shapes = [(512, 512, 256), (1024, 384, 700), (256, 640, 1000), (512, 512, 256)]
     Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 950 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
-    Xs = [I.make_activations(1, L.n_in, I.seed_for(5, 960 + i)) for i, L in enumerate(Ls)]
+    Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 960 + i)) for i, L in enumerate(Ls)]
     layers = [G.pack(L) for L in Ls]
     stack = B.dbf_stack_create(layers)
     try:
         x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
-        n_y = sum(L.n_out for L in Ls)
+        n_y = batch * sum(L.n_out for L in Ls)
         for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA_SPLIT, "mfma_split"), (B.GEMV_PERSIST, "persist")):
             G.say("graph capture [%s]" % name)
             y_eager = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
-            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_eager.data_ptr(), 1, G.stream_handle(), kind)
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_eager.data_ptr(), batch, G.stream_handle(), kind)
             torch.cuda.synchronize()
             want = y_eager.cpu().view(torch.int16).numpy().copy()
             y_graph = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
@@ -364,7 +365,7 @@ def test_stack_call_replayed_from_a_captured_graph():
             side.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(side):
                 graph.capture_begin()
-                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_graph.data_ptr(), 1, side.cuda_stream, kind)
+                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_graph.data_ptr(), batch, side.cuda_stream, kind)
                 graph.capture_end()
             torch.cuda.current_stream().wait_stream(side)
             for rep in range(4):
