@@ -596,6 +596,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
 #if DBF_PROLOGUE_PRIO
     __builtin_amdgcn_s_setprio(0);
 #endif
+    // The accumulators start at zero and are cleared again right after every reduction (unconditionally: a
+    // conditional clear at the top of a row tile becomes 32 selects or 64 register copies).
+#pragma unroll
+    for (int gi = 0; gi < NCG; ++gi)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
     for (;;) {  // chunks of columns (a single one unless the batch is large)
         if (SHARED == 1) {
             // columns [64 c0, 64 cend) of the 2 * batch planes, 16 bytes per thread and round
@@ -614,12 +620,6 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         const bool last_chunk = cend >= ct_end;
 
         for (int rtl = 0; rtl < it.nrt; ++rtl) {
-            if (c0 == ct_first) {
-#pragma unroll
-                for (int gi = 0; gi < NCG; ++gi)
-#pragma unroll
-                    for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
-            }
             // ---- stream this wavefront's tiles of (row tile, chunk) -----------------------
             // Slot j is consumed and then refilled in place, so PF-1 loads stay in flight and
             // no register copies are needed; the operand of the next step is read from LDS
@@ -691,6 +691,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                         for (int i = 0; i < 4; ++i)
                             atomicAdd(&rb[col * RB_STRIDE + 4 * g + (16 * s + i)], acc[gi][s][i]);
                 }
+#pragma unroll
+                for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
             }
             ++tile_no;
             __syncthreads();
