@@ -36,6 +36,7 @@
 // A B-stage workgroup never waits, so every wait ends; should the bound be hit anyway the
 // workgroup goes on (its result is then wrong) and counts a time-out the host can read.
 #include <cstdlib>
+#include <type_traits>
 
 #include "dbf_kernels.h"
 
@@ -342,7 +343,10 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // into LDS and read from there as at batch 1.  SHARED == 2 (rows that do not fit the LDS of a workgroup at this
 // batch): no operand in LDS at all; the 16 operand bytes a lane needs for a tile are requested from memory (the
 // planes are L2 resident: every item of the layer reads them) together with the tile, in the same ring.
-template <int NCG, bool PIECES, int SHARED>
+// SINGLE: every item of the launch streams its columns as one chunk (the launcher knows): the first group of
+// tiles of a row tile then starts from zero accumulators by giving the matrix instructions a zero addend,
+// and the 32 accumulator registers are never cleared (2 of 47 vector instructions per tile).
+template <int NCG, bool PIECES, int SHARED, bool SINGLE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
@@ -637,7 +641,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 xp[gi] = xq + xrow[gi] + xo_base + w * 64;
                 if (SHARED != 2) xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
             }
-            for (int i0 = 0; i0 < steps; i0 += PF) {
+            // (one group = PF tiles; `fresh`: the group's first tile starts the row tile's sums)
+            auto group = [&](auto fresh) {
+                constexpr bool FRESH = decltype(fresh)::value;
                 const int g_ok = (int)(p_rt < it.nrt);
                 const int g_ct = c0 + w + 4 * p_i;
                 const unsigned g_off = (unsigned)(p_rt * it.n_ct + g_ct) * DBF_TILE_BYTES;
@@ -657,8 +663,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                         a.w = (int)(buf[j].w & msk);
 #pragma unroll
                         for (int gi = 0; gi < NCG; ++gi)
-                            acc[gi][s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, SHARED == 2 ? xb[j][gi % XB_N] : xr[j & 1][gi],
-                                                                               acc[gi][s], 0, 0, 0);
+                            acc[gi][s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+                                a, SHARED == 2 ? xb[j][gi % XB_N] : xr[j & 1][gi],
+                                (FRESH && j == 0) ? (v4i){0, 0, 0, 0} : acc[gi][s], 0, 0, 0);
                     }
                     fetch_at(j, g_off + (unsigned)j * 4u * DBF_TILE_BYTES, g_ct + 4 * j, g_ok & (int)(g_ct + 4 * j < cend));
                 }
@@ -667,7 +674,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 const int wrap = (int)(p_i + PF == steps);  // (steps is a multiple of PF)
                 p_i = wrap ? 0 : p_i + PF;
                 p_rt += wrap;
+            };
+            int i0 = 0;
+            if (SINGLE) {  // (steps >= PF: a chunk is never empty)
+                group(std::true_type{});
+                i0 = PF;
             }
+            for (; i0 < steps; i0 += PF) group(std::false_type{});
             // After the last row tile the ring holds PF placeholder loads that nobody will
             // consume.  They must have landed before the compiler may reuse their registers
             // (it considers them dead from here on): wait, with the slots as operands so that
@@ -691,8 +704,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                         for (int i = 0; i < 4; ++i)
                             atomicAdd(&rb[col * RB_STRIDE + 4 * g + (16 * s + i)], acc[gi][s][i]);
                 }
+                if (!SINGLE) {
 #pragma unroll
-                for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
+                    for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
+                }
             }
             ++tile_no;
             __syncthreads();
@@ -909,25 +924,28 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
     const size_t smem = mfma_smem_bytes(batch, ch_tiles, shared_q);
     // column pieces (small batches only)
     if (shared_q == 2 && batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 2>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (shared_q == 2)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 2>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (shared_q && batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 1>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 1, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (shared_q)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 1>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 1, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (pieces)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, 0>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                           n_layers, use_sync, x, y, batch, ch_tiles);
+    else if (batch <= 8 && ch_tiles >= dbf_col_tiles(max_cols))
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else if (batch <= 8)
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     else
-        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 0>), dim3(n_items), dim3(256), smem, stream, items, sync,
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles);
     return hipGetLastError();
 }
