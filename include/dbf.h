@@ -27,8 +27,9 @@
  *   - Launching entry points (dbf_gemv*, dbf_gemm, dbf_stack_gemv) are
  *     asynchronous on the caller's HIP stream (a hipStream_t passed as void*,
  *     NULL = the default stream), allocate nothing and do not synchronise.  A
- *     layer holds scratch for its middle activations, so one layer (or stack)
- *     must not run on two streams at the same time.
+ *     layer holds scratch for its middle activations and, for batches of 2 and
+ *     more, for its quantised stage inputs, so one layer must not run on two
+ *     streams at the same time, be it directly or through stacks that hold it.
  *   - Non-finite activations give unspecified (but memory-safe) results.
  *
  * Canonical sign-bit format (the paper defines none; this is the interchange
