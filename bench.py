@@ -314,9 +314,10 @@ def build_stream(B, I, torch, np, specs, cfg_no, batch):
     return layers, stack, x_all, y_all
 
 
-def stream_length_bench(B, I, torch, np, layers, spec, R2, batch, kind, stream, steps=100, warmup=100):
+def stream_length_bench(B, I, torch, np, layers, spec, R2, batch, kind, stream, steps=200, warmup=300):
     """The config-2 stream with R2 distinct layers: reuses the packed layers of the main run (and
-    packs more if R2 is larger); returns the step time and the achieved rate."""
+    packs more if R2 is larger); returns the step time and the achieved rate.  Same protocol as the main
+    run (300 untimed steps first: the clocks need tens of milliseconds of load to settle)."""
     extra = []
     for i in range(len(layers), R2):
         L = I.make_layer(spec["n_in"], spec["n_out"], spec["k"], seed=I.seed_for(2, i))
