@@ -118,29 +118,25 @@ __global__ __launch_bounds__(256) void dbf_svid_col_dots_kernel(const float* __r
 }
 
 // v_raw[j] = sum over chunks of partial[chunk][j]: four interleaved running sums (chunks c = 0, 4, 8, ... in the
-// first, and so on; the loads of a round are independent), combined as ((s0 + s1) + s2) + s3; and
-// ss_part[workgroup] = sum of v_raw[j]^2 over the workgroup's 64 columns (butterfly order).
-// 64 threads per workgroup, so that even 4096 columns spread over 64 compute units.
-__global__ __launch_bounds__(64) void dbf_svid_col_reduce_kernel(const float* __restrict__ partial, int chunks, int cols,
-                                                              float* __restrict__ v, float* __restrict__ ss_part) {
-    const int j = blockIdx.x * 64 + threadIdx.x;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    if (j < cols) {
-        int c = 0;
-        for (; c + 4 <= chunks; c += 4) {
-            s0 += partial[(size_t)(c + 0) * cols + j];
-            s1 += partial[(size_t)(c + 1) * cols + j];
-            s2 += partial[(size_t)(c + 2) * cols + j];
-            s3 += partial[(size_t)(c + 3) * cols + j];
-        }
-        if (c + 0 < chunks) s0 += partial[(size_t)(c + 0) * cols + j];
-        if (c + 1 < chunks) s1 += partial[(size_t)(c + 1) * cols + j];
-        if (c + 2 < chunks) s2 += partial[(size_t)(c + 2) * cols + j];
+// first, and so on), combined as ((s0 + s1) + s2) + s3; and ss_part[workgroup] = sum of v_raw[j]^2 over the
+// workgroup's 64 columns (butterfly order).  Workgroup = 64 columns x the 4 running sums (one wavefront each: a
+// thread's chain of dependent loads is a quarter of the chunks), combined through LDS in that fixed order.
+__global__ __launch_bounds__(256) void dbf_svid_col_reduce_kernel(const float* __restrict__ partial, int chunks, int cols,
+                                                               float* __restrict__ v, float* __restrict__ ss_part) {
+    __shared__ float part[4][64];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + lane;
+    float s = 0.f;
+    if (j < cols)
+        for (int c = q; c < chunks; c += 4) s += partial[(size_t)c * cols + j];
+    part[q][lane] = s;
+    __syncthreads();
+    if (q == 0) {
+        const float vj = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        if (j < cols) v[j] = vj;
+        const float ss = wave_sum_f(vj * vj);
+        if (lane == 0) ss_part[blockIdx.x] = ss;
     }
-    const float vj = ((s0 + s1) + s2) + s3;
-    if (j < cols) v[j] = vj;
-    const float ss = wave_sum_f(vj * vj);
-    if (threadIdx.x == 0) ss_part[blockIdx.x] = ss;
 }
 
 // The two factors from the unnormalised iterate: m = v_raw / ||v_raw|| (in place) and
@@ -251,7 +247,7 @@ extern "C" int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* 
                                ss_part, n_ss, u, vec_ok);
         hipLaunchKernelGGL(dbf_svid_col_dots_kernel, dim3((cols + COL_BLOCK - 1) / COL_BLOCK, chunks), dim3(256), 0, st,
                            Z, rows, cols, u, partial);
-        hipLaunchKernelGGL(dbf_svid_col_reduce_kernel, dim3(n_ss), dim3(64), 0, st, partial, chunks, cols, v, ss_part);
+        hipLaunchKernelGGL(dbf_svid_col_reduce_kernel, dim3(n_ss), dim3(256), 0, st, partial, chunks, cols, v, ss_part);
     }
     const int longest = rows > cols ? rows : cols;
     hipLaunchKernelGGL(dbf_svid_finish_kernel, dim3((longest + 255) / 256), dim3(256), 0, st, u, rows, ss_part, n_ss, v,
