@@ -163,6 +163,9 @@ int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
  *                the fp16 matrix cores with fp32 accumulation; the middle activations are
  *                rounded once to fp16.
  *
+ *   DBF_GEMM_AUTO (dbf_gemm): DBF_GEMM_I8; calls of up to DBF_MAX_BATCH tokens are run as a decode
+ *                batch (dbf_gemv), which gives the same bits at a third of the latency.
+ *
  * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1 (at most 65535 * 64).
  * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes (enough
  * for either variant), 256-byte aligned, contents undefined on return.  Asynchronous on the

@@ -64,6 +64,9 @@ def test_gemm_agrees_with_gemv_rows():
         # the int8 variant quantises exactly as the matrix-core decode kernel does: same integers,
         # same scales, so the fp16 outputs are identical
         assert np.array_equal(G.run_gemm(layer, X, B.GEMM_I8), G.run_gemv(layer, X, B.GEMV_MFMA_SPLIT))
+        # dbf_gemm (DBF_GEMM_AUTO) runs up to 16 tokens as a decode batch: the same bits again, also for T = 1 and 5
+        for T in (1, 5, 16):
+            assert np.array_equal(G.run_gemm(layer, X[:T], B.GEMM_AUTO), G.run_gemm(layer, X[:T], B.GEMM_I8)), T
     finally:
         layer.close()
 
