@@ -182,11 +182,14 @@ def main():
         # duration is taken from the HIP events around the back-to-back timed steps (the
         # per-launch events of the timed entry point add a few microseconds of launch latency).
         if batch == 1 or args.kind != "auto":
-            dom, dom_ms, dom_bytes = "dbf_items_mfma_kernel<%d, false, 0> (B and A stages fused)" % ncg, ms_per_step, bytes_layer * R
+            # (<operand column groups, column pieces, shared quantised input, single chunk>: rows of up to
+            #  14080 columns stay in LDS as one chunk at batch 1, which all benchmark shapes are)
+            dom, dom_ms, dom_bytes = ("dbf_items_mfma_kernel<%d, false, 0, %s> (B and A stages fused)"
+                                      % (ncg, "true" if batch == 1 else "true|false")), ms_per_step, bytes_layer * R
         elif msB_avg >= msA_avg:  # batches of 2 and more: input quantiser + items, per stage
-            dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2>)" % ncg, msB_avg, bytes_b * R
+            dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2, false>)" % ncg, msB_avg, bytes_b * R
         else:
-            dom, dom_ms, dom_bytes = "A-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2>)" % ncg, msA_avg, bytes_a * R
+            dom, dom_ms, dom_bytes = "A-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2, false>)" % ncg, msA_avg, bytes_a * R
     elif msB_avg >= msA_avg:
         dom, dom_ms, dom_bytes = "B-stage launch", msB_avg, bytes_b * R
     else:
@@ -194,7 +197,7 @@ def main():
     if args.kind == "valu":
         dom += " of dbf_stage_valu_kernel"
     elif args.kind == "mfma_split":
-        dom += " of dbf_items_mfma_kernel<%d, false, 0>" % ncg
+        dom += " of dbf_items_mfma_kernel<%d, false, 0, true|false>" % ncg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
