@@ -150,3 +150,32 @@ def test_admm_argument_errors():
         bad[pos] = val
         with pytest.raises(B.DbfError):
             B.dbf_admm_step(*bad)
+
+
+def test_admm_iterations_on_the_device_approach_a_factorisable_target():
+    """Twenty consecutive updates on the device (state kept there, each call the next iteration) on a target
+    W = B A* with A* of the SVID form, from a start far away: the residual ||B A - W|| of the projected iterate
+    must fall to under a hundredth of the start's, as the fp64 oracle's does (its own pin shows a thousandth
+    after 30 updates)."""
+    rng = np.random.default_rng(21)
+    p, q, r = 300, 96, 160
+    Bm = (rng.standard_normal((p, q)) / np.sqrt(p)).astype(np.float32)
+    S_star = np.where(rng.random((q, r)) < 0.5, 1.0, -1.0)
+    A_star = rng.uniform(0.5, 1.5, q)[:, None] * S_star * rng.uniform(0.5, 1.5, r)[None, :]
+    W = (Bm.astype(np.float64) @ A_star).astype(np.float32)
+    Minv, C = _constants(Bm, W, 1.0)
+    S0 = np.where(rng.random((q, r)) < 0.5, 1, -1).astype(np.int8)
+    a0, m0 = np.full(q, 0.1, dtype=np.float32), np.full(r, 0.1, dtype=np.float32)
+    dev = DeviceState(Minv, C, S0, a0, m0, np.zeros((q, r), dtype=np.float32))
+    B64, W64 = Bm.astype(np.float64), W.astype(np.float64)
+
+    def residual(state):
+        S, a, m, _ = state
+        return np.linalg.norm(B64 @ (a[:, None] * S * m[None, :]) - W64)
+
+    res0 = residual(dev.host())
+    for _ in range(20):
+        dev.step(1.0, 3)
+    res = residual(dev.host())
+    G.say("  residual %.3e -> %.3e" % (res0, res))
+    assert res < 1e-2 * res0

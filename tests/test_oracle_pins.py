@@ -542,3 +542,32 @@ def test_admm_precomputed_form_matches_and_rejects_bad_shapes():
         O.admm_step(B, W[:5], rho, S, a, m, U, 1)
     with pytest.raises(ValueError):
         O.admm_step(B, W, 0.0, S, a, m, U, 1)
+
+
+def test_admm_iterations_approach_a_factorisable_target():
+    """Behaviour over several updates: with W = B A* (A* of the SVID form) and a start far from A*, repeated
+    updates bring the projected iterate A = a . S . m^T closer to a least-squares fit: the residual ||B A - W||
+    after 30 updates is a thousandth of the start's (here the iteration recovers an exact fit).  (ADMM on this non-convex set has no guarantee, but a wrong
+    sign in the dual update or in the right-hand side makes the residual grow instead; seeds fixed.)"""
+    rng = np.random.default_rng(21)
+    p, q, r = 40, 12, 16
+    B = rng.standard_normal((p, q)) / math.sqrt(p)
+    S_star = np.where(rng.random((q, r)) < 0.5, 1.0, -1.0)
+    A_star = rng.uniform(0.5, 1.5, q)[:, None] * S_star * rng.uniform(0.5, 1.5, r)[None, :]
+    W = B @ A_star
+    S = np.where(rng.random((q, r)) < 0.5, 1.0, -1.0)
+    a, m, U = np.full(q, 0.1), np.full(r, 0.1), np.zeros((q, r))
+    res0 = np.linalg.norm(B @ (a[:, None] * S * m[None, :]) - W)
+    for _ in range(30):
+        S, a, m, U, _ = O.admm_step(B, W, 1.0, S, a, m, U, 3)
+    res = np.linalg.norm(B @ (a[:, None] * S * m[None, :]) - W)
+    assert res < 1e-3 * res0, (res0, res)
+    # and a corrupted dual update (U - W_hat + A' instead of U + W_hat - A') does not get there
+    S2 = np.where(np.random.default_rng(22).random((q, r)) < 0.5, 1.0, -1.0)
+    a2, m2, U2 = np.full(q, 0.1), np.full(r, 0.1), np.zeros((q, r))
+    for _ in range(30):
+        S2n, a2n, m2n, U2n, W_hat = O.admm_step(B, W, 1.0, S2, a2, m2, U2, 3)
+        U2 = U2 - W_hat + a2n[:, None] * S2n * m2n[None, :]
+        S2, a2, m2 = S2n, a2n, m2n
+    res_bad = np.linalg.norm(B @ (a2[:, None] * S2 * m2[None, :]) - W)
+    assert res < res_bad
