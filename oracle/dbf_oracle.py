@@ -52,11 +52,12 @@ def unpack_signs(words, rows: int, cols: int) -> np.ndarray:
     need = (cols + 31) // 32
     if words.shape[1] != need:
         raise ValueError("expected %d words per row, got %d" % (need, words.shape[1]))
-    out = np.empty((rows, cols), dtype=np.float64)
-    for c in range(cols):
-        bit = (words[:, c // 32] >> np.uint32(c % 32)) & np.uint32(1)
-        out[:, c] = np.where(bit == 1, 1.0, -1.0)
-    return out
+    # bytes of a little-endian word in memory order are bits 0-7, 8-15, 16-23, 24-31, and within a byte
+    # "little" bit order lists the least significant bit first: position c of the unpacked row is bit c mod 32
+    # of word c div 32
+    as_bytes = np.ascontiguousarray(words.astype("<u4")).view(np.uint8).reshape(rows, 4 * need)
+    bits = np.unpackbits(as_bytes, axis=1, bitorder="little")[:, :cols]
+    return np.where(bits == 1, 1.0, -1.0)
 
 
 def pack_signs(S) -> np.ndarray:
@@ -225,8 +226,7 @@ def admm_step_from(Minv, C, rho: float, S, a, m, U, svid_iters: int):
     forms them once per outer iteration and repeats only what is written here.
 
         A     = a . S . m^T                       (the current iterate, in SVID form)
-        W_hat = Minv^T (C + rho (A - U))          (Minv is symmetric in exact arithmetic; it is applied
-                                                   transposed so that the result is defined for any input)
+        W_hat = Minv (C + rho (A - U))            (as printed: the inverse times the right-hand side)
         Z     = W_hat + U
         (S', a', m') = SVID(Z);   A' = a' . S' . m'^T
         U'    = U + W_hat - A'
@@ -242,7 +242,7 @@ def admm_step_from(Minv, C, rho: float, S, a, m, U, svid_iters: int):
     if Minv.shape != (q, q) or S.shape != (q, r) or U.shape != (q, r) or a.shape != (q,) or m.shape != (r,):
         raise ValueError("shape mismatch")
     A = a[:, None] * S * m[None, :]
-    W_hat = Minv.T @ (C + rho * (A - U))
+    W_hat = Minv @ (C + rho * (A - U))
     S2, a2, m2 = svid(W_hat + U, svid_iters)
     A2 = a2[:, None] * S2 * m2[None, :]
     return S2, a2, m2, U + W_hat - A2, W_hat

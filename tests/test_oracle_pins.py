@@ -532,10 +532,16 @@ def test_admm_precomputed_form_matches_and_rejects_bad_shapes():
     pre = O.admm_step_from(Minv, B.T @ W, rho, S, a, m, U, 3)
     for x, y in zip(full, pre):
         assert np.array_equal(x, y)
-    # a non-symmetric "inverse" is applied transposed (the documented convention)
+    # the precomputed form applies its first argument from the left as it stands (no transpose): with a
+    # non-symmetric matrix in its place, W_hat solves M2^-1 X = rhs, which a library solve checks
     M2 = Minv + np.triu(np.ones((6, 6)), 1) * 0.01
     A = a[:, None] * S * m[None, :]
-    assert np.allclose(O.admm_step_from(M2, B.T @ W, rho, S, a, m, U, 1)[4], M2.T @ (B.T @ W + rho * (A - U)))
+    rhs = B.T @ W + rho * (A - U)
+    W_hat2 = O.admm_step_from(M2, B.T @ W, rho, S, a, m, U, 1)[4]
+    assert np.allclose(np.linalg.solve(M2, W_hat2), rhs, rtol=0, atol=1e-11)
+    assert not np.allclose(np.linalg.solve(M2.T, W_hat2), rhs, rtol=0, atol=1e-4)
+    # and the full update solves (B^T B + rho I) W_hat = rhs
+    assert np.allclose(np.linalg.solve(B.T @ B + rho * np.eye(6), rhs), full[4], rtol=0, atol=1e-12)
     with pytest.raises(ValueError):
         O.admm_step_from(Minv[:5], B.T @ W, rho, S, a, m, U, 1)
     with pytest.raises(ValueError):
