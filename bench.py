@@ -45,18 +45,82 @@ def algorithmic_bytes(n_in, n_out, k, batch):
     return bits + vecs + io, stage_b, stage_a
 
 
+def kernel_source_hash():
+    """First 16 hex digits of the SHA-256 of the sources that decide what the decode launch does and reads (the
+    kernel, the launch plans, the shared structs): counter readings are quoted only for the sources they were
+    taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2505_11076_amd", "csrc")
+    for name in ("dbf_gemv_mfma.hip", "dbf_api.hip", "dbf_internal.h", "dbf_kernels.h"):
+        with open(os.path.join(csrc, name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+class Protocol:
+    """How every rate in this file is timed, so that all figures of one output line stand on the same footing:
+      1. settle: the step itself, back to back and untimed, for at least `settle_ms` of GPU time.  (After idle
+         -- the host packs layers between measurements -- the shader clock is cut back about 1.5 ms into the
+         load and needs about 60 ms to come back; without this phase a short run measures that transient.)
+      2. `warmup` untimed steps;
+      3. `steps` timed steps between two HIP events on the launch stream, nothing else in between.
+    run() returns (ms per step, a dict that states what was actually done)."""
+
+    def __init__(self, torch, steps, warmup, settle_ms):
+        self.torch, self.steps, self.warmup, self.settle_ms = torch, int(steps), int(warmup), float(settle_ms)
+
+    def run(self, step, steps=None, warmup=None):
+        torch = self.torch
+        steps = self.steps if steps is None else int(steps)
+        warmup = self.warmup if warmup is None else int(warmup)
+        ev = torch.cuda.Event
+        settle_steps, settle_ms = 0, 0.0
+        if self.settle_ms > 0:
+            # bursts of steps until the phase has lasted settle_ms on the GPU's own clock: a first short one gives
+            # the step time (its very first launch is slow), the later ones are sized from what has been seen
+            s0 = ev(enable_timing=True)
+            s0.record()
+            burst = 4
+            while True:
+                for _ in range(burst):
+                    step()
+                s1 = ev(enable_timing=True)
+                s1.record()
+                s1.synchronize()
+                settle_steps += burst
+                settle_ms = s0.elapsed_time(s1)
+                if settle_ms >= self.settle_ms:
+                    break
+                per_step = max(settle_ms / settle_steps, 1e-3)
+                burst = max(4, int((self.settle_ms - settle_ms) / per_step) + 1)
+        for _ in range(warmup):
+            step()
+        e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        return ms, {"steps": steps, "warmup": warmup, "settle_ms": round(settle_ms, 1), "settle_steps": settle_steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=300,
-                    help="untimed steps before the timed ones (a step is ~0.1 ms; the GPU clocks need a few "
-                         "tens of ms of load to settle after the idle set-up phase)")
+    ap.add_argument("--steps", type=int, default=200, help="timed steps (of the main run and of every sub-measurement)")
+    ap.add_argument("--warmup", type=int, default=20, help="untimed steps right before the timed ones")
+    ap.add_argument("--settle-ms", type=float, default=200.0,
+                    help="before the warm-up steps of every measurement the same step runs back to back, untimed, for "
+                         "at least this many ms of GPU time: after an idle phase (the host packs layers) the shader "
+                         "clock starts high, is cut back about 1.5 ms into the load and takes about 60 ms to come "
+                         "back (profiles/decode_cold_start_config2_stream512.txt); reported as `settle` in the output")
     ap.add_argument("--layers", type=int, default=512,
                     help="distinct layers in the stream (config2); 512 layers = 1.07 GB of sign bits, about what "
                          "one decode step of a 7B model streams; 256 and 1024 are reported next to it")
     ap.add_argument("--batch", type=int, default=1)
-    ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split", "persist"], default="auto")
+    ap.add_argument("--kind", choices=["auto", "valu", "mfma", "mfma_split"], default="auto")
     ap.add_argument("--workload", choices=["config2", "config5"], default="config2",
                     help="config2: 256 distinct 4096x4096 k=2048 layers (the headline); config5: the 224 linear "
                          "layers of a Llama-2-7B-shaped decoder at 1.5 bits/weight as the main workload")
@@ -76,10 +140,22 @@ def main():
                     help="only the ADMM update measurement (dbf_admm_step for a 4096 x 4096 weight at 1 and 2 bits)")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
+    ap.add_argument("--cold-series", type=int, default=0, metavar="N",
+                    help="only a time series: after the set-up (GPU idle while the layers are packed) and an extra idle "
+                         "pause, N steps back to back with a HIP event between every two; prints the per-step times")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy and a 1 GiB streaming read of known size, so that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: read the counter_collection CSVs of two rocprofv3 --pmc runs (FETCH_SIZE, then "
+                         "WRITE_SIZE) of `bench.py --stream-only --copy-calibration ...`, scale the readings by what the "
+                         "same counters read for the 1 GiB copy / 1 GiB read of that run, and write profiles/traffic.json "
+                         "for the workload named by the other flags")
+    ap.add_argument("--no-table4", action="store_true", help="skip the 1- and 2-bit rows of the second workload")
     args = ap.parse_args()
+    if args.traffic_from:
+        print(json.dumps(traffic_from(args)))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path uses no collectives); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -94,24 +170,24 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.lib()
-    kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA,
-            "mfma_split": B.GEMV_MFMA_SPLIT, "persist": B.GEMV_PERSIST}[args.kind]
+    kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA, "mfma_split": B.GEMV_MFMA_SPLIT}[args.kind]
+    proto = Protocol(torch, args.steps, args.warmup, args.settle_ms)
     if args.prefill_only:
         st = torch.cuda.current_stream().cuda_stream
-        print(json.dumps({"prefill": prefill_bench(B, I, torch, np, st), "mfma_probe": mfma_probe(B, torch, st)}))
+        print(json.dumps({"prefill": prefill_bench(B, I, torch, np, st, proto), "mfma_probe": mfma_probe(B, torch, st)}))
         return
     if args.prune:
         print(json.dumps({"prune_middle": prune_bench(B, I, torch, np)}))
         return
     if args.svid:
-        print(json.dumps({"svid": svid_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
+        print(json.dumps({"svid": svid_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream, proto)}))
         return
     if args.admm:
-        print(json.dumps({"admm": admm_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream)}))
+        print(json.dumps({"admm": admm_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream, proto)}))
         return
     if args.table4:
         print(json.dumps({"table4": table4_bench(B, I, torch, np, args.batch, kind,
-                                                 torch.cuda.current_stream().cuda_stream)}))
+                                                 torch.cuda.current_stream().cuda_stream, proto)}))
         return
     cfg = I.CONFIG2
     n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
@@ -141,16 +217,11 @@ def main():
     def step():
         B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    if args.cold_series:
+        print(json.dumps(cold_series(torch, np, step, args.cold_series, R, setup_s)))
+        return
+
+    ms_per_step, main_protocol = proto.run(step)
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -174,10 +245,7 @@ def main():
     bytes_layer, bytes_b, bytes_a = bytes_step / R, sum(p[1] for p in per_layer) / R, sum(p[2] for p in per_layer) / R
     value = bytes_step / (ms_per_step * 1e-3) / 1e9
     ncg = 1 if batch <= 8 else 2
-    if args.kind == "persist" and batch == 1:
-        # one persistent launch walks every item of the step
-        dom, dom_ms, dom_bytes = "dbf_decode_persistent_kernel (B and A stages, one launch)", ms_per_step, bytes_layer * R
-    elif args.kind in ("auto", "mfma", "persist"):
+    if args.kind in ("auto", "mfma"):
         # One launch does both stages of every layer, so a step IS one kernel: its average
         # duration is taken from the HIP events around the back-to-back timed steps (the
         # per-launch events of the timed entry point add a few microseconds of launch latency).
@@ -199,13 +267,24 @@ def main():
     elif args.kind == "mfma_split":
         dom += " of dbf_items_mfma_kernel<%d, false, 0, true|false>" % ncg
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    traffic = None
+    # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs (profiles/traffic.json, written by
+    # --traffic-from): quoted only if it was measured on this kernel, these sources and this workload.
+    traffic, traffic_note = None, "no counter run recorded for this kernel / workload"
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath) and args.workload == "config2" and R == 512 and batch == 1:
+    if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("bench_default_bytes_per_launch")
-        except Exception:
-            traffic = None
+            rec = json.load(open(tpath))
+            want = {"workload": args.workload, "layers_per_step": R, "batch": batch, "kernel_variant": args.kind}
+            if rec.get("source_sha16") != kernel_source_hash():
+                traffic_note = "stale: the kernel sources changed after the counter run (profiles/traffic.json)"
+            elif any(rec.get(k_) != v_ for k_, v_ in want.items()):
+                traffic_note = "the recorded counter run is for another workload"
+            elif not dom.startswith(rec.get("kernel", "?")):
+                traffic_note = "the recorded counter run is for another kernel"
+            else:
+                traffic, traffic_note = rec.get("bytes_per_launch"), "rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy"
+        except Exception as exc:
+            traffic_note = "profiles/traffic.json unreadable: %r" % (exc,)
 
     # ---- isolated single layer, cache warm -----------------------------------------------------
     iso = None
@@ -235,9 +314,13 @@ def main():
         "isolated_layer_us": iso,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "avg_launch_ms": round(dom_ms, 5),
+                     "traffic_note": traffic_note, "avg_launch_ms": round(dom_ms, 5),
                      "first_launch_ms": round(msB_avg, 5), "second_launch_ms": round(msA_avg, 5),
                      "algorithmic_bytes_per_launch": dom_bytes},
+        "settle": dict(main_protocol, what="the same step, back to back and untimed, before the warm-up steps: after "
+                       "the idle set-up the shader clock is cut back ~1.5 ms into the load and needs ~60 ms to return "
+                       "(profiles/decode_cold_start_config2_stream512.txt); every sub-measurement of this line does the "
+                       "same and states its own steps / warmup / settle_ms under `protocol`"),
         "setup_s": round(setup_s, 2),
     }
 
@@ -250,22 +333,21 @@ def main():
 
     # ---- the same stream at other lengths (launch head and tail are fixed costs per step) ------
     if args.workload == "config2" and not args.stream_only:
-        by_len = {str(R): {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2)}}
+        by_len = {str(R): {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2), "protocol": main_protocol}}
         for R2 in (256, 1024):
             if R2 == R:
                 continue
             try:
-                by_len[str(R2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R2, batch, kind, stream)
+                by_len[str(R2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R2, batch, kind, stream, proto)
             except Exception as exc:  # reported, never hidden
                 by_len[str(R2)] = {"error": repr(exc)}
         out["by_stream_length"] = by_len
         if batch == 1:
             # the same stream at the other batch sizes of the workload (configuration 2: batch 4 and 16)
-            by_batch = {"1": {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2)}}
+            by_batch = {"1": {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2), "protocol": main_protocol}}
             for b2 in (4, 16):
                 try:
-                    by_batch[str(b2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R, b2, kind, stream,
-                                                            steps=40, warmup=20)
+                    by_batch[str(b2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R, b2, kind, stream, proto)
                 except Exception as exc:  # reported, never hidden
                     by_batch[str(b2)] = {"error": repr(exc)}
             out["by_batch"] = by_batch
@@ -278,14 +360,21 @@ def main():
     # ---- the 224-layer decoder stack (second decode workload) -----------------------------------
     if args.workload == "config2" and not args.no_config5 and not args.stream_only:
         try:
-            out["config5_stack"] = config5_bench(B, I, torch, np, batch, kind, stream)
+            out["config5_stack"] = config5_bench(B, I, torch, np, batch, kind, stream, proto)
         except Exception as exc:  # reported, never hidden
             out["config5_stack"] = {"error": repr(exc)}
+
+    # ---- second workload: the layer sizes of the paper's matrix-vector timing table, 1 and 2 bits per weight --
+    if args.workload == "config2" and not args.no_table4 and not args.stream_only:
+        try:
+            out["table4"] = table4_bench(B, I, torch, np, batch, kind, stream, proto, bits_only=(1.0, 2.0))
+        except Exception as exc:  # reported, never hidden
+            out["table4"] = {"error": repr(exc)}
 
     # ---- prefill (matrix-core path) ---------------------------------------------------------------
     if not args.no_prefill and not args.stream_only:
         try:
-            out["prefill"] = prefill_bench(B, I, torch, np, stream)
+            out["prefill"] = prefill_bench(B, I, torch, np, stream, proto)
             out["mfma_probe"] = mfma_probe(B, torch, stream)
         except Exception as exc:  # reported, never hidden
             out["prefill"] = {"error": repr(exc)}
@@ -297,6 +386,83 @@ def main():
                                            per_layer[0][0], cfg_no, R)
 
     print(json.dumps(out))
+
+
+def traffic_from(args):
+    """HBM bytes per launch of the decode kernel from two counter runs (see --traffic-from).  The counters count in
+    units that differ between machines, so each is scaled by its reading for a transfer of known size in the
+    same run: FETCH_SIZE by the 1 GiB streaming read of dbf_probe_read_kernel, WRITE_SIZE by the 1 GiB device copy
+    (the dispatch with the largest reading that is not one of this library's kernels)."""
+    import csv
+
+    def per_dispatch(path, counter):
+        acc = {}
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            key = (int(r["Dispatch_Id"]), r["Kernel_Name"])
+            acc[key] = acc.get(key, 0.0) + float(r["Counter_Value"])
+        return acc
+
+    gib = float(1 << 30)
+    fetch = per_dispatch(args.traffic_from[0], "FETCH_SIZE")
+    write = per_dispatch(args.traffic_from[1], "WRITE_SIZE")
+    probe = [v for (d, n), v in fetch.items() if "dbf_probe_read_kernel" in n]
+    copy_w = max(v for (d, n), v in write.items() if "dbf_" not in n)
+    if not probe or copy_w <= 0:
+        raise SystemExit("the counter runs hold no calibration dispatches (run bench.py with --copy-calibration)")
+    fetch_unit, write_unit = gib / (sum(probe) / len(probe)), gib / copy_w
+    kf = sorted((d, n, v) for (d, n), v in fetch.items() if "dbf_items_mfma_kernel" in n)
+    kw = sorted((d, n, v) for (d, n), v in write.items() if "dbf_items_mfma_kernel" in n)
+    if not kf or not kw:
+        raise SystemExit("no decode kernel dispatches in the counter runs")
+    name = kf[0][1].split("(")[0]
+    fb = sum(v for _, _, v in kf) / len(kf) * fetch_unit
+    wb = sum(v for _, _, v in kw) / len(kw) * write_unit
+    rec = {"kernel": name, "workload": args.workload, "layers_per_step": args.layers if args.workload == "config2" else 224,
+           "batch": args.batch, "kernel_variant": args.kind, "source_sha16": kernel_source_hash(),
+           "bytes_per_launch": int(round(fb + wb)), "fetch_bytes": int(round(fb)), "write_bytes": int(round(wb)),
+           "fetch_size_count_bytes": fetch_unit, "write_size_count_bytes": write_unit,
+           "dispatches_averaged": [len(kf), len(kw)],
+           "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on bench.py --stream-only --copy-calibration "
+                     "(commands in profiles/decode_fused_kernel_config2_stream512.txt)"}
+    with open(os.path.join(ROOT, "profiles", "traffic.json"), "w") as fh:
+        json.dump(rec, fh, indent=1)
+        fh.write("\n")
+    return rec
+
+
+def cold_series(torch, np, step, n, layers_per_step, setup_s):
+    """Per-step times of the first n steps after the GPU has been idle (the set-up packs layers on the host;
+    one more second of sleep on top), from HIP events recorded between the steps on the launch stream."""
+    torch.cuda.synchronize()
+    time.sleep(1.0)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(n):
+        step()
+        ev[i + 1].record()
+    t_issue = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    t_all = time.perf_counter() - t0
+    us = np.array([ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(n)])
+    cum_ms = np.cumsum(us) / 1e3
+
+    def mean(a, b):
+        return round(float(us[a:b].mean()), 2) if b <= n and b > a else None
+
+    windows = {}
+    for a, b in ((0, 1), (1, 5), (5, 25), (25, 50), (50, 100), (100, 200), (200, 300), (300, 500), (500, 1000),
+                 (1000, 2000)):
+        if b <= n:
+            windows["%d-%d" % (a, b)] = {"mean_us": mean(a, b), "min_us": round(float(us[a:b].min()), 2),
+                                         "max_us": round(float(us[a:b].max()), 2),
+                                         "ends_at_ms": round(float(cum_ms[b - 1]), 2)}
+    return {"cold_series": {"layers_per_step": layers_per_step, "steps": n, "setup_s": round(setup_s, 2),
+                            "idle_before_s": 1.0, "host_issue_s": round(t_issue, 4), "host_total_s": round(t_all, 4),
+                            "windows": windows, "first_40_us": [round(float(v), 1) for v in us[:40]],
+                            "every_25th_us": [round(float(v), 1) for v in us[::25]]}}
 
 
 def build_stream(B, I, torch, np, specs, cfg_no, batch):
@@ -317,10 +483,9 @@ def build_stream(B, I, torch, np, specs, cfg_no, batch):
     return layers, stack, x_all, y_all
 
 
-def stream_length_bench(B, I, torch, np, layers, spec, R2, batch, kind, stream, steps=200, warmup=300):
+def stream_length_bench(B, I, torch, np, layers, spec, R2, batch, kind, stream, proto):
     """The config-2 stream with R2 distinct layers: reuses the packed layers of the main run (and
-    packs more if R2 is larger); returns the step time and the achieved rate.  Same protocol as the main
-    run (300 untimed steps first: the clocks need tens of milliseconds of load to settle)."""
+    packs more if R2 is larger); returns the step time and the achieved rate, timed like the main run."""
     extra = []
     for i in range(len(layers), R2):
         L = I.make_layer(spec["n_in"], spec["n_out"], spec["k"], seed=I.seed_for(2, i))
@@ -332,44 +497,26 @@ def stream_length_bench(B, I, torch, np, layers, spec, R2, batch, kind, stream, 
         x_host = I.random_activations_fp16(rng, 1, R2 * batch * spec["n_in"])
         x = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
         y = torch.zeros(R2 * batch * spec["n_out"], dtype=torch.float16, device="cuda")
-        for _ in range(warmup):
-            B.dbf_stack_gemv(stack, x.data_ptr(), y.data_ptr(), batch, stream, kind)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            B.dbf_stack_gemv(stack, x.data_ptr(), y.data_ptr(), batch, stream, kind)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+        ms, protocol = proto.run(lambda: B.dbf_stack_gemv(stack, x.data_ptr(), y.data_ptr(), batch, stream, kind))
         nbytes = algorithmic_bytes(spec["n_in"], spec["n_out"], spec["k"], batch)[0] * R2
-        return {"ms_per_step": round(ms, 5), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 2)}
+        return {"ms_per_step": round(ms, 5), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 2), "protocol": protocol}
     finally:
         stack.close()
         for l in extra:
             l.close()
 
 
-def config5_bench(B, I, torch, np, batch, kind, stream, steps=60, warmup=60):
+def config5_bench(B, I, torch, np, batch, kind, stream, proto):
     """One decode pass over all 224 linear layers of the Llama-2-7B-shaped stack (1.21 GB of signs)."""
     specs = I.llama2_7b_stack_shapes()
     layers, stack, x_all, y_all = build_stream(B, I, torch, np, specs, 5, batch)
     try:
-        for _ in range(warmup):
-            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
+        ms, protocol = proto.run(lambda: B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind))
         nbytes = float(sum(algorithmic_bytes(sp["n_in"], sp["n_out"], sp["k"], batch)[0] for sp in specs))
         gbps = nbytes / (ms * 1e-3) / 1e9
         res = {"layers": len(specs), "batch": batch, "ms_per_token_pass": round(ms, 5),
                "token_passes_per_s": round(1e3 / ms, 1), "GBps": round(gbps, 2),
-               "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": nbytes, "steps": steps,
+               "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4), "algorithmic_bytes": nbytes, "protocol": protocol,
                "note": "all linear layers of a 32-block decoder at 1.5 bits/weight, one stack call per pass, "
                        "independent inputs per layer (no attention / norms between them)"}
         if batch == 1:  # the workload's other batch size: 16 tokens per pass through the same stack
@@ -379,19 +526,10 @@ def config5_bench(B, I, torch, np, batch, kind, stream, steps=60, warmup=60):
             x_host = I.random_activations_fp16(rng, 1, sum(b2 * sp["n_in"] for sp in specs))
             x2 = torch.from_numpy(x_host.view(np.int16).copy()).cuda().view(torch.float16).reshape(-1)
             y2 = torch.zeros(sum(b2 * sp["n_out"] for sp in specs), dtype=torch.float16, device="cuda")
-            for _ in range(10):
-                B.dbf_stack_gemv(stack, x2.data_ptr(), y2.data_ptr(), b2, stream, kind)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(20):
-                B.dbf_stack_gemv(stack, x2.data_ptr(), y2.data_ptr(), b2, stream, kind)
-            e1.record()
-            torch.cuda.synchronize()
-            ms2 = e0.elapsed_time(e1) / 20
+            ms2, protocol2 = proto.run(lambda: B.dbf_stack_gemv(stack, x2.data_ptr(), y2.data_ptr(), b2, stream, kind))
             nb2 = float(sum(algorithmic_bytes(sp["n_in"], sp["n_out"], sp["k"], b2)[0] for sp in specs))
             res["batch16"] = {"ms_per_pass": round(ms2, 5), "tokens_per_s": round(b2 * 1e3 / ms2, 1),
-                              "GBps": round(nb2 / (ms2 * 1e-3) / 1e9, 2)}
+                              "GBps": round(nb2 / (ms2 * 1e-3) / 1e9, 2), "protocol": protocol2}
         return res
     finally:
         stack.close()
@@ -409,12 +547,14 @@ PAPER_TABLE4_US = {
 }
 
 
-def table4_bench(B, I, torch, np, batch, kind, stream):
+def table4_bench(B, I, torch, np, batch, kind, stream, proto, bits_only=None):
     """Every (shape, bits per weight) of the second workload: the isolated call (cache warm) and a
     stream of distinct copies of the layer (at least 512 MB of signs, at most 256 copies) in one
     stack call per step."""
     rows = []
     for ci, cfg in enumerate(I.table4_configs()):
+        if bits_only is not None and cfg["bits"] not in bits_only:
+            continue
         n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
         nbytes = algorithmic_bytes(n_in, n_out, k, batch)[0]
         R = int(min(256, max(2, -(-(512 << 20) // nbytes))))
@@ -424,23 +564,13 @@ def table4_bench(B, I, torch, np, batch, kind, stream):
             xs = x_all[: batch * n_in]
             ys = y_all[: batch * n_out]
             iso = isolated_latency(B, torch, np, layers[0], xs, ys, batch, stream, kind)
-            steps = max(20, min(200, int(0.05 / (nbytes * R / 5e12))))
-            for _ in range(steps):
-                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(steps):
-                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / steps
+            ms, protocol = proto.run(lambda: B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, stream, kind))
             gbps = nbytes * R / (ms * 1e-3) / 1e9
             rows.append({"n_out": n_out, "n_in": n_in, "bits": cfg["bits"], "k": k,
                          "isolated_us_p50": iso["p50"], "back_to_back_us": iso["back_to_back_us"],
                          "stream_layers": R, "stream_us_per_layer": round(ms * 1e3 / R, 3),
                          "stream_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-                         "paper_rtx4090_us": PAPER_TABLE4_US.get((n_out, n_in), {}).get(cfg["bits"])})
+                         "protocol": protocol, "paper_rtx4090_us": PAPER_TABLE4_US.get((n_out, n_in), {}).get(cfg["bits"])})
         finally:
             stack.close()
             for l in layers:
@@ -479,7 +609,7 @@ def prune_bench(B, I, torch, np):
     return res
 
 
-def svid_bench(B, I, torch, np, stream, iters=8):
+def svid_bench(B, I, torch, np, stream, proto, iters=8):
     """dbf_svid (signs + `iters` rounds of power iteration) on two factor-sized fp32 matrices.  Bytes:
     Z is read once for the signs and twice per round (row dots, column dots); the packed signs and
     the vectors are negligible next to it."""
@@ -493,17 +623,7 @@ def svid_bench(B, I, torch, np, stream, iters=8):
         wsb = B.dbf_svid_workspace_bytes(rows, cols)
         ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
         args = (z.data_ptr(), rows, cols, iters, a.data_ptr(), m.data_ptr(), bits.data_ptr(), ws.data_ptr(), wsb, stream)
-        for _ in range(5):
-            B.dbf_svid(*args)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        n = 20
-        e0.record()
-        for _ in range(n):
-            B.dbf_svid(*args)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / n
+        ms, protocol = proto.run(lambda: B.dbf_svid(*args))
         nbytes = (2.0 * iters + 1.0) * rows * cols * 4.0
         t0 = time.time()
         from oracle import dbf_oracle as O
@@ -512,11 +632,11 @@ def svid_bench(B, I, torch, np, stream, iters=8):
         res["%dx%d_iters%d" % (rows, cols, iters)] = {
             "ms_per_call": round(ms, 4), "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-            "cpu_oracle_s": round(cpu_s, 3)}
+            "cpu_oracle_s": round(cpu_s, 3), "protocol": protocol}
     return res
 
 
-def admm_bench(B, I, torch, np, stream, svid_iters=2, rho=1.0):
+def admm_bench(B, I, torch, np, stream, proto, svid_iters=2, rho=1.0):
     """dbf_admm_step for the factor of a 4096 x 4096 weight with q = 2048 and q = 4096 middle channels (1 and 2
     bits per weight): the q x q x r fp32 contraction dominates (2 q^2 r flops, priced against the fp32
     matrix-core peak); around it the step reads or writes a q x r fp32 matrix 7 + 2 * svid_iters times
@@ -529,24 +649,15 @@ def admm_bench(B, I, torch, np, stream, svid_iters=2, rho=1.0):
         Minv = np.linalg.inv(B64.T @ B64 + rho * np.eye(q)).astype(np.float32)
         Cm = (B64.T @ W.astype(np.float64)).astype(np.float32)
         words = B.dbf_signs_to_bits_host(S)
-        d = {"Minv": torch.from_numpy(Minv).cuda(), "C": torch.from_numpy(Cm).cuda(), "a": torch.from_numpy(a).cuda(),
+        d = {"Minv": torch.from_numpy(np.ascontiguousarray(Minv.T)).cuda(), "C": torch.from_numpy(Cm).cuda(), "a": torch.from_numpy(a).cuda(),
              "m": torch.from_numpy(m).cuda(), "U": torch.from_numpy(U).cuda(),
              "bits": torch.from_numpy(B.dbf_tile_host(q, r, words)).cuda()}
         wsb = B.dbf_admm_workspace_bytes(q, r)
         ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
         args = (d["Minv"].data_ptr(), d["C"].data_ptr(), q, r, rho, svid_iters, d["a"].data_ptr(), d["m"].data_ptr(),
                 d["bits"].data_ptr(), d["U"].data_ptr(), ws.data_ptr(), wsb, stream)
-        for _ in range(3):
-            B.dbf_admm_step(*args)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        n = 20
-        e0.record()
-        for _ in range(n):
-            B.dbf_admm_step(*args)   # every call is the next ADMM iteration on the updated iterate
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / n
+        # (every call is the next ADMM iteration on the updated iterate)
+        ms, protocol = proto.run(lambda: B.dbf_admm_step(*args))
         flops = 2.0 * q * q * r
         nbytes = (7.0 + 2.0 * svid_iters) * q * r * 4.0 + 4.0 * q * q
         t0 = time.time()
@@ -558,7 +669,7 @@ def admm_bench(B, I, torch, np, stream, svid_iters=2, rho=1.0):
             "ms_per_step": round(ms, 4), "contraction_flops": flops,
             "tflops_whole_step": round(flops / (ms * 1e-3) / 1e12, 2),
             "frac_of_f32_mfma_peak_whole_step": round(flops / (ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
-            "elementwise_bytes": nbytes, "cpu_oracle_s": round(cpu_s, 3)}
+            "elementwise_bytes": nbytes, "cpu_oracle_s": round(cpu_s, 3), "protocol": protocol}
     return res
 
 
@@ -604,10 +715,10 @@ def read_ceiling(B, torch, stream):
     return probe.numel() * 5 / (p0.elapsed_time(p1) * 1e-3) / 1e9
 
 
-def prefill_bench(B, I, torch, np, stream):
-    """Both config-4 shapes at T = 2048, default variant (int8 matrix cores) and, next to it, the
-    fp16 variant.  TFLOP/s counts the factored work 2*T*k*(n_in+n_out) for either variant (the
-    int8 variant issues twice the multiply-adds, two int8 planes, at twice the rate)."""
+def prefill_bench(B, I, torch, np, stream, proto):
+    """Both config-4 shapes at T = 2048.  TFLOP/s counts the factored work 2*T*k*(n_in+n_out) and is priced
+    against the dense fp16 matrix-core peak (the kernel issues twice the multiply-adds, two int8 planes, at
+    twice the fp16 rate: the same fraction against the int8 peak)."""
     res = {}
     for cfg in I.CONFIG4:
         n_in, n_out, k, T = cfg["n_in"], cfg["n_out"], cfg["k"], cfg["T"]
@@ -622,26 +733,11 @@ def prefill_bench(B, I, torch, np, stream):
         y = torch.zeros((T, n_out), dtype=torch.float16, device="cuda")
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         flops = 2.0 * T * k * (n_in + n_out)
-        entry = {}
-        for name, kind in (("int8", B.GEMM_I8), ("f16", B.GEMM_F16)):
-            for _ in range(5):
-                B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream, kind)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            n = 20
-            e0.record()
-            for _ in range(n):
-                B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream, kind)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / n
-            tf = flops / (ms * 1e-3) / 1e12
-            entry[name] = {"ms": round(ms, 4), "tflops": round(tf, 2),
-                           "frac_of_f16_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4)}
-        best = entry["int8"]  # the default variant
-        res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)] = {"ms": best["ms"], "tflops": best["tflops"],
-                                                       "frac_of_f16_mfma_peak": best["frac_of_f16_mfma_peak"],
-                                                       "variant": "int8 (default)", "by_variant": entry}
+        ms, protocol = proto.run(lambda: B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), ws_bytes, stream))
+        tf = flops / (ms * 1e-3) / 1e12
+        res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)] = {
+            "ms": round(ms, 4), "tflops": round(tf, 2), "frac_of_f16_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
+            "variant": "int8 matrix cores, 16-bit fixed-point activations", "protocol": protocol}
         layer.close()
     return res
 
