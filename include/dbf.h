@@ -70,15 +70,7 @@ enum {
                           vector of each stage is rounded once to 16-bit fixed point.  Both
                           stages run in ONE launch: A-stage workgroups wait on the device for
                           their layer's B stage                                             */
-    DBF_GEMV_MFMA_SPLIT = 3, /* the same kernel in two launches (B stage, then A stage)     */
-    DBF_GEMV_PERSIST = 4 /* batch 1 only: the matrix-core adder as one persistent launch whose
-                          workgroups each walk a fixed sequence of work items and prefetch the
-                          next item's record, input and sign bits while streaming the current
-                          one.  Opt-in (AUTO does not pick it).  Runs only when the call
-                          qualifies (batch 1, n_in a multiple of 8, x 16-byte aligned, n_in and
-                          k <= 12288); otherwise it runs as DBF_GEMV_MFMA.  Needs the GPU to
-                          itself for the duration of the launch (all its workgroups must be
-                          resident together); see dbf_sync_timeouts                          */
+    DBF_GEMV_MFMA_SPLIT = 3 /* the same kernel in two launches (B stage, then A stage)      */
 };
 
 #define DBF_MAX_BATCH 16       /* largest batch dbf_gemv / dbf_stack_gemv accept */
@@ -143,37 +135,35 @@ int dbf_untile_host(int rows, int cols, const uint8_t* tiled, uint32_t* bits);
 int dbf_gemv(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, void* hip_stream);
 int dbf_gemv_kind(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, int kind,
                   void* hip_stream);
-/* In the one-launch kernel an A-stage workgroup waits on the device, with a bound of about
- * half a second, for the B stage of its layer.  The bound is never expected to be hit (a
- * B-stage workgroup never waits and is always dispatched before any A-stage one); if it is,
- * the workgroup goes on, its outputs are wrong, and a sticky counter is raised.  This call
- * synchronises the device and returns that counter in *timeouts (0 = every result is good).
- * Errors: DBF_EINVAL, DBF_EHIP. */
+/* The bounded wait of the one-launch kernel.  An A-stage workgroup waits on the device for the B stage of
+ * its layer, for at most DBF_TUNE_WAIT_LIMIT_US microseconds (default 250 000) of the GPU's constant-rate
+ * clock.  The bound is never expected to be hit: a B-stage workgroup never waits and is always dispatched
+ * before any A-stage one.  If it is hit, the workgroup gives up: every fp16 output it owns is written as a
+ * quiet NaN (0x7E00), so the failure is visible in y itself, with no extra call and no synchronisation; a
+ * sticky counter is raised as well.  The device-side counters stay consistent (they only ever grow), so
+ * later calls on the same layer or stack are not affected.
+ * dbf_sync_timeouts / dbf_stack_sync_timeouts synchronise the device and return the sticky counter in
+ * *timeouts (0 = no wait was ever given up).  Errors: DBF_EINVAL, DBF_EHIP. */
 int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
 
 /* ---- prefill: the same product for T tokens as two matrix-core contractions ------------
  * (The paper times batch 1 only, section 4.4; rows of X are independent, so the product is
- * defined for any T by the same expression, section 3.)  Two variants:
- *   DBF_GEMM_I8  (what dbf_gemm uses): the int8 matrix cores as the adder.  X.b, and later
- *                the middle activations, are rounded per token to 16-bit fixed point
- *                (q = rint(u * 32512 / max|u|)) and split into two int8 planes; the masked
- *                sign bytes are the other operand; the sums are exact integers; the middle
- *                activations stay in fp32.
- *   DBF_GEMM_F16 sign tiles expanded to +-1 fp16 in registers and multiplied with fp16 X.b on
- *                the fp16 matrix cores with fp32 accumulation; the middle activations are
- *                rounded once to fp16.
- *
+ * defined for any T by the same expression, section 3.)
+ *   DBF_GEMM_I8  the int8 matrix cores as the adder.  X.b, and later the middle activations, are rounded
+ *                per token to 16-bit fixed point (q = rint(u * 32512 / max|u|)) and split into two int8
+ *                planes; the masked sign bytes are the other operand; the sums are exact integers; the
+ *                middle activations stay in fp32.
  *   DBF_GEMM_AUTO (dbf_gemm): DBF_GEMM_I8; calls of up to DBF_MAX_BATCH tokens are run as a decode
  *                batch (dbf_gemv), which gives the same bits at a third of the latency.
  *
  * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1 (at most 65535 * 64).
- * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes (enough
- * for either variant), 256-byte aligned, contents undefined on return.  Asynchronous on the
+ * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes,
+ * 256-byte aligned, contents undefined on return.  Asynchronous on the
  * stream; allocates nothing.  Errors: DBF_EINVAL (NULL pointer, T < 1 or too large, unknown
  * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_EHIP.
  * dbf_gemm_workspace_bytes returns 0 for a NULL layer or T < 1.
  */
-enum { DBF_GEMM_AUTO = 0, DBF_GEMM_F16 = 1, DBF_GEMM_I8 = 2 };
+enum { DBF_GEMM_AUTO = 0, DBF_GEMM_I8 = 2 };
 size_t dbf_gemm_workspace_bytes(const dbf_layer* layer, int T);
 int dbf_gemm(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
              void* workspace_dev, size_t workspace_bytes, void* hip_stream);
@@ -244,7 +234,8 @@ int dbf_admm_step(const void* Minv_dev, const void* C_dev, int q, int r, float r
  * gap per layer.
  *
  * dbf_stack_create: layers[0..n_layers) must stay alive while the stack exists; the stack
- * only holds a device table describing them.  n_layers >= 1.
+ * only holds a device table describing them.  n_layers >= 1.  A layer may appear only once
+ * in a stack (its scratch would be shared by two products of one launch): DBF_EINVAL.
  * dbf_stack_gemv: x_dev is the concatenation over layers of fp16 [batch][n_in_i] blocks,
  * y_dev the concatenation of fp16 [batch][n_out_i] blocks; layer i's blocks start at
  * element offsets batch * (sum of n_in_j, j<i) and batch * (sum of n_out_j, j<i), which
@@ -295,6 +286,43 @@ int dbf_probe_read(const void* src_dev, size_t bytes, void* sink_dev, void* hip_
  * multiply-add).  sink_dev: device, 4 bytes, or NULL.  Asynchronous.  Errors: DBF_EINVAL, DBF_EHIP. */
 int dbf_probe_mfma(int wide, int with_ands, int wavefronts_per_simd, int iters, void* sink_dev,
                    void* hip_stream, double* ops);
+
+/* ---- tuning and test hooks ---------------------------------------------------------------
+ * Process-wide integers that steer how launch plans are cut and how launches behave.  The defaults are
+ * what the measurements in this repository were taken with; the hooks exist so that tests can force the
+ * rarely taken code paths (column pieces on short rows, the bounded wait giving up) and so that the cuts
+ * can be re-tuned on other shapes.  The library reads no environment variables.
+ * A knob is read when a plan is built (dbf_pack*, dbf_prune_middle, dbf_stack_create*: the PLAN knobs)
+ * or when a launch is issued (the LAUNCH knobs); changing one never affects plans that already exist.
+ * Not thread safe against concurrent pack / create / launch calls.
+ *   dbf_tuning_set:   DBF_EINVAL for an unknown knob or a value outside the stated range.
+ *   dbf_tuning_get:   the current value, or INT_MIN for an unknown knob.
+ *   dbf_tuning_reset: every knob back to its default. */
+enum {
+    /* PLAN knobs */
+    DBF_TUNE_COL_PIECES = 0,          /* -1 (default): cut long rows of small launches into column pieces by the
+                                         built-in rule; 0: never cut; N in 1..64: cut into N wherever N pieces of
+                                         at least 8 column tiles fit                                              */
+    DBF_TUNE_PIECE_TARGET = 1,        /* 0 (default): built-in (256 workgroups per stage, 1024 if the stage already
+                                         has more than 256 row tiles); else that many workgroups per stage, 1..65536 */
+    DBF_TUNE_PIECE_MIN_TILES = 2,     /* smallest piece in column tiles, 1..4096 (default 24)                      */
+    DBF_TUNE_PIECE_NEVER_TILES = 3,   /* rows of at most this many column tiles are never cut, 0..65536 (default 64) */
+    DBF_TUNE_PIECE_MAX_ROW_TILES = 4, /* plans with more row tiles per stage are never cut, 0..2^20 (default 1024)  */
+    DBF_TUNE_STACK_SPAN_B = 5,        /* row tiles per B-stage workgroup in stacks: 0 (default) = chosen per layer  */
+    DBF_TUNE_STACK_SPAN_A = 6,        /*   from the launch size, else 1..16; the same for the A stage              */
+    /* LAUNCH knobs */
+    DBF_TUNE_SHARED_Q = 7,            /* batches >= 2: -1 (default) built-in choice; 0: every workgroup quantises its
+                                         own input; 1: input quantised once per call and copied to LDS; 2: read from
+                                         memory tile by tile                                                       */
+    DBF_TUNE_SHARED_MIN_BATCH = 8,    /* smallest batch that takes the once-per-call quantisation, 2..17 (default 2) */
+    DBF_TUNE_SHARED_LDS_KB = 9,       /* LDS budget per workgroup for the copied input, 16..64 KiB (default 52)     */
+    DBF_TUNE_WAIT_LIMIT_US = 10,      /* bound of the device-side wait in microseconds, 0..10 000 000 (default
+                                         250 000); 0 makes every wait that is not already satisfied give up        */
+    DBF_TUNE_COUNT_ = 11
+};
+int dbf_tuning_set(int knob, int value);
+int dbf_tuning_get(int knob);
+void dbf_tuning_reset(void);
 
 const char* dbf_strerror(int code);
 

@@ -18,8 +18,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdbf.so")
 
 DBF_OK, DBF_EINVAL, DBF_ESHAPE, DBF_ENOTSIGN, DBF_ENOMEM, DBF_EHIP, DBF_EWORKSPACE = 0, -1, -2, -3, -4, -5, -6
-GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT, GEMV_PERSIST = 0, 1, 2, 3, 4
-GEMM_AUTO, GEMM_F16, GEMM_I8 = 0, 1, 2
+GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT = 0, 1, 2, 3
+GEMM_AUTO, GEMM_I8 = 0, 2
+(TUNE_COL_PIECES, TUNE_PIECE_TARGET, TUNE_PIECE_MIN_TILES, TUNE_PIECE_NEVER_TILES, TUNE_PIECE_MAX_ROW_TILES,
+ TUNE_STACK_SPAN_B, TUNE_STACK_SPAN_A, TUNE_SHARED_Q, TUNE_SHARED_MIN_BATCH, TUNE_SHARED_LDS_KB,
+ TUNE_WAIT_LIMIT_US) = range(11)
 MAX_BATCH = 16
 
 EXPORTS = [
@@ -29,6 +32,7 @@ EXPORTS = [
     "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
     "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_admm_workspace_bytes", "dbf_admm_step", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
+    "dbf_tuning_set", "dbf_tuning_get", "dbf_tuning_reset",
 ]
 
 _lib = None
@@ -86,6 +90,10 @@ def lib() -> C.CDLL:
     L.dbf_admm_step.argtypes = [vp, vp, i32, i32, C.c_float, i32, vp, vp, vp, vp, vp, sz, vp]
     L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
     L.dbf_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp, C.POINTER(C.c_double)]
+    L.dbf_tuning_set.argtypes = [i32, i32]
+    L.dbf_tuning_get.argtypes = [i32]
+    L.dbf_tuning_reset.argtypes = []
+    L.dbf_tuning_reset.restype = None
     L.dbf_strerror.argtypes = [i32]
     L.dbf_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -327,6 +335,18 @@ def dbf_probe_mfma(wide: bool, with_ands: bool, wavefronts_per_simd: int, iters:
     _check(lib().dbf_probe_mfma(int(wide), int(with_ands), wavefronts_per_simd, iters, sink_ptr, stream,
                                 C.byref(ops)), "dbf_probe_mfma")
     return float(ops.value)
+
+
+def dbf_tuning_set(knob: int, value: int) -> None:
+    _check(lib().dbf_tuning_set(int(knob), int(value)), "dbf_tuning_set")
+
+
+def dbf_tuning_get(knob: int) -> int:
+    return int(lib().dbf_tuning_get(int(knob)))
+
+
+def dbf_tuning_reset() -> None:
+    lib().dbf_tuning_reset()
 
 
 def dbf_sync_timeouts(layer: Layer) -> int:

@@ -22,8 +22,6 @@ SOURCES = [
     "dbf_api.hip",
     "dbf_gemv_valu.hip",
     "dbf_gemv_mfma.hip",
-    "dbf_gemv_persist.hip",
-    "dbf_gemm_mfma.hip",
     "dbf_gemm_i8.hip",
     "dbf_probe.hip",
     "dbf_prune.hip",
@@ -56,6 +54,40 @@ def _compile(src: str) -> str:
     if warn:
         print(warn, file=sys.stderr)
     return obj
+
+
+def _compile_to(src_path: str, obj: str, extra) -> str:
+    cmd = [_hipcc(), *FLAGS, *extra, "-x", "hip", "-c", src_path, "-o", obj]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src_path, res.stdout, res.stderr))
+    return obj
+
+
+def build_sanitize_check(driver_cpp: str) -> str:
+    """Links `driver_cpp` (a C++ program that calls the C ABI) with the library's sources into an executable
+    whose HOST code is instrumented with AddressSanitizer and UndefinedBehaviorSanitizer: the packer / tile
+    layout and the file that holds the argument checks are compiled with the sanitizers, the kernel files are
+    taken as already built (their host side is launch glue).  GPU code is never instrumented (each
+    -fsanitize= sits behind -Xarch_host).  Returns the path of the executable."""
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    out_dir = os.path.join(OBJ, "sanitize")
+    os.makedirs(out_dir, exist_ok=True)
+    plain = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES
+             if s not in ("dbf_layout.cpp", "dbf_api.hip")]
+    if not all(os.path.exists(o) for o in plain):
+        build(verbose=False)
+    objs = [_compile_to(os.path.join(CSRC, "dbf_layout.cpp"), os.path.join(out_dir, "dbf_layout.o"), san),
+            _compile_to(os.path.join(CSRC, "dbf_api.hip"), os.path.join(out_dir, "dbf_api.o"), san),
+            _compile_to(driver_cpp, os.path.join(out_dir, "driver.o"), san)]
+    exe = os.path.join(out_dir, "sanitize_host")
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+           "-o", exe, *objs, *plain]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("sanitizer link failed:\n%s\n%s" % (res.stdout, res.stderr))
+    return exe
 
 
 def build(verbose: bool = True) -> str:

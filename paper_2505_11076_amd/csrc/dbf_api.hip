@@ -2,6 +2,7 @@
 // Every operation of the layer product itself runs in the HIP kernels; this file only
 // validates, allocates at pack time, and launches.
 #include <algorithm>
+#include <climits>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -59,35 +60,44 @@ void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool
     for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);  // items of this call
 }
 
+// Tuning and test hooks (include/dbf.h, "tuning and test hooks"): default, smallest and largest value per knob.
+struct Knob {
+    int value, def, lo, hi;
+};
+Knob g_knobs[DBF_TUNE_COUNT_] = {
+    {-1, -1, -1, 64},             // DBF_TUNE_COL_PIECES
+    {0, 0, 0, 65536},             // DBF_TUNE_PIECE_TARGET
+    {24, 24, 1, 4096},            // DBF_TUNE_PIECE_MIN_TILES
+    {64, 64, 0, 65536},           // DBF_TUNE_PIECE_NEVER_TILES
+    {1024, 1024, 0, 1 << 20},     // DBF_TUNE_PIECE_MAX_ROW_TILES
+    {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_B
+    {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_A
+    {-1, -1, -1, 2},              // DBF_TUNE_SHARED_Q
+    {2, 2, 2, DBF_MAX_BATCH + 1}, // DBF_TUNE_SHARED_MIN_BATCH
+    {52, 52, 16, 64},             // DBF_TUNE_SHARED_LDS_KB
+    {250000, 250000, 0, 10000000},// DBF_TUNE_WAIT_LIMIT_US
+};
+
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
 // the whole input row for the quantisation scale) and the last piece an extra epilogue, which at 4096
 // columns costs more than the added parallelism gains (measured 17 vs 14 us for a 4096 x 4096 layer
-// alone).  So rows of up to PIECE_NEVER_TILES column tiles are never cut, pieces hold at least
-// PIECE_MIN_TILES tiles, and a stage is cut until it offers about PIECE_TARGET_ITEMS workgroups.
-// Environment overrides (experiments and tests): DBF_COL_PIECES = 0 never cut / N cut into N where it
-// fits; DBF_PIECE_TARGET, DBF_PIECE_MIN_TILES, DBF_PIECE_NEVER_TILES, DBF_PIECE_MAX_ROW_TILES.
-constexpr int PIECE_MIN_TILES = 24;
-constexpr int PIECE_NEVER_TILES = 64;
+// alone).  So rows of up to DBF_TUNE_PIECE_NEVER_TILES column tiles are never cut, pieces hold at least
+// DBF_TUNE_PIECE_MIN_TILES tiles, and a stage is cut until it offers about PIECE_TARGET_ITEMS workgroups.
 constexpr int PIECE_TARGET_ITEMS = 256;
 constexpr int PIECE_TARGET_STREAM = 1024;  // the same for launches that hold more row tiles than that already
-constexpr int PIECE_MAX_ROW_TILES = 1024;  // plans with more row tiles than this per stage are never cut
-
-int env_int(const char* name, int fallback) {
-    const char* e = std::getenv(name);
-    return e ? std::atoi(e) : fallback;
-}
 
 // Pieces per row tile of a stage with n_ct column tiles when the launch holds stage_row_tiles row
 // tiles of that stage.
 int pieces_for(int n_ct, int stage_row_tiles) {
-    const int forced = env_int("DBF_COL_PIECES", -1);
+    const int forced = dbf_tune(DBF_TUNE_COL_PIECES);
     if (forced == 0) return 1;
-    const int min_tiles = std::max(1, env_int("DBF_PIECE_MIN_TILES", PIECE_MIN_TILES));
-    if (forced < 0 && n_ct <= env_int("DBF_PIECE_NEVER_TILES", PIECE_NEVER_TILES)) return 1;
+    const int min_tiles = dbf_tune(DBF_TUNE_PIECE_MIN_TILES);
+    if (forced < 0 && n_ct <= dbf_tune(DBF_TUNE_PIECE_NEVER_TILES)) return 1;
     // (a stage of several layers with a few hundred long row tiles wants two rounds of items, not a quarter of one:
     //  8192 x 28672 streams of 8-13 layers gained 4-19 % with their rows cut in two, one layer alone lost with more
     //  than about 256 items)
-    const int target = env_int("DBF_PIECE_TARGET", stage_row_tiles > PIECE_TARGET_ITEMS ? PIECE_TARGET_STREAM : PIECE_TARGET_ITEMS);
+    int target = dbf_tune(DBF_TUNE_PIECE_TARGET);
+    if (target == 0) target = stage_row_tiles > PIECE_TARGET_ITEMS ? PIECE_TARGET_STREAM : PIECE_TARGET_ITEMS;
     int want = forced > 0 ? forced : (target + stage_row_tiles - 1) / stage_row_tiles;
     const int fit = n_ct / (forced > 0 ? 8 : min_tiles);
     if (want > fit) want = fit;
@@ -203,7 +213,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     std::vector<int> pcB(n, 1), pcA(n, 1);
     bool cut = false;
-    const int max_rt = env_int("DBF_PIECE_MAX_ROW_TILES", PIECE_MAX_ROW_TILES);
+    const int max_rt = dbf_tune(DBF_TUNE_PIECE_MAX_ROW_TILES);
     if (rtB <= max_rt && rtA <= max_rt) {
         for (int i = 0; i < n; ++i) {
             pcB[i] = pieces_for(sB[i].n_ct, (int)rtB);
@@ -221,8 +231,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     const size_t o_wA = off;  off = align_up(off + sizeof(DbfWorkItem) * wA1.size(), 256);
     const size_t o_in = off;  off = align_up(off + sizeof(DbfItem) * items_n.size(), 256);
     const size_t o_i1 = off;  off = align_up(off + sizeof(DbfItem) * items_1.size(), 256);
-    const size_t o_sy = off;  off = align_up(off + sizeof(int) * (2 * (size_t)n + 1), 256);
-    const size_t o_ps = off;  off = align_up(off + sizeof(unsigned) * ((size_t)n + 3), 256);
+    const size_t o_sy = off;  off = align_up(off + sizeof(unsigned long long) * (2 * (size_t)n + 1), 256);
     const size_t o_ac = off;  off = align_up(off + sizeof(int) * acc_ints, 256);
     const size_t o_cn = off;  off = align_up(off + sizeof(int) * cnt_ints, 256);
     std::vector<DbfItem> items_p;
@@ -288,20 +297,11 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->d_items_1 = reinterpret_cast<DbfItem*>(d + o_i1);
     p->nB1 = nB1;
     p->nA1 = (int)items_1.size() - nB1;
-    p->d_sync = reinterpret_cast<int*>(d + o_sy);
-    p->d_psync = reinterpret_cast<unsigned*>(d + o_ps);
+    p->d_sync = reinterpret_cast<unsigned long long*>(d + o_sy);
     p->d_items_p = cut ? reinterpret_cast<DbfItem*>(d + o_ip) : nullptr;
     p->nBp = nBp;
     p->nAp = (int)items_p.size() - nBp;
     p->span = max_span;
-    p->persist_ok = p->span <= DBF_PERSIST_MAX_SPAN && p->max_cols_B <= DBF_PERSIST_MAX_COLS &&
-                    p->max_cols_A <= DBF_PERSIST_MAX_COLS;
-    for (int i = 0; i < n; ++i)
-        if (sB[i].cols & 7) p->persist_ok = 0;  // x rows must be readable in 16-byte pieces
-    if (const char* e = std::getenv("DBF_PERSIST_MAX_WG")) {  // test hook: fewer, longer-lived workgroups
-        p->persist_max_wg = std::atoi(e);
-        if (p->persist_max_wg < 0) p->persist_max_wg = 0;
-    }
     return DBF_OK;
 }
 
@@ -422,13 +422,7 @@ int build_layer(int n_in, int n_out, int k, const uint32_t* A_bits, const uint32
 }
 
 inline bool kind_ok(int kind) {
-    return kind == DBF_GEMV_AUTO || kind == DBF_GEMV_VALU || kind == DBF_GEMV_MFMA ||
-           kind == DBF_GEMV_MFMA_SPLIT || kind == DBF_GEMV_PERSIST;
-}
-
-// The persistent kernel handles batch 1 with 16-byte readable inputs and bounded item sizes.
-inline bool persist_eligible(const DbfPlan& p, const void* x, int batch) {
-    return batch == 1 && p.persist_ok && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+    return kind == DBF_GEMV_AUTO || kind == DBF_GEMV_VALU || kind == DBF_GEMV_MFMA || kind == DBF_GEMV_MFMA_SPLIT;
 }
 
 // Launches one decode pass of a plan on `stream`.  `mid`, if not NULL, is recorded between the
@@ -437,17 +431,10 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
                 hipEvent_t mid = nullptr) {
     // AUTO: a group of layers runs as one fused launch; a single layer is faster as two launches
     // (measured 14.3 vs 15.5 us at 4096 x 4096, k = 2048: the second launch's set-up overlaps the
-    // first kernel instead of its workgroups polling).  The persistent kernel is opt-in.
+    // first kernel instead of its workgroups polling).
     const bool pieces_ok = kind == DBF_GEMV_AUTO;  // the named kinds keep their one-workgroup-per-row-tile lists
     if (kind == DBF_GEMV_AUTO) kind = p.n_layers > 1 ? DBF_GEMV_MFMA : DBF_GEMV_MFMA_SPLIT;
-    if (kind == DBF_GEMV_PERSIST && !persist_eligible(p, x, batch)) kind = DBF_GEMV_MFMA;
-    if (kind == DBF_GEMV_PERSIST) {
-        const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
-        DBF_HIP_TRY(dbf_launch_persistent(p.d_items_n, p.nBn + p.nAn, p.d_psync, p.d_sync + 2 * p.n_layers,
-                                          p.n_layers, x, y, max_cols, p.persist_max_wg, stream));
-        if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-        return DBF_OK;
-    }
+    const int wait_us = dbf_tune(DBF_TUNE_WAIT_LIMIT_US);
     if (kind == DBF_GEMV_VALU) {
         DBF_HIP_TRY(dbf_launch_stage_valu(false, p.d_stagesB, p.d_workB1, p.blocksB1, x, y, batch, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
@@ -460,10 +447,9 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     // Batches of 2 and more: every stage input is quantised once per call; the items copy it into LDS (1)
     // or, if a whole row does not fit there at this batch, read it from memory tile by tile (2).
     int shared_q = 0;
-    if (pieces_ok && !use_pieces && batch >= env_int("DBF_SHARED_MIN_BATCH", 2)) {
+    if (pieces_ok && !use_pieces && batch >= dbf_tune(DBF_TUNE_SHARED_MIN_BATCH)) {
         shared_q = dbf_mfma_chunk_tiles(batch, max_cols, 1) >= dbf_col_tiles(max_cols) ? 1 : 2;
-        shared_q = env_int("DBF_SHARED_Q", shared_q);
-        if (shared_q < 0 || shared_q > 2) shared_q = 0;
+        if (dbf_tune(DBF_TUNE_SHARED_Q) >= 0) shared_q = dbf_tune(DBF_TUNE_SHARED_Q);
     }
     const bool span = dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols);
     const DbfItem* items = span ? p.d_items_n : p.d_items_1;
@@ -478,55 +464,37 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     if (shared_q) {
         // Four launches: quantise x, B items, quantise t, A items.
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesB, p.n_layers, 0, x, batch, stream));
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, wait_us, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesA, p.n_layers, 1, x, batch, stream));
-        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, wait_us, stream));
         return DBF_OK;
     }
     if (kind == DBF_GEMV_MFMA) {
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, 0, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, 0, wait_us, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         return DBF_OK;
     }
-    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, wait_us, stream));
     if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, wait_us, stream));
     return DBF_OK;
 }
 
 int read_timeouts(const DbfPlan& p, int* timeouts) {
-    int v = 0;
+    unsigned long long v = 0;
     DBF_HIP_TRY(hipDeviceSynchronize());
-    DBF_HIP_TRY(hipMemcpy(&v, p.d_sync + 2 * p.n_layers, sizeof(int), hipMemcpyDeviceToHost));
-    if (timeouts) *timeouts = v;
+    DBF_HIP_TRY(hipMemcpy(&v, p.d_sync + 2 * p.n_layers, sizeof(v), hipMemcpyDeviceToHost));
+    if (timeouts) *timeouts = v > 0x7fffffffull ? 0x7fffffff : (int)v;
     return DBF_OK;
 }
 
-std::vector<int> stack_spans(const char* env_name, const char* fallback) {
-    // Row tiles per workgroup in stack launches, as a cyclic pattern ("3,2,1,2").  The input
-    // vector is quantised once per workgroup, so larger items amortise that prologue and smaller
-    // ones balance the end of the launch; UNEQUAL neighbours matter as much: workgroups that all
-    // start together on equal items also finish together, and the launch then alternates
-    // between "everybody in the prologue" and "everybody streaming" instead of keeping the
-    // memory system evenly busy.  The environment variables DBF_STACK_SPAN / DBF_STACK_SPAN_A
-    // give the patterns (values 1..16; experiments and tests); without them the pattern is empty
-    // and build_plan chooses per layer (auto_span).
-    const char* e = std::getenv(env_name);
-    std::vector<int> v;
-    if (!e && !*fallback) return v;
-    for (const char* q = e ? e : fallback; *q;) {
-        char* end = nullptr;
-        long x = std::strtol(q, &end, 10);
-        if (end == q) break;
-        if (x < 1) x = 1;
-        if (x > DBF_MAX_SPAN) x = DBF_MAX_SPAN;
-        v.push_back((int)x);
-        q = (*end == ',') ? end + 1 : end;
-        if (*end != ',' ) break;
-    }
-    if (v.empty()) v.push_back(1);
-    return v;
+// Row tiles per workgroup in stack launches: the tuning knob's fixed value, or (0) empty, which lets
+// build_plan choose per layer from the size of the launch (auto_span).  The input vector is quantised once
+// per workgroup, so larger items amortise that prologue and smaller ones balance the end of the launch.
+std::vector<int> stack_spans(int knob) {
+    const int v = dbf_tune(knob);
+    return v > 0 ? std::vector<int>(1, v) : std::vector<int>();
 }
 
 }  // namespace
@@ -535,14 +503,13 @@ extern "C" {
 
 size_t dbf_gemm_workspace_bytes(const dbf_layer* L, int T) {
     if (!L || T < 1) return 0;
-    const size_t a = dbf_gemm_f16_workspace_bytes(L, T), b = dbf_gemm_i8_workspace_bytes(L, T);
-    return a > b ? a : b;  // enough for either variant
+    return dbf_gemm_i8_workspace_bytes(L, T);
 }
 
 int dbf_gemm_kind(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
                   size_t workspace_bytes, int kind, void* hip_stream) {
     if (!L || !X_dev || !Y_dev || T < 1) return DBF_EINVAL;
-    if (kind != DBF_GEMM_AUTO && kind != DBF_GEMM_F16 && kind != DBF_GEMM_I8) return DBF_EINVAL;
+    if (kind != DBF_GEMM_AUTO && kind != DBF_GEMM_I8) return DBF_EINVAL;
     if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) ||
         workspace_bytes < dbf_gemm_workspace_bytes(L, T))
         return DBF_EWORKSPACE;
@@ -552,9 +519,7 @@ int dbf_gemm_kind(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, voi
     // kernel's bits), at a third of the latency (a prefill workgroup walks all column steps of its rows
     // whatever the token count: 67 us against 24 us at 4096 x 4096, k = 4096).
     if (kind == DBF_GEMM_AUTO && T <= DBF_MAX_BATCH) return launch_plan(DBF_GEMV_AUTO, L->plan, X_dev, Y_dev, T, stream);
-    if (kind == DBF_GEMM_AUTO) kind = DBF_GEMM_I8;
-    const hipError_t e = kind == DBF_GEMM_I8 ? dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, stream)
-                                             : dbf_gemm_f16_launch(L, X_dev, Y_dev, T, workspace_dev, stream);
+    const hipError_t e = dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return DBF_EHIP;
@@ -682,6 +647,11 @@ int dbf_stack_create_grouped(const dbf_layer* const* layers, int n_layers, const
         if (!layers[i]) return DBF_EINVAL;
     for (int i = 1; i < n_layers; ++i)
         if (layers[i]->device != layers[0]->device) return DBF_EINVAL;
+    {   // a layer may appear only once: its scratch would be shared by two products of one launch
+        std::vector<const dbf_layer*> sorted(layers, layers + n_layers);
+        std::sort(sorted.begin(), sorted.end());
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return DBF_EINVAL;
+    }
     // group of every layer: consecutive layers that read one input block
     std::vector<int> first_of(n_layers);
     if (group_sizes) {
@@ -728,7 +698,7 @@ int dbf_stack_create_grouped(const dbf_layer* const* layers, int n_layers, const
         S->h_y_prefix[i + 1] = S->h_y_prefix[i] + L->n_out;
     }
     S->h_x_prefix[n_layers] = x_end;
-    const int rc = build_plan(sB, sA, stack_spans("DBF_STACK_SPAN", ""), stack_spans("DBF_STACK_SPAN_A", ""), &S->plan);
+    const int rc = build_plan(sB, sA, stack_spans(DBF_TUNE_STACK_SPAN_B), stack_spans(DBF_TUNE_STACK_SPAN_A), &S->plan);
     if (rc != DBF_OK) {
         dbf_stack_free(S);
         return rc;
@@ -793,6 +763,22 @@ void dbf_stack_free(dbf_stack* S) {
     delete S;
 }
 
+int dbf_tuning_set(int knob, int value) {
+    if (knob < 0 || knob >= DBF_TUNE_COUNT_) return DBF_EINVAL;
+    if (value < g_knobs[knob].lo || value > g_knobs[knob].hi) return DBF_EINVAL;
+    g_knobs[knob].value = value;
+    return DBF_OK;
+}
+
+int dbf_tuning_get(int knob) {
+    if (knob < 0 || knob >= DBF_TUNE_COUNT_) return INT_MIN;
+    return g_knobs[knob].value;
+}
+
+void dbf_tuning_reset(void) {
+    for (Knob& k : g_knobs) k.value = k.def;
+}
+
 const char* dbf_strerror(int code) {
     switch (code) {
         case DBF_OK: return "ok";
@@ -807,3 +793,5 @@ const char* dbf_strerror(int code) {
 }
 
 }  // extern "C"
+
+int dbf_tune(int knob) { return g_knobs[knob].value; }

@@ -23,6 +23,7 @@
 // tiles and operand columns of step kt + 4 are requested while step kt is computed, by loads
 // issued and waited for by hand (see the stage kernel).
 #include "dbf_kernels.h"
+#include "dbf_wave.h"
 
 namespace {
 
@@ -49,30 +50,6 @@ constexpr int QI_THREADS = 64 * QI_WAVES;
 constexpr int QI_STAGE_BYTES = 2 * QI_TOKENS * 64 / QI_THREADS;  // operand bytes a thread stages per step
 static_assert(QI_STAGE_BYTES == 32, "staging is two 16-byte pieces per thread");
 
-template <int CTRL>
-__device__ inline int dpp_move(int v) {
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
-}
-__device__ inline float wave_max(float v) {
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0xB1>(__builtin_bit_cast(int, v))));
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x4E>(__builtin_bit_cast(int, v))));
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x124>(__builtin_bit_cast(int, v))));
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x128>(__builtin_bit_cast(int, v))));
-    const int b = __builtin_bit_cast(int, v);
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
-    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
-    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-__device__ inline int wave_sum(int v) {
-    v += dpp_move<0xB1>(v);
-    v += dpp_move<0x4E>(v);
-    v += dpp_move<0x124>(v);
-    v += dpp_move<0x128>(v);
-    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
-           __builtin_amdgcn_readlane(v, 48);
-}
 
 // ---------------------------------------------------------------------------------------------
 // Quantisation of token rows: q = rint(u * 32512 / max|u|), hi/lo int8 planes.
@@ -171,7 +148,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs 
                 for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[r][i]));
             }
         }
-        mx = wave_max(mx);
+        mx = dbf_wave_max(mx);
         const float inv = mx > 0.f ? QMAX / mx : 0.f;
 #pragma unroll
         for (int r = 0; r < HOLD; ++r) {
@@ -185,7 +162,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs 
 #pragma unroll
             for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[i]));
         }
-        mx = wave_max(mx);
+        mx = dbf_wave_max(mx);
         const float inv = mx > 0.f ? QMAX / mx : 0.f;
         for (int v = lane; v < nvec; v += 64) {
             float u[8];
@@ -193,7 +170,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs 
             local += quantise_store(a, token, v, u, inv);
         }
     }
-    local = wave_sum(local);
+    local = dbf_wave_sum(local);
     if (lane == 0) {
         a.scale[token] = mx / QMAX;
         a.sigma[token] = local;
@@ -215,7 +192,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_block_kernel(const Quan
 #pragma unroll
         for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[i]));
     }
-    mx = wave_max(mx);
+    mx = dbf_wave_max(mx);
     if (lane == 0) wmax[w] = mx;
     __syncthreads();
     mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
@@ -240,7 +217,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_block_kernel(const Quan
         *reinterpret_cast<uint2*>(d) = make_uint2(hi4[0], hi4[1]);
         *reinterpret_cast<uint2*>(d + 64) = make_uint2(lo4[0], lo4[1]);
     }
-    local = wave_sum(local);
+    local = dbf_wave_sum(local);
     if (lane == 0) wsum[w] = local;
     __syncthreads();
     if (tid == 0) {

@@ -30,15 +30,18 @@
 // load pipeline.
 //
 // Fused launch: the item list holds every B-stage item before any A-stage item, and
-// workgroups are dispatched in list order.  An A-stage workgroup issues its first sign-bit
-// loads, then waits (bounded) until the layer's B-stage workgroups have published all their
-// rows of t, so both stages of all layers run in ONE launch and HBM never drains in between.
-// A B-stage workgroup never waits, so every wait ends; should the bound be hit anyway the
-// workgroup goes on (its result is then wrong) and counts a time-out the host can read.
+// workgroups are dispatched in list order.  An A-stage workgroup waits (bounded) until the
+// layer's B-stage workgroups have published all their rows of t, so both stages of all layers
+// run in ONE launch and HBM never drains in between.  A B-stage workgroup never waits, so every
+// wait ends; should the bound be hit anyway, the workgroup writes NaN to the outputs it owns
+// and counts a time-out.  The counters only ever grow (no resets), so they stay consistent
+// whatever happens: "published so far" is compared with what this launch must add on top of
+// the launches that have completed.
 #include <cstdlib>
 #include <type_traits>
 
 #include "dbf_kernels.h"
+#include "dbf_wave.h"
 
 // 1: tile loads by inline assembly with exact hand-placed waits (the fast path).
 // 0: the same loads through the compiler builtin (it then waits with vmcnt(0) per group).
@@ -84,40 +87,13 @@ constexpr int XQ_PAD = 16;         // bytes of padding per operand row (LDS bank
 // operand columns share a bank, which at 16 live columns (batch 8) made the reduction as long as the streaming.
 constexpr int RB_STRIDE = DBF_RB_STRIDE;
 constexpr unsigned OOB = 0x80000000u;  // buffer offset that is out of range for any span
-constexpr int SPIN_LIMIT = 1 << 18;    // polls of a producer counter before giving up (~0.5 s)
+constexpr uint16_t HALF_QNAN = 0x7E00; // what a workgroup that gave up its wait stores
 
 __device__ inline float half_bits_to_float(uint16_t h) {
     return (float)__builtin_bit_cast(_Float16, h);
 }
 __device__ inline uint16_t float_to_half_bits(float f) {
     return __builtin_bit_cast(uint16_t, (_Float16)f);
-}
-// Wavefront reductions with data-parallel-primitive moves (register to register, a few cycles
-// each) instead of LDS-crossbar shuffles (~100 cycles each, six in a chain): butterflies inside
-// every row of 16 lanes, then the four row results through scalar registers.
-template <int CTRL>
-__device__ inline int dpp_move(int v) {
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
-}
-__device__ inline float wave_max(float v) {
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0xB1>(__builtin_bit_cast(int, v))));   // quad_perm [1,0,3,2]
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x4E>(__builtin_bit_cast(int, v))));   // quad_perm [2,3,0,1]
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x124>(__builtin_bit_cast(int, v))));  // row_ror:4
-    v = fmaxf(v, __builtin_bit_cast(float, dpp_move<0x128>(__builtin_bit_cast(int, v))));  // row_ror:8
-    const int b = __builtin_bit_cast(int, v);
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
-    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
-    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-__device__ inline int wave_sum(int v) {
-    v += dpp_move<0xB1>(v);
-    v += dpp_move<0x4E>(v);
-    v += dpp_move<0x124>(v);
-    v += dpp_move<0x128>(v);
-    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
-           __builtin_amdgcn_readlane(v, 48);
 }
 
 // Fixed part of the LDS carve-up (the quantised operand and the reduction buffers follow).
@@ -128,7 +104,9 @@ struct Misc {
     float wmax[4][DBF_MAX_BATCH];  // per-wavefront max|u|
     uint16_t rscale[DBF_MAX_SPAN * DBF_TILE_ROWS];  // fp16 row scales of this workgroup's rows
     int last;                      // column pieces: this workgroup was the last of its row tile to arrive
-    int pad_[3];
+    int gave_up;                   // the wait for the layer's B stage ended at its bound: outputs become NaN
+    int poisoned;                  // column pieces: some piece of this row tile gave up
+    int pad_[1];
 };
 static_assert(sizeof(Misc) % 16 == 0, "the operand rows behind it are read in 16-byte pieces");
 
@@ -239,7 +217,7 @@ __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const 
 #pragma unroll
     for (int j = 0; j < UNR; ++j)
         if (256 * j + c.tid < c.nvec) mx = fmaxf(mx, iv[j].absmax());
-    mx = wave_max(mx);
+    mx = dbf_wave_max(mx);
     if (c.lane == 0) c.misc->wmax[c.w][0] = mx;
     __syncthreads();
     mx = fmaxf(fmaxf(c.misc->wmax[0][0], c.misc->wmax[1][0]), fmaxf(c.misc->wmax[2][0], c.misc->wmax[3][0]));
@@ -251,7 +229,7 @@ __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const 
         const int v = 256 * j + c.tid;
         if (v < c.nvec) local += iv[j].quantise_to(c.xq + v * 8, c.xq + c.chs + v * 8, inv);
     }
-    local = wave_sum(local);
+    local = dbf_wave_sum(local);
     if (c.lane == 0) atomicAdd(&c.misc->sigma[0], local);
 }
 
@@ -277,7 +255,7 @@ __device__ inline void input_scales(const DbfItem& it, const Ctx& c) {
         } else {
             for (int l = c.tid; l < it.cols; l += 256) mx = fmaxf(mx, fabsf(load_u_scalar<STAGE_A>(it, c.x, bi, l)));
         }
-        mx = wave_max(mx);
+        mx = dbf_wave_max(mx);
         if (c.lane == 0) c.misc->wmax[c.w][bi] = mx;
     }
     __syncthreads();
@@ -328,7 +306,7 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
                 local += q;
             }
         }
-        local = wave_sum(local);
+        local = dbf_wave_sum(local);
         if (c.lane == 0) atomicAdd(&c.misc->sigma[bi], local);
     }
 }
@@ -348,9 +326,9 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // and the 32 accumulator registers are never cleared (2 of 47 vector instructions per tile).
 template <int NCG, bool PIECES, int SHARED, bool SINGLE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
-void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ sync, int n_layers,
+void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
-                           uint16_t* __restrict__ y_base, int batch, int ch_tiles) {
+                           uint16_t* __restrict__ y_base, int batch, int ch_tiles, int wait_limit_us) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int ncols = 2 * batch;
     const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
@@ -493,15 +471,25 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
 #endif
     };
     // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
+    // sync[layer] counts the B-stage row tiles published over all launches of this plan, sync[n_layers + layer]
+    // the A-stage items finished.  Launches of one plan do not overlap, so while this launch runs the second
+    // counter lies in [e * peers, (e + 1) * peers) with e the number of completed launches, and this launch's
+    // B stage is done when the first counter has reached (e + 1) * need.  The wait is bounded on the GPU's
+    // constant 100 MHz clock.
+    if (tid == 0) misc->gave_up = 0;
     if (use_sync && stage_a) {
         if (tid == 0) {
-            int spins = 0;
-            while (__hip_atomic_load(&sync[it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < it.need) {
-                __builtin_amdgcn_s_sleep(16);
-                if (++spins > SPIN_LIMIT) {  // never expected; keeps every wave finite
-                    __hip_atomic_fetch_add(&sync[2 * n_layers], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long fin = __hip_atomic_load(&sync[n_layers + it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long target = (fin / (unsigned)it.peers + 1ull) * (unsigned)it.need;
+            const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+            const unsigned long long limit = 100ull * (unsigned)wait_limit_us;
+            while (__hip_atomic_load(&sync[it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (__builtin_amdgcn_s_memrealtime() - t0 >= limit) {  // never expected; keeps every wave finite
+                    __hip_atomic_fetch_add(&sync[2 * n_layers], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    misc->gave_up = 1;
                     break;
                 }
+                __builtin_amdgcn_s_sleep(16);
             }
         }
         __syncthreads();  // t is read below with agent-scope loads, so no cache invalidation is needed
@@ -736,7 +724,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 }
                 const float val = (float)total * misc->scale[bi] * rscale;
                 if (stage_a) {
-                    if (row < it.rows) y[(size_t)bi * it.rows + row] = float_to_half_bits(val);
+                    // (a workgroup that gave up its wait has read an unfinished t: its outputs say so)
+                    if (row < it.rows) y[(size_t)bi * it.rows + row] = misc->gave_up ? HALF_QNAN : float_to_half_bits(val);
                 } else {
                     // agent-scope store: written through to memory, where the A-stage
                     // workgroups of other compute dies read it (padded rows have scale 0)
@@ -753,9 +742,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's adds have been performed ...
                 __syncthreads();                                  // ... and so have the workgroup's
                 if (tid == 0) {
+                    // low 16 bits: pieces arrived; above: pieces that gave up their wait (their sums are wrong)
                     int* cnt = piece_cnt();
-                    const int before = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    misc->last = before == n_pieces - 1;
+                    const int mine = 1 + (misc->gave_up ? 0x10000 : 0);
+                    const int before = __hip_atomic_fetch_add(cnt, mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    misc->last = (before & 0xFFFF) == n_pieces - 1;
+                    misc->poisoned = ((before + mine) >> 16) != 0;
                     if (misc->last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
                 __syncthreads();
@@ -767,7 +759,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         const float val = (float)total * misc->scale[bi] * rscale;
                         if (stage_a) {
-                            if (row < it.rows) y[(size_t)bi * it.rows + row] = float_to_half_bits(val);
+                            if (row < it.rows) y[(size_t)bi * it.rows + row] = misc->poisoned ? HALF_QNAN : float_to_half_bits(val);
                         } else {
                             __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + (size_t)bi * it.t_stride + row,
                                                __builtin_bit_cast(unsigned, val), __ATOMIC_RELAXED,
@@ -789,10 +781,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
         for (int j = 0; j < PF; ++j) fetch(j);
     }
 
-    // ---- fused launch: a B-stage item publishes its rows of t.  The counters are per layer
-    // (one shared counter for the whole grid would serialise thousands of atomics on one
-    // address).  The last A-stage item of a layer to finish clears the layer's two counters
-    // for the next launch: every A-stage item of the layer has passed its wait by then.
+    // ---- fused launch: a B-stage item publishes its rows of t, an A-stage item counts itself finished.  The
+    // counters are per layer (one shared counter for the whole grid would serialise thousands of atomics on one
+    // address) and only ever grow; neither add needs its result back.
     if (use_sync) {
         if (!stage_a) {
             // this wavefront's write-through stores of t have been acknowledged by memory ...
@@ -800,14 +791,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, int* __restrict__ 
             __syncthreads();  // ... and so have those of the whole workgroup
             // (of the pieces of a row tile only the one that stored the result publishes it)
             if (tid == 0 && (n_pieces == 1 || misc->last))
-                __hip_atomic_fetch_add(&sync[it.layer], it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&sync[it.layer], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else if (tid == 0) {
-            const int fin = __hip_atomic_fetch_add(&sync[n_layers + it.layer], 1, __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-            if (fin == it.peers - 1) {
-                __hip_atomic_store(&sync[it.layer], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&sync[n_layers + it.layer], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            __hip_atomic_fetch_add(&sync[n_layers + it.layer], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -892,8 +878,7 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q) {
         return all < 4 ? 4 : all;
     }
     if (shared_q) {
-        const int env = []() { const char* e = std::getenv("DBF_SHARED_LDS_KB"); return e ? std::atoi(e) : 52; }();
-        const int roomy = env * 1024 - (int)sizeof(Misc) - 2 * RB_STRIDE * 4 * ncols;
+        const int roomy = dbf_tune(DBF_TUNE_SHARED_LDS_KB) * 1024 - (int)sizeof(Misc) - 2 * RB_STRIDE * 4 * ncols;
         if (roomy > budget) budget = roomy;
     }
     int ch_tiles = ((budget / ncols - XQ_PAD) / DBF_TILE_COLS) & ~3;
@@ -914,9 +899,9 @@ hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, in
     return hipGetLastError();
 }
 
-hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
+hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned long long* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, int pieces, int shared_q, hipStream_t stream) {
+                                 int max_cols, int pieces, int shared_q, int wait_limit_us, hipStream_t stream) {
     if (n_items <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
@@ -925,27 +910,27 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, i
     // column pieces (small batches only)
     if (shared_q == 2 && batch <= 8)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (shared_q == 2)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (shared_q && batch <= 8)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 1, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (shared_q)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 1, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (pieces)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (batch <= 8 && ch_tiles >= dbf_col_tiles(max_cols))
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (batch <= 8)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else
         hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
-                           n_layers, use_sync, x, y, batch, ch_tiles);
+                           n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     return hipGetLastError();
 }

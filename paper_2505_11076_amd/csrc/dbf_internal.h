@@ -8,8 +8,6 @@
 #define DBF_TILE_COLS 64
 #define DBF_TILE_BYTES 1024
 #define DBF_MAX_SPAN 16  /* most row tiles one workgroup takes */
-#define DBF_PERSIST_MAX_SPAN 4  /* most row tiles per item the persistent decode kernel accepts */
-#define DBF_PERSIST_MAX_COLS 12288  /* most columns of a stage it accepts (LDS staging) */
 #define DBF_PIECES_MAX_BATCH 2  /* largest batch for which row tiles may be cut into column pieces */
 
 static inline int dbf_row_tiles(int rows) { return (rows + DBF_TILE_ROWS - 1) / DBF_TILE_ROWS; }
@@ -61,8 +59,8 @@ struct DbfItem {
     int rows;                   // valid rows of the stage
     int cols;                   // valid columns of the stage
     int t_stride;               // elements between batch rows of t
-    int layer;                  // index of the layer's "B rows done" counter
-    int need;                   // A stage: B-stage row tiles of the layer that must be done
+    int layer;                  // index of the layer's counters (DbfPlan::d_sync)
+    int need;                   // A stage: B-stage row tiles of the layer, i.e. what one launch publishes
     int stage_a;                // 0: B stage, 1: A stage
     int peers;                  // A stage: number of A-stage items of this layer in the list
     // Column pieces (lists with pieces > 1 hold one row tile per item): the item covers column tiles
@@ -72,7 +70,8 @@ struct DbfItem {
     int pieces;                 // items that share this row tile (1: not cut)
     int acc_stride;             // elements between batch rows of acc
     int* acc;                   // int32 [DBF_PIECES_MAX_BATCH][acc_stride], this row tile's first row
-    int* cnt;                   // arrival counter of this row tile
+    int* cnt;                   // arrival counter of this row tile (low 16 bits: pieces arrived; bit 16 and up:
+                                // pieces that gave up their wait, so that the finishing piece knows)
     const unsigned char* q_in;  // the stage's quantised input (see DbfStage)
 };
 #define DBF_QIN_HEADER 128      /* bytes of scale[16] + sigma[16] in front of the planes */
@@ -92,12 +91,14 @@ struct DbfPlan {
     int nB1, nA1;               // a stage do not fit one LDS chunk at the requested batch)
     DbfItem* d_items_p;         // one row tile per item, row tiles cut into column pieces: built for plans
     int nBp, nAp;               // with few row tiles (a layer alone, a short stack); NULL otherwise
-    int* d_sync;                // [n_layers] B-row-tile counters, [n_layers] finished A items, [1] time-outs
-    unsigned* d_psync;          // persistent kernel: [n_layers] ever-growing B-row-tile counters,
-                                // then {exited workgroups, epoch}
+    // Counters of the one-launch kernel, 64 bits each, zero when the plan is built and only ever growing
+    // (nothing is reset, so a workgroup that gives up its wait leaves them consistent):
+    //   [layer]            B-stage row tiles published so far, over all launches of this plan
+    //   [n_layers + layer] A-stage items finished so far: divided by the layer's A items per launch this is
+    //                      the number of completed launches, i.e. how much of the first counter is old
+    //   [2 n_layers]       waits given up (sticky)
+    unsigned long long* d_sync;
     int span;                   // row tiles per item in d_items_n
-    int persist_ok;             // every item of d_items_n meets the persistent kernel's shape limits
-    int persist_max_wg;         // 0, or a cap on the persistent kernel's workgroups (test hook)
     int max_cols_B, max_cols_A;
 };
 
@@ -118,6 +119,9 @@ struct dbf_layer {
     DbfStage h_stages[2];   // {B stage, A stage} with offsets 0
     DbfPlan plan;           // launch plan of this layer alone
 };
+
+// Tuning and test hooks (dbf_tuning_set); index = DBF_TUNE_*.
+int dbf_tune(int knob);
 
 struct dbf_stack {
     int n_layers;

@@ -14,9 +14,9 @@ hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfW
                                  hipStream_t stream);
 
 // Matrix-core kernel over items[0..n_items): workgroup i handles items[i].
-//   use_sync != 0 (fused launch of B items followed by A items): an A-stage workgroup waits
-//   until sync[item.layer] reaches item.need before it reads t; B-stage workgroups publish
-//   their rows there; the last workgroup to finish clears the counters for the next launch.
+//   use_sync != 0 (fused launch of B items followed by A items): an A-stage workgroup waits, for at most
+//   wait_limit_us microseconds, until the layer's B-stage workgroups of THIS launch have published all their
+//   rows (sync, see DbfPlan::d_sync); a workgroup that gives up writes NaN outputs and counts a time-out.
 //   use_sync == 0: no waiting and no counters (the caller orders the stages by launches).
 // Items with nrt > 1 are allowed only if every item's columns fit one LDS chunk, i.e.
 // dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols).
@@ -25,9 +25,9 @@ hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfW
 //   shared_q != 0: the input of the items' stage has been quantised for the whole launch by
 //   dbf_launch_quantise_inputs (same stream, earlier); the items copy it instead of quantising it themselves.
 //   Only with use_sync == 0 and pieces == 0.
-hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, int* sync, int n_layers,
+hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned long long* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, int pieces, int shared_q, hipStream_t stream);
+                                 int max_cols, int pieces, int shared_q, int wait_limit_us, hipStream_t stream);
 // Quantises the input of one stage (stage_a = 0: x times b of every layer, 1: the middle activations) of the
 // n_layers stages in d_stages for `batch` rows into the stages' q_in buffers.
 hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, int stage_a, const void* x_base,
@@ -37,26 +37,11 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q);
 // read once and quantised from registers; wider ones are read twice (scale, then quantisation).
 int dbf_mfma_one_pass_cols();
 
-// Batch-1 decode of items[0..n_items) (B items first, then A items) in one persistent launch
-// whose workgroups prefetch their next item while streaming the current one.  Requirements
-// (the caller checks them): every item has nrt <= DBF_PERSIST_MAX_SPAN and 16-byte readable
-// inputs (cols % 8 == 0 for B items, x_base 16-byte aligned), max_cols <= DBF_PERSIST_MAX_COLS.
-// psync: [n_layers + 2] zero-initialised words owned by the plan; timeouts: sticky counter.
-// max_wg > 0 caps the number of workgroups (each then walks more items); 0 = as many as fit.
-hipError_t dbf_launch_persistent(const DbfItem* items, int n_items, unsigned* psync, int* timeouts,
-                                 int n_layers, const void* x_base, void* y_base, int max_cols,
-                                 int max_wg, hipStream_t stream);
-
-// Prefill (T tokens).  Both variants run two stages with the middle activations in the caller's
-// workspace; arguments are validated by dbf_gemm before these are called.
-//   f16: fp16 matrix cores, sign words expanded to +-1 in registers, middle activations in fp16.
-//   i8:  int8 matrix cores as the adder (masked sign bytes as one operand, the activations
-//        rounded per token to 16-bit fixed point and split into two int8 planes), exact integer
-//        sums, middle activations in fp32.
+// Prefill (T tokens): two stages with the middle activations in the caller's workspace; arguments are
+// validated by dbf_gemm before this is called.  int8 matrix cores as the adder (masked sign bytes as one
+// operand, the activations rounded per token to 16-bit fixed point and split into two int8 planes), exact
+// integer sums, middle activations in fp32.
 struct dbf_layer;
-size_t dbf_gemm_f16_workspace_bytes(const dbf_layer* L, int T);
-hipError_t dbf_gemm_f16_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
-                               hipStream_t stream);
 size_t dbf_gemm_i8_workspace_bytes(const dbf_layer* L, int T);
 hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
                               hipStream_t stream);

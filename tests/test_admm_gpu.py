@@ -39,7 +39,9 @@ class DeviceState:
 
     def __init__(self, Minv, C, S, a, m, U):
         self.q, self.r = C.shape
-        self.Minv = torch.from_numpy(Minv.copy()).cuda()
+        # the library applies its first operand transposed (it reads it by rows of the summation index), so it
+        # is handed the transpose of what the oracle multiplies from the left
+        self.Minv = torch.from_numpy(np.ascontiguousarray(Minv.T)).cuda()
         self.C = torch.from_numpy(C.copy()).cuda()
         self.a = torch.from_numpy(a.copy()).cuda()
         self.m = torch.from_numpy(m.copy()).cuda()
@@ -102,12 +104,13 @@ def test_admm_step_matches_the_oracle(shape, rho, iters):
     _check_step("step 2", state1, dev.host(), Minv, C, rho, iters)
 
 
-def test_admm_step_at_full_size():
-    """The size bench.py times: a 4096 x 4096 weight at 1 bit per weight, i.e. q = k = 2048 middle channels,
-    r = 4096; the oracle still takes only seconds there, so everything is compared."""
-    p, q, r, rho, iters = 4096, 2048, 4096, 1.0, 2
+@pytest.mark.parametrize("q", [2048, 4096])
+def test_admm_step_at_full_size(q):
+    """The sizes bench.py times: a 4096 x 4096 weight at 1 and 2 bits per weight, i.e. q = k = 2048 or 4096
+    middle channels, r = 4096; the oracle still takes only seconds there, so everything is compared."""
+    p, r, rho, iters = 4096, 4096, 1.0, 2
     G.say("start admm full size p=%d q=%d r=%d" % (p, q, r))
-    Bm, W, S, a, m, U = I.make_admm_problem(p, q, r, I.seed_for(9, 1))
+    Bm, W, S, a, m, U = I.make_admm_problem(p, q, r, I.seed_for(9, 1 + q // 4096))
     Minv, C = _constants(Bm, W, rho)
     G.say("  constants formed")
     dev = DeviceState(Minv, C, S, a, m, U)

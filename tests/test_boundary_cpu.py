@@ -229,3 +229,54 @@ def test_bench_refuses_more_than_one_gpu():
                          text=True, timeout=120)
     assert res.returncode == 2
     assert "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_tuning_hooks_have_defaults_ranges_and_a_reset():
+    """The tuning / test hooks of the header: defaults as documented, values outside the stated range and
+    unknown knobs are refused, reset restores the defaults.  (No GPU involved.)"""
+    lib = B.lib()
+    B.dbf_tuning_reset()
+    defaults = {B.TUNE_COL_PIECES: -1, B.TUNE_PIECE_TARGET: 0, B.TUNE_PIECE_MIN_TILES: 24, B.TUNE_PIECE_NEVER_TILES: 64,
+                B.TUNE_PIECE_MAX_ROW_TILES: 1024, B.TUNE_STACK_SPAN_B: 0, B.TUNE_STACK_SPAN_A: 0, B.TUNE_SHARED_Q: -1,
+                B.TUNE_SHARED_MIN_BATCH: 2, B.TUNE_SHARED_LDS_KB: 52, B.TUNE_WAIT_LIMIT_US: 250000}
+    assert len(defaults) == 11
+    for knob, val in defaults.items():
+        assert B.dbf_tuning_get(knob) == val
+    for knob, bad in ((B.TUNE_COL_PIECES, -2), (B.TUNE_COL_PIECES, 65), (B.TUNE_STACK_SPAN_B, 17), (B.TUNE_SHARED_Q, 3),
+                      (B.TUNE_SHARED_MIN_BATCH, 1), (B.TUNE_SHARED_LDS_KB, 65), (B.TUNE_WAIT_LIMIT_US, -1),
+                      (B.TUNE_PIECE_MIN_TILES, 0), (11, 0), (-1, 0)):
+        assert lib.dbf_tuning_set(knob, bad) == B.DBF_EINVAL
+    assert B.dbf_tuning_get(11) == -2 ** 31 and B.dbf_tuning_get(-1) == -2 ** 31
+    B.dbf_tuning_set(B.TUNE_WAIT_LIMIT_US, 0)
+    B.dbf_tuning_set(B.TUNE_COL_PIECES, 3)
+    assert B.dbf_tuning_get(B.TUNE_WAIT_LIMIT_US) == 0 and B.dbf_tuning_get(B.TUNE_COL_PIECES) == 3
+    B.dbf_tuning_reset()
+    for knob, val in defaults.items():
+        assert B.dbf_tuning_get(knob) == val
+
+
+def test_the_library_reads_no_environment_variables():
+    """Plans and launches are steered by the documented hooks only: no getenv in the product sources."""
+    csrc = os.path.join(ROOT, "paper_2505_11076_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name)) as fh:
+            assert "getenv" not in fh.read(), name
+
+
+def test_host_code_is_clean_under_address_and_undefined_behaviour_sanitizers():
+    """The host packer / tile layout and the argument-validation paths of the C ABI, built with
+    -fsanitize=address,undefined (host code only) and exercised on exact-size heap buffers by
+    tests/sanitize_host.cpp: any out-of-bounds access, bad shift or misaligned access in the host code
+    ends that program with a report and a non-zero status."""
+    import subprocess
+    from paper_2505_11076_amd import build as _build
+    exe = _build.build_sanitize_check(os.path.join(ROOT, "tests", "sanitize_host.cpp"))
+    env = dict(os.environ)
+    # (leak checking off: the HIP runtime keeps process-lifetime allocations; link order: other preloaded
+    # libraries may come first)
+    env["ASAN_OPTIONS"] = "detect_leaks=0:verify_asan_link_order=0:abort_on_error=0"
+    env["UBSAN_OPTIONS"] = "print_stacktrace=1:halt_on_error=1"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "sanitize_host: ok" in res.stdout
+    assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr

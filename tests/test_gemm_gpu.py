@@ -1,6 +1,6 @@
 """GPU parity of the prefill path (dbf_gemm: two matrix-core contractions) against
-the fp64 dense-W' oracle on the same seeded inputs, for both variants: int8 matrix
-cores with 16-bit fixed-point activations (the default) and fp16 matrix cores.
+the fp64 dense-W' oracle on the same seeded inputs, the int8 matrix cores as the adder
+with 16-bit fixed-point activations.
 Gate as for decode: gated relative error <= 2e-3.
 """
 import numpy as np
@@ -16,24 +16,20 @@ import gpu_util as G
 pytestmark = pytest.mark.gpu
 
 
-KINDS = [(B.GEMM_I8, "i8"), (B.GEMM_F16, "f16")]
+KINDS = [(B.GEMM_I8, "i8"), (B.GEMM_AUTO, "auto")]
 
 
-def _case(n_in, n_out, k, T, seed, rows=None):
+def _case(n_in, n_out, k, T, seed, mode="dense"):
     L = I.make_layer(n_in, n_out, k, seed)
     X = I.make_activations(T, n_in, seed)
     layer = G.pack(L)
     try:
-        ref = O.forward_from_packed(X if rows is None else X[rows], L, "dense")
+        G.say("oracle (%s) n_in=%d n_out=%d k=%d T=%d" % (mode, n_in, n_out, k, T))
+        ref = O.forward_from_packed(X, L, mode)
         for kind, name in KINDS:
             what = "gemm[%s] n_in=%d n_out=%d k=%d T=%d seed=%d" % (name, n_in, n_out, k, T, seed)
             G.say("start " + what)
-            y = G.run_gemm(layer, X, kind)
-            if rows is None:
-                G.check(y, ref, what)
-            else:
-                # large case: the oracle evaluates a sample of token rows (each output row one by one)
-                G.check(y[rows], ref, what + " (sampled rows)")
+            G.check(G.run_gemm(layer, X, kind), ref, what)
     finally:
         layer.close()
 
@@ -71,16 +67,13 @@ def test_gemm_agrees_with_gemv_rows():
         layer.close()
 
 
-def test_config4_square_prefill():
-    cfg = I.CONFIG4[0]
-    rows = np.arange(0, cfg["T"], 37)
-    _case(cfg["n_in"], cfg["n_out"], cfg["k"], cfg["T"], seed=I.seed_for(4, 100), rows=rows)
-
-
-def test_config4_down_projection_prefill():
-    cfg = I.CONFIG4[1]
-    rows = np.array([0, 1, 63, 64, 1000, 1023, 1024, 2047])
-    _case(cfg["n_in"], cfg["n_out"], cfg["k"], cfg["T"], seed=I.seed_for(4, 101), rows=rows)
+@pytest.mark.parametrize("idx", [0, 1])
+def test_config4_prefill_every_token(idx):
+    """Both prefill shapes at T = 2048, every one of the 2048 x 4096 outputs against the oracle's staged
+    mode (the forward-pass expression left to right in fp64, which the oracle's own pins tie to the dense
+    product to 1e-12; forming W' densely first would cost 2.7e11 more multiply-adds at k = 5970)."""
+    cfg = I.CONFIG4[idx]
+    _case(cfg["n_in"], cfg["n_out"], cfg["k"], cfg["T"], seed=I.seed_for(4, 100 + idx), mode="staged")
 
 
 def test_gemm_argument_errors():
@@ -101,5 +94,6 @@ def test_gemm_argument_errors():
         assert lib.dbf_gemm(h, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), need - 1, None) == B.DBF_EWORKSPACE
         assert lib.dbf_gemm(h, x.data_ptr(), y.data_ptr(), T, ws.data_ptr() + 16, need, None) == B.DBF_EWORKSPACE
         assert lib.dbf_gemm_workspace_bytes(h, 0) == 0
+        assert lib.dbf_gemm_kind(h, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), need, 1, None) == B.DBF_EINVAL  # withdrawn
     finally:
         layer.close()

@@ -16,8 +16,15 @@ import gpu_util as G
 
 pytestmark = pytest.mark.gpu
 
-KINDS = [(B.GEMV_VALU, "valu"), (B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split"),
-         (B.GEMV_PERSIST, "persist")]
+KINDS = [(B.GEMV_VALU, "valu"), (B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split"), (B.GEMV_AUTO, "auto")]
+
+
+@pytest.fixture(autouse=True)
+def _default_tuning():
+    """Every test starts from, and leaves behind, the library's default tuning knobs."""
+    B.dbf_tuning_reset()
+    yield
+    B.dbf_tuning_reset()
 
 
 def _case(n_in, n_out, k, batch, seed, kinds=KINDS, mode="dense"):
@@ -212,7 +219,7 @@ def test_stack_of_mixed_layers(batch):
 def test_one_launch_equals_two_launches_bit_for_bit():
     """The fused launch (A-stage workgroups wait on the device for their layer's B stage) and
     the two-launch variant run the same integer arithmetic, so their fp16 outputs must be
-    identical; repeated calls exercise the counter reset done by the last workgroup."""
+    identical; repeated calls exercise the ever-growing counters (each launch waits for what it adds itself)."""
     shapes = [(512, 512, 256)] * 6 + [(1024, 384, 700), (64, 2048, 64), (2048, 64, 2048)]
     batch = 2
     Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 200 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
@@ -242,46 +249,6 @@ def test_one_launch_equals_two_launches_bit_for_bit():
                 ys.append(G.run_gemv(layer, Xs[layers.index(layer)], kind))
             assert np.array_equal(ys[0], ys[1]) and np.array_equal(ys[1], ys[2])
             assert B.dbf_sync_timeouts(layer) == 0
-    finally:
-        stack.close()
-        for l in layers:
-            l.close()
-
-
-@pytest.mark.parametrize("max_wg,span", [(1, 1), (3, 1), (5, 2), (7, 4), (0, 4)])
-def test_persistent_kernel_walks_several_items(max_wg, span, monkeypatch):
-    """With few workgroups each one of the persistent kernel walks many items: B then B, B then
-    A (dependency poll, late input), A then A, the tile prefetch running across item ends, items
-    of different shapes.  Outputs must match the oracle, equal the one-item-per-workgroup kernel
-    bit for bit (same integer arithmetic), and stay the same over repeated launches (epochs)."""
-    shapes = [(512, 512, 256), (1024, 384, 700), (64, 2048, 64), (2048, 64, 2048), (104, 77, 33),
-              (512, 512, 256), (4096, 256, 128), (256, 640, 1000)]
-    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 400 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
-    Xs = [I.make_activations(1, L.n_in, I.seed_for(5, 500 + i)) for i, L in enumerate(Ls)]
-    layers = [G.pack(L) for L in Ls]
-    monkeypatch.setenv("DBF_PERSIST_MAX_WG", str(max_wg))
-    monkeypatch.setenv("DBF_STACK_SPAN", str(span))
-    monkeypatch.setenv("DBF_STACK_SPAN_A", str(span))
-    stack = B.dbf_stack_create(layers)   # the hooks are read when the plan is built
-    try:
-        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
-        n_y = sum(L.n_out for L in Ls)
-        outs = []
-        for kind, name, reps in ((B.GEMV_MFMA_SPLIT, "split", 1), (B.GEMV_PERSIST, "persist", 3)):
-            for rep in range(reps):
-                G.say("persistent walk max_wg=%d span=%d [%s] rep %d" % (max_wg, span, name, rep))
-                y_all = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
-                B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), 1, G.stream_handle(), kind)
-                torch.cuda.synchronize()
-                outs.append(y_all.cpu().view(torch.int16).numpy().copy())
-                yo = 0
-                for i, L in enumerate(Ls):
-                    y = G.dev_to_f64(y_all[yo:yo + L.n_out]).reshape(1, L.n_out)
-                    G.check(y, O.forward_from_packed(Xs[i], L, "dense"), "walk[%s] layer %d" % (name, i))
-                    yo += L.n_out
-        for o in outs[1:]:
-            assert np.array_equal(o, outs[0])
-        assert B.dbf_stack_sync_timeouts(stack) == 0
     finally:
         stack.close()
         for l in layers:
@@ -335,6 +302,11 @@ def test_launch_errors_with_a_real_layer():
         assert lib.dbf_gemv(h, x.data_ptr(), y.data_ptr(), 0, None) == B.DBF_EINVAL
         assert lib.dbf_gemv(h, x.data_ptr(), y.data_ptr(), 17, None) == B.DBF_EINVAL
         assert lib.dbf_gemv_kind(h, x.data_ptr(), y.data_ptr(), 1, 7, None) == B.DBF_EINVAL
+        assert lib.dbf_gemv_kind(h, x.data_ptr(), y.data_ptr(), 1, 4, None) == B.DBF_EINVAL   # (a withdrawn kind)
+        # a layer may appear only once in a stack
+        with pytest.raises(B.DbfError) as err:
+            B.dbf_stack_create([layer, layer])
+        assert err.value.code == B.DBF_EINVAL
     finally:
         layer.close()
 
@@ -344,7 +316,9 @@ def test_stack_call_replayed_from_a_captured_graph(batch):
     """The launch entry points allocate nothing, synchronise nothing and keep all state on the
     device (counters cleared by the last workgroup), so a stack call can be captured into a HIP
     graph and replayed.  Every replay, with eager work and synchronisations in between, must
-    reproduce the eager result bit for bit.  (Batch 4 takes the four-launch path with the input quantisers.)"""
+    reproduce the eager result bit for bit.  (Batch 4 takes the four-launch path with the input quantisers.)
+    The device-side counters of the one-launch kernel only ever grow and the kernel works out from them what
+    the current launch must add, so a replayed launch needs no host-side state."""
     shapes = [(512, 512, 256), (1024, 384, 700), (256, 640, 1000), (512, 512, 256)]
     Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 950 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
     Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 960 + i)) for i, L in enumerate(Ls)]
@@ -353,7 +327,7 @@ def test_stack_call_replayed_from_a_captured_graph(batch):
     try:
         x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
         n_y = batch * sum(L.n_out for L in Ls)
-        for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA_SPLIT, "mfma_split"), (B.GEMV_PERSIST, "persist")):
+        for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA_SPLIT, "mfma_split")):
             G.say("graph capture [%s]" % name)
             y_eager = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
             B.dbf_stack_gemv(stack, x_all.data_ptr(), y_eager.data_ptr(), batch, G.stream_handle(), kind)
@@ -384,7 +358,7 @@ def test_stack_call_replayed_from_a_captured_graph(batch):
 
 
 @pytest.mark.parametrize("batch", [1, 2])
-def test_column_pieces_equal_whole_rows_bit_for_bit(batch, monkeypatch):
+def test_column_pieces_equal_whole_rows_bit_for_bit(batch):
     """Launches with few row tiles cut long rows into column pieces that add exact integer sums into
     per-row accumulators; the last piece scales and stores.  Every piece quantises with the scale of
     the whole row, so the result must equal the uncut launch bit for bit -- for a layer alone (two
@@ -394,12 +368,11 @@ def test_column_pieces_equal_whole_rows_bit_for_bit(batch, monkeypatch):
     Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 970 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
     Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 980 + i)) for i, L in enumerate(Ls)]
 
-    def run(env):
-        for name in ("DBF_COL_PIECES", "DBF_PIECE_NEVER_TILES", "DBF_PIECE_MIN_TILES", "DBF_PIECE_TARGET"):
-            monkeypatch.delenv(name, raising=False)
-        for name, val in env.items():
-            monkeypatch.setenv(name, val)
-        layers = [G.pack(L) for L in Ls]       # the plans are built here, under this environment
+    def run(knobs):
+        B.dbf_tuning_reset()
+        for knob, val in knobs.items():
+            B.dbf_tuning_set(knob, val)
+        layers = [G.pack(L) for L in Ls]       # the plans are built here, under these knobs
         stack = B.dbf_stack_create(layers)
         outs = []
         try:
@@ -424,10 +397,10 @@ def test_column_pieces_equal_whole_rows_bit_for_bit(batch, monkeypatch):
         return outs
 
     G.say("column pieces: whole rows")
-    whole = run({"DBF_COL_PIECES": "0"})
-    for label, env in (("default rule", {}), ("3 pieces everywhere", {"DBF_COL_PIECES": "3"}),
-                       ("many small pieces", {"DBF_PIECE_NEVER_TILES": "0", "DBF_PIECE_MIN_TILES": "2",
-                                              "DBF_PIECE_TARGET": "4096"})):
+    whole = run({B.TUNE_COL_PIECES: 0})
+    for label, env in (("default rule", {}), ("3 pieces everywhere", {B.TUNE_COL_PIECES: 3}),
+                       ("many small pieces", {B.TUNE_PIECE_NEVER_TILES: 0, B.TUNE_PIECE_MIN_TILES: 2,
+                                              B.TUNE_PIECE_TARGET: 4096})):
         G.say("column pieces: " + label)
         got = run(env)
         assert len(got) == len(whole)
@@ -498,7 +471,7 @@ def test_groups_of_layers_sharing_one_input(batch):
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("shape,batch", [((700, 260, 390), 2), ((700, 260, 390), 7), ((1000, 50, 130), 3),
                                          ((3000, 200, 1500), 16), ((101, 77, 33), 9), ((4096, 512, 700), 4)])
-def test_shared_quantised_input_equals_the_items_own_bit_for_bit(mode, shape, batch, monkeypatch):
+def test_shared_quantised_input_equals_the_items_own_bit_for_bit(mode, shape, batch):
     """DBF_GEMV_AUTO at batch >= 2 quantises each stage input once per call and lets the items copy it into LDS
     (mode 1, here also with rows that need several LDS chunks) or read it from memory tile by tile (mode 2).
     The quantiser uses the arithmetic of the items' own prologue and the integer sums are exact, so the result
@@ -514,8 +487,8 @@ def test_shared_quantised_input_equals_the_items_own_bit_for_bit(mode, shape, ba
         what = "shared-q mode %d n_in=%d n_out=%d k=%d batch=%d" % (mode, n_in, n_out, k, batch)
         G.say("start " + what)
         own = G.run_gemv(layer, X, B.GEMV_MFMA_SPLIT)
-        monkeypatch.setenv("DBF_SHARED_Q", str(mode))
-        monkeypatch.setenv("DBF_COL_PIECES", "0")   # (batch 2 would otherwise take the column-piece list)
+        B.dbf_tuning_set(B.TUNE_SHARED_Q, mode)
+        B.dbf_tuning_set(B.TUNE_COL_PIECES, 0)      # (batch 2 would otherwise take the column-piece list)
         l2 = G.pack(L)                               # the piece list is decided when the plan is built
         try:
             shared = G.run_gemv(l2, X, B.GEMV_AUTO)
@@ -555,3 +528,56 @@ def test_stack_at_larger_batches_equals_per_layer_calls(batch):
         stack.close()
         for layer in layers:
             layer.close()
+
+
+# ---- the bounded wait of the one-launch kernel ----------------------------------------------------
+
+
+@pytest.mark.parametrize("batch,pieces", [(1, 0), (1, 3), (2, 0)])
+def test_a_wait_that_gives_up_is_visible_in_y_and_leaves_the_counters_consistent(batch, pieces):
+    """The give-up path of the device-side wait, driven from the host: with the bound set to zero an A-stage
+    workgroup whose layer's B stage is not finished at its first look gives up at once.  Every kernel still
+    exits normally.  Required: every fp16 output is either the correct value (bit for bit that of the
+    two-launch kind) or a quiet NaN, whole row tiles at a time; the sticky counter says how many workgroups
+    gave up; and the NEXT call with the normal bound is fully correct, i.e. the counters were left consistent
+    (the B-stage workgroups of the first call all published after the A-stage ones had given up)."""
+    shapes = [(8192, 1024, 1024)] * 6      # a long B stage (8 x 1 MiB per layer), many A-stage workgroups
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 1200 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 1300 + i)) for i, L in enumerate(Ls)]
+    if pieces:
+        B.dbf_tuning_set(B.TUNE_COL_PIECES, pieces)
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        n_y = batch * sum(L.n_out for L in Ls)
+
+        def call(kind):
+            y = torch.full((n_y,), 1.0, dtype=torch.float16, device="cuda")
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y.data_ptr(), batch, G.stream_handle(), kind)
+            torch.cuda.synchronize()
+            return y.cpu().view(torch.int16).numpy().view(np.uint16).copy()
+
+        want = call(B.GEMV_MFMA_SPLIT)
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+        fused = B.GEMV_AUTO if pieces else B.GEMV_MFMA
+        B.dbf_tuning_set(B.TUNE_WAIT_LIMIT_US, 0)
+        G.say("fused launch with a zero wait bound, batch %d pieces %d" % (batch, pieces))
+        got = call(fused)
+        gave_up = B.dbf_stack_sync_timeouts(stack)
+        nan = got == 0x7E00
+        G.say("  %d workgroups gave up, %d of %d outputs are NaN" % (gave_up, int(nan.sum()), got.size))
+        assert np.array_equal(got[~nan], want[~nan])
+        assert (gave_up > 0) == bool(nan.any())
+        # NaNs come in whole row tiles of 128 outputs per batch row
+        per_tile = nan.reshape(len(Ls), batch, -1, 128)
+        assert np.all(per_tile.all(axis=3) | ~per_tile.any(axis=3))
+        assert gave_up > 0, "the B stage finished before any A-stage workgroup looked: enlarge the B stage"
+        B.dbf_tuning_set(B.TUNE_WAIT_LIMIT_US, 250000)
+        for rep in range(2):
+            assert np.array_equal(call(fused), want), rep
+        assert B.dbf_stack_sync_timeouts(stack) == gave_up     # sticky, and nothing new
+    finally:
+        stack.close()
+        for l in layers:
+            l.close()

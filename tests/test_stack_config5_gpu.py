@@ -5,8 +5,8 @@ times (default kind, batch 1), plus batch 16.
 
 The fp64 oracle cannot decode 224 full layers in test time, so:
   * the seven layers of the first decoder block are compared element by element (staged fp64);
-  * every eighth layer after that is compared on 64 sampled outputs per batch row, each
-    computed one by one by the oracle from all of B and the sampled rows of A;
+  * every other layer is compared on 64 sampled outputs per batch row, each computed one by one
+    by the oracle from all of B and the sampled rows of A;
   * EVERY layer is checked against a property that holds at any size: for i.i.d. signs the
     outputs have variance a_i^2 * sum_j m_j^2 * sum_l (b_l x_l)^2, so the measured rms over a
     layer's outputs must match the predicted one (this catches a layer fed the wrong x block,
@@ -42,10 +42,7 @@ def test_config5_stack_full_size(batch):
     for i, sp in enumerate(specs):
         L = I.make_layer(sp["n_in"], sp["n_out"], sp["k"], seed=I.seed_for(5, i))
         layers.append(G.pack(L))
-        full = i < 7
-        sampled = (not full) and i % 8 == 0
-        # keep the host copy of the bits only where the oracle will need them
-        Ls.append(L if (full or sampled) else I.LayerInputs(L.n_in, L.n_out, L.k, None, None, L.a, L.m, L.b))
+        Ls.append(L)
         if i % 32 == 31:
             G.say("  packed %d" % (i + 1))
     stack = B.dbf_stack_create(layers)
@@ -71,13 +68,12 @@ def test_config5_stack_full_size(batch):
             want = _predicted_rms(L, Xs[i])
             # n_out >= 4096 samples per row: the sample rms is within a few percent of the law
             assert np.all(np.abs(rms / want - 1.0) < 0.08), (i, rms, want)
-            if L.A_bits is None:
-                continue
             if i < 7:
                 G.say("  layer %d: all outputs against the staged oracle" % i)
                 G.check(y, O.forward_from_packed(Xs[i], L, "staged"), "config5 layer %d" % i)
             else:
-                G.say("  layer %d: 64 sampled outputs" % i)
+                if i % 32 == 7:
+                    G.say("  layers %d..: 64 sampled outputs each" % i)
                 rows = np.sort(rows_rng.choice(n_out, size=64, replace=False))
                 ref = O.forward_rows_from_packed(Xs[i], L, rows)
                 # (the gate's floor, the row rms, is estimated from the 64 sampled reference values)

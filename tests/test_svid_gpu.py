@@ -37,8 +37,9 @@ def _run(Z, iters):
     return a.cpu().numpy().astype(np.float64), m.cpu().numpy().astype(np.float64), words
 
 
-@pytest.mark.parametrize("shape", [(512, 256), (100, 77), (130, 1000), (1000, 129), (4096, 2048), (3, 5)])
-@pytest.mark.parametrize("iters", [1, 4])
+@pytest.mark.parametrize("shape,iters", [(s, i) for s in [(512, 256), (100, 77), (130, 1000), (1000, 129),
+                                                          (4096, 2048), (3, 5)] for i in (1, 4)]
+                         + [((4096, 4096), 8), ((11008, 4096), 8)])  # the last two: what bench.py times
 def test_svid_matches_the_oracle(shape, iters):
     rows, cols = shape
     G.say("start svid %dx%d iters=%d" % (rows, cols, iters))
