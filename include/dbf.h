@@ -170,6 +170,22 @@ int dbf_gemm(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
 int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
                   void* workspace_dev, size_t workspace_bytes, int kind, void* hip_stream);
 
+/* dbf_gemm_static: dbf_gemm for callers that cannot allocate or pass a workspace -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same kernels and the same bits as
+ * dbf_gemm_kind(..., DBF_GEMM_I8, ...), for every T >= 1, with the scratch (quantised activations, fp32 middle
+ * activations) in a static device array of DBF_GEMM_STATIC_BYTES that each GPU the library runs on holds
+ * until the process ends.  Calls no hipMalloc / hipFree or any allocating routine.
+ *   Limit: dbf_gemm_workspace_bytes(layer, T) <= DBF_GEMM_STATIC_BYTES, else
+ *   DBF_EWORKSPACE and nothing is launched (T = 512 at 11008 -> 4096, k = 5970 needs 28.4 MiB; 1024 tokens of
+ *   a 4096 x 4096, k = 2048 layer 20 MiB).  The current device must be the layer's (DBF_EINVAL).
+ *   The first call on a device looks up the array's address (hipGetSymbolAddress); make it outside graph capture.
+ *   Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (two streams,
+ *   two threads) race and give wrong results; calls on one stream are ordered and safe.  Nothing in the array
+ *   has to be zero and nothing is kept between calls.
+ * Asynchronous on hip_stream.  Errors: DBF_EINVAL, DBF_EWORKSPACE, DBF_EHIP. */
+#define DBF_GEMM_STATIC_BYTES (32u << 20)
+int dbf_gemm_static(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T, void* hip_stream);
+
 /* ---- middle-channel pruning (paper, section 3.5 "Nonuniform layer compression ratios") ------
  * The paper treats the middle dimension as channels and keeps those with the highest scores
  * (the scores need gradients and are the caller's business).  dbf_prune_middle makes the new,

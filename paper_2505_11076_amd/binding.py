@@ -24,11 +24,13 @@ GEMM_AUTO, GEMM_I8 = 0, 2
  TUNE_STACK_SPAN_B, TUNE_STACK_SPAN_A, TUNE_SHARED_Q, TUNE_SHARED_MIN_BATCH, TUNE_SHARED_LDS_KB,
  TUNE_WAIT_LIMIT_US) = range(11)
 MAX_BATCH = 16
+GEMM_STATIC_BYTES = 32 << 20  # DBF_GEMM_STATIC_BYTES
 
 EXPORTS = [
     "dbf_pack", "dbf_pack_bits", "dbf_unpack_bits", "dbf_dims", "dbf_free",
     "dbf_tiled_bytes", "dbf_signs_to_bits_host", "dbf_tile_host", "dbf_untile_host",
     "dbf_gemv", "dbf_gemv_kind", "dbf_sync_timeouts", "dbf_gemm_workspace_bytes", "dbf_gemm", "dbf_gemm_kind",
+    "dbf_gemm_static",
     "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
     "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_admm_workspace_bytes", "dbf_admm_step", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
@@ -74,6 +76,7 @@ def lib() -> C.CDLL:
     L.dbf_gemm_workspace_bytes.restype = sz
     L.dbf_gemm.argtypes = [vp, vp, vp, i32, vp, sz, vp]
     L.dbf_gemm_kind.argtypes = [vp, vp, vp, i32, vp, sz, i32, vp]
+    L.dbf_gemm_static.argtypes = [vp, vp, vp, i32, vp]
     L.dbf_stack_create.argtypes = [pp, i32, pp]
     L.dbf_stack_create_grouped.argtypes = [pp, i32, C.POINTER(C.c_int), i32, pp]
     L.dbf_stack_offsets.argtypes = [vp, i32, i32, C.POINTER(sz), C.POINTER(sz)]
@@ -256,6 +259,11 @@ def dbf_gemm(layer: Layer, X_ptr: int, Y_ptr: int, T: int, workspace_ptr: int, w
              stream: int = 0, kind: int = GEMM_AUTO) -> None:
     _check(lib().dbf_gemm_kind(layer.handle, X_ptr, Y_ptr, T, workspace_ptr, workspace_bytes, kind, stream),
            "dbf_gemm")
+
+
+def dbf_gemm_static(layer: Layer, X_ptr: int, Y_ptr: int, T: int, stream: int = 0) -> None:
+    """dbf_gemm with the scratch in the library's static device array (allocates nothing)."""
+    _check(lib().dbf_gemm_static(layer.handle, X_ptr, Y_ptr, T, stream), "dbf_gemm_static")
 
 
 # ---- stacks --------------------------------------------------------------------------------

@@ -23,6 +23,7 @@ SOURCES = [
     "dbf_gemv_valu.hip",
     "dbf_gemv_mfma.hip",
     "dbf_gemm_i8.hip",
+    "dbf_gemm_static.hip",
     "dbf_probe.hip",
     "dbf_prune.hip",
     "dbf_svid.hip",
