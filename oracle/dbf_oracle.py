@@ -25,7 +25,8 @@ channels against zeroing their scales and against a per-entry loop; the SVID pro
 against the singular value decomposition it converges to, exact rank-one inputs and its
 fixed point; the ADMM update against the normal equations of its least-squares step, an augmented
 least-squares solve by a library routine, its fixed point at an exactly factorisable W and the scalar
-closed form.  No function here is "parity unpinned".
+closed form; its constant matrices against library solves and the entry-by-entry definition of the fixed
+factor.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -246,6 +247,34 @@ def admm_step_from(Minv, C, rho: float, S, a, m, U, svid_iters: int):
     S2, a2, m2 = svid(W_hat + U, svid_iters)
     A2 = a2[:, None] * S2 * m2[None, :]
     return S2, a2, m2, U + W_hat - A2, W_hat
+
+
+def admm_constants(B, W, rho: float):
+    """The two matrices of the update that stay constant while B and W are fixed (section 3.2):
+    Minv = (B^T B + rho I)^-1 and C = B^T W.  The paper does not say how it solves the system; B^T B + rho I
+    is symmetric positive definite, and the textbook route is taken: Cholesky factorisation G = L L^T, then
+    G^-1 = L^-T L^-1.  Returns (Minv, C), fp64."""
+    B = np.asarray(B, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    if B.ndim != 2 or W.ndim != 2 or B.shape[0] != W.shape[0] or rho <= 0.0:
+        raise ValueError("B (p x q), W (p x r), rho > 0")
+    q = B.shape[1]
+    G = B.T @ B + rho * np.eye(q)
+    L = np.linalg.cholesky(G)
+    Linv = np.linalg.inv(L)
+    return Linv.T @ Linv, B.T @ W
+
+
+def fixed_factor_dense(S, b, m2) -> np.ndarray:
+    """The fixed factor of the least-squares form as a dense matrix: B = diag(b) S^T diag(m2) (p x q) for a sign
+    matrix S (q x p) with scale vectors b (p) and m2 (q) -- the transposed right factor m2 . B_pm1 . b^T of the
+    paper's alternating minimisation (section 3.2)."""
+    S = np.asarray(S, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    m2 = np.asarray(m2, dtype=np.float64)
+    if S.ndim != 2 or b.shape != (S.shape[1],) or m2.shape != (S.shape[0],):
+        raise ValueError("S (q x p), b (p), m2 (q)")
+    return b[:, None] * S.T * m2[None, :]
 
 
 def admm_step(B, W, rho: float, S, a, m, U, svid_iters: int):

@@ -550,6 +550,40 @@ def test_admm_precomputed_form_matches_and_rejects_bad_shapes():
         O.admm_step(B, W, 0.0, S, a, m, U, 1)
 
 
+def test_admm_constants_against_library_solves_and_the_fixed_factor_entry_by_entry():
+    """Minv from the Cholesky route must be the inverse a general solver finds (and symmetric, and a two-sided
+    inverse); C is a plain product; feeding both to the precomputed form gives the full update.  The dense
+    fixed factor is checked entry by entry with scalar loops on an asymmetric shape (catches a transposed S, b
+    and m2 swapped)."""
+    B, W, S, a, m, U = _admm_case(14, 9, 5, 31)
+    for rho in (1.0, 0.05, 7.0):
+        Minv, C = O.admm_constants(B, W, rho)
+        G = B.T @ B + rho * np.eye(9)
+        assert np.allclose(Minv, np.linalg.solve(G, np.eye(9)), rtol=0, atol=1e-12 * np.max(np.abs(Minv)) * np.linalg.cond(G))
+        assert np.allclose(Minv @ G, np.eye(9), atol=1e-12) and np.allclose(G @ Minv, np.eye(9), atol=1e-12)
+        assert np.array_equal(Minv, Minv.T) or np.allclose(Minv, Minv.T, rtol=0, atol=1e-15)
+        assert np.allclose(C, np.array([[sum(B[l, j] * W[l, o] for l in range(14)) for o in range(5)] for j in range(9)]),
+                           rtol=1e-13, atol=1e-13)
+        full = O.admm_step(B, W, rho, S, a, m, U, 2)
+        pre = O.admm_step_from(Minv, C, rho, S, a, m, U, 2)
+        assert np.array_equal(full[0], pre[0])
+        for x, y in zip(full[1:], pre[1:]):
+            assert np.allclose(x, y, rtol=0, atol=1e-11)
+    rng = np.random.default_rng(8)
+    q, p = 4, 7
+    Sg = np.where(rng.random((q, p)) < 0.5, 1.0, -1.0)
+    b, m2 = rng.uniform(0.5, 2.0, p), rng.uniform(0.5, 2.0, q)
+    Bd = O.fixed_factor_dense(Sg, b, m2)
+    assert Bd.shape == (p, q)
+    for l in range(p):
+        for j in range(q):
+            assert Bd[l, j] == b[l] * Sg[j, l] * m2[j]
+    with pytest.raises(ValueError):
+        O.fixed_factor_dense(Sg, m2, b)
+    with pytest.raises(ValueError):
+        O.admm_constants(B, W[:3], 1.0)
+
+
 def test_admm_iterations_approach_a_factorisable_target():
     """Behaviour over several updates: with W = B A* (A* of the SVID form) and a start far from A*, repeated
     updates bring the projected iterate A = a . S . m^T closer to a least-squares fit: the residual ||B A - W||
