@@ -637,21 +637,29 @@ def svid_bench(B, I, torch, np, stream, proto, iters=8):
 
 
 def admm_bench(B, I, torch, np, stream, proto, svid_iters=2, rho=1.0):
-    """dbf_admm_step for the factor of a 4096 x 4096 weight with q = 2048 and q = 4096 middle channels (1 and 2
-    bits per weight): the q x q x r fp32 contraction dominates (2 q^2 r flops, priced against the fp32
-    matrix-core peak); around it the step reads or writes a q x r fp32 matrix 7 + 2 * svid_iters times
-    (C, U in, R out; R in; U in, Z out; Z in for the signs and twice per round; Z in, U out).
-    The constant matrices are formed with numpy beforehand (not timed: once per outer iteration)."""
+    """The ADMM update for the factor of a 4096 x 4096 weight with q = 2048 and q = 4096 middle channels (1 and 2
+    bits per weight), starting from the PACKED fixed factor: dbf_admm_prepare forms C = B^T W and
+    Minv = (B^T B + rho I)^-1 on the device (once per outer iteration; timed on its own), dbf_admm_step is the
+    repeated part.  In the step the q x q x r fp32 contraction dominates (2 q^2 r flops, priced against the fp32
+    matrix-core peak); around it the step reads or writes a q x r fp32 matrix 7 + 2 * svid_iters times.  The
+    preparation is 2 p q^2 (B^T B) + 2 p q r (B^T W) + q^3 / 3 (Cholesky) + q^3 / 3 (inverse of the factor) +
+    2 q^3 (its Gram matrix) flops."""
+    from oracle import dbf_oracle as O
     res = {}
     for p, q, r in ((4096, 2048, 4096), (4096, 4096, 4096)):
-        Bm, W, S, a, m, U = I.make_admm_problem(p, q, r, I.seed_for(9, q))
-        B64 = Bm.astype(np.float64)
-        Minv = np.linalg.inv(B64.T @ B64 + rho * np.eye(q)).astype(np.float32)
-        Cm = (B64.T @ W.astype(np.float64)).astype(np.float32)
-        words = B.dbf_signs_to_bits_host(S)
-        d = {"Minv": torch.from_numpy(np.ascontiguousarray(Minv.T)).cuda(), "C": torch.from_numpy(Cm).cuda(), "a": torch.from_numpy(a).cuda(),
-             "m": torch.from_numpy(m).cuda(), "U": torch.from_numpy(U).cuda(),
-             "bits": torch.from_numpy(B.dbf_tile_host(q, r, words)).cuda()}
+        S_B, m2, b, W, S, a, m, U = I.make_admm_packed_problem(p, q, r, I.seed_for(9, q))
+        dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+        d = {"bitsB": dev(B.dbf_tile_host(q, p, B.dbf_signs_to_bits_host(S_B))), "m2": dev(m2), "b": dev(b), "W": dev(W),
+             "Minv": torch.zeros((q, q), dtype=torch.float32, device="cuda"),
+             "C": torch.zeros((q, r), dtype=torch.float32, device="cuda"),
+             "a": dev(a), "m": dev(m), "U": dev(U), "bits": dev(B.dbf_tile_host(q, r, B.dbf_signs_to_bits_host(S))),
+             "flag": torch.zeros(1, dtype=torch.int32, device="cuda")}
+        pwsb = B.dbf_admm_prepare_workspace_bytes(p, q, r)
+        pws = torch.zeros(pwsb, dtype=torch.uint8, device="cuda")
+        pargs = (d["bitsB"].data_ptr(), d["m2"].data_ptr(), d["b"].data_ptr(), d["W"].data_ptr(), p, q, r, rho,
+                 d["Minv"].data_ptr(), d["C"].data_ptr(), pws.data_ptr(), pwsb, d["flag"].data_ptr(), stream)
+        ms_prep, protocol_prep = proto.run(lambda: B.dbf_admm_prepare(*pargs))
+        assert int(d["flag"].item()) == 0
         wsb = B.dbf_admm_workspace_bytes(q, r)
         ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
         args = (d["Minv"].data_ptr(), d["C"].data_ptr(), q, r, rho, svid_iters, d["a"].data_ptr(), d["m"].data_ptr(),
@@ -659,17 +667,24 @@ def admm_bench(B, I, torch, np, stream, proto, svid_iters=2, rho=1.0):
         # (every call is the next ADMM iteration on the updated iterate)
         ms, protocol = proto.run(lambda: B.dbf_admm_step(*args))
         flops = 2.0 * q * q * r
+        prep_flops = 2.0 * p * q * q + 2.0 * p * q * r + 2.0 * q ** 3 / 3.0 + 2.0 * q ** 3
         nbytes = (7.0 + 2.0 * svid_iters) * q * r * 4.0 + 4.0 * q * q
         t0 = time.time()
-        from oracle import dbf_oracle as O
-        O.admm_step_from(Minv.astype(np.float64), Cm.astype(np.float64), rho, S.astype(np.float64),
-                         a.astype(np.float64), m.astype(np.float64), U.astype(np.float64), svid_iters)
+        Minv64, C64 = O.admm_constants(O.fixed_factor_dense(S_B, b, m2), W, rho)
+        cpu_prep_s = time.time() - t0
+        t0 = time.time()
+        O.admm_step_from(Minv64, C64, rho, S.astype(np.float64), a.astype(np.float64), m.astype(np.float64),
+                         U.astype(np.float64), svid_iters)
         cpu_s = time.time() - t0
         res["q%d_r%d_svid%d" % (q, r, svid_iters)] = {
             "ms_per_step": round(ms, 4), "contraction_flops": flops,
             "tflops_whole_step": round(flops / (ms * 1e-3) / 1e12, 2),
             "frac_of_f32_mfma_peak_whole_step": round(flops / (ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
-            "elementwise_bytes": nbytes, "cpu_oracle_s": round(cpu_s, 3), "protocol": protocol}
+            "elementwise_bytes": nbytes, "cpu_oracle_s": round(cpu_s, 3), "protocol": protocol,
+            "prepare": {"ms": round(ms_prep, 4), "flops": prep_flops,
+                        "tflops": round(prep_flops / (ms_prep * 1e-3) / 1e12, 2),
+                        "frac_of_f32_mfma_peak": round(prep_flops / (ms_prep * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS, 4),
+                        "cpu_oracle_s": round(cpu_prep_s, 3), "protocol": protocol_prep}}
     return res
 
 

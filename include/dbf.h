@@ -222,8 +222,9 @@ int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* a_dev, void
  * The compression solves min ||B X - W|| with X constrained to the SVID form a . S . m^T by ADMM (the
  * alternating minimisation's subproblem min_A ||A B - W|| has this form after transposition):
  *     W_hat = (B^T B + rho I)^-1 (B^T W + rho (A - U)),   A' = SVID(W_hat + U),   U' = U + W_hat - A'.
- * B and W do not change during the inner iterations, so the caller forms the two constant matrices once
+ * B and W do not change during the inner iterations, so the two constant matrices are formed once
  *     Minv = (B^T B + rho I)^-1   (q x q),      C = B^T W   (q x r)
+ * (dbf_admm_prepare below does that on the device from the packed fixed factor; any other source will do)
  * and this call does what is repeated, on the device, with the iterate kept in its factored form:
  *     Z = Minv^T (C + rho (a . S . m^T - U)) + U;   (S, a, m) <- SVID(Z);   U <- Z - a . S . m^T.
  * (Minv is symmetric in exact arithmetic; it is applied transposed, i.e. read by rows of the summation
@@ -242,6 +243,32 @@ size_t dbf_admm_workspace_bytes(int q, int r); /* 0 if the sizes are out of rang
 int dbf_admm_step(const void* Minv_dev, const void* C_dev, int q, int r, float rho, int svid_iters,
                   void* a_dev, void* m_dev, void* bits_dev, void* U_dev, void* workspace_dev,
                   size_t workspace_bytes, void* hip_stream);
+
+/* dbf_admm_prepare: the two constant matrices of that update, formed on the device with the fixed factor left in
+ * its packed form (section 3.2: B and W do not change during the inner iterations; section 3.2 "alternating
+ * minimisation": the fixed factor is itself a sign matrix with two scale vectors).  In the least-squares form
+ * min ||B X - W|| the fixed factor is
+ *     B = diag(b) S^T diag(m2)   (p x q),   i.e.  B[l][j] = b[l] * S[j][l] * m2[j],
+ * with S (q x p, entries +-1) the packed sign matrix (for the left-factor update of a layer: S = the layer's B
+ * signs, q = k, p = n_in, b its input scales, m2 the part of the middle scales that stays with it).  Computes
+ *     C = B^T W  (q x r)     and     Minv = (B^T B + rho I)^-1  (q x q)
+ * by fp32 matrix-core contractions that read the sign tiles directly (B is never stored densely), a blocked
+ * Cholesky factorisation B^T B + rho I = R^T R (blocks of 128), the inverse of the factor and one more
+ * contraction.  The outputs are what dbf_admm_step takes (Minv is symmetric up to rounding).
+ *   bits_dev: device, dbf_tiled_bytes(q, p) bytes: S in the tile layout, rows q, columns p (read only).
+ *   m2_dev: device fp32 [q];  b_dev: device fp32 [p];  W_dev: device fp32 [p][r] row major (all read only).
+ *   rho > 0.   Minv_dev: device fp32 [q][q] out;   C_dev: device fp32 [q][r] out.
+ *   workspace_dev: device, 256-byte aligned, >= dbf_admm_prepare_workspace_bytes(p, q, r) bytes (a q x q matrix
+ *          and the inverses of the diagonal blocks).
+ *   not_positive_definite_dev: device int (4-byte aligned) or NULL: set to the number of diagonal blocks whose
+ *          factorisation met a non-positive pivot (0 = fine; with rho > 0 the matrix is positive definite and
+ *          this only happens when rounding swamps rho).  Read it with an ordinary stream-ordered copy.
+ * Asynchronous on hip_stream, allocates nothing, results do not depend on scheduling.
+ * Errors: DBF_EINVAL (null or misaligned pointers, sizes out of range, rho <= 0 or not finite), DBF_EWORKSPACE, DBF_EHIP. */
+size_t dbf_admm_prepare_workspace_bytes(int p, int q, int r); /* 0 if the sizes are out of range */
+int dbf_admm_prepare(const void* bits_dev, const void* m2_dev, const void* b_dev, const void* W_dev, int p, int q, int r,
+                     float rho, void* Minv_dev, void* C_dev, void* workspace_dev, size_t workspace_bytes,
+                     int* not_positive_definite_dev, void* hip_stream);
 
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a

@@ -33,7 +33,7 @@ EXPORTS = [
     "dbf_gemm_static",
     "dbf_stack_create", "dbf_stack_create_grouped", "dbf_stack_offsets", "dbf_stack_gemv", "dbf_stack_gemv_timed",
     "dbf_stack_sync_timeouts", "dbf_stack_free",
-    "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_admm_workspace_bytes", "dbf_admm_step", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
+    "dbf_prune_middle", "dbf_svid_workspace_bytes", "dbf_svid", "dbf_admm_workspace_bytes", "dbf_admm_step", "dbf_admm_prepare_workspace_bytes", "dbf_admm_prepare", "dbf_probe_read", "dbf_probe_mfma", "dbf_strerror",
     "dbf_tuning_set", "dbf_tuning_get", "dbf_tuning_reset",
 ]
 
@@ -91,6 +91,9 @@ def lib() -> C.CDLL:
     L.dbf_admm_workspace_bytes.argtypes = [i32, i32]
     L.dbf_admm_workspace_bytes.restype = sz
     L.dbf_admm_step.argtypes = [vp, vp, i32, i32, C.c_float, i32, vp, vp, vp, vp, vp, sz, vp]
+    L.dbf_admm_prepare_workspace_bytes.argtypes = [i32, i32, i32]
+    L.dbf_admm_prepare_workspace_bytes.restype = sz
+    L.dbf_admm_prepare.argtypes = [vp, vp, vp, vp, i32, i32, i32, C.c_float, vp, vp, vp, sz, vp, vp]
     L.dbf_probe_read.argtypes = [vp, sz, vp, vp]
     L.dbf_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp, C.POINTER(C.c_double)]
     L.dbf_tuning_set.argtypes = [i32, i32]
@@ -229,6 +232,16 @@ def dbf_admm_step(minv_ptr: int, c_ptr: int, q: int, r: int, rho: float, svid_it
                   bits_ptr: int, u_ptr: int, ws_ptr: int, ws_bytes: int, stream: int = 0) -> None:
     _check(lib().dbf_admm_step(minv_ptr, c_ptr, q, r, float(rho), svid_iters, a_ptr, m_ptr, bits_ptr, u_ptr,
                                ws_ptr, ws_bytes, stream), "dbf_admm_step")
+
+
+def dbf_admm_prepare_workspace_bytes(p: int, q: int, r: int) -> int:
+    return int(lib().dbf_admm_prepare_workspace_bytes(p, q, r))
+
+
+def dbf_admm_prepare(bits_ptr: int, m2_ptr: int, b_ptr: int, w_ptr: int, p: int, q: int, r: int, rho: float,
+                     minv_ptr: int, c_ptr: int, ws_ptr: int, ws_bytes: int, flag_ptr: int = 0, stream: int = 0) -> None:
+    _check(lib().dbf_admm_prepare(bits_ptr, m2_ptr, b_ptr, w_ptr, p, q, r, float(rho), minv_ptr, c_ptr, ws_ptr,
+                                  ws_bytes, flag_ptr, stream), "dbf_admm_prepare")
 
 
 def dbf_unpack_bits(layer: Layer):

@@ -170,3 +170,21 @@ def make_admm_problem(p: int, q: int, r: int, seed: int):
     m = rng.uniform(0.2, 1.5, r).astype(np.float32)
     U = (0.3 * rng.standard_normal((q, r))).astype(np.float32)
     return B, W, S, a, m, U
+
+
+def make_admm_packed_problem(p: int, q: int, r: int, seed: int):
+    """The same update with the fixed factor in its packed form (section 3.2: the factor that stays fixed in an
+    alternating step is itself a sign matrix with two scale vectors): signs S_B (q x p, +-1 as int8), the scales
+    m2 (q, U[0.5, 1.5)) and b (p, U[0.5, 1.5) / sqrt(p), so that the columns of the dense factor have norms of order
+    one and B^T B + rho I a condition number of a few units), plus W, the iterate and the dual as in
+    make_admm_problem.  Returns (S_B, m2, b, W, S, a, m, U), fp32 / int8."""
+    rng = np.random.default_rng(seed + 950)
+    S_B = np.where(rng.random((q, p)) < 0.5, 1, -1).astype(np.int8)
+    m2 = rng.uniform(0.5, 1.5, q).astype(np.float32)
+    b = (rng.uniform(0.5, 1.5, p) / np.sqrt(p)).astype(np.float32)
+    W = rng.standard_normal((p, r)).astype(np.float32)
+    S = np.where(rng.random((q, r)) < 0.5, 1, -1).astype(np.int8)
+    a = rng.uniform(0.2, 1.5, q).astype(np.float32)
+    m = rng.uniform(0.2, 1.5, r).astype(np.float32)
+    U = (0.3 * rng.standard_normal((q, r))).astype(np.float32)
+    return S_B, m2, b, W, S, a, m, U

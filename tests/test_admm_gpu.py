@@ -64,7 +64,7 @@ class DeviceState:
             self.U.cpu().numpy().astype(np.float64)
 
 
-def _check_step(what, before, after, Minv, C, rho, iters):
+def _check_step(what, before, after, Minv, C, rho, iters, z_gate=Z_GATE):
     S0, a0, m0, U0 = before
     S1, a1, m1, U1 = after
     S_ref, a_ref, m_ref, U_ref, W_hat = O.admm_step_from(Minv.astype(np.float64), C.astype(np.float64), rho, S0, a0,
@@ -74,13 +74,13 @@ def _check_step(what, before, after, Minv, C, rho, iters):
     assert np.all(np.isfinite(U1)) and np.all(np.isfinite(a1)) and np.all(np.isfinite(m1)), what
     Z_gpu = U1 + a1[:, None] * S1 * m1[None, :]
     ez = np.max(np.abs(Z_gpu - Z_ref)) / rms
-    decided = np.abs(Z_ref) > Z_GATE * rms
+    decided = np.abs(Z_ref) > z_gate * rms
     ea = np.max(np.abs(a1 - a_ref)) / np.max(np.abs(a_ref))
     em = np.max(np.abs(m1 - m_ref)) / np.max(np.abs(m_ref))
     eu = np.max(np.abs(U1 - U_ref)[decided]) / (np.max(a_ref) * np.max(m_ref))
     G.say("  %s: Z err %.2e of rms (gate %.0e), undecided signs %d of %d, a %.2e m %.2e (tol %.1e), U %.2e (tol %.0e)"
-          % (what, ez, Z_GATE, int(np.sum(~decided)), decided.size, ea, em, VEC_TOL, eu, U_TOL))
-    assert ez <= Z_GATE, what
+          % (what, ez, z_gate, int(np.sum(~decided)), decided.size, ea, em, VEC_TOL, eu, U_TOL))
+    assert ez <= z_gate, what
     assert np.array_equal(S1[decided], S_ref[decided]), what + ": sign bits differ"
     assert np.sum(~decided) <= max(4, decided.size // 1000), what
     assert ea <= VEC_TOL and em <= VEC_TOL, what
@@ -117,6 +117,117 @@ def test_admm_step_at_full_size(q):
     state0 = dev.host()
     dev.step(rho, iters)
     _check_step("full size", state0, dev.host(), Minv, C, rho, iters)
+
+
+# ---- the constant matrices formed on the device from the packed fixed factor -------------------------
+#
+# Gates.  C = B^T W is an fp32 matrix-core sum of p products per entry: as for Z, 1e-4 of rms(C).  Minv comes
+# from a blocked fp32 Cholesky factorisation of G = B^T B + rho I, the inverse of the factor and one more
+# contraction; the backward error of Cholesky is of order q * 2^-24 * ||G|| and the inverse amplifies it by
+# the condition number (a few units for these inputs: rows of comparable norm, rho of order one), so entries
+# of Minv are good to about q * 2^-24 * cond(G) * max|Minv| ~ 1e-3 at worst for q = 4096, typically a
+# hundredth of that.  Gate: 3e-4 of max|Minv| -- and what matters downstream is tested with it: the update
+# that starts from the packed factor must pass the same gates as the one that is handed fp64-made constants,
+# with the gate on Z doubled (Z inherits the error of Minv times the right-hand side).
+C_GATE = 1e-4
+MINV_GATE = 3e-4
+
+
+class PackedProblem:
+    def __init__(self, p, q, r, seed):
+        self.p, self.q, self.r = p, q, r
+        self.S_B, self.m2, self.b, self.W, self.S, self.a, self.m, self.U = I.make_admm_packed_problem(p, q, r, seed)
+        self.B_dense = O.fixed_factor_dense(self.S_B, self.b, self.m2)
+
+    def prepare_on_device(self, rho):
+        p, q, r = self.p, self.q, self.r
+        tiled = B.dbf_tile_host(q, p, O.pack_signs(self.S_B.astype(np.float64)))
+        bits = torch.from_numpy(tiled.copy()).cuda()
+        m2, b, W = (torch.from_numpy(x.copy()).cuda() for x in (self.m2, self.b, self.W))
+        Minv = torch.full((q, q), float("nan"), dtype=torch.float32, device="cuda")
+        Cm = torch.full((q, r), float("nan"), dtype=torch.float32, device="cuda")
+        flag = torch.full((1,), 77, dtype=torch.int32, device="cuda")
+        wsb = B.dbf_admm_prepare_workspace_bytes(p, q, r)
+        ws = torch.full((wsb,), 0xA5, dtype=torch.uint8, device="cuda")
+        B.dbf_admm_prepare(bits.data_ptr(), m2.data_ptr(), b.data_ptr(), W.data_ptr(), p, q, r, rho, Minv.data_ptr(),
+                           Cm.data_ptr(), ws.data_ptr(), wsb, flag.data_ptr(), G.stream_handle())
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        return Minv.cpu().numpy(), Cm.cpu().numpy()
+
+
+def _check_constants(what, prob, rho, Minv, Cm):
+    Minv_ref, C_ref = O.admm_constants(prob.B_dense, prob.W, rho)
+    assert np.all(np.isfinite(Minv)) and np.all(np.isfinite(Cm)), what
+    ec = np.max(np.abs(Cm - C_ref)) / np.sqrt(np.mean(C_ref ** 2))
+    em = np.max(np.abs(Minv - Minv_ref)) / np.max(np.abs(Minv_ref))
+    es = np.max(np.abs(Minv - Minv.T)) / np.max(np.abs(Minv_ref))
+    G.say("  %s: C err %.2e of rms (gate %.0e), Minv err %.2e of max (gate %.0e), asymmetry %.1e"
+          % (what, ec, C_GATE, em, MINV_GATE, es))
+    assert ec <= C_GATE and em <= MINV_GATE and es <= MINV_GATE, what
+
+
+@pytest.mark.parametrize("shape", [(5, 3, 4), (200, 130, 150), (300, 257, 129), (700, 520, 516), (1000, 64, 200),
+                                   (128, 128, 128), (77, 300, 50)])
+@pytest.mark.parametrize("rho", [1.0, 0.3])
+def test_admm_prepare_matches_the_oracle_and_feeds_the_update(shape, rho):
+    """From the packed fixed factor, W and rho alone: the constants formed on the device against the oracle's,
+    then one update that uses them against the oracle's full update (dense B, fp64)."""
+    p, q, r = shape
+    G.say("start admm prepare p=%d q=%d r=%d rho=%g" % (p, q, r, rho))
+    prob = PackedProblem(p, q, r, I.seed_for(9, 100 + p + q + r))
+    Minv, Cm = prob.prepare_on_device(rho)
+    _check_constants("constants", prob, rho, Minv, Cm)
+    # (DeviceState hands the library the transpose of its first argument: Minv reaches it exactly as it was made)
+    dev = DeviceState(np.ascontiguousarray(Minv.T), Cm, prob.S, prob.a, prob.m, prob.U)
+    state0 = dev.host()
+    dev.step(rho, 2)
+    Minv64, C64 = O.admm_constants(prob.B_dense, prob.W, rho)
+    _check_step("update from the packed factor", state0, dev.host(), Minv64, C64, rho, 2, z_gate=2 * Z_GATE)
+
+
+@pytest.mark.parametrize("q", [2048, 4096])
+def test_admm_prepare_at_full_size(q):
+    p, r, rho = 4096, 4096, 1.0
+    G.say("start admm prepare full size p=%d q=%d r=%d" % (p, q, r))
+    prob = PackedProblem(p, q, r, I.seed_for(9, 50 + q // 2048))
+    Minv, Cm = prob.prepare_on_device(rho)
+    _check_constants("constants at full size", prob, rho, Minv, Cm)
+
+
+def test_admm_prepare_argument_errors_and_the_definiteness_flag():
+    p, q, r = 64, 32, 16
+    prob = PackedProblem(p, q, r, 3)
+    bits = torch.from_numpy(B.dbf_tile_host(q, p, O.pack_signs(prob.S_B.astype(np.float64))).copy()).cuda()
+    f = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    m2, b, W = f(prob.m2), f(prob.b), f(prob.W)
+    Minv = torch.zeros((q, q), dtype=torch.float32, device="cuda")
+    Cm = torch.zeros((q, r), dtype=torch.float32, device="cuda")
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    wsb = B.dbf_admm_prepare_workspace_bytes(p, q, r)
+    assert wsb >= 4 * q * q and B.dbf_admm_prepare_workspace_bytes(0, q, r) == 0
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    ok = [bits.data_ptr(), m2.data_ptr(), b.data_ptr(), W.data_ptr(), p, q, r, 1.0, Minv.data_ptr(), Cm.data_ptr(),
+          ws.data_ptr(), wsb, flag.data_ptr(), 0]
+    B.dbf_admm_prepare(*ok)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    for pos, val in ((0, 0), (1, 0), (2, 0), (3, 0), (4, 0), (5, 0), (6, 0), (7, 0.0), (7, float("nan")), (8, 0), (9, 0),
+                     (10, 0), (11, wsb - 1), (10, ws.data_ptr() + 8), (12, flag.data_ptr() + 2)):
+        bad = list(ok)
+        bad[pos] = val
+        with pytest.raises(B.DbfError):
+            B.dbf_admm_prepare(*bad)
+    # a pivot that is not positive (here: a NaN scale, which the entry point does not support but must survive):
+    # the flag is raised, nothing hangs or faults
+    nan_m2 = prob.m2.copy()
+    nan_m2[0] = np.nan
+    m2n = f(nan_m2)
+    bad = list(ok)
+    bad[1] = m2n.data_ptr()
+    B.dbf_admm_prepare(*bad)
+    torch.cuda.synchronize()
+    assert int(flag.item()) >= 1
 
 
 def test_admm_fixed_point_on_an_exactly_factorisable_target():
