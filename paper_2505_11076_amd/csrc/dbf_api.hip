@@ -31,7 +31,6 @@ inline bool shape_ok(int n_in, int n_out, int k) {
 // `pattern`, cyclically; `phase` carries the position in the pattern from layer to layer.
 void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool stage_a,
                   int need, const std::vector<int>& pattern, int* phase) {
-    const size_t first = out.size();
     for (int rt = 0; rt < st.n_rt;) {
         const int span = pattern[(size_t)(*phase)++ % pattern.size()];
         DbfItem it;
@@ -57,7 +56,6 @@ void append_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool
         out.push_back(it);
         rt += it.nrt;
     }
-    for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);  // items of this call
 }
 
 // Tuning and test hooks (include/dbf.h, "tuning and test hooks"): default, smallest and largest value per knob.
@@ -108,7 +106,6 @@ int pieces_for(int n_ct, int stage_row_tiles) {
 // equal size.  acc / cnt: this stage's accumulators (row 0) and arrival counters (row tile 0).
 void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer, bool stage_a, int need,
                         int pieces, int* acc, int acc_stride, int* cnt) {
-    const size_t first = out.size();
     for (int rt = 0; rt < st.n_rt; ++rt) {
         for (int pc = 0; pc < pieces; ++pc) {
             DbfItem it;
@@ -137,7 +134,6 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
             out.push_back(it);
         }
     }
-    for (size_t i = first; i < out.size(); ++i) out[i].peers = (int)(out.size() - first);
 }
 
 // Row tiles per workgroup for one stage of one layer in a launch whose stage holds `stage_tiles` tiles
@@ -258,6 +254,12 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
             row_tiles_before += sA[i].n_rt;
         }
     }
+    // what one launch adds to a layer's counters, in every item of every list
+    for (std::vector<DbfItem>* list : {&items_n, &items_1, &items_p})
+        for (DbfItem& it : *list) {
+            it.need = sB[it.layer].n_rt;
+            it.peers = sA[it.layer].n_rt;
+        }
     const size_t o_ip = off;  off = align_up(off + sizeof(DbfItem) * items_p.size(), 256);
     std::vector<uint8_t> image(off, 0);
     std::memcpy(image.data() + o_sB, sB.data(), sizeof(DbfStage) * n);

@@ -471,11 +471,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #endif
     };
     // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
-    // sync[layer] counts the B-stage row tiles published over all launches of this plan, sync[n_layers + layer]
-    // the A-stage items finished.  Launches of one plan do not overlap, so while this launch runs the second
-    // counter lies in [e * peers, (e + 1) * peers) with e the number of completed launches, and this launch's
-    // B stage is done when the first counter has reached (e + 1) * need.  The wait is bounded on the GPU's
-    // constant 100 MHz clock.
+    // sync[layer] counts the B-stage row tiles published over all one-launch calls of this plan, sync[n_layers +
+    // layer] the A-stage row tiles finished: what one call adds to either (it.need, it.peers: the layer's B and A
+    // row tiles) does not depend on how the call's list cuts the layer into items, so calls may switch lists.
+    // Launches of one plan do not overlap, so while this launch runs the second counter lies in [e * peers,
+    // (e + 1) * peers) with e the number of completed launches, and this launch's B stage is done when the first
+    // counter has reached (e + 1) * need.  The wait is bounded on the GPU's constant 100 MHz clock.
     if (tid == 0) misc->gave_up = 0;
     if (use_sync && stage_a) {
         if (tid == 0) {
@@ -792,8 +793,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             // (of the pieces of a row tile only the one that stored the result publishes it)
             if (tid == 0 && (n_pieces == 1 || misc->last))
                 __hip_atomic_fetch_add(&sync[it.layer], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else if (tid == 0) {
-            __hip_atomic_fetch_add(&sync[n_layers + it.layer], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if (tid == 0 && (n_pieces == 1 || misc->last)) {
+            // (of the pieces of a row tile only the one that stored the result counts it)
+            __hip_atomic_fetch_add(&sync[n_layers + it.layer], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

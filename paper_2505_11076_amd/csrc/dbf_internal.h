@@ -60,9 +60,9 @@ struct DbfItem {
     int cols;                   // valid columns of the stage
     int t_stride;               // elements between batch rows of t
     int layer;                  // index of the layer's counters (DbfPlan::d_sync)
-    int need;                   // A stage: B-stage row tiles of the layer, i.e. what one launch publishes
+    int need;                   // B-stage row tiles of the layer: what one launch adds to the "published" counter
     int stage_a;                // 0: B stage, 1: A stage
-    int peers;                  // A stage: number of A-stage items of this layer in the list
+    int peers;                  // A-stage row tiles of the layer: what one launch adds to the "finished" counter
     // Column pieces (lists with pieces > 1 hold one row tile per item): the item covers column tiles
     // [ct0, ct0 + ct_n) of its row tile; the pieces of a row tile add their exact integer sums into
     // acc and the last one to arrive (cnt) scales and stores the result, and clears both.
@@ -94,8 +94,9 @@ struct DbfPlan {
     // Counters of the one-launch kernel, 64 bits each, zero when the plan is built and only ever growing
     // (nothing is reset, so a workgroup that gives up its wait leaves them consistent):
     //   [layer]            B-stage row tiles published so far, over all launches of this plan
-    //   [n_layers + layer] A-stage items finished so far: divided by the layer's A items per launch this is
+    //   [n_layers + layer] A-stage row tiles finished so far: divided by the layer's A row tiles this is
     //                      the number of completed launches, i.e. how much of the first counter is old
+    // (what a launch adds is the same whichever of the plan's lists it uses)
     //   [2 n_layers]       waits given up (sticky)
     unsigned long long* d_sync;
     int span;                   // row tiles per item in d_items_n
