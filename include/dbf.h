@@ -357,11 +357,16 @@ enum {
     DBF_TUNE_SHARED_Q = 7,            /* batches >= 2: -1 (default) built-in choice; 0: every workgroup quantises its
                                          own input; 1: input quantised once per call and copied to LDS; 2: read from
                                          memory tile by tile                                                       */
-    DBF_TUNE_SHARED_MIN_BATCH = 8,    /* smallest batch that takes the once-per-call quantisation, 2..17 (default 2) */
+    DBF_TUNE_SHARED_MIN_BATCH = 8,    /* smallest batch that takes the once-per-call quantisation, 1..17 (default 2) */
     DBF_TUNE_SHARED_LDS_KB = 9,       /* LDS budget per workgroup for the copied input, 16..64 KiB (default 52)     */
     DBF_TUNE_WAIT_LIMIT_US = 10,      /* bound of the device-side wait in microseconds, 0..10 000 000 (default
                                          250 000); 0 makes every wait that is not already satisfied give up        */
-    DBF_TUNE_COUNT_ = 11
+    /* PLAN knob */
+    DBF_TUNE_LONG_ROWS = 11,          /* -1 (default): plans of several layers, most of whose sign bytes are in layers
+                                         with one stage input longer than 6144 values and the other longer than 4096,
+                                         quantise every stage input once per call at batch 1 too (four launches per
+                                         call instead of one); 0: no plan does; 1: every plan does                  */
+    DBF_TUNE_COUNT_ = 12
 };
 int dbf_tuning_set(int knob, int value);
 int dbf_tuning_get(int knob);

@@ -71,9 +71,10 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_B
     {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_A
     {-1, -1, -1, 2},              // DBF_TUNE_SHARED_Q
-    {2, 2, 2, DBF_MAX_BATCH + 1}, // DBF_TUNE_SHARED_MIN_BATCH
+    {2, 2, 1, DBF_MAX_BATCH + 1}, // DBF_TUNE_SHARED_MIN_BATCH
     {52, 52, 16, 64},             // DBF_TUNE_SHARED_LDS_KB
     {250000, 250000, 0, 10000000},// DBF_TUNE_WAIT_LIMIT_US
+    {-1, -1, -1, 1},              // DBF_TUNE_LONG_ROWS
 };
 
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
@@ -143,10 +144,13 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
 // k = 2048: 5.7 TB/s at 2 and 4 row tiles for the two stages against 5.4 at 1 and 1; k = 4096: 5.7 TB/s at
 // 2 and 2 against 4.8 at 4 and 4), and rows too wide for the one-pass prologue, which read the input twice,
 // always want the longest items (8192 x 8192, k = 8192: 3.9 TB/s at 4 against 3.0 at 1).
-int auto_span(const DbfStage& st, long long stage_tiles) {
-    constexpr long long WANT_ITEMS = 2048;
+// Plans whose stage inputs are quantised once per call (long_rows) start a workgroup on a copy of int8 planes, so
+// neither rule about the prologue applies; they did best with about 1000 items per stage (8192 x 28672 streams,
+// k = 6371: 4.7 TB/s at 1 and 2 row tiles per item against 3.9 at 4).
+int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows) {
+    const long long WANT_ITEMS = long_rows ? 1024 : 2048;
     constexpr int MAX_AUTO_SPAN = 4;
-    if (st.cols > dbf_mfma_one_pass_cols()) return MAX_AUTO_SPAN;
+    if (!long_rows && st.cols > dbf_mfma_one_pass_cols()) return MAX_AUTO_SPAN;
     long long item_tiles = stage_tiles / WANT_ITEMS;
     if (item_tiles > 256) item_tiles = 256;
     int span = (int)((2 * item_tiles + st.n_ct) / (2 * st.n_ct));  // item_tiles / n_ct, rounded to nearest
@@ -175,6 +179,24 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
         if (sB[i].cols > p->max_cols_B) p->max_cols_B = sB[i].cols;
         if (sA[i].cols > p->max_cols_A) p->max_cols_A = sA[i].cols;
     }
+    // Several layers most of whose sign bytes sit in layers with long stage inputs -- one longer than the one-pass
+    // prologue holds, so that every workgroup would read it twice (for the scale, then for the rounding: as many
+    // bytes as a third to a half of the workgroup's signs), and the other longer than 4096: such plans quantise
+    // every stage input once per call at every batch, in launches of their own.  Measured on streams of 0.5 GB:
+    // 8192 x 28672 at 1 bit per weight 3.06 -> 4.7 TB/s, 8192 x 8192 at 2 bits 4.09 -> 5.0; with the other stage
+    // short (8192 x 8192 or 4096 x 14336 at 1 bit) the one-launch path is as fast or faster (5.36 against 5.2 TB/s).
+    {
+        const int lr = dbf_tune(DBF_TUNE_LONG_ROWS);
+        double bytes_long = 0, bytes_all = 0;
+        for (int i = 0; i < n; ++i) {
+            const int hi = sB[i].cols > sA[i].cols ? sB[i].cols : sA[i].cols;
+            const int lo = sB[i].cols > sA[i].cols ? sA[i].cols : sB[i].cols;
+            const double bytes = ((double)sB[i].n_rt * sB[i].n_ct + (double)sA[i].n_rt * sA[i].n_ct) * DBF_TILE_BYTES;
+            bytes_all += bytes;
+            if (hi > dbf_mfma_one_pass_cols() && lo > 4096) bytes_long += bytes;
+        }
+        p->long_rows = lr == 1 || (lr < 0 && n > 1 && 2 * bytes_long > bytes_all);
+    }
     const std::vector<int> one(1, 1);
     // row tiles per item: the given pattern, or (empty pattern) chosen per layer from the size of the launch
     long long tiles_B = 0, tiles_A = 0;
@@ -184,7 +206,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     int max_span = 1;
     auto pattern_for = [&](const std::vector<int>& given, const DbfStage& st, long long stage_tiles) {
-        std::vector<int> v = given.empty() ? std::vector<int>(1, auto_span(st, stage_tiles)) : given;
+        std::vector<int> v = given.empty() ? std::vector<int>(1, auto_span(st, stage_tiles, p->long_rows != 0)) : given;
         for (int x : v) max_span = x > max_span ? x : max_span;
         return v;
     };
@@ -210,7 +232,9 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     std::vector<int> pcB(n, 1), pcA(n, 1);
     bool cut = false;
     const int max_rt = dbf_tune(DBF_TUNE_PIECE_MAX_ROW_TILES);
-    if (rtB <= max_rt && rtA <= max_rt) {
+    if (p->long_rows) {
+        // (no pieces: the rows are cheap to start on, and whole row tiles per workgroup did better)
+    } else if (rtB <= max_rt && rtA <= max_rt) {
         for (int i = 0; i < n; ++i) {
             pcB[i] = pieces_for(sB[i].n_ct, (int)rtB);
             pcA[i] = pieces_for(sA[i].n_ct, (int)rtA);
@@ -445,12 +469,15 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     }
     // several row tiles per workgroup only if all columns of both stages fit one LDS chunk
     const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
-    const bool use_pieces = pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH;
+    const bool use_pieces = pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH && !p.long_rows;
     // Batches of 2 and more: every stage input is quantised once per call; the items copy it into LDS (1)
     // or, if a whole row does not fit there at this batch, read it from memory tile by tile (2).
     int shared_q = 0;
-    if (pieces_ok && !use_pieces && batch >= dbf_tune(DBF_TUNE_SHARED_MIN_BATCH)) {
+    if (pieces_ok && !use_pieces && (batch >= dbf_tune(DBF_TUNE_SHARED_MIN_BATCH) || p.long_rows)) {
         shared_q = dbf_mfma_chunk_tiles(batch, max_cols, 1) >= dbf_col_tiles(max_cols) ? 1 : 2;
+        // (batch 1 of a long-rows plan: no LDS copy, more workgroups per compute unit; 4096 x 14336 and 8192 x 8192
+        //  streams ran 2-5 % faster than with the copy)
+        if (p.long_rows && batch == 1) shared_q = 2;
         if (dbf_tune(DBF_TUNE_SHARED_Q) >= 0) shared_q = dbf_tune(DBF_TUNE_SHARED_Q);
     }
     const bool span = dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols);

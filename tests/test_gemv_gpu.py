@@ -530,6 +530,49 @@ def test_stack_at_larger_batches_equals_per_layer_calls(batch):
             layer.close()
 
 
+@pytest.mark.parametrize("forced", [False, True])
+def test_long_rows_plans_quantise_once_per_call_at_every_batch(forced):
+    """A stack most of whose sign bytes are in layers with long stage inputs (one above 6144 values, the other above
+    4096) quantises every stage input once per call at batch 1 and 2 as well (DBF_GEMV_AUTO; `forced`: the knob
+    instead of the rule, on a stack the rule would leave alone).  The quantiser uses the arithmetic of the items'
+    own prologue and the sums are exact integers, so every batch must give, bit for bit, the two-launch kind's
+    result on a plan built without the rule; batch 1 is also checked against the oracle."""
+    shapes = [(6400, 200, 4160), (4160, 130, 6272), (512, 512, 256)] if not forced else [(700, 260, 390), (1000, 50, 130)]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 1700 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    B.dbf_tuning_set(B.TUNE_LONG_ROWS, 0)
+    plain_layers = [G.pack(L) for L in Ls]
+    plain = B.dbf_stack_create(plain_layers)
+    B.dbf_tuning_set(B.TUNE_LONG_ROWS, 1 if forced else -1)
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        for batch in (1, 2, 1, 5, 16, 1):
+            Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 1800 + 10 * batch + i)) for i, L in enumerate(Ls)]
+            x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+            n_y = batch * sum(L.n_out for L in Ls)
+            outs = []
+            for st, kind in ((plain, B.GEMV_MFMA_SPLIT), (stack, B.GEMV_AUTO)):
+                G.say("long rows forced=%s batch %d kind %d" % (forced, batch, kind))
+                y = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
+                B.dbf_stack_gemv(st, x_all.data_ptr(), y.data_ptr(), batch, G.stream_handle(), kind)
+                torch.cuda.synchronize()
+                outs.append(y)
+            assert np.array_equal(outs[0].cpu().view(torch.int16).numpy(), outs[1].cpu().view(torch.int16).numpy()), batch
+            if batch == 1:
+                got = G.dev_to_f64(outs[1])
+                at = 0
+                for L, X in zip(Ls, Xs):
+                    ref = O.forward_from_packed(X, L, "dense")
+                    G.check(got[at:at + L.n_out].reshape(1, L.n_out), ref, "long rows n_in=%d k=%d" % (L.n_in, L.k))
+                    at += L.n_out
+        assert B.dbf_stack_sync_timeouts(stack) == 0
+    finally:
+        stack.close()
+        plain.close()
+        for l in layers + plain_layers:
+            l.close()
+
+
 # ---- the bounded wait of the one-launch kernel ----------------------------------------------------
 
 
