@@ -144,9 +144,9 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
 // k = 2048: 5.7 TB/s at 2 and 4 row tiles for the two stages against 5.4 at 1 and 1; k = 4096: 5.7 TB/s at
 // 2 and 2 against 4.8 at 4 and 4), and rows too wide for the one-pass prologue, which read the input twice,
 // always want the longest items (8192 x 8192, k = 8192: 3.9 TB/s at 4 against 3.0 at 1).
-// Plans whose stage inputs are quantised once per call (long_rows) start a workgroup on a copy of int8 planes, so
-// neither rule about the prologue applies; they did best with about 1000 items per stage (8192 x 28672 streams,
-// k = 6371: 4.7 TB/s at 1 and 2 row tiles per item against 3.9 at 4).
+// Long-rows plans take this list at batch 1, where their workgroups read the quantised input tile by tile and
+// have no prologue to amortise: they did best with about 1000 items per stage (8192 x 28672 streams, k = 6371:
+// 4.7 TB/s at 1 and 2 row tiles per item against 3.9 at 4, which makes 240 items).
 int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows) {
     const long long WANT_ITEMS = long_rows ? 1024 : 2048;
     constexpr int MAX_AUTO_SPAN = 4;
@@ -157,6 +157,21 @@ int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows) {
     if (span < 1) span = 1;
     if (span > MAX_AUTO_SPAN) span = MAX_AUTO_SPAN;
     return span;
+}
+
+// The same for the launches of batches of 2 and more, which take a stage input quantised once per call: a workgroup
+// starts on a copy of up to 52 KiB of int8 planes, two launches per stage leave more of a tail, and fewer, longer
+// items did better: about 512 per stage, of equal length within a layer.  Measured on 512 layers of 4096 x 4096,
+// k = 2048 at batch 2 / 4 / 8: 5.36 / 4.76 / 3.85 TB/s with 16 row tiles per item against 5.10 / 4.53 / 3.72 with
+// 2 and 4 (768 items per stage: 5.30 / 4.50 / 3.75).
+int shared_span(const DbfStage& st, long long stage_tiles) {
+    constexpr long long WANT_ITEMS = 512;
+    const long long item_tiles = stage_tiles / WANT_ITEMS;
+    long long span = (2 * item_tiles + st.n_ct) / (2 * st.n_ct);
+    if (span < 1) span = 1;
+    if (span > DBF_MAX_SPAN) span = DBF_MAX_SPAN;
+    const long long per_layer = (st.n_rt + span - 1) / span;  // items of equal length
+    return (int)((st.n_rt + per_layer - 1) / per_layer);
 }
 
 void free_plan(DbfPlan& p) {
@@ -216,6 +231,19 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     phase = 0;
     for (int i = 0; i < n; ++i)
         append_items(items_n, sA[i], i, true, sB[i].n_rt, pattern_for(span_a, sA[i], tiles_A), &phase);
+    // (the list of the launches that take a shared quantised input)
+    auto shared_pattern_for = [&](const std::vector<int>& given, const DbfStage& st, long long stage_tiles) {
+        std::vector<int> v = given.empty() ? std::vector<int>(1, shared_span(st, stage_tiles)) : given;
+        for (int x : v) max_span = x > max_span ? x : max_span;
+        return v;
+    };
+    std::vector<DbfItem> items_s;
+    phase = 0;
+    for (int i = 0; i < n; ++i) append_items(items_s, sB[i], i, false, 0, shared_pattern_for(span_b, sB[i], tiles_B), &phase);
+    const int nBs = (int)items_s.size();
+    phase = 0;
+    for (int i = 0; i < n; ++i)
+        append_items(items_s, sA[i], i, true, sB[i].n_rt, shared_pattern_for(span_a, sA[i], tiles_A), &phase);
     phase = 0;
     for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, one, &phase);
     nB1 = (int)items_1.size();
@@ -251,6 +279,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     const size_t o_wA = off;  off = align_up(off + sizeof(DbfWorkItem) * wA1.size(), 256);
     const size_t o_in = off;  off = align_up(off + sizeof(DbfItem) * items_n.size(), 256);
     const size_t o_i1 = off;  off = align_up(off + sizeof(DbfItem) * items_1.size(), 256);
+    const size_t o_is = off;  off = align_up(off + sizeof(DbfItem) * items_s.size(), 256);
     const size_t o_sy = off;  off = align_up(off + sizeof(unsigned long long) * (2 * (size_t)n + 1), 256);
     const size_t o_ac = off;  off = align_up(off + sizeof(int) * acc_ints, 256);
     const size_t o_cn = off;  off = align_up(off + sizeof(int) * cnt_ints, 256);
@@ -279,7 +308,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
         }
     }
     // what one launch adds to a layer's counters, in every item of every list
-    for (std::vector<DbfItem>* list : {&items_n, &items_1, &items_p})
+    for (std::vector<DbfItem>* list : {&items_n, &items_1, &items_s, &items_p})
         for (DbfItem& it : *list) {
             it.need = sB[it.layer].n_rt;
             it.peers = sA[it.layer].n_rt;
@@ -292,6 +321,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     std::memcpy(image.data() + o_wA, wA1.data(), sizeof(DbfWorkItem) * wA1.size());
     std::memcpy(image.data() + o_in, items_n.data(), sizeof(DbfItem) * items_n.size());
     std::memcpy(image.data() + o_i1, items_1.data(), sizeof(DbfItem) * items_1.size());
+    std::memcpy(image.data() + o_is, items_s.data(), sizeof(DbfItem) * items_s.size());
     void* dev = nullptr;
     hipError_t e = hipMalloc(&dev, off);
     if (e == hipSuccess) {
@@ -323,6 +353,9 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->d_items_1 = reinterpret_cast<DbfItem*>(d + o_i1);
     p->nB1 = nB1;
     p->nA1 = (int)items_1.size() - nB1;
+    p->d_items_s = reinterpret_cast<DbfItem*>(d + o_is);
+    p->nBs = nBs;
+    p->nAs = (int)items_s.size() - nBs;
     p->d_sync = reinterpret_cast<unsigned long long*>(d + o_sy);
     p->d_items_p = cut ? reinterpret_cast<DbfItem*>(d + o_ip) : nullptr;
     p->nBp = nBp;
@@ -481,8 +514,9 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
         if (dbf_tune(DBF_TUNE_SHARED_Q) >= 0) shared_q = dbf_tune(DBF_TUNE_SHARED_Q);
     }
     const bool span = dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols);
-    const DbfItem* items = span ? p.d_items_n : p.d_items_1;
-    int nB = span ? p.nBn : p.nB1, nA = span ? p.nAn : p.nA1;
+    const bool long_list = shared_q && batch >= 2;  // fewer, longer items (shared_span)
+    const DbfItem* items = !span ? p.d_items_1 : long_list ? p.d_items_s : p.d_items_n;
+    int nB = !span ? p.nB1 : long_list ? p.nBs : p.nBn, nA = !span ? p.nA1 : long_list ? p.nAs : p.nAn;
     int pieces = 0;
     if (use_pieces) {  // few row tiles: cut them into column pieces
         items = p.d_items_p;

@@ -87,6 +87,8 @@ struct DbfPlan {
     int blocksB1, blocksA1;
     DbfItem* d_items_n;         // matrix-core items, up to `span` row tiles each: B items, then A items
     int nBn, nAn;
+    DbfItem* d_items_s;         // the same with the row tiles per item chosen for the launches of batches of 2 and
+    int nBs, nAs;               // more, which take a stage input quantised once per call (fewer, longer items)
     DbfItem* d_items_1;         // the same with one row tile per item (used when the columns of
     int nB1, nA1;               // a stage do not fit one LDS chunk at the requested batch)
     DbfItem* d_items_p;         // one row tile per item, row tiles cut into column pieces: built for plans
