@@ -194,7 +194,8 @@ struct Ctx {
     Misc* misc;
     signed char* xq;
     const uint16_t* x;  // B stage input rows (fp16), unused in the A stage
-    int chs;            // bytes per operand row in LDS
+    int chs;            // bytes from the high plane of a batch row to its low plane (LDS: the operand row's length)
+    int tstride;        // TILED destinations only: bytes from one column tile of a plane to the next
     int tid, lane, w;
     int batch;
     bool fast;          // 16-byte vector loads are possible
@@ -204,7 +205,9 @@ struct Ctx {
 // The decode case in one pass: the row was loaded once into registers (by the kernel's
 // prologue, see there); reduce max|u| and quantise from the registers.
 // Contains one barrier; ends with the operand in LDS (not yet synchronised).
-template <bool STAGE_A>
+// TILED: the destination is not an LDS operand row but the per-call buffer of a stage (DbfStage::q_in), in which
+// the 64 bytes a plane has for one column tile are followed by the next plane's.
+template <bool STAGE_A, bool TILED = false>
 __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const v4u (&r1)[UNR]) {
     InputVec<STAGE_A> iv[UNR];
     float mx = 0.f;
@@ -227,7 +230,8 @@ __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const 
 #pragma unroll
     for (int j = 0; j < UNR; ++j) {
         const int v = 256 * j + c.tid;
-        if (v < c.nvec) local += iv[j].quantise_to(c.xq + v * 8, c.xq + c.chs + v * 8, inv);
+        const int at = TILED ? (v >> 3) * c.tstride + (v & 7) * 8 : v * 8;
+        if (v < c.nvec) local += iv[j].quantise_to(c.xq + at, c.xq + c.chs + at, inv);
     }
     local = dbf_wave_sum(local);
     if (c.lane == 0) atomicAdd(&c.misc->sigma[0], local);
@@ -269,7 +273,7 @@ __device__ inline void input_scales(const DbfItem& it, const Ctx& c) {
 }
 
 // General case, second pass: quantise columns [64*c0, 64*cend) of every batch row into LDS.
-template <bool STAGE_A, int W>
+template <bool STAGE_A, int W, bool TILED = false>
 __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int c0, int cend) {
     for (int bi = 0; bi < c.batch; ++bi) {
         const float inv = c.misc->inv[bi];
@@ -288,7 +292,8 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 #pragma unroll
                 for (int j = 0; j < W; ++j) {
                     const int v = base + 256 * j + c.tid;
-                    if (v < v1) local += iv[j].quantise_to(hi_row + (v - v0) * 8, lo_row + (v - v0) * 8, inv);
+                    const int at = TILED ? ((v - v0) >> 3) * c.tstride + ((v - v0) & 7) * 8 : (v - v0) * 8;
+                    if (v < v1) local += iv[j].quantise_to(hi_row + at, lo_row + at, inv);
                 }
             }
         } else {
@@ -301,8 +306,10 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
                 }
                 const int lo = ((q + 128) & 255) - 128;
                 const int hi = (q - lo) >> 8;
-                hi_row[l - c0 * 64] = (signed char)hi;
-                lo_row[l - c0 * 64] = (signed char)lo;
+                const int rel = l - c0 * 64;
+                const int at = TILED ? (rel >> 6) * c.tstride + (rel & 63) : rel;
+                hi_row[at] = (signed char)hi;
+                lo_row[at] = (signed char)lo;
                 local += q;
             }
         }
@@ -385,9 +392,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     int steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
     int p_rt = 0, p_i = 0;
     v4u buf[PF];
-    // SHARED == 2: the operand ring.  A second buffer resource covers the 2 * batch planes of the stage; lane
-    // (g, c) of column group gi reads bytes 16 g .. 16 g + 15 of the tile's 64 columns of plane row 16 gi + c
-    // (unused operand columns alias a valid row).  A slot's loads are issued as (tile, operand[0], operand[1]).
+    // SHARED == 2: the operand ring.  A second buffer resource covers the 2 * batch planes of the stage, laid out
+    // column tile by column tile (per tile: plane 0's 64 bytes, plane 1's, ...), so that what a wavefront reads for a
+    // tile is one contiguous run of 64 * 2 * batch bytes; lane (g, c) of column group gi reads bytes 16 g .. 16 g +
+    // 15 of plane 16 gi + c (unused operand columns alias a valid plane).  A slot's loads are issued as (tile,
+    // operand[0], operand[1]).  (With whole plane rows one after the other every lane of a load touched a cache
+    // line of its own: 8 KiB moved from the L2 per 1 KiB used, and that traffic bounded batches 5-16.)
     constexpr int XB_N = SHARED == 2 ? NCG : 1;
     constexpr int SLOT_LOADS = SHARED == 2 ? 1 + NCG : 1;
     v4i xb[PF][XB_N];
@@ -402,14 +412,14 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
         for (int gi = 0; gi < XB_N; ++gi) {
             const int col = 16 * gi + c;
-            x_lane_off[gi] = (unsigned)((col < ncols ? col : col % ncols) * it.n_ct * DBF_TILE_COLS + 16 * g);
+            x_lane_off[gi] = (unsigned)((col < ncols ? col : col % ncols) * DBF_TILE_COLS + 16 * g);
         }
     }
     auto fetch_operand = [&](int j, int ct, int ok) {
         if (SHARED == 2) {
 #pragma unroll
             for (int gi = 0; gi < XB_N; ++gi) {
-                const unsigned voff = ok ? x_lane_off[gi] + (unsigned)ct * DBF_TILE_COLS : OOB;
+                const unsigned voff = ok ? x_lane_off[gi] + (unsigned)(ct * ncols) * DBF_TILE_COLS : OOB;
                 asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(xb[j][gi]) : "v"(voff), "s"(xrsrc) : "memory");
             }
         }
@@ -498,7 +508,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 
     // ---- prologue ------------------------------------------------------------------------------
     Ctx cx;
-    cx.misc = misc;  cx.xq = xq;  cx.x = x;  cx.chs = chs;
+    cx.misc = misc;  cx.xq = xq;  cx.x = x;  cx.chs = chs;  cx.tstride = 0;
     cx.tid = tid;  cx.lane = lane;  cx.w = w;  cx.batch = batch;
     cx.nvec = it.n_ct * 8;
     cx.nvec_x = it.cols >> 3;
@@ -598,13 +608,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     for (;;) {  // chunks of columns (a single one unless the batch is large)
         if (SHARED == 1) {
             // columns [64 c0, 64 cend) of the 2 * batch planes, 16 bytes per thread and round
-            const unsigned char* planes = it.q_in + DBF_QIN_HEADER + (size_t)c0 * DBF_TILE_COLS;
+            // (in the buffer the planes alternate column tile by column tile; in LDS every plane is one row)
+            const unsigned char* planes = it.q_in + DBF_QIN_HEADER + (size_t)c0 * ncols * DBF_TILE_COLS;
             const int per_row = (cend - c0) * (DBF_TILE_COLS / 16);
-            const size_t q_stride = (size_t)it.n_ct * DBF_TILE_COLS;
             for (int r = 0; r < ncols; ++r)
                 for (int i = tid; i < per_row; i += 256)
-                    *reinterpret_cast<v4u*>(xq + r * chs + 16 * i) =
-                        *reinterpret_cast<const v4u*>(planes + r * q_stride + 16 * (size_t)i);
+                    *reinterpret_cast<v4u*>(xq + r * chs + 16 * i) = *reinterpret_cast<const v4u*>(
+                        planes + ((size_t)(i >> 2) * ncols + r) * DBF_TILE_COLS + 16 * (i & 3));
         } else if (SHARED == 0 && !one_pass) {
             if (stage_a) input_quantise_chunk<true, IN_W>(it, cx, c0, cend);
             else input_quantise_chunk<false, IN_W>(it, cx, c0, cend);
@@ -817,12 +827,13 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
     it.cols = st.cols;
     it.n_ct = st.n_ct;
     const uint16_t* x = x_base + st.x_off * batch;
-    const size_t q_stride = (size_t)st.n_ct * DBF_TILE_COLS;
+    // destination: per column tile the 2 * batch planes' 64 bytes one after the other; this row's are 2 bi, 2 bi + 1
     Ctx cx;
     cx.misc = &misc;
-    cx.xq = reinterpret_cast<signed char*>(st.q_in + DBF_QIN_HEADER + (size_t)(2 * bi) * q_stride);
+    cx.xq = reinterpret_cast<signed char*>(st.q_in + DBF_QIN_HEADER + (size_t)(2 * bi) * DBF_TILE_COLS);
     cx.x = x + (size_t)bi * st.cols;
-    cx.chs = (int)q_stride;
+    cx.chs = DBF_TILE_COLS;
+    cx.tstride = 2 * batch * DBF_TILE_COLS;
     cx.tid = threadIdx.x;  cx.lane = threadIdx.x & 63;  cx.w = threadIdx.x >> 6;
     cx.batch = 1;   // this block's row is "batch row 0" of the helpers
     cx.nvec = st.n_ct * 8;
@@ -846,10 +857,10 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
                 r1[j] = *reinterpret_cast<const v4u*>(it.in_scale + 8 * (size_t)v);
             }
         }
-        input_one_pass<STAGE_A>(cx, r0, r1);
+        input_one_pass<STAGE_A, true>(cx, r0, r1);
     } else {
         input_scales<STAGE_A, WIDE>(it, cx);
-        input_quantise_chunk<STAGE_A, WIDE>(it, cx, 0, st.n_ct);
+        input_quantise_chunk<STAGE_A, WIDE, true>(it, cx, 0, st.n_ct);
     }
     __syncthreads();
     if (threadIdx.x == 0) {

@@ -29,9 +29,10 @@ struct DbfStage {
     int rows, cols;             // valid rows / cols
     int t_stride;               // elements between batch rows of t
     int pad_;
-    unsigned char* q_in;        // the stage's input quantised once per call (batches of 2 and more):
-                                // float scale[16], int sigma[16], then int8 [2 * 16][n_ct * 64] planes
-                                // (row 2 bi = high bytes, 2 bi + 1 = low bytes of batch row bi)
+    unsigned char* q_in;        // the stage's input quantised once per call (batches of 2 and more, long-rows
+                                // plans): float scale[16], int sigma[16], then int8 [n_ct][2 * batch][64]: per
+                                // column tile the 64 bytes of plane 0, of plane 1, ... (plane 2 bi = high bytes,
+                                // 2 bi + 1 = low bytes of batch row bi); room for 2 * 16 planes
 };
 
 // Work item of the vector-ALU kernel: one 128-row tile of one layer.
