@@ -356,7 +356,7 @@ enum {
     /* LAUNCH knobs */
     DBF_TUNE_SHARED_Q = 7,            /* batches >= 2: -1 (default) built-in choice; 0: every workgroup quantises its
                                          own input; 1: input quantised once per call and copied to LDS; 2: read from
-                                         memory tile by tile                                                       */
+                                         memory tile by tile; 3: the same with a row tile per wavefront             */
     DBF_TUNE_SHARED_MIN_BATCH = 8,    /* smallest batch that takes the once-per-call quantisation, 1..17 (default 2) */
     DBF_TUNE_SHARED_LDS_KB = 9,       /* LDS budget per workgroup for the copied input, 16..64 KiB (default 52)     */
     DBF_TUNE_WAIT_LIMIT_US = 10,      /* bound of the device-side wait in microseconds, 0..10 000 000 (default

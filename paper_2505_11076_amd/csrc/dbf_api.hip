@@ -70,7 +70,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {1024, 1024, 0, 1 << 20},     // DBF_TUNE_PIECE_MAX_ROW_TILES
     {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_B
     {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_A
-    {-1, -1, -1, 2},              // DBF_TUNE_SHARED_Q
+    {-1, -1, -1, 3},              // DBF_TUNE_SHARED_Q
     {2, 2, 1, DBF_MAX_BATCH + 1}, // DBF_TUNE_SHARED_MIN_BATCH
     {52, 52, 16, 64},             // DBF_TUNE_SHARED_LDS_KB
     {250000, 250000, 0, 10000000},// DBF_TUNE_WAIT_LIMIT_US
@@ -170,8 +170,10 @@ int shared_span(const DbfStage& st, long long stage_tiles) {
     long long span = (2 * item_tiles + st.n_ct) / (2 * st.n_ct);
     if (span < 1) span = 1;
     if (span > DBF_MAX_SPAN) span = DBF_MAX_SPAN;
-    const long long per_layer = (st.n_rt + span - 1) / span;  // items of equal length
-    return (int)((st.n_rt + per_layer - 1) / per_layer);
+    const long long per_layer = (st.n_rt + span - 1) / span;  // items of equal length ...
+    span = (st.n_rt + per_layer - 1) / per_layer;
+    if (span >= 4) span = (span + 3) & ~3ll;                  // ... in whole groups of four row tiles, one per wavefront
+    return (int)(span > DBF_MAX_SPAN ? DBF_MAX_SPAN : span);
 }
 
 void free_plan(DbfPlan& p) {
@@ -356,6 +358,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     p->d_items_s = reinterpret_cast<DbfItem*>(d + o_is);
     p->nBs = nBs;
     p->nAs = (int)items_s.size() - nBs;
+    p->rows_ok = 2 * (rtB + rtA) >= 7 * (long long)items_s.size();  // at least 3.5 row tiles per item on average
     p->d_sync = reinterpret_cast<unsigned long long*>(d + o_sy);
     p->d_items_p = cut ? reinterpret_cast<DbfItem*>(d + o_ip) : nullptr;
     p->nBp = nBp;
@@ -511,6 +514,11 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
         // (batch 1 of a long-rows plan: no LDS copy, more workgroups per compute unit; 4096 x 14336 and 8192 x 8192
         //  streams ran 2-5 % faster than with the copy)
         if (p.long_rows && batch == 1) shared_q = 2;
+        // (a list of long items: a row tile per wavefront, the four wavefronts of a workgroup reading the same
+        //  operand from memory at the same time.  512 layers of 4096 x 4096, k = 2048: 5.63 / 5.27 / 4.61 / 3.34 TB/s
+        //  at batch 2 / 4 / 8 / 16 against 5.42 / 4.80 with the LDS copy and 3.98 / 2.60 with every wavefront
+        //  reading the operand of its own column tiles)
+        if (batch >= 2 && p.rows_ok) shared_q = 3;
         if (dbf_tune(DBF_TUNE_SHARED_Q) >= 0) shared_q = dbf_tune(DBF_TUNE_SHARED_Q);
     }
     const bool span = dbf_mfma_chunk_tiles(batch, max_cols, shared_q) >= dbf_col_tiles(max_cols);

@@ -341,7 +341,14 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
     Misc* misc = reinterpret_cast<Misc*>(smem);
     signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
-    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + (SHARED == 2 ? 0 : ((ncols * chs + 15) & ~15)));  // [2][ncols][128]
+    // RING: the operand comes from memory with the tile (SHARED 2 and 3).  ROWS (SHARED 3): the four wavefronts
+    // do not share a row tile's column tiles but take a row tile each, all of them walking the same columns at
+    // the same time -- so three of the four reads of an operand hit the compute unit's first-level cache --
+    // and reduce into a buffer of their own.
+    constexpr bool RING = SHARED >= 2, ROWS = SHARED == 3;
+    constexpr int N_RED = ROWS ? 4 : 2;  // reduction buffers
+    constexpr int RT_STEP = ROWS ? 4 : 1;  // row tiles the workgroup works on at a time
+    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + (RING ? 0 : ((ncols * chs + 15) & ~15)));  // [N_RED][ncols][128]
 
 #if DBF_PROLOGUE_PRIO
     // (experiment: wavefront priority raised for the prologue.  The arbiter favours older
@@ -389,8 +396,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     const int n_pieces = PIECES ? it.pieces : 1;
     int c0 = ct_first;
     int cend = min(ct_end, c0 + ch_tiles);
-    int steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
-    int p_rt = 0, p_i = 0;
+    // (steps of a wavefront per row tile and chunk: every fourth column tile, or with ROWS every one)
+    auto steps_of = [&](int n_tiles) { return ((ROWS ? n_tiles : (n_tiles + 3) >> 2) + PF - 1) / PF * PF; };
+    int steps = steps_of(cend - c0);
+    int p_rt = 0, p_i = 0;  // (ROWS: p_rt counts groups of four row tiles, of which this wavefront takes the w-th)
     v4u buf[PF];
     // SHARED == 2: the operand ring.  A second buffer resource covers the 2 * batch planes of the stage, laid out
     // column tile by column tile (per tile: plane 0's 64 bytes, plane 1's, ...), so that what a wavefront reads for a
@@ -398,12 +407,12 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     // 15 of plane 16 gi + c (unused operand columns alias a valid plane).  A slot's loads are issued as (tile,
     // operand[0], operand[1]).  (With whole plane rows one after the other every lane of a load touched a cache
     // line of its own: 8 KiB moved from the L2 per 1 KiB used, and that traffic bounded batches 5-16.)
-    constexpr int XB_N = SHARED == 2 ? NCG : 1;
-    constexpr int SLOT_LOADS = SHARED == 2 ? 1 + NCG : 1;
+    constexpr int XB_N = RING ? NCG : 1;
+    constexpr int SLOT_LOADS = RING ? 1 + NCG : 1;
     v4i xb[PF][XB_N];
     v4u xrsrc = {0, 0, 0, 0};
     unsigned x_lane_off[XB_N] = {};
-    if (SHARED == 2) {
+    if (RING) {
         const uint64_t pa = reinterpret_cast<uint64_t>(it.q_in + DBF_QIN_HEADER);
         xrsrc.x = __builtin_amdgcn_readfirstlane((unsigned)pa);
         xrsrc.y = __builtin_amdgcn_readfirstlane((unsigned)(pa >> 32) & 0xFFFFu);
@@ -416,7 +425,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
         }
     }
     auto fetch_operand = [&](int j, int ct, int ok) {
-        if (SHARED == 2) {
+        if (RING) {
 #pragma unroll
             for (int gi = 0; gi < XB_N; ++gi) {
                 const unsigned voff = ok ? x_lane_off[gi] + (unsigned)(ct * ncols) * DBF_TILE_COLS : OOB;
@@ -440,9 +449,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     };
     auto fetch = [&](int j) {
         v4u& dst = buf[j];
-        const int ct = c0 + w + 4 * p_i;
-        const int ok = (int)(p_rt < it.nrt) & (int)(ct < cend);
-        const unsigned off = (unsigned)(p_rt * it.n_ct + ct) * DBF_TILE_BYTES;
+        const int ct = ROWS ? c0 + p_i : c0 + w + 4 * p_i;
+        const int rt = ROWS ? 4 * p_rt + w : p_rt;
+        const int ok = (int)(rt < it.nrt) & (int)(ct < cend);
+        const unsigned off = (unsigned)(rt * it.n_ct + ct) * DBF_TILE_BYTES;
         const unsigned voff = lane_off + (ok ? off : OOB);
 #if DBF_ASM_LOADS
         asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen " DBF_LOAD_BITS
@@ -459,9 +469,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     };
     auto wait_slot = [&](int j) {
 #if DBF_ASM_LOADS
-        if (SHARED == 2 && NCG == 2)
+        if (RING && NCG == 2)
             asm volatile("s_waitcnt vmcnt(%3)" : "+v"(buf[j]), "+v"(xb[j][0]), "+v"(xb[j][XB_N - 1]) : "n"((PF - 1) * SLOT_LOADS) : "memory");
-        else if (SHARED == 2)
+        else if (RING)
             asm volatile("s_waitcnt vmcnt(%2)" : "+v"(buf[j]), "+v"(xb[j][0]) : "n"((PF - 1) * SLOT_LOADS) : "memory");
         else
             asm volatile("s_waitcnt vmcnt(%1)" : "+v"(buf[j]) : "n"(PF - 1) : "memory");
@@ -473,7 +483,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
         for (int j = 0; j < PF; ++j) {
             asm volatile("" : "+v"(buf[j]));
-            if (SHARED == 2) {
+            if (RING) {
 #pragma unroll
                 for (int gi = 0; gi < XB_N; ++gi) asm volatile("" : "+v"(xb[j][gi]));
             }
@@ -561,7 +571,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
     for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(in0[j]), "+v"(in1[j]));
 
-    for (int i = tid; i < 2 * RB_STRIDE * ncols; i += 256) red[i] = 0;
+    for (int i = tid; i < N_RED * RB_STRIDE * ncols; i += 256) red[i] = 0;
     if (tid < DBF_MAX_BATCH) misc->sigma[tid] = 0;
     // row scales: read by the epilogues, which come after several barriers
 #pragma unroll
@@ -622,7 +632,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
         __syncthreads();
         const bool last_chunk = cend >= ct_end;
 
-        for (int rtl = 0; rtl < it.nrt; ++rtl) {
+        for (int rtl = 0; rtl < it.nrt; rtl += RT_STEP) {
             // ---- stream this wavefront's tiles of (row tile, chunk) -----------------------
             // Slot j is consumed and then refilled in place, so PF-1 loads stay in flight and
             // no register copies are needed; the operand of the next step is read from LDS
@@ -638,19 +648,21 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi) {
                 xp[gi] = xq + xrow[gi] + xo_base + w * 64;
-                if (SHARED != 2) xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
+                if (!RING) xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
             }
             // (one group = PF tiles; `fresh`: the group's first tile starts the row tile's sums)
             auto group = [&](auto fresh) {
                 constexpr bool FRESH = decltype(fresh)::value;
-                const int g_ok = (int)(p_rt < it.nrt);
-                const int g_ct = c0 + w + 4 * p_i;
-                const unsigned g_off = (unsigned)(p_rt * it.n_ct + g_ct) * DBF_TILE_BYTES;
+                constexpr int CT_STEP = ROWS ? 1 : 4;  // column tiles from one step of a wavefront to the next
+                const int g_rt = ROWS ? 4 * p_rt + w : p_rt;
+                const int g_ok = (int)(g_rt < it.nrt);
+                const int g_ct = ROWS ? c0 + p_i : c0 + w + 4 * p_i;
+                const unsigned g_off = (unsigned)(g_rt * it.n_ct + g_ct) * DBF_TILE_BYTES;
 #pragma unroll
                 for (int j = 0; j < PF; ++j) {
 #pragma unroll
                     for (int gi = 0; gi < NCG; ++gi)
-                        if (SHARED != 2) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * 4 * DBF_TILE_COLS);
+                        if (!RING) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * 4 * DBF_TILE_COLS);
                     wait_slot(j);
 #pragma unroll
                     for (int s = 0; s < 8; ++s) {
@@ -663,10 +675,11 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
                         for (int gi = 0; gi < NCG; ++gi)
                             acc[gi][s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-                                a, SHARED == 2 ? xb[j][gi % XB_N] : xr[j & 1][gi],
+                                a, RING ? xb[j][gi % XB_N] : xr[j & 1][gi],
                                 (FRESH && j == 0) ? (v4i){0, 0, 0, 0} : acc[gi][s], 0, 0, 0);
                     }
-                    fetch_at(j, g_off + (unsigned)j * 4u * DBF_TILE_BYTES, g_ct + 4 * j, g_ok & (int)(g_ct + 4 * j < cend));
+                    fetch_at(j, g_off + (unsigned)(j * CT_STEP) * DBF_TILE_BYTES, g_ct + CT_STEP * j,
+                             g_ok & (int)(g_ct + CT_STEP * j < cend));
                 }
 #pragma unroll
                 for (int gi = 0; gi < NCG; ++gi) xp[gi] += PF * 4 * DBF_TILE_COLS;
@@ -685,14 +698,16 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             // (it considers them dead from here on): wait, with the slots as operands so that
             // they stay allocated up to this point.  Nothing real is in flight any more, so
             // the wait is short.
-            if (rtl + 1 == it.nrt) retire_ring();
+            if (rtl + RT_STEP >= it.nrt) retire_ring();
             if (!last_chunk) continue;  // (only with nrt == 1) keep accumulating over chunks
 
             // ---- combine the four wavefronts (integer adds: exact, order independent) -----
             // acc[gi][s][i] of lane (g, c) is row 16*s + 4*g + i, column 16*gi + c.  The two
             // reduction buffers alternate, so one barrier per row tile is enough: a buffer is
             // cleared by its readers one barrier before anybody adds to it again.
-            int* rb = red + (tile_no & 1) * RB_STRIDE * ncols;
+            // (ROWS: nothing to combine -- every wavefront has a row tile's whole sums -- but the buffers bring them
+            // into the layout of the epilogue: one per wavefront, and a second barrier before they are reused.)
+            int* rb = red + (ROWS ? w : (tile_no & 1)) * RB_STRIDE * ncols;
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi) {
                 const int col = 16 * gi + c;
@@ -710,40 +725,45 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             }
             ++tile_no;
             __syncthreads();
-            const int row = it.row0 + rtl * DBF_TILE_ROWS + rho;
-            const float rscale = half_bits_to_float(misc->rscale[rtl * DBF_TILE_ROWS + rho]);
-            for (int bi = tid >> 7; bi < batch; bi += 2) {
-                int* ph = &rb[(2 * bi) * RB_STRIDE + rho];  // column-major: [operand column][row of the tile]
-                int vh = ph[0], vl = ph[RB_STRIDE];
-                ph[0] = 0;
-                ph[RB_STRIDE] = 0;
-                if (e_s < 7) {
-                    vh >>= e_s;
-                    vl >>= e_s;
-                } else {
-                    vh = -(vh >> 7);
-                    vl = -(vl >> 7);
-                }
-                // (sigma covers the columns this workgroup quantised: its own piece, or, in the one-pass
-                // case, the whole row -- then only the first piece subtracts it)
-                const int sig = (one_pass && ct_first != 0) ? 0 : misc->sigma[bi];
-                const int total = 2 * (vh * 256 + vl) - sig;
-                if (n_pieces > 1) {  // a column piece: add the exact integer sum; the last piece to arrive finishes the row
-                    __hip_atomic_fetch_add(piece_acc() + (size_t)bi * piece_acc_stride() + rho, total, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                    continue;
-                }
-                const float val = (float)total * misc->scale[bi] * rscale;
-                if (stage_a) {
-                    // (a workgroup that gave up its wait has read an unfinished t: its outputs say so)
-                    if (row < it.rows) y[(size_t)bi * it.rows + row] = misc->gave_up ? HALF_QNAN : float_to_half_bits(val);
-                } else {
-                    // agent-scope store: written through to memory, where the A-stage
-                    // workgroups of other compute dies read it (padded rows have scale 0)
-                    __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + (size_t)bi * it.t_stride + row,
-                                       __builtin_bit_cast(unsigned, val), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int r4 = 0; r4 < RT_STEP && rtl + r4 < it.nrt; ++r4) {  // the row tiles just finished
+                const int rte = rtl + r4;
+                if (ROWS) rb = red + r4 * RB_STRIDE * ncols;
+                const int row = it.row0 + rte * DBF_TILE_ROWS + rho;
+                const float rscale = half_bits_to_float(misc->rscale[rte * DBF_TILE_ROWS + rho]);
+                for (int bi = tid >> 7; bi < batch; bi += 2) {
+                    int* ph = &rb[(2 * bi) * RB_STRIDE + rho];  // column-major: [operand column][row of the tile]
+                    int vh = ph[0], vl = ph[RB_STRIDE];
+                    ph[0] = 0;
+                    ph[RB_STRIDE] = 0;
+                    if (e_s < 7) {
+                        vh >>= e_s;
+                        vl >>= e_s;
+                    } else {
+                        vh = -(vh >> 7);
+                        vl = -(vl >> 7);
+                    }
+                    // (sigma covers the columns this workgroup quantised: its own piece, or, in the one-pass
+                    // case, the whole row -- then only the first piece subtracts it)
+                    const int sig = (one_pass && ct_first != 0) ? 0 : misc->sigma[bi];
+                    const int total = 2 * (vh * 256 + vl) - sig;
+                    if (n_pieces > 1) {  // a column piece: add the exact integer sum; the last piece to arrive finishes the row
+                        __hip_atomic_fetch_add(piece_acc() + (size_t)bi * piece_acc_stride() + rho, total, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                        continue;
+                    }
+                    const float val = (float)total * misc->scale[bi] * rscale;
+                    if (stage_a) {
+                        // (a workgroup that gave up its wait has read an unfinished t: its outputs say so)
+                        if (row < it.rows) y[(size_t)bi * it.rows + row] = misc->gave_up ? HALF_QNAN : float_to_half_bits(val);
+                    } else {
+                        // agent-scope store: written through to memory, where the A-stage
+                        // workgroups of other compute dies read it (padded rows have scale 0)
+                        __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + (size_t)bi * it.t_stride + row,
+                                           __builtin_bit_cast(unsigned, val), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
+            if (ROWS) __syncthreads();  // the buffers are clear before the next row tiles' sums arrive
         }
         if (last_chunk) {
             if (n_pieces > 1) {
@@ -785,7 +805,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
         __syncthreads();  // every wavefront is done reading this chunk's operand
         c0 = cend;
         cend = min(ct_end, c0 + ch_tiles);
-        steps = (((cend - c0 + 3) >> 2) + PF - 1) / PF * PF;
+        steps = steps_of(cend - c0);
         p_rt = 0;
         p_i = 0;
 #pragma unroll
@@ -871,8 +891,8 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
 
 size_t mfma_smem_bytes(int batch, int ch_tiles, int shared_q) {
     const int ncols = 2 * batch;
-    const size_t xq = shared_q == 2 ? 0 : ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
-    return sizeof(Misc) + xq + 2 * (size_t)RB_STRIDE * ncols * sizeof(int);
+    const size_t xq = shared_q >= 2 ? 0 : ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
+    return sizeof(Misc) + xq + (shared_q == 3 ? 4 : 2) * (size_t)RB_STRIDE * ncols * sizeof(int);
 }
 
 }  // namespace
@@ -886,7 +906,7 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q) {
     // (52 KiB each, of which the reduction buffers take 1 KiB per operand row) if that lets a whole row stay
     // in LDS, so that an item can take several row tiles.
     int budget = batch > 8 ? 32768 : 28672;
-    if (shared_q == 2) {  // no operand in LDS: the whole row is one "chunk"
+    if (shared_q >= 2) {  // no operand in LDS: the whole row is one "chunk"
         const int all = (dbf_col_tiles(max_cols) + 3) & ~3;
         return all < 4 ? 4 : all;
     }
@@ -920,6 +940,25 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned lon
     uint16_t* y = static_cast<uint16_t*>(y_base);
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols, shared_q);
     const size_t smem = mfma_smem_bytes(batch, ch_tiles, shared_q);
+    if (shared_q == 3) {
+        // (more than 64 KiB of LDS at the largest batches: the limit has to be raised per kernel, once)
+        static const hipError_t raised = [] {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<1, false, 3, false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<2, false, 3, false>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            return e;
+        }();
+        if (raised != hipSuccess) return raised;
+        if (batch <= 8)
+            hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 3, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                               n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
+        else
+            hipLaunchKernelGGL((dbf_items_mfma_kernel<2, false, 3, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
+                               n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
+        return hipGetLastError();
+    }
     // column pieces (small batches only)
     if (shared_q == 2 && batch <= 8)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 2, false>), dim3(n_items), dim3(256), smem, stream, items, sync,

@@ -243,7 +243,7 @@ def test_tuning_hooks_have_defaults_ranges_and_a_reset():
     assert len(defaults) == 12
     for knob, val in defaults.items():
         assert B.dbf_tuning_get(knob) == val
-    for knob, bad in ((B.TUNE_COL_PIECES, -2), (B.TUNE_COL_PIECES, 65), (B.TUNE_STACK_SPAN_B, 17), (B.TUNE_SHARED_Q, 3),
+    for knob, bad in ((B.TUNE_COL_PIECES, -2), (B.TUNE_COL_PIECES, 65), (B.TUNE_STACK_SPAN_B, 17), (B.TUNE_SHARED_Q, 4),
                       (B.TUNE_SHARED_MIN_BATCH, 0), (B.TUNE_SHARED_LDS_KB, 65), (B.TUNE_WAIT_LIMIT_US, -1),
                       (B.TUNE_PIECE_MIN_TILES, 0), (B.TUNE_LONG_ROWS, 2), (12, 0), (-1, 0)):
         assert lib.dbf_tuning_set(knob, bad) == B.DBF_EINVAL

@@ -468,12 +468,13 @@ def test_groups_of_layers_sharing_one_input(batch):
 # ---- batches of 2 and more: input quantised once per call ---------------------------------------
 
 
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 3])
 @pytest.mark.parametrize("shape,batch", [((700, 260, 390), 2), ((700, 260, 390), 7), ((1000, 50, 130), 3),
                                          ((3000, 200, 1500), 16), ((101, 77, 33), 9), ((4096, 512, 700), 4)])
 def test_shared_quantised_input_equals_the_items_own_bit_for_bit(mode, shape, batch):
     """DBF_GEMV_AUTO at batch >= 2 quantises each stage input once per call and lets the items copy it into LDS
-    (mode 1, here also with rows that need several LDS chunks) or read it from memory tile by tile (mode 2).
+    (mode 1, here also with rows that need several LDS chunks) or read it from memory tile by tile (mode 2; mode 3:
+    a row tile per wavefront -- here, with one row tile per work item, three of the four wavefronts idle).
     The quantiser uses the arithmetic of the items' own prologue and the integer sums are exact, so the result
     must equal, bit for bit, the kind in which every item quantises for itself (checked against the oracle
     here too).  Shapes with columns that are no multiple of 8 take the scalar input path."""
@@ -500,6 +501,44 @@ def test_shared_quantised_input_equals_the_items_own_bit_for_bit(mode, shape, ba
         assert np.array_equal(again, own), what + " (second call)"
     finally:
         layer.close()
+
+
+@pytest.mark.parametrize("span", [4, 5, 16])
+@pytest.mark.parametrize("batch", [2, 7, 16])
+def test_a_row_tile_per_wavefront_equals_per_layer_calls(batch, span):
+    """Work items of `span` row tiles whose wavefronts take a row tile each (groups of four; the last group of an
+    item, and of a layer, may be short) and read the quantised input from memory: bit for bit the per-layer
+    two-launch result, on layers with 1 to 17 row tiles per stage and ragged columns."""
+    shapes = [(520, 1030, 2100), (1000, 130, 77), (4100, 1300, 600), (96, 2176, 640)]
+    Ls = [I.make_layer(n_in, n_out, k, I.seed_for(1, 190 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    plain = [G.pack(L) for L in Ls]
+    B.dbf_tuning_set(B.TUNE_STACK_SPAN_B, span)
+    B.dbf_tuning_set(B.TUNE_STACK_SPAN_A, span)
+    B.dbf_tuning_set(B.TUNE_SHARED_Q, 3)
+    B.dbf_tuning_set(B.TUNE_COL_PIECES, 0)
+    layers = [G.pack(L) for L in Ls]
+    stack = B.dbf_stack_create(layers)
+    try:
+        G.say("start rows-per-wavefront stack batch=%d span=%d" % (batch, span))
+        Xs = [I.make_activations(batch, L.n_in, 400 + i) for i, L in enumerate(Ls)]
+        x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+        for rep in range(2):   # (the second call finds the reduction buffers and counters as the first left them)
+            y_all = torch.full((sum(batch * L.n_out for L in Ls),), float("nan"), dtype=torch.float16, device="cuda")
+            B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle(), B.GEMV_AUTO)
+            torch.cuda.synchronize()
+            got = G.dev_to_f64(y_all)
+            at = 0
+            for L, layer, X in zip(Ls, plain, Xs):
+                B.dbf_tuning_reset()
+                want = G.run_gemv(layer, X, B.GEMV_MFMA_SPLIT)
+                B.dbf_tuning_set(B.TUNE_SHARED_Q, 3)
+                n = batch * L.n_out
+                assert np.array_equal(got[at:at + n].reshape(batch, L.n_out), want), (L.n_in, L.n_out, L.k, rep)
+                at += n
+    finally:
+        stack.close()
+        for layer in layers + plain:
+            layer.close()
 
 
 @pytest.mark.parametrize("batch", [4, 16])
