@@ -255,9 +255,9 @@ def main():
             dom, dom_ms, dom_bytes = ("dbf_items_mfma_kernel<%d, false, 0, %s> (B and A stages fused)"
                                       % (ncg, "true" if batch == 1 else "true|false")), ms_per_step, bytes_layer * R
         elif msB_avg >= msA_avg:  # batches of 2 and more: input quantiser + items, per stage
-            dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2, false>)" % ncg, msB_avg, bytes_b * R
+            dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2|3, false>)" % ncg, msB_avg, bytes_b * R
         else:
-            dom, dom_ms, dom_bytes = "A-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2, false>)" % ncg, msA_avg, bytes_a * R
+            dom, dom_ms, dom_bytes = "A-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2|3, false>)" % ncg, msA_avg, bytes_a * R
     elif msB_avg >= msA_avg:
         dom, dom_ms, dom_bytes = "B-stage launch", msB_avg, bytes_b * R
     else:
@@ -416,7 +416,8 @@ def traffic_from(args):
     kw = sorted((d, n, v) for (d, n), v in write.items() if "dbf_items_mfma_kernel" in n)
     if not kf or not kw:
         raise SystemExit("no decode kernel dispatches in the counter runs")
-    name = kf[0][1].split("(")[0]
+    import re
+    name = re.search(r"dbf_items_mfma_kernel<[^>]*>", kf[0][1]).group(0)
     fb = sum(v for _, _, v in kf) / len(kf) * fetch_unit
     wb = sum(v for _, _, v in kw) / len(kw) * write_unit
     rec = {"kernel": name, "workload": args.workload, "layers_per_step": args.layers if args.workload == "config2" else 224,
