@@ -194,7 +194,8 @@ struct Ctx {
     Misc* misc;
     signed char* xq;
     const uint16_t* x;  // B stage input rows (fp16), unused in the A stage
-    int chs;            // bytes per operand row in LDS
+    int chs;            // bytes from the high plane of a batch row to its low plane (LDS: the operand row's length)
+    int tstride;        // TILED destinations only: bytes from one column tile of a plane to the next
     int tid, lane, w;
     int batch;
     bool fast;          // 16-byte vector loads are possible
@@ -204,7 +205,9 @@ struct Ctx {
 // The decode case in one pass: the row was loaded once into registers (by the kernel's
 // prologue, see there); reduce max|u| and quantise from the registers.
 // Contains one barrier; ends with the operand in LDS (not yet synchronised).
-template <bool STAGE_A>
+// TILED: the destination is not an LDS operand row but the per-call buffer of a stage (DbfStage::q_in), in which
+// the 64 bytes a plane has for one column tile are followed by the next plane's.
+template <bool STAGE_A, bool TILED = false>
 __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const v4u (&r1)[UNR]) {
     InputVec<STAGE_A> iv[UNR];
     float mx = 0.f;
@@ -227,7 +230,8 @@ __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const 
 #pragma unroll
     for (int j = 0; j < UNR; ++j) {
         const int v = 256 * j + c.tid;
-        if (v < c.nvec) local += iv[j].quantise_to(c.xq + v * 8, c.xq + c.chs + v * 8, inv);
+        const int at = TILED ? (v >> 3) * c.tstride + (v & 7) * 8 : v * 8;
+        if (v < c.nvec) local += iv[j].quantise_to(c.xq + at, c.xq + c.chs + at, inv);
     }
     local = dbf_wave_sum(local);
     if (c.lane == 0) atomicAdd(&c.misc->sigma[0], local);
@@ -269,7 +273,7 @@ __device__ inline void input_scales(const DbfItem& it, const Ctx& c) {
 }
 
 // General case, second pass: quantise columns [64*c0, 64*cend) of every batch row into LDS.
-template <bool STAGE_A, int W>
+template <bool STAGE_A, int W, bool TILED = false>
 __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int c0, int cend) {
     for (int bi = 0; bi < c.batch; ++bi) {
         const float inv = c.misc->inv[bi];
@@ -288,7 +292,8 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 #pragma unroll
                 for (int j = 0; j < W; ++j) {
                     const int v = base + 256 * j + c.tid;
-                    if (v < v1) local += iv[j].quantise_to(hi_row + (v - v0) * 8, lo_row + (v - v0) * 8, inv);
+                    const int at = TILED ? ((v - v0) >> 3) * c.tstride + ((v - v0) & 7) * 8 : (v - v0) * 8;
+                    if (v < v1) local += iv[j].quantise_to(hi_row + at, lo_row + at, inv);
                 }
             }
         } else {
@@ -301,8 +306,10 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
                 }
                 const int lo = ((q + 128) & 255) - 128;
                 const int hi = (q - lo) >> 8;
-                hi_row[l - c0 * 64] = (signed char)hi;
-                lo_row[l - c0 * 64] = (signed char)lo;
+                const int rel = l - c0 * 64;
+                const int at = TILED ? (rel >> 6) * c.tstride + (rel & 63) : rel;
+                hi_row[at] = (signed char)hi;
+                lo_row[at] = (signed char)lo;
                 local += q;
             }
         }
@@ -511,7 +518,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 
     // ---- prologue ------------------------------------------------------------------------------
     Ctx cx;
-    cx.misc = misc;  cx.xq = xq;  cx.x = x;  cx.chs = chs;
+    cx.misc = misc;  cx.xq = xq;  cx.x = x;  cx.chs = chs;  cx.tstride = 0;
     cx.tid = tid;  cx.lane = lane;  cx.w = w;  cx.batch = batch;
     cx.nvec = it.n_ct * 8;
     cx.nvec_x = it.cols >> 3;
@@ -823,107 +830,62 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     }
 }
 
-// The input of one stage of every layer of a launch, quantised once: a wavefront per (layer, batch row) reads the
-// row (x times b, or the fp32 middle activations), finds max|u| and writes q = rint(u * 32512 / max|u|) as two int8
-// planes, with the scale and the sum of the q in front (DbfStage::q_in; per column tile the 64 bytes of plane 0,
-// of plane 1, ...: planes 2 bi and 2 bi + 1 are this row's).  The arithmetic is that of the items' own prologue
-// (the same functions; the maximum and the integer sum do not depend on the order), so a launch that takes its
-// input from here gives the same bits.  A wavefront alone, no barriers: rows of up to 4096 values stay in its
-// registers (16 loads of 16 bytes per lane in flight at once), longer ones are read twice, 4096 values at a time.
+// The input of one stage of every layer of a launch, quantised once: block (layer, batch row) reads the row
+// (x times b, or the fp32 middle activations), finds max|u| and writes q = rint(u * 32512 / max|u|) as two
+// int8 planes, with the scale and the sum of the q in front (DbfStage::q_in).  The arithmetic is that of the
+// items' own prologue (the same functions), so a launch that takes its input from here gives the same bits.
 template <bool STAGE_A>
-__global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage* __restrict__ stages, int n_layers,
+__global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage* __restrict__ stages,
                                                                  const uint16_t* __restrict__ x_base, int batch) {
-    constexpr int RW = 8;  // vector items (8 values each) per lane and round
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= n_layers * batch) return;
-    const DbfStage st = stages[r / batch];
-    const int bi = r % batch;
-    DbfItem it;  // (what the scalar loader reads)
+    __shared__ Misc misc;
+    const DbfStage st = stages[blockIdx.x];
+    const int bi = blockIdx.y;
+    DbfItem it;
     it.t = st.t + (size_t)bi * st.t_stride;
     it.t_stride = st.t_stride;
     it.in_scale = st.in_scale;
     it.cols = st.cols;
-    const uint16_t* x = x_base + st.x_off * batch + (size_t)bi * st.cols;
-    signed char* q = reinterpret_cast<signed char*>(st.q_in + DBF_QIN_HEADER + (size_t)(2 * bi) * DBF_TILE_COLS);
-    const int tstride = 2 * batch * DBF_TILE_COLS;  // bytes from one column tile of a plane to the next
-    const int nvec = st.n_ct * 8, nvec_x = st.cols >> 3;
-    const bool fast = STAGE_A || ((st.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
-    // vector item v of the row (plain loads: the middle activations were written by an earlier launch)
-    auto load = [&](InputVec<STAGE_A>& iv, int v) {
-        const int vc = min(v, nvec - 1);
-        if (STAGE_A) {
-            iv.r0 = *reinterpret_cast<const v4u*>(it.t + 8 * (size_t)vc);
-            iv.r1 = *reinterpret_cast<const v4u*>(it.t + 8 * (size_t)vc + 4);
-        } else {
-            iv.r0 = vc < nvec_x ? *reinterpret_cast<const v4u*>(x + 8 * (size_t)vc) : (v4u){0, 0, 0, 0};  // beyond x: zero
-            iv.r1 = *reinterpret_cast<const v4u*>(it.in_scale + 8 * (size_t)vc);
-        }
-    };
-    float mx = 0.f;
-    int sum = 0;
-    float inv = 0.f;
-    if (fast && nvec <= 64 * RW) {
-        InputVec<STAGE_A> iv[RW];
+    it.n_ct = st.n_ct;
+    const uint16_t* x = x_base + st.x_off * batch;
+    // destination: per column tile the 2 * batch planes' 64 bytes one after the other; this row's are 2 bi, 2 bi + 1
+    Ctx cx;
+    cx.misc = &misc;
+    cx.xq = reinterpret_cast<signed char*>(st.q_in + DBF_QIN_HEADER + (size_t)(2 * bi) * DBF_TILE_COLS);
+    cx.x = x + (size_t)bi * st.cols;
+    cx.chs = DBF_TILE_COLS;
+    cx.tstride = 2 * batch * DBF_TILE_COLS;
+    cx.tid = threadIdx.x;  cx.lane = threadIdx.x & 63;  cx.w = threadIdx.x >> 6;
+    cx.batch = 1;   // this block's row is "batch row 0" of the helpers
+    cx.nvec = st.n_ct * 8;
+    cx.nvec_x = st.cols >> 3;
+    cx.fast = STAGE_A || ((st.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
+    if (threadIdx.x == 0) misc.sigma[0] = 0;
+    __syncthreads();
+    if (cx.fast && cx.nvec <= 256 * UNR) {
+        // the row fits the registers of the workgroup: read once (plain loads: the middle activations were
+        // written by an earlier launch), reduce, quantise from the registers
+        v4u r0[UNR], r1[UNR];
 #pragma unroll
-        for (int j = 0; j < RW; ++j) load(iv[j], 64 * j + lane);
-#pragma unroll
-        for (int j = 0; j < RW; ++j)
-            if (64 * j + lane < nvec) mx = fmaxf(mx, iv[j].absmax());
-        mx = dbf_wave_max(mx);
-        inv = mx > 0.f ? QMAX / mx : 0.f;
-#pragma unroll
-        for (int j = 0; j < RW; ++j) {
-            const int v = 64 * j + lane;
-            signed char* dst = q + (v >> 3) * tstride + (v & 7) * 8;
-            if (v < nvec) sum += iv[j].quantise_to(dst, dst + DBF_TILE_COLS, inv);
-        }
-    } else if (fast) {
-        for (int base = 0; base < nvec; base += 64 * RW) {
-            InputVec<STAGE_A> iv[RW];
-#pragma unroll
-            for (int j = 0; j < RW; ++j) load(iv[j], base + 64 * j + lane);
-#pragma unroll
-            for (int j = 0; j < RW; ++j)
-                if (base + 64 * j + lane < nvec) mx = fmaxf(mx, iv[j].absmax());
-        }
-        mx = dbf_wave_max(mx);
-        inv = mx > 0.f ? QMAX / mx : 0.f;
-        for (int base = 0; base < nvec; base += 64 * RW) {
-            InputVec<STAGE_A> iv[RW];
-#pragma unroll
-            for (int j = 0; j < RW; ++j) load(iv[j], base + 64 * j + lane);
-#pragma unroll
-            for (int j = 0; j < RW; ++j) {
-                const int v = base + 64 * j + lane;
-                signed char* dst = q + (v >> 3) * tstride + (v & 7) * 8;
-                if (v < nvec) sum += iv[j].quantise_to(dst, dst + DBF_TILE_COLS, inv);
+        for (int j = 0; j < UNR; ++j) {
+            const int v = min(256 * j + cx.tid, cx.nvec - 1);
+            if (STAGE_A) {
+                r0[j] = *reinterpret_cast<const v4u*>(it.t + 8 * (size_t)v);
+                r1[j] = *reinterpret_cast<const v4u*>(it.t + 8 * (size_t)v + 4);
+            } else {
+                const int vx = max(min(v, cx.nvec_x - 1), 0);
+                r0[j] = *reinterpret_cast<const v4u*>(cx.x + 8 * (size_t)vx);
+                r1[j] = *reinterpret_cast<const v4u*>(it.in_scale + 8 * (size_t)v);
             }
         }
+        input_one_pass<STAGE_A, true>(cx, r0, r1);
     } else {
-        // (x cannot be read in 16-byte pieces: value by value, the padding columns as zeros)
-        for (int l = lane; l < st.cols; l += 64) mx = fmaxf(mx, fabsf(load_u_scalar<STAGE_A>(it, x, 0, l)));
-        mx = dbf_wave_max(mx);
-        inv = mx > 0.f ? QMAX / mx : 0.f;
-        for (int l = lane; l < st.n_ct * DBF_TILE_COLS; l += 64) {
-            int qv = 0;
-            if (l < st.cols) {
-                float f = rintf(load_u_scalar<STAGE_A>(it, x, 0, l) * inv);
-                f = fminf(fmaxf(f, -QMAX), QMAX);
-                qv = (int)f;
-            }
-            const int lo = ((qv + 128) & 255) - 128;
-            const int hi = (qv - lo) >> 8;
-            signed char* dst = q + (l >> 6) * tstride + (l & 63);
-            dst[0] = (signed char)hi;
-            dst[DBF_TILE_COLS] = (signed char)lo;
-            sum += qv;
-        }
+        input_scales<STAGE_A, WIDE>(it, cx);
+        input_quantise_chunk<STAGE_A, WIDE, true>(it, cx, 0, st.n_ct);
     }
-    sum = dbf_wave_sum(sum);
-    if (lane == 0) {
-        reinterpret_cast<float*>(st.q_in)[bi] = mx / QMAX;
-        reinterpret_cast<int*>(st.q_in + 64)[bi] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        reinterpret_cast<float*>(st.q_in)[bi] = misc.scale[0];
+        reinterpret_cast<int*>(st.q_in + 64)[bi] = misc.sigma[0];
     }
 }
 
@@ -963,11 +925,10 @@ hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, in
                                       int batch, hipStream_t stream) {
     if (n_layers <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
-    const dim3 grid((unsigned)(((long long)n_layers * batch + 3) / 4));  // a wavefront per row
     if (stage_a)
-        hipLaunchKernelGGL(dbf_quantise_inputs_kernel<true>, grid, dim3(256), 0, stream, d_stages, n_layers, x, batch);
+        hipLaunchKernelGGL(dbf_quantise_inputs_kernel<true>, dim3(n_layers, batch), dim3(256), 0, stream, d_stages, x, batch);
     else
-        hipLaunchKernelGGL(dbf_quantise_inputs_kernel<false>, grid, dim3(256), 0, stream, d_stages, n_layers, x, batch);
+        hipLaunchKernelGGL(dbf_quantise_inputs_kernel<false>, dim3(n_layers, batch), dim3(256), 0, stream, d_stages, x, batch);
     return hipGetLastError();
 }
 
