@@ -172,7 +172,14 @@ int shared_span(const DbfStage& st, long long stage_tiles) {
     if (span > DBF_MAX_SPAN) span = DBF_MAX_SPAN;
     const long long per_layer = (st.n_rt + span - 1) / span;  // items of equal length ...
     span = (st.n_rt + per_layer - 1) / per_layer;
-    if (span >= 4) span = (span + 3) & ~3ll;                  // ... in whole groups of four row tiles, one per wavefront
+    // ... in whole groups of four row tiles, one per wavefront, unless that leaves the stage with too few items to
+    // fill the chip (8192 x 28672 streams of 19 layers at batch 4: 4.13 TB/s with 475 items of two row tiles, whose
+    // wavefronts share the column tiles, against 3.74 with 247 items of four)
+    if (span >= 2) {
+        const long long up = (span + 3) & ~3ll, down = span & ~3ll;
+        if (stage_tiles / (up * st.n_ct) >= 256) span = up;  // (at least one item per compute unit)
+        else if (down >= 4) span = down;
+    }
     return (int)(span > DBF_MAX_SPAN ? DBF_MAX_SPAN : span);
 }
 
