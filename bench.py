@@ -590,7 +590,7 @@ def prune_bench(B, I, torch, np):
     res = {}
     for cfg in I.CONFIG4:
         n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
-        k2 = I.middle_size(1.5, n_out, n_in)
+        k2 = I.CONFIG4_PRUNED_K[(n_out, n_in)]
         L = I.make_layer(n_in, n_out, k, seed=I.seed_for(4, n_in))
         layer = B.dbf_pack_bits(n_in, n_out, k, L.A_bits, L.B_bits, L.a, L.m, L.b)
         keep = np.sort(np.random.default_rng(I.seed_for(4, 77)).choice(k, size=k2, replace=False)).astype(np.int32)

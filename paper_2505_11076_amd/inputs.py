@@ -122,20 +122,29 @@ def make_svid_matrix(rows: int, cols: int, seed: int) -> np.ndarray:
 
 # Second workload: the layer sizes of the paper's matrix-vector timing table (Table 4: Llama-3
 # shapes, printed as rows x columns of W = n_out x n_in) plus the grouped-query k/v projection
-# 4096 -> 1024, each at the table's four sizes in bits per weight.  The middle size follows the
-# storage formula k = floor(bits * n*m / (n+m)) (section 3, "Middle dimension size").
+# 4096 -> 1024, each at the table's four sizes in bits per weight.  The middle sizes are written out
+# (they follow the storage formula of section 3, "Middle dimension size"; a CPU test checks them
+# against the oracle's statement of it -- this module holds none of the method's arithmetic).
 TABLE4_SHAPES = [                                                # (n_out, n_in)
     (4096, 4096), (4096, 14336), (8192, 8192), (8192, 28672), (1024, 4096),
 ]
 TABLE4_BITS = [1.0, 1.5, 2.0, 2.3]
+TABLE4_K = {                                                     # (n_out, n_in) -> k at the four sizes
+    (4096, 4096): [2048, 3072, 4096, 4710],
+    (4096, 14336): [3185, 4778, 6371, 7327],
+    (8192, 8192): [4096, 6144, 8192, 9420],
+    (8192, 28672): [6371, 9557, 12743, 14654],
+    (1024, 4096): [819, 1228, 1638, 1884],
+}
+CONFIG4_PRUNED_K = {(4096, 4096): 3072, (4096, 11008): 4477}     # (n_out, n_in) -> k at 1.5 bits per weight
 
 
-def middle_size(bits: float, n_out: int, n_in: int) -> int:
-    return int(np.floor(bits * n_out * n_in / (n_out + n_in)))
+def table4_k(bits: float, n_out: int, n_in: int) -> int:
+    return TABLE4_K[(n_out, n_in)][TABLE4_BITS.index(bits)]
 
 
 def table4_configs() -> list[dict]:
-    return [dict(n_in=n_in, n_out=n_out, k=middle_size(bits, n_out, n_in), bits=bits)
+    return [dict(n_in=n_in, n_out=n_out, k=table4_k(bits, n_out, n_in), bits=bits)
             for (n_out, n_in) in TABLE4_SHAPES for bits in TABLE4_BITS]
 
 

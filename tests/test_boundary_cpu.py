@@ -217,6 +217,11 @@ def test_second_workload_middle_sizes_follow_the_storage_formula():
         n, m, k = cfg["n_out"], cfg["n_in"], cfg["k"]
         assert k == O.middle_dim_for_bits(cfg["bits"], n, m)
         assert O.bits_per_weight(n, m, k) <= cfg["bits"] < O.bits_per_weight(n, m, k + 1)
+    # (the sizes the pruning benchmark cuts the prefill shapes down to, and those of the 224-layer stack: 1.5 bits)
+    for (n, m), k in I.CONFIG4_PRUNED_K.items():
+        assert k == O.middle_dim_for_bits(1.5, n, m)
+    assert {(c["n_out"], c["n_in"], c["k"]) for c in I.llama2_7b_stack_shapes(1)} == {
+        (n, m, O.middle_dim_for_bits(1.5, n, m)) for (n, m) in ((4096, 4096), (11008, 4096), (4096, 11008))}
 
 
 def test_bench_refuses_more_than_one_gpu():

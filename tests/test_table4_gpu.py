@@ -30,7 +30,7 @@ CASES.append((4096, 14336, 1.5, 4))
 
 @pytest.mark.parametrize("n_out,n_in,bits,batch", CASES)
 def test_table4_layer(n_out, n_in, bits, batch):
-    k = I.middle_size(bits, n_out, n_in)
+    k = I.table4_k(bits, n_out, n_in)
     what = "table4 n_out=%d n_in=%d bits=%.1f k=%d batch=%d" % (n_out, n_in, bits, k, batch)
     G.say("start " + what)
     seed = I.seed_for(6, n_out + n_in + int(10 * bits))
