@@ -64,6 +64,13 @@ def check(y_gpu: np.ndarray, y_ref: np.ndarray, what: str, tol: float = TOL) -> 
     delta = np.abs(y_gpu - y_ref)
     y_adj = y_ref + np.sign(y_gpu - y_ref) * np.maximum(delta - 2.0 ** -25, 0.0)
     err = O.gated_relative_error(y_adj, y_ref)
-    say("%s: gated rel err %.3e (tol %.1e)" % (what, err, tol))
+    # (also the plain relative error over the outputs that are at least as large as their row's rms, where the gate
+    #  and the plain definition coincide: reported, and bounded by the same assertion)
+    ref2 = y_ref if y_ref.ndim > 1 else y_ref[None, :]
+    adj2 = y_adj if y_adj.ndim > 1 else y_adj[None, :]
+    big = np.abs(ref2) >= np.sqrt(np.mean(ref2 * ref2, axis=1, keepdims=True))
+    big &= ref2 != 0.0
+    plain = float(np.max(np.abs(adj2[big] - ref2[big]) / np.abs(ref2[big]))) if big.any() else 0.0
+    say("%s: gated rel err %.3e, plain rel err over |y| >= rms %.3e (tol %.1e)" % (what, err, plain, tol))
     assert err <= tol, "%s: error %.3e > %.1e" % (what, err, tol)
     return err
