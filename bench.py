@@ -345,7 +345,7 @@ def main():
         if batch == 1:
             # the same stream at the other batch sizes of the workload (configuration 2: batch 4 and 16)
             by_batch = {"1": {"ms_per_step": round(ms_per_step, 5), "GBps": round(value, 2), "protocol": main_protocol}}
-            for b2 in (4, 16):
+            for b2 in (2, 4, 8, 16):
                 try:
                     by_batch[str(b2)] = stream_length_bench(B, I, torch, np, layers, specs[0], R, b2, kind, stream, proto)
                 except Exception as exc:  # reported, never hidden
