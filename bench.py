@@ -364,6 +364,14 @@ def main():
         except Exception as exc:  # reported, never hidden
             out["config5_stack"] = {"error": repr(exc)}
 
+    # ---- the MLP shapes of configuration 3 (gate / up and down projection at ~1 and ~2 bits per weight) ----------
+    if args.workload == "config2" and not args.no_table4 and not args.stream_only:
+        try:
+            cfgs = [dict(c, bits=round(c["k"] * (c["n_in"] + c["n_out"]) / (c["n_in"] * c["n_out"]), 2)) for c in I.CONFIG3]
+            out["config3_mlp"] = table4_bench(B, I, torch, np, batch, kind, stream, proto, cfgs=cfgs)
+        except Exception as exc:  # reported, never hidden
+            out["config3_mlp"] = {"error": repr(exc)}
+
     # ---- second workload: the layer sizes of the paper's matrix-vector timing table, 1 and 2 bits per weight --
     if args.workload == "config2" and not args.no_table4 and not args.stream_only:
         try:
@@ -548,12 +556,12 @@ PAPER_TABLE4_US = {
 }
 
 
-def table4_bench(B, I, torch, np, batch, kind, stream, proto, bits_only=None):
-    """Every (shape, bits per weight) of the second workload: the isolated call (cache warm) and a
-    stream of distinct copies of the layer (at least 512 MB of signs, at most 256 copies) in one
+def table4_bench(B, I, torch, np, batch, kind, stream, proto, bits_only=None, cfgs=None):
+    """Every (shape, bits per weight) of the second workload (or the shapes in `cfgs`): the isolated call (cache
+    warm) and a stream of distinct copies of the layer (at least 512 MB of signs, at most 256 copies) in one
     stack call per step."""
     rows = []
-    for ci, cfg in enumerate(I.table4_configs()):
+    for ci, cfg in enumerate(I.table4_configs() if cfgs is None else cfgs):
         if bits_only is not None and cfg["bits"] not in bits_only:
             continue
         n_in, n_out, k = cfg["n_in"], cfg["n_out"], cfg["k"]
