@@ -7,9 +7,13 @@
 // starts from the constant unit vector and runs `iters` rounds of
 //     u <- |Z| v / ||.||,   v <- |Z|^T u,   sigma <- ||v||,   v <- v / sigma;      a = sigma u,  m = v.
 //
-// Everything is bound by reading Z (fp32, rows x cols, row major): two passes per round (row dots,
-// column dots) and one for the signs.  A round is three launches: the normalisations are not passes of
-// their own.  The iterate is kept unnormalised (u_raw = |Z| v, v_raw = |Z|^T u_raw; the length of u
+// Everything is bound by reading Z (fp32, rows x cols, row major).  A round needs u = |Z| v before any of
+// v' = |Z|^T u -- but only row by row: the term of row i in v' needs u_i alone, and u_i needs row i alone.  So
+// ONE pass over Z does a whole round (dbf_svid_round_kernel): a workgroup of 16 wavefronts holds a batch of whole
+// rows in registers, forms their dots with v, and adds the rows, weighted by those dots, into its partial column
+// sums; a second, small launch sums the partial sums over the workgroups.  Rows too long for that (more than
+// 24576 columns) or not readable in 16-byte pieces, and matrices of fewer than 24 Mi entries (where it is slower),
+// take two passes per round (row dots, column dots) and a reduce launch.  In both forms the normalisations are not passes of their own.  The iterate is kept unnormalised (u_raw = |Z| v, v_raw = |Z|^T u_raw; the length of u
 // cancels in v / ||v||), the column reduction leaves the squared length of v_raw as one partial sum per
 // workgroup, and the next row pass scales by 1 / ||v_raw|| on the fly; the last kernel forms
 // m = v_raw / ||v_raw|| and a = sigma u = u_raw ||v_raw|| / ||u_raw||^2.  All reductions have a fixed
@@ -20,6 +24,7 @@
 //   norms        partial sums of squares per 64 columns (v) or per thread stride (u), combined in a fixed tree;
 //   signs        one workgroup per 128 x 64 tile, a thread per four bytes of the tile.
 #include "dbf_kernels.h"
+#include "dbf_wave.h"
 
 namespace {
 
@@ -27,6 +32,12 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int COL_CHUNK_ROWS = 64;   // rows per partial sum of the column pass
 constexpr int COL_BLOCK = 256;       // columns per workgroup of the column pass
+constexpr int ROUND_THREADS = 1024;  // workgroup of the one-pass round
+// Matrices below this many entries take the two-pass round: a workgroup of the one-pass round then holds too few
+// rows to keep its loads ahead of its barriers.  Measured, 8 rounds, two passes / one pass in ms: 4096 x 4096 0.254 /
+// 0.299, 2048 x 4096 0.183 / 0.221, 6144 x 4096 0.361 / 0.336, 11008 x 4096 0.587 / 0.452, 4096 x 11008 0.507 / 0.410,
+// 16384 x 4096 0.866 / 0.578, 8192 x 8192 0.933 / 0.551.
+constexpr size_t ROUND_MIN_ENTRIES = (size_t)24 << 20;
 
 __device__ inline float wave_sum_f(float v) {
 #pragma unroll
@@ -75,6 +86,111 @@ __global__ __launch_bounds__(256) void dbf_svid_row_dots_kernel(const float* __r
         inv = nrm > 0.f ? 1.0f / nrm : 0.f;
     }
     if (lane == 0) u[row] = s * inv;
+}
+
+// One round in one pass.  Workgroup = 1024 threads = 16 wavefronts, one per compute unit (512-thread workgroups,
+// two or three per compute unit, were slower); it takes `rows_per_wg` consecutive rows, RB at a time.  Thread t
+// holds, of every row of the batch, the CPL float4s at columns 4 t + 4096 k (k < CPL), so a wavefront's load of a
+// row segment is 1 KiB contiguous.  Per batch: the next batch's loads are issued first (register double buffer:
+// the barrier below puts all 16 wavefronts in step, so nothing else hides the latency), then every wavefront
+// forms its part of the RB row dots (register-to-register reduction), leaves it in LDS, and after ONE barrier
+// (two LDS buffers alternate) every thread sums the 16 parts in wavefront order, scales by 1 / ||v_raw|| -> u_raw
+// of the RB rows (threads 0 .. RB-1 store them), and adds |z| u_raw of its columns into its CPL float4
+// accumulators.  At the end the accumulators are the workgroup's partial column sums: partial[workgroup][column].
+// FIRST: v = 1 / sqrt(cols) everywhere, v_raw is not read.  All sums have a fixed order.
+template <int CPL, bool FIRST>
+__global__ __launch_bounds__(ROUND_THREADS) void dbf_svid_round_kernel(const float* __restrict__ Z, int rows, int cols,
+                                                              const float* __restrict__ v,
+                                                              const float* __restrict__ ss_part, int n_ss,
+                                                              float* __restrict__ u, float* __restrict__ partial,
+                                                              int rows_per_wg) {
+    constexpr int RB = CPL == 1 ? 8 : CPL == 2 ? 4 : CPL <= 4 ? 2 : 1;  // rows per batch: about 32 registers per buffer
+    __shared__ float dots[2][ROUND_THREADS / 64][RB];
+    __shared__ float inv_s;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int row0 = blockIdx.x * rows_per_wg;
+    const int row_end = min(rows, row0 + rows_per_wg);
+    v4f vv[CPL], acc[CPL];
+    bool live[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        const int col = 4 * tid + 4 * ROUND_THREADS * k;
+        live[k] = col < cols;  // (cols is a multiple of 4)
+        vv[k] = (!FIRST && live[k]) ? *reinterpret_cast<const v4f*>(v + col) : (v4f){0.f, 0.f, 0.f, 0.f};
+        acc[k] = (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    if (w == 0) {
+        float inv;
+        if (FIRST) {
+            inv = 1.0f / sqrtf((float)cols);
+        } else {
+            const float nrm = sqrtf(wave_total(ss_part, n_ss, lane));
+            inv = nrm > 0.f ? 1.0f / nrm : 0.f;
+        }
+        if (lane == 0) inv_s = inv;
+    }
+    // (no branch around a load: rows beyond the workgroup's are read as its last row and get weight zero below,
+    //  columns beyond the matrix are read as the row's first and get v = 0 / are masked, so that all loads of a
+    //  batch are in flight together)
+    auto load_batch = [&](v4f (&z)[RB][CPL], int r0) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const int row = min(r0 + r, row_end - 1);
+#pragma unroll
+            for (int k = 0; k < CPL; ++k)
+                z[r][k] = *reinterpret_cast<const v4f*>(Z + (size_t)row * cols + (live[k] ? 4 * tid + 4 * ROUND_THREADS * k : 0));
+        }
+    };
+    auto abs4 = [](v4f a) { return (v4f){fabsf(a.x), fabsf(a.y), fabsf(a.z), fabsf(a.w)}; };
+    v4f za[RB][CPL], zb[RB][CPL];
+    load_batch(za, row0);
+    int buf = 0;
+    // (two batches per trip, so that the two register buffers keep their names)
+    auto process = [&](v4f (&z)[RB][CPL], int r0) {
+        float part[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            float sdot = 0.f;
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+                const v4f a = abs4(z[r][k]);
+                if (FIRST) sdot += live[k] ? (a.x + a.y) + (a.z + a.w) : 0.f;
+                else sdot += a.x * vv[k].x + a.y * vv[k].y + a.z * vv[k].z + a.w * vv[k].w;
+            }
+            part[r] = dbf_wave_sum_f(sdot);
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) dots[buf][w][r] = part[r];
+        }
+        __syncthreads();
+        const float inv = inv_s;
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            float tot = 0.f;
+#pragma unroll
+            for (int q = 0; q < ROUND_THREADS / 64; ++q) tot += dots[buf][q][r];
+            const float ur = r0 + r < row_end ? tot * inv : 0.f;
+            if (tid == r && r0 + r < row_end) u[r0 + r] = ur;
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) {
+                const v4f a = abs4(z[r][k]);
+                acc[k].x += a.x * ur;  acc[k].y += a.y * ur;  acc[k].z += a.z * ur;  acc[k].w += a.w * ur;  // (dead columns: never stored)
+            }
+        }
+        buf ^= 1;
+    };
+    for (int r0 = row0; r0 < row_end; r0 += 2 * RB) {
+        load_batch(zb, r0 + RB);       // (rows beyond the workgroup's read as zeros without touching memory)
+        process(za, r0);
+        if (r0 + RB < row_end) {
+            load_batch(za, r0 + 2 * RB);
+            process(zb, r0 + RB);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < CPL; ++k)
+        if (live[k]) *reinterpret_cast<v4f*>(partial + (size_t)blockIdx.x * cols + 4 * tid + 4 * ROUND_THREADS * k) = acc[k];
 }
 
 // partial[chunk][j] = sum over the chunk's rows i of |Z[i][j]| u[i]
@@ -191,12 +307,29 @@ __global__ __launch_bounds__(256) void dbf_svid_signs_kernel(const float* __rest
 }
 
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+// Rows per workgroup of the one-pass round: one workgroup per compute unit (256 in all), at least 8 rows each.
+inline int round_rows_per_wg(int rows) {
+    const int per = (rows + 255) / 256;
+    return per < 8 ? 8 : per;
+}
+template <int CPL>
+void launch_round(bool first, int n_wg, hipStream_t st, const float* Z, int rows, int cols, const float* v,
+                  const float* ss_part, int n_ss, float* u, float* partial, int rows_per_wg) {
+    if (first)
+        hipLaunchKernelGGL((dbf_svid_round_kernel<CPL, true>), dim3(n_wg), dim3(ROUND_THREADS), 0, st, Z, rows, cols, v, ss_part, n_ss,
+                           u, partial, rows_per_wg);
+    else
+        hipLaunchKernelGGL((dbf_svid_round_kernel<CPL, false>), dim3(n_wg), dim3(ROUND_THREADS), 0, st, Z, rows, cols, v, ss_part, n_ss,
+                           u, partial, rows_per_wg);
+}
 struct SvidWorkspace {
     size_t u, v, partial, scalars, total;
 };
 inline SvidWorkspace svid_workspace(int rows, int cols) {
     SvidWorkspace w;
-    const size_t chunks = ((size_t)rows + COL_CHUNK_ROWS - 1) / COL_CHUNK_ROWS;
+    size_t chunks = ((size_t)rows + COL_CHUNK_ROWS - 1) / COL_CHUNK_ROWS;
+    const size_t n_wg = ((size_t)rows + round_rows_per_wg(rows) - 1) / round_rows_per_wg(rows);
+    if (n_wg > chunks) chunks = n_wg;  // partial sums: one row per 64-row chunk or per workgroup of the one-pass round
     size_t off = 0;
     w.u = off;        off = up256(off + 4 * (size_t)rows);
     w.v = off;        off = up256(off + 4 * (size_t)cols);
@@ -238,7 +371,21 @@ extern "C" int dbf_svid(const void* Z_dev, int rows, int cols, int iters, void* 
 
     hipLaunchKernelGGL(dbf_svid_signs_kernel, dim3(n_ct, n_rt), dim3(256), 0, st, Z, rows, cols, n_ct,
                        static_cast<uint8_t*>(bits_dev));
+    const int cpl = (cols + 4 * ROUND_THREADS - 1) / (4 * ROUND_THREADS);  // float4s per thread and row in the one-pass round
+    const int rpw = round_rows_per_wg(rows), n_wg = (rows + rpw - 1) / rpw;
     for (int it = 0; it < iters; ++it) {
+        if (vec_ok && cpl <= 6 && (size_t)rows * cols >= ROUND_MIN_ENTRIES) {  // (7 float4s per thread and row spill)
+            switch (cpl) {
+                case 1: launch_round<1>(it == 0, n_wg, st, Z, rows, cols, v, ss_part, n_ss, u, partial, rpw); break;
+                case 2: launch_round<2>(it == 0, n_wg, st, Z, rows, cols, v, ss_part, n_ss, u, partial, rpw); break;
+                case 3: launch_round<3>(it == 0, n_wg, st, Z, rows, cols, v, ss_part, n_ss, u, partial, rpw); break;
+                case 4: launch_round<4>(it == 0, n_wg, st, Z, rows, cols, v, ss_part, n_ss, u, partial, rpw); break;
+                case 5: launch_round<5>(it == 0, n_wg, st, Z, rows, cols, v, ss_part, n_ss, u, partial, rpw); break;
+                default: launch_round<6>(it == 0, n_wg, st, Z, rows, cols, v, ss_part, n_ss, u, partial, rpw); break;
+            }
+            hipLaunchKernelGGL(dbf_svid_col_reduce_kernel, dim3(n_ss), dim3(256), 0, st, partial, n_wg, cols, v, ss_part);
+            continue;
+        }
         if (it == 0)
             hipLaunchKernelGGL(dbf_svid_row_dots_kernel<true>, dim3((rows + 3) / 4), dim3(256), 0, st, Z, rows, cols, v,
                                ss_part, n_ss, u, vec_ok);

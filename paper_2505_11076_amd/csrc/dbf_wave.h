@@ -32,4 +32,19 @@ __device__ inline int dbf_wave_sum(int v) {
            __builtin_amdgcn_readlane(v, 48);
 }
 
+// Sum of a float over the wavefront, the same value in every lane: each row of 16 lanes is summed by its
+// lane 0 in a fixed tree, the four row sums are added as (r0 + r1) + (r2 + r3).
+__device__ inline float dbf_wave_sum_f(float v) {
+    v += __builtin_bit_cast(float, dbf_dpp_move<0xB1>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, dbf_dpp_move<0x4E>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, dbf_dpp_move<0x124>(__builtin_bit_cast(int, v)));
+    v += __builtin_bit_cast(float, dbf_dpp_move<0x128>(__builtin_bit_cast(int, v)));
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
 #endif  // DBF_WAVE_H

@@ -38,7 +38,12 @@ def _run(Z, iters):
 
 
 @pytest.mark.parametrize("shape,iters", [(s, i) for s in [(512, 256), (100, 77), (130, 1000), (1000, 129),
-                                                          (4096, 2048), (3, 5)] for i in (1, 4)]
+                                                          (4096, 2048), (3, 5),
+                                                          (300, 4100), (77, 11008), (24, 24580)]
+                          for i in (1, 4)]
+                         # matrices large enough for the one-pass round (1, 2, 3 and 6 float4s per thread and row,
+                         # ragged last batches of rows; 24580 columns are too many for it)
+                         + [((6151, 4096), 3), ((3100, 8196), 2), ((2309, 11008), 2), ((1033, 24576), 2), ((1100, 24580), 2)]
                          + [((4096, 4096), 8), ((11008, 4096), 8)])  # the last two: what bench.py times
 def test_svid_matches_the_oracle(shape, iters):
     rows, cols = shape
