@@ -177,6 +177,77 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs 
     }
 }
 
+// One workgroup per token, the row held in registers (HOLD vector items of 8 columns per thread: rows of up to
+// 2048 * HOLD columns that can be read in 16-byte pieces).  Straight-line: every load of the row is issued before
+// anything waits (vector items beyond the row are read as its last one and zeroed afterwards); the four
+// wavefronts exchange their maxima and sums through LDS.  With 8192 wavefronts of little work each instead of
+// 2048 of much, the launch is as long as one memory round trip and a little arithmetic.
+template <bool FROM_F32, int HOLD>
+__global__ __launch_bounds__(256) void dbf_quantise_rows_held_kernel(const QuantArgs a) {
+    __shared__ float wmax[4];
+    __shared__ int wsum[4];
+    const int token = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nvec = a.kp >> 3, nreal = a.cols >> 3;
+    float u[HOLD][8];
+    if (FROM_F32) {
+        const float* row = static_cast<const float*>(a.src) + (size_t)token * a.ld;
+        v4f f0[HOLD], f1[HOLD];
+#pragma unroll
+        for (int r = 0; r < HOLD; ++r) {
+            const int c0 = 8 * min(tid + 256 * r, nreal - 1);
+            f0[r] = *reinterpret_cast<const v4f*>(row + c0);
+            f1[r] = *reinterpret_cast<const v4f*>(row + c0 + 4);
+        }
+#pragma unroll
+        for (int r = 0; r < HOLD; ++r) {
+            const bool in = tid + 256 * r < nreal;
+            u[r][0] = in ? f0[r].x : 0.f;  u[r][1] = in ? f0[r].y : 0.f;
+            u[r][2] = in ? f0[r].z : 0.f;  u[r][3] = in ? f0[r].w : 0.f;
+            u[r][4] = in ? f1[r].x : 0.f;  u[r][5] = in ? f1[r].y : 0.f;
+            u[r][6] = in ? f1[r].z : 0.f;  u[r][7] = in ? f1[r].w : 0.f;
+        }
+    } else {
+        const uint16_t* row = static_cast<const uint16_t*>(a.src) + (size_t)token * a.ld;
+        h8 xv[HOLD], bv[HOLD];
+#pragma unroll
+        for (int r = 0; r < HOLD; ++r) {
+            const int c0 = 8 * min(tid + 256 * r, nreal - 1);
+            xv[r] = *reinterpret_cast<const h8*>(row + c0);
+            bv[r] = *reinterpret_cast<const h8*>(a.col_scale + c0);
+        }
+#pragma unroll
+        for (int r = 0; r < HOLD; ++r) {
+            const bool in = tid + 256 * r < nreal;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) u[r][i] = in ? (float)xv[r][i] * (float)bv[r][i] : 0.f;
+        }
+    }
+    float mx = 0.f;
+#pragma unroll
+    for (int r = 0; r < HOLD; ++r)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mx = fmaxf(mx, fabsf(u[r][i]));
+    mx = dbf_wave_max(mx);
+    if (lane == 0) wmax[w] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    const float inv = mx > 0.f ? QMAX / mx : 0.f;
+    int local = 0;
+#pragma unroll
+    for (int r = 0; r < HOLD; ++r) {
+        const int v = tid + 256 * r;
+        if (v < nvec) local += quantise_store(a, token, v, u[r], inv);
+    }
+    local = dbf_wave_sum(local);
+    if (lane == 0) wsum[w] = local;
+    __syncthreads();
+    if (tid == 0) {
+        a.scale[token] = mx / QMAX;
+        a.sigma[token] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    }
+}
+
 // One workgroup per token: for rows too long to hold in a wavefront's registers.
 template <bool FROM_F32>
 __global__ __launch_bounds__(256) void dbf_quantise_rows_block_kernel(const QuantArgs a) {
@@ -409,6 +480,21 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     }
 }
 
+// The quantiser for a row length: rows held in registers where they can be read in 16-byte pieces (up to 4096 and up
+// to 12288 padded columns), else a wavefront or a workgroup per token that reads value by value / twice.
+template <bool FROM_F32>
+void launch_quantise(const QuantArgs& q, size_t kp, int T, hipStream_t stream) {
+    const bool straight = q.vec_ok && (q.cols & 7) == 0 && q.cols >= 8;
+    if (straight && kp <= 4096)
+        hipLaunchKernelGGL((dbf_quantise_rows_held_kernel<FROM_F32, 2>), dim3(T), dim3(256), 0, stream, q);
+    else if (straight && kp <= 12288)
+        hipLaunchKernelGGL((dbf_quantise_rows_held_kernel<FROM_F32, 6>), dim3(T), dim3(256), 0, stream, q);
+    else if (kp <= 4096)
+        hipLaunchKernelGGL(dbf_quantise_rows_kernel<FROM_F32>, dim3((T + 3) / 4), dim3(256), 0, stream, q);
+    else
+        hipLaunchKernelGGL(dbf_quantise_rows_block_kernel<FROM_F32>, dim3(T), dim3(256), 0, stream, q);
+}
+
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // workspace carve-up (all sections 256-byte aligned)
@@ -453,8 +539,7 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     q1.scale = reinterpret_cast<float*>(base + w.sc1);  q1.sigma = reinterpret_cast<int*>(base + w.sg1);
     q1.T = T;  q1.Tp = (T + 63) & ~63;  q1.cols = L->n_in;  q1.kp = kp1;  q1.ld = L->n_in;
     q1.vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
-    if (kp1 <= 4096) hipLaunchKernelGGL(dbf_quantise_rows_kernel<false>, dim3((T + 3) / 4), dim3(256), 0, stream, q1);
-    else hipLaunchKernelGGL(dbf_quantise_rows_block_kernel<false>, dim3(T), dim3(256), 0, stream, q1);
+    launch_quantise<false>(q1, kp1, T, stream);
 
     StageArgs s1;
     s1.bits = L->dB;  s1.row_scale = L->dm;
@@ -471,8 +556,7 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     q2.scale = reinterpret_cast<float*>(base + w.sc2);  q2.sigma = reinterpret_cast<int*>(base + w.sg2);
     q2.T = T;  q2.Tp = q1.Tp;  q2.cols = kp2 < ks ? kp2 : ks;  q2.kp = kp2;  q2.ld = ks;
     q2.vec_ok = 1;
-    if (kp2 <= 4096) hipLaunchKernelGGL(dbf_quantise_rows_kernel<true>, dim3((T + 3) / 4), dim3(256), 0, stream, q2);
-    else hipLaunchKernelGGL(dbf_quantise_rows_block_kernel<true>, dim3(T), dim3(256), 0, stream, q2);
+    launch_quantise<true>(q2, kp2, T, stream);
 
     StageArgs s2;
     s2.bits = L->dA;  s2.row_scale = L->da;
