@@ -44,14 +44,48 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# Kernels that issue loads by inline assembly and wait for them by hand (the tile and operand rings).  The compiler
+# does not know that such a load is still in flight: if it SPILLS the destination register right after the asm
+# statement, it reuses the register -- for an address, say -- and the data that lands later overwrites it: a memory
+# fault on the GPU, not a wrong number.  So these kernels must be built without a single spilled vector register;
+# the build checks the compiler's own resource report and refuses the library otherwise.
+NO_SPILL = {"dbf_gemv_mfma.hip": "dbf_items_mfma_kernel", "dbf_gemm_i8.hip": "dbf_gemm_i8_stage_kernel"}
+REMARK = "-Rpass-analysis=kernel-resource-usage"
+
+
+def _check_no_spills(src: str, stderr: str) -> None:
+    name, bad = None, []
+    for line in stderr.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[")[0].strip()
+        elif "VGPRs Spill:" in line and name and NO_SPILL[src] in name:
+            n = int(line.split("VGPRs Spill:")[1].split("[")[0].strip())
+            if n:
+                bad.append("%s: %d spilled vector registers" % (name, n))
+    if bad:
+        raise RuntimeError("%s: kernels with hand-issued loads must not spill registers (an in-flight load would land in "
+                           "a register the compiler has reused):\n  %s" % (src, "\n  ".join(bad)))
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = [REMARK] if src in NO_SPILL else []
+    cmd = [_hipcc(), *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, res.stdout, res.stderr))
+    if src in NO_SPILL:
+        _check_no_spills(src, res.stderr)
     noise = "is not a recognized feature for this target"
-    warn = "\n".join(l for l in res.stderr.splitlines() if noise not in l).strip()
+    kept, skip = [], 0
+    for l in res.stderr.splitlines():
+        if REMARK in l:  # (a remark and the two lines of source context under it)
+            skip = 2
+        elif skip and ("|" in l[:12]):
+            skip -= 1
+        elif noise not in l and not l.endswith("remarks generated when compiling for gfx950."):
+            kept.append(l)
+    warn = "\n".join(kept).strip()
     if warn:
         print(warn, file=sys.stderr)
     return obj
