@@ -286,3 +286,20 @@ def test_host_code_is_clean_under_address_and_undefined_behaviour_sanitizers():
     assert res.returncode == 0, res.stdout + res.stderr
     assert "sanitize_host: ok" in res.stdout
     assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr
+
+
+def test_build_refuses_spills_in_kernels_with_hand_issued_loads():
+    """Kernels that issue loads by inline assembly must be built without spilled vector registers (an in-flight
+    load would land in a register the compiler has already reused: a GPU memory fault).  The build reads the
+    compiler's resource report; this checks the reader on a report with and without spills."""
+    from paper_2505_11076_amd import build as Bd
+    ok = ("x.hip:1:1: remark: Function Name: _ZN1a21dbf_items_mfma_kernelILi1EEEvv [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     VGPRs: 109 [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     VGPRs Spill: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark: Function Name: _ZN1a26dbf_quantise_inputs_kernelILb1EEEvv [-Rpass-analysis=kernel-resource-usage]\n"
+          "x.hip:1:1: remark:     VGPRs Spill: 7 [-Rpass-analysis=kernel-resource-usage]\n")
+    Bd._check_no_spills("dbf_gemv_mfma.hip", ok)   # (a kernel without hand-issued loads may spill)
+    bad = ok.replace("VGPRs Spill: 0", "VGPRs Spill: 12")
+    with pytest.raises(RuntimeError, match="12 spilled vector registers"):
+        Bd._check_no_spills("dbf_gemv_mfma.hip", bad)
+    assert set(Bd.NO_SPILL) == {"dbf_gemv_mfma.hip", "dbf_gemm_i8.hip"}
