@@ -323,11 +323,14 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // other instantiation is the hot one (long streams of layers of up to 4096 columns at batch 1)
 // and carries none of that code.
 // SHARED != 0: the stage input was quantised once for the whole launch by dbf_quantise_inputs_kernel (batches
-// of 2 and more, where every item quantising all batch rows itself would cost more than streaming its tiles):
-// the prologue takes scales and sums from there.  SHARED == 1: the int8 planes of the item's columns are copied
-// into LDS and read from there as at batch 1.  SHARED == 2 (rows that do not fit the LDS of a workgroup at this
-// batch): no operand in LDS at all; the 16 operand bytes a lane needs for a tile are requested from memory (the
-// planes are L2 resident: every item of the layer reads them) together with the tile, in the same ring.
+// of 2 and more, where every item quantising all batch rows itself would cost more than streaming its tiles;
+// stacks of layers with long stage inputs at batch 1 too): the prologue takes scales and sums from there.
+// SHARED == 1: the int8 planes of the item's columns are copied into LDS and read from there as at batch 1.
+// SHARED == 2 (rows that do not fit the LDS of a workgroup at this batch): no operand in LDS at all; the 16
+// operand bytes a lane needs for a tile are requested from memory (the planes are L2 resident: every item of
+// the layer reads them) together with the tile, in the same ring.  SHARED == 3: as 2, but every wavefront takes
+// a row tile of its own and all four walk the same column tiles together, so that their operand reads meet in
+// the compute unit's vector cache (lists of long items: what streams take at batch 2 and more).
 // SINGLE: every item of the launch streams its columns as one chunk (the launcher knows): the first group of
 // tiles of a row tile then starts from zero accumulators by giving the matrix instructions a zero addend,
 // and the 32 accumulator registers are never cleared (2 of 47 vector instructions per tile).
