@@ -63,8 +63,13 @@ enum {
 
 /* Which decode kernel dbf_gemv_kind runs. */
 enum {
-    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses: DBF_GEMV_MFMA for a group of layers,
-                          DBF_GEMV_MFMA_SPLIT for a single layer (measured faster there)  */
+    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses.  Batch 1: DBF_GEMV_MFMA for a group of layers,
+                          DBF_GEMV_MFMA_SPLIT for a single layer (measured faster there), long rows
+                          of short launches cut into column pieces.  Batches of 2 and more -- and
+                          groups of layers with long stage inputs at batch 1 too, see
+                          DBF_TUNE_LONG_ROWS -- quantise each stage input once per call: four
+                          launches (quantise x, B stage, quantise t, A stage).  Every choice gives
+                          the same bits as DBF_GEMV_MFMA and DBF_GEMV_MFMA_SPLIT                  */
     DBF_GEMV_VALU = 1, /* fp32 add/subtract per sign bit on the vector ALU (exact fp32 sums) */
     DBF_GEMV_MFMA = 2, /* sign bytes fed to the int8 matrix cores as the adder; the input
                           vector of each stage is rounded once to 16-bit fixed point.  Both
@@ -124,8 +129,8 @@ int dbf_untile_host(int rows, int cols, const uint8_t* tiled, uint32_t* bits);
 /* ---- decode: Y = X W'^T for a few tokens -----------------------------------------------
  * The forward-pass expression of section 3, evaluated in two stages: the B stage
  * t = ((x . b) B^T) . m (the middle rescale is fused into its epilogue), then the A stage
- * y = (t A^T) . a.  fp32 (or exact integer) accumulation, fp32 middle activations.  The
- * default kernel runs both stages in one launch (see DBF_GEMV_MFMA).
+ * y = (t A^T) . a.  fp32 (or exact integer) accumulation, fp32 middle activations.  How many
+ * launches a call makes depends on the kind (see DBF_GEMV_AUTO); all are issued on `hip_stream`.
  *
  * x_dev: device, fp16 [batch][n_in] row-major, tightly packed.
  * y_dev: device, fp16 [batch][n_out] row-major, written in full.
@@ -273,8 +278,8 @@ int dbf_admm_prepare(const void* bits_dev, const void* m2_dev, const void* b_dev
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
  * benchmark stream of layers): the B and A stages of all layers run in one launch (two for
- * DBF_GEMV_VALU and DBF_GEMV_MFMA_SPLIT), so the sign bits stream from HBM without a launch
- * gap per layer.
+ * DBF_GEMV_VALU and DBF_GEMV_MFMA_SPLIT, four where DBF_GEMV_AUTO quantises the stage inputs once
+ * per call), so the sign bits stream from HBM without a launch gap per layer.
  *
  * dbf_stack_create: layers[0..n_layers) must stay alive while the stack exists; the stack
  * only holds a device table describing them.  n_layers >= 1.  A layer may appear only once
