@@ -332,7 +332,8 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     std::memcpy(image.data() + o_i1, items_1.data(), sizeof(DbfItem) * items_1.size());
     std::memcpy(image.data() + o_is, items_s.data(), sizeof(DbfItem) * items_s.size());
     void* dev = nullptr;
-    hipError_t e = hipMalloc(&dev, off);
+    hipError_t e = dbf_mfma_prepare();
+    if (e == hipSuccess) e = hipMalloc(&dev, off);
     if (e == hipSuccess) {
         for (DbfItem& it : items_p) {  // rebase the accumulator and counter addresses
             it.acc = reinterpret_cast<int*>(static_cast<uint8_t*>(dev) + reinterpret_cast<size_t>(it.acc));

@@ -924,6 +924,22 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q) {
     return ch_tiles;
 }
 
+// The row-per-wavefront kernels take more than 64 KiB of LDS at the largest batches: the limit has to be raised
+// per kernel, once per process.  Called when a launch plan is built -- not at the first launch, which may sit
+// inside a stream capture -- and again, for nothing, by the launcher.
+hipError_t dbf_mfma_prepare() {
+    static const hipError_t raised = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<1, false, 3, false>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<2, false, 3, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e != hipSuccess) (void)hipGetLastError();
+        return e;
+    }();
+    return raised;
+}
+
 hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, int stage_a, const void* x_base,
                                       int batch, hipStream_t stream) {
     if (n_layers <= 0) return hipSuccess;
@@ -944,15 +960,7 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned lon
     const int ch_tiles = dbf_mfma_chunk_tiles(batch, max_cols, shared_q);
     const size_t smem = mfma_smem_bytes(batch, ch_tiles, shared_q);
     if (shared_q == 3) {
-        // (more than 64 KiB of LDS at the largest batches: the limit has to be raised per kernel, once)
-        static const hipError_t raised = [] {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<1, false, 3, false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<2, false, 3, false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            return e;
-        }();
+        const hipError_t raised = dbf_mfma_prepare();  // (done when the plan was built; repeated calls cost nothing)
         if (raised != hipSuccess) return raised;
         if (batch <= 8)
             hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 3, false>), dim3(n_items), dim3(256), smem, stream, items, sync,

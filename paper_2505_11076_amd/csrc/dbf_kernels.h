@@ -36,6 +36,8 @@ int dbf_mfma_chunk_tiles(int batch, int max_cols, int shared_q);
 // Widest input row (columns) the matrix-core kernel's one-pass prologue takes at batch 1: such rows are
 // read once and quantised from registers; wider ones are read twice (scale, then quantisation).
 int dbf_mfma_one_pass_cols();
+// One-time, per-process set-up of the matrix-core decode kernels (LDS limits); cheap to call again.
+hipError_t dbf_mfma_prepare();
 
 // Prefill (T tokens): two stages with the middle activations in the caller's workspace; arguments are
 // validated by dbf_gemm before this is called.  int8 matrix cores as the adder (masked sign bytes as one
