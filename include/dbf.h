@@ -80,6 +80,11 @@ enum {
 
 #define DBF_MAX_BATCH 16       /* largest batch dbf_gemv / dbf_stack_gemv accept */
 #define DBF_MAX_DIM (1 << 20)  /* largest n_in, n_out or k                       */
+/* Longest stage input (n_in for the B stage, k for the A stage) the integer matrix-core paths take.  They add the
+ * 16-bit fixed-point inputs (|q| <= 32512) in int32: a sum over more than 66051 inputs need not fit, whatever the
+ * order.  Layers with a longer stage input are decoded by the vector-ALU kernel (fp32 sums) under DBF_GEMV_AUTO;
+ * the kinds that name the matrix-core kernel, and the prefill entry points beyond 16 tokens, return DBF_ESHAPE. */
+#define DBF_INT_PATH_MAX_COLS 65536
 
 /* ---- packing (offline, once per layer) -------------------------------------------------
  * Section 3 ("Double binary factorization"): the five operands of a layer.
@@ -134,7 +139,8 @@ int dbf_untile_host(int rows, int cols, const uint8_t* tiled, uint32_t* bits);
  *
  * x_dev: device, fp16 [batch][n_in] row-major, tightly packed.
  * y_dev: device, fp16 [batch][n_out] row-major, written in full.
- * batch: 1..DBF_MAX_BATCH.  Errors: DBF_EINVAL, DBF_EHIP.
+ * batch: 1..DBF_MAX_BATCH.  Errors: DBF_EINVAL, DBF_ESHAPE (a kind that names the matrix-core kernel on a layer
+ * with n_in or k above DBF_INT_PATH_MAX_COLS), DBF_EHIP.
  * dbf_gemv_kind selects the kernel variant (DBF_GEMV_*); dbf_gemv is DBF_GEMV_AUTO.
  */
 int dbf_gemv(const dbf_layer* layer, const void* x_dev, void* y_dev, int batch, void* hip_stream);
@@ -165,7 +171,8 @@ int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
  * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes,
  * 256-byte aligned, contents undefined on return.  Asynchronous on the
  * stream; allocates nothing.  Errors: DBF_EINVAL (NULL pointer, T < 1 or too large, unknown
- * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_EHIP.
+ * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_ESHAPE (more than DBF_MAX_BATCH tokens on
+ * a layer with n_in or k above DBF_INT_PATH_MAX_COLS), DBF_EHIP.
  * dbf_gemm_workspace_bytes returns 0 for a NULL layer or T < 1.
  */
 enum { DBF_GEMM_AUTO = 0, DBF_GEMM_I8 = 2 };
@@ -187,7 +194,8 @@ int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
  *   Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (two streams,
  *   two threads) race and give wrong results; calls on one stream are ordered and safe.  Nothing in the array
  *   has to be zero and nothing is kept between calls.
- * Asynchronous on hip_stream.  Errors: DBF_EINVAL, DBF_EWORKSPACE, DBF_EHIP. */
+ * Asynchronous on hip_stream.  Errors: DBF_EINVAL, DBF_EWORKSPACE, DBF_ESHAPE (n_in or k above
+ * DBF_INT_PATH_MAX_COLS), DBF_EHIP. */
 #define DBF_GEMM_STATIC_BYTES (32u << 20)
 int dbf_gemm_static(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T, void* hip_stream);
 

@@ -502,6 +502,13 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     // AUTO: a group of layers runs as one fused launch; a single layer is faster as two launches
     // (measured 14.3 vs 15.5 us at 4096 x 4096, k = 2048: the second launch's set-up overlaps the
     // first kernel instead of its workgroups polling).
+    // Stage inputs too long for exact int32 sums (DBF_INT_PATH_MAX_COLS): the vector-ALU kernel, or an error for the
+    // kinds that name the matrix-core kernel.
+    const int longest = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
+    if (longest > DBF_INT_PATH_MAX_COLS) {
+        if (kind == DBF_GEMV_MFMA || kind == DBF_GEMV_MFMA_SPLIT) return DBF_ESHAPE;
+        kind = DBF_GEMV_VALU;
+    }
     const bool pieces_ok = kind == DBF_GEMV_AUTO;  // the named kinds keep their one-workgroup-per-row-tile lists
     if (kind == DBF_GEMV_AUTO) kind = p.n_layers > 1 ? DBF_GEMV_MFMA : DBF_GEMV_MFMA_SPLIT;
     const int wait_us = dbf_tune(DBF_TUNE_WAIT_LIMIT_US);
@@ -598,6 +605,7 @@ int dbf_gemm_kind(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, voi
     // kernel's bits), at a third of the latency (a prefill workgroup walks all column steps of its rows
     // whatever the token count: 67 us against 24 us at 4096 x 4096, k = 4096).
     if (kind == DBF_GEMM_AUTO && T <= DBF_MAX_BATCH) return launch_plan(DBF_GEMV_AUTO, L->plan, X_dev, Y_dev, T, stream);
+    if (L->n_in > DBF_INT_PATH_MAX_COLS || L->k > DBF_INT_PATH_MAX_COLS) return DBF_ESHAPE;  // (int32 sums: see dbf.h)
     const hipError_t e = dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();

@@ -451,7 +451,8 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
                     vh = -vh;
                     vl = -vl;
                 }
-                const int total = 2 * (vh * 256 + vl) - tsigma;
+                // (2 * the sum of the set bits' q may pass 2^31 on the way to a total that fits: modular arithmetic)
+                const int total = (int)(2u * (unsigned)(vh * 256 + vl) - (unsigned)tsigma);
                 const float rs = (float)__builtin_bit_cast(_Float16, a.row_scale[n0 + i]);
                 v[i] = (float)total * tscale * rs;
             }

@@ -34,6 +34,7 @@ hipError_t scratch_of(int device, void** out) {
 extern "C" int dbf_gemm_static(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* hip_stream) {
     if (!L || !X_dev || !Y_dev || T < 1) return DBF_EINVAL;
     if ((T + 63) / 64 > 65535) return DBF_EINVAL;
+    if (L->n_in > DBF_INT_PATH_MAX_COLS || L->k > DBF_INT_PATH_MAX_COLS) return DBF_ESHAPE;  // (int32 sums: see dbf.h)
     const size_t need = dbf_gemm_i8_workspace_bytes(L, T);
     if (need > DBF_GEMM_STATIC_BYTES) return DBF_EWORKSPACE;  // beyond the static scratch: use dbf_gemm
     int device = -1;

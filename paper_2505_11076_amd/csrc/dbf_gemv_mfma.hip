@@ -748,7 +748,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                     // (sigma covers the columns this workgroup quantised: its own piece, or, in the one-pass
                     // case, the whole row -- then only the first piece subtracts it)
                     const int sig = (one_pass && ct_first != 0) ? 0 : misc->sigma[bi];
-                    const int total = 2 * (vh * 256 + vl) - sig;
+                    // (2 * the sum of the set bits' q may pass 2^31 on the way to a total that fits: modular arithmetic)
+                    const int total = (int)(2u * (unsigned)(vh * 256 + vl) - (unsigned)sig);
                     if (n_pieces > 1) {  // a column piece: add the exact integer sum; the last piece to arrive finishes the row
                         __hip_atomic_fetch_add(piece_acc() + (size_t)bi * piece_acc_stride() + rho, total, __ATOMIC_RELAXED,
                                                __HIP_MEMORY_SCOPE_AGENT);
