@@ -147,16 +147,30 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
 // Long-rows plans take this list at batch 1, where their workgroups read the quantised input tile by tile and
 // have no prologue to amortise: they did best with about 1000 items per stage (8192 x 28672 streams, k = 6371:
 // 4.7 TB/s at 1 and 2 row tiles per item against 3.9 at 4, which makes 240 items).
+// Items are at most 256 KiB and at most 8 row tiles (rows of 32-48 column tiles get 8 and 5 instead of 4: the 224-layer
+// Llama-2-7B stack 5.92 -> 6.01 TB/s, nothing else moved by more than 1 %), and a layer's items are of equal length
+// to within one row tile (balanced_spans).  Asking for half as many items of twice the size helped where it left
+// whole rounds of equal items (512 layers of 4096 x 4096, k = 2048: +2.3 %; 64 of them: +7 %) and cost 2.5-7 % on
+// streams of k = 3072-4096 and of 8192 x 8192 layers: not taken.
 int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows) {
     const long long WANT_ITEMS = long_rows ? 1024 : 2048;
-    constexpr int MAX_AUTO_SPAN = 4;
-    if (!long_rows && st.cols > dbf_mfma_one_pass_cols()) return MAX_AUTO_SPAN;
+    const int MAX_AUTO_SPAN = long_rows ? 4 : 8;
+    if (!long_rows && st.cols > dbf_mfma_one_pass_cols()) return 4;
     long long item_tiles = stage_tiles / WANT_ITEMS;
     if (item_tiles > 256) item_tiles = 256;
     int span = (int)((2 * item_tiles + st.n_ct) / (2 * st.n_ct));  // item_tiles / n_ct, rounded to nearest
     if (span < 1) span = 1;
     if (span > MAX_AUTO_SPAN) span = MAX_AUTO_SPAN;
     return span;
+}
+
+// The row tiles of a stage in as many items as `span` row tiles per item need, of equal length to within one row
+// tile (32 row tiles at 5 per item: 5 5 5 5 4 4 4 instead of 5 5 5 5 5 5 2).
+std::vector<int> balanced_spans(int n_rt, int span) {
+    const int items = (n_rt + span - 1) / span, base = n_rt / items, longer = n_rt % items;
+    std::vector<int> out;
+    for (int q = 0; q < items; ++q) out.push_back(base + (q < longer ? 1 : 0));
+    return out;
 }
 
 // The same for the launches of batches of 2 and more, which take a stage input quantised once per call: a workgroup
@@ -229,12 +243,16 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
         tiles_A += (long long)sA[i].n_rt * sA[i].n_ct;
     }
     int max_span = 1;
+    int phase = 0;
     auto pattern_for = [&](const std::vector<int>& given, const DbfStage& st, long long stage_tiles) {
-        std::vector<int> v = given.empty() ? std::vector<int>(1, auto_span(st, stage_tiles, p->long_rows != 0)) : given;
+        std::vector<int> v = given;
+        if (given.empty()) {  // (a pattern of this layer's own: it starts at its first item)
+            v = balanced_spans(st.n_rt, auto_span(st, stage_tiles, p->long_rows != 0));
+            phase = 0;
+        }
         for (int x : v) max_span = x > max_span ? x : max_span;
         return v;
     };
-    int phase = 0;
     for (int i = 0; i < n; ++i) append_items(items_n, sB[i], i, false, 0, pattern_for(span_b, sB[i], tiles_B), &phase);
     nBn = (int)items_n.size();
     phase = 0;
