@@ -44,7 +44,7 @@ struct DbfWorkItem {
 };
 
 // Work item of the matrix-core kernel: `nrt` consecutive row tiles of one stage of one layer,
-// with everything the workgroup needs in one 96-byte record (one scalar load, no second hop
+// with everything the workgroup needs in one 120-byte record (scalar loads, no second hop
 // through a per-layer table).  A launch list holds all B-stage items first, then all A-stage
 // items, so that a fused launch dispatches every producer before any consumer.
 struct DbfItem {

@@ -206,9 +206,10 @@ __global__ __launch_bounds__(256) void dbf_svid_col_dots_kernel(const float* __r
     if (vec) {
         // rows beyond the matrix are read as the last row with weight zero: no branch in the loop, so
         // the loads of several rounds are in flight together
+        static_assert(COL_CHUNK_ROWS % 4 == 0, "four row lanes share a chunk evenly");
 #pragma unroll
-        for (int i = rl; i < COL_CHUNK_ROWS; i += 4) {
-            const int row = row0 + i;
+        for (int ii = 0; ii < COL_CHUNK_ROWS / 4; ++ii) {
+            const int row = row0 + rl + 4 * ii;
             const int rc = min(row, rows - 1);
             const float w = row < rows ? u[rc] : 0.f;
             const v4f a = *reinterpret_cast<const v4f*>(Z + (size_t)rc * cols + col);
