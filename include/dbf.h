@@ -83,7 +83,8 @@ enum {
 /* Longest stage input (n_in for the B stage, k for the A stage) the integer matrix-core paths take.  They add the
  * 16-bit fixed-point inputs (|q| <= 32512) in int32: a sum over more than 66051 inputs need not fit, whatever the
  * order.  Layers with a longer stage input are decoded by the vector-ALU kernel (fp32 sums) under DBF_GEMV_AUTO;
- * the kinds that name the matrix-core kernel, and the prefill entry points beyond 16 tokens, return DBF_ESHAPE. */
+ * the kinds that name the matrix-core kernel, and the prefill beyond what dbf_gemm hands to the decode kernels
+ * (32 tokens; dbf_gemm_static: any), return DBF_ESHAPE. */
 #define DBF_INT_PATH_MAX_COLS 65536
 
 /* ---- packing (offline, once per layer) -------------------------------------------------
@@ -164,15 +165,15 @@ int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
  *                per token to 16-bit fixed point (q = rint(u * 32512 / max|u|)) and split into two int8
  *                planes; the masked sign bytes are the other operand; the sums are exact integers; the
  *                middle activations stay in fp32.
- *   DBF_GEMM_AUTO (dbf_gemm): DBF_GEMM_I8; calls of up to DBF_MAX_BATCH tokens are run as a decode
- *                batch (dbf_gemv), which gives the same bits at a third of the latency.
+ *   DBF_GEMM_AUTO (dbf_gemm): DBF_GEMM_I8; calls of up to 2 * DBF_MAX_BATCH tokens are run as one or two
+ *                decode batches (dbf_gemv), which give the same bits at a third to two thirds of the latency.
  *
  * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1 (at most 65535 * 64).
  * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes,
  * 256-byte aligned, contents undefined on return.  Asynchronous on the
  * stream; allocates nothing.  Errors: DBF_EINVAL (NULL pointer, T < 1 or too large, unknown
- * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_ESHAPE (more than DBF_MAX_BATCH tokens on
- * a layer with n_in or k above DBF_INT_PATH_MAX_COLS), DBF_EHIP.
+ * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_ESHAPE (more than 2 * DBF_MAX_BATCH tokens
+ * on a layer with n_in or k above DBF_INT_PATH_MAX_COLS), DBF_EHIP.
  * dbf_gemm_workspace_bytes returns 0 for a NULL layer or T < 1.
  */
 enum { DBF_GEMM_AUTO = 0, DBF_GEMM_I8 = 2 };

@@ -622,7 +622,17 @@ int dbf_gemm_kind(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, voi
     // Up to 16 tokens are a decode batch: the same fixed-point arithmetic (the int8 prefill gives the decode
     // kernel's bits), at a third of the latency (a prefill workgroup walks all column steps of its rows
     // whatever the token count: 67 us against 24 us at 4096 x 4096, k = 4096).
-    if (kind == DBF_GEMM_AUTO && T <= DBF_MAX_BATCH) return launch_plan(DBF_GEMV_AUTO, L->plan, X_dev, Y_dev, T, stream);
+    // Up to 32 tokens are two such batches, one after the other (4096 x 4096, k = 4096: 35-46 us for 17-32 tokens
+    // against 64-65; 11008 -> 4096, k = 5970: 53-67 against 119-120; at 48 tokens three batches lose on the first).
+    if (kind == DBF_GEMM_AUTO && T <= 2 * DBF_MAX_BATCH) {
+        for (int t0 = 0; t0 < T; t0 += DBF_MAX_BATCH) {
+            const int nb = T - t0 < DBF_MAX_BATCH ? T - t0 : DBF_MAX_BATCH;
+            const int rc = launch_plan(DBF_GEMV_AUTO, L->plan, static_cast<const uint16_t*>(X_dev) + (size_t)t0 * L->n_in,
+                                       static_cast<uint16_t*>(Y_dev) + (size_t)t0 * L->n_out, nb, stream);
+            if (rc != DBF_OK) return rc;
+        }
+        return DBF_OK;
+    }
     if (L->n_in > DBF_INT_PATH_MAX_COLS || L->k > DBF_INT_PATH_MAX_COLS) return DBF_ESHAPE;  // (int32 sums: see dbf.h)
     const hipError_t e = dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, stream);
     if (e != hipSuccess) {

@@ -67,6 +67,27 @@ def test_gemm_agrees_with_gemv_rows():
         layer.close()
 
 
+@pytest.mark.parametrize("shape", [(512, 512, 256), (1000, 130, 77), (4100, 333, 600)])
+def test_up_to_32_tokens_run_as_decode_batches_with_the_same_bits(shape):
+    """dbf_gemm hands 17 ... 32 tokens to the decode kernels as two batches (16 and the rest); 33 tokens and more take
+    the prefill kernels.  Either way the outputs are those of the prefill kernels bit for bit, and within the gate of
+    the oracle."""
+    n_in, n_out, k = shape
+    L = I.make_layer(n_in, n_out, k, seed=I.seed_for(4, 60 + k))
+    X = I.make_activations(40, n_in, I.seed_for(4, 61 + k))
+    ref = O.forward_from_packed(X, L, "staged")
+    layer = G.pack(L)
+    try:
+        for T in (17, 24, 31, 32, 33, 40):
+            what = "gemm[auto] n_in=%d n_out=%d k=%d T=%d" % (n_in, n_out, k, T)
+            G.say("start " + what)
+            y = G.run_gemm(layer, X[:T], B.GEMM_AUTO)
+            G.check(y, ref[:T], what)
+            assert np.array_equal(y, G.run_gemm(layer, X[:T], B.GEMM_I8)), what
+    finally:
+        layer.close()
+
+
 @pytest.mark.parametrize("idx", [0, 1])
 def test_config4_prefill_every_token(idx):
     """Both prefill shapes at T = 2048, every one of the 2048 x 4096 outputs against the oracle's staged

@@ -4,7 +4,7 @@ The largest dimension, 2^20, in each of the three places it can stand: the input
 row tiles in the A stage) and the middle size (8192 row tiles in the B stage, rows of 16384 column tiles in the A
 stage).  A stage input longer than DBF_INT_PATH_MAX_COLS = 65536 is beyond what the integer matrix-core paths can
 add exactly in int32, so the default kind runs those layers on the vector-ALU kernel, the kinds that name the
-matrix-core kernel and the prefill entry point refuse them (DBF_ESHAPE).
+matrix-core kernel and the prefill kernels (dbf_gemm beyond 32 tokens) refuse them (DBF_ESHAPE).
 
 The longest stage input the integer paths do take, 65536: random inputs through every kind and the prefill, and
 the adversarial input -- every product x_l b_l at the quantiser's full scale and a row of B with all signs equal,
@@ -52,12 +52,15 @@ def test_decode_at_the_largest_dimension(which):
             for kind in (B.GEMV_MFMA, B.GEMV_MFMA_SPLIT):
                 rc = B.lib().dbf_gemv_kind(layer.handle, x.data_ptr(), y.data_ptr(), 1, kind, G.stream_handle())
                 assert rc == B.DBF_ESHAPE, (kind, rc)
-            X17 = G.f16_to_dev(I.make_activations(17, n_in, seed=2))
-            Y17 = torch.zeros((17, n_out), dtype=torch.float16, device="cuda")
-            wsb = B.dbf_gemm_workspace_bytes(layer, 17)
+            # (up to 32 tokens dbf_gemm runs decode batches, which take such layers; beyond, the prefill kernels refuse)
+            X33 = G.f16_to_dev(I.make_activations(33, n_in, seed=2))
+            Y33 = torch.zeros((33, n_out), dtype=torch.float16, device="cuda")
+            wsb = B.dbf_gemm_workspace_bytes(layer, 33)
             ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device="cuda")
-            rc = B.lib().dbf_gemm(layer.handle, X17.data_ptr(), Y17.data_ptr(), 17, ws.data_ptr(), wsb, G.stream_handle())
+            rc = B.lib().dbf_gemm(layer.handle, X33.data_ptr(), Y33.data_ptr(), 33, ws.data_ptr(), wsb, G.stream_handle())
             assert rc == B.DBF_ESHAPE, rc
+            X20 = I.make_activations(20, n_in, seed=I.seed_for(1, 930))
+            G.check(G.run_gemm(layer, X20, B.GEMM_AUTO), O.forward_from_packed(X20, L, "staged"), "20 tokens, largest " + which)
     finally:
         layer.close()
 
