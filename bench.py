@@ -768,6 +768,12 @@ def prefill_bench(B, I, torch, np, stream, proto):
         res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)] = {
             "ms": round(ms, 4), "tflops": round(tf, 2), "frac_of_f16_mfma_peak": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
             "variant": "int8 matrix cores, 16-bit fixed-point activations", "protocol": protocol}
+        # few tokens (latency bound): up to 32 run as decode batches, up to 512 with the columns of a stage cut into shares
+        few = {}
+        for Tf in (16, 32, 64, 256):
+            ms_f, _ = proto.run(lambda: B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), Tf, ws.data_ptr(), ws_bytes, stream))
+            few["T%d" % Tf] = round(ms_f * 1e3, 1)
+        res["%dx%d_k%d_T%d" % (n_in, n_out, k, T)]["us_per_call_few_tokens"] = few
         layer.close()
     return res
 

@@ -169,8 +169,10 @@ int dbf_sync_timeouts(const dbf_layer* layer, int* timeouts);
  *                decode batches (dbf_gemv), which give the same bits at a third to two thirds of the latency.
  *
  * X_dev: device fp16 [T][n_in]; Y_dev: device fp16 [T][n_out]; T >= 1 (at most 65535 * 64).
- * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes,
- * 256-byte aligned, contents undefined on return.  Asynchronous on the
+ * workspace_dev: device scratch of at least dbf_gemm_workspace_bytes(layer, T) bytes (up to 512 tokens that
+ * includes room for the integer sums of stages whose columns are cut into shares over more workgroups: calls of
+ * few tokens would otherwise leave most of the chip idle; same bits), 256-byte aligned, contents need not be
+ * anything on entry and are undefined on return.  Asynchronous on the
  * stream; allocates nothing.  Errors: DBF_EINVAL (NULL pointer, T < 1 or too large, unknown
  * kind), DBF_EWORKSPACE (NULL, misaligned or short workspace), DBF_ESHAPE (more than 2 * DBF_MAX_BATCH tokens
  * on a layer with n_in or k above DBF_INT_PATH_MAX_COLS), DBF_EHIP.
@@ -188,9 +190,10 @@ int dbf_gemm_kind(const dbf_layer* layer, const void* X_dev, void* Y_dev, int T,
  * dbf_gemm_kind(..., DBF_GEMM_I8, ...), for every T >= 1, with the scratch (quantised activations, fp32 middle
  * activations) in a static device array of DBF_GEMM_STATIC_BYTES that each GPU the library runs on holds
  * until the process ends.  Calls no hipMalloc / hipFree or any allocating routine.
- *   Limit: dbf_gemm_workspace_bytes(layer, T) <= DBF_GEMM_STATIC_BYTES, else
- *   DBF_EWORKSPACE and nothing is launched (T = 512 at 11008 -> 4096, k = 5970 needs 28.4 MiB; 1024 tokens of
- *   a 4096 x 4096, k = 2048 layer 20 MiB).  The current device must be the layer's (DBF_EINVAL).
+ *   Limit: every call with dbf_gemm_workspace_bytes(layer, T) <= DBF_GEMM_STATIC_BYTES is taken, and so is a
+ *   call of up to 512 tokens that fits without the room for the sums of column shares (it then runs unsplit);
+ *   else DBF_EWORKSPACE and nothing is launched (T = 512 at 11008 -> 4096, k = 5970 needs 28.4 MiB unsplit; 1024
+ *   tokens of a 4096 x 4096, k = 2048 layer 20 MiB).  The current device must be the layer's (DBF_EINVAL).
  *   The first call on a device looks up the array's address (hipGetSymbolAddress); make it outside graph capture.
  *   Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (two streams,
  *   two threads) race and give wrong results; calls on one stream are ordered and safe.  Nothing in the array
@@ -380,7 +383,12 @@ enum {
                                          with one stage input longer than 6144 values and the other longer than 4096,
                                          quantise every stage input once per call at batch 1 too (four launches per
                                          call instead of one); 0: no plan does; 1: every plan does                  */
-    DBF_TUNE_COUNT_ = 12
+    /* LAUNCH knob */
+    DBF_TUNE_GEMM_SPLITS = 12,        /* dbf_gemm / dbf_gemm_static of up to 512 tokens: -1 (default): a stage that
+                                         would start at most 64 workgroups (256 rows x 64 tokens each) cuts its
+                                         columns into 4 shares; 1: never; N in 2..1024: N shares (at most one per
+                                         64 columns)                                                               */
+    DBF_TUNE_COUNT_ = 13
 };
 int dbf_tuning_set(int knob, int value);
 int dbf_tuning_get(int knob);

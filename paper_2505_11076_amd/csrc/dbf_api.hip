@@ -75,6 +75,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {52, 52, 16, 64},             // DBF_TUNE_SHARED_LDS_KB
     {250000, 250000, 0, 10000000},// DBF_TUNE_WAIT_LIMIT_US
     {-1, -1, -1, 1},              // DBF_TUNE_LONG_ROWS
+    {-1, -1, -1, 1024},           // DBF_TUNE_GEMM_SPLITS
 };
 
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
@@ -634,7 +635,7 @@ int dbf_gemm_kind(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, voi
         return DBF_OK;
     }
     if (L->n_in > DBF_INT_PATH_MAX_COLS || L->k > DBF_INT_PATH_MAX_COLS) return DBF_ESHAPE;  // (int32 sums: see dbf.h)
-    const hipError_t e = dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, stream);
+    const hipError_t e = dbf_gemm_i8_launch(L, X_dev, Y_dev, T, workspace_dev, workspace_bytes, stream);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         return DBF_EHIP;

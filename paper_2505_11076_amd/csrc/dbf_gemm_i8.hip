@@ -44,6 +44,7 @@ constexpr int QI_TSPLIT = QI_TOKENS / (16 * QI_TB);       // token slices of a r
 #ifndef DBF_QI_XCD_REMAP
 #define DBF_QI_XCD_REMAP 1
 #endif
+
 constexpr int QI_WAVES = QI_ROWTILES * QI_TSPLIT;
 constexpr int QI_OCC = 2;           // wavefronts per SIMD (the accumulators leave room for no more)
 constexpr int QI_THREADS = 64 * QI_WAVES;
@@ -69,7 +70,18 @@ struct QuantArgs {
     int T, Tp, cols, kp;
     long long ld;     // elements between token rows of src
     int vec_ok;       // rows can be read in 16-byte (fp16) / 32-byte (fp32) pieces
+    v4u* zero;        // 16-byte pieces this launch clears on the side (the column splits' sums and counters), or NULL
+    unsigned zero_v4;
 };
+
+// The integer sums and arrival counters of the stage kernels' column splits must start at zero, and a caller's
+// workspace holds anything: the first quantiser launch of a call, which runs before either stage, clears them,
+// its threads sharing the pieces evenly.
+__device__ inline void zero_share(const QuantArgs& a) {
+    if (!a.zero) return;
+    const unsigned n_thr = gridDim.x * blockDim.x;
+    for (unsigned i = blockIdx.x * blockDim.x + threadIdx.x; i < a.zero_v4; i += n_thr) a.zero[i] = (v4u){0, 0, 0, 0};
+}
 
 template <bool FROM_F32>
 __device__ inline void load8(const QuantArgs& a, int token, int v, float (&u)[8]) {
@@ -130,6 +142,7 @@ __device__ inline int quantise_store(const QuantArgs& a, int token, int v, const
 // twice (the second read hits in L2).
 template <bool FROM_F32>
 __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs a) {
+    zero_share(a);
     constexpr int HOLD = 8;  // vectors of 8 columns a lane can hold
     const int lane = threadIdx.x & 63;
     const int token = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -184,6 +197,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_kernel(const QuantArgs 
 // 2048 of much, the launch is as long as one memory round trip and a little arithmetic.
 template <bool FROM_F32, int HOLD>
 __global__ __launch_bounds__(256) void dbf_quantise_rows_held_kernel(const QuantArgs a) {
+    zero_share(a);
     __shared__ float wmax[4];
     __shared__ int wsum[4];
     const int token = blockIdx.x;
@@ -251,6 +265,7 @@ __global__ __launch_bounds__(256) void dbf_quantise_rows_held_kernel(const Quant
 // One workgroup per token: for rows too long to hold in a wavefront's registers.
 template <bool FROM_F32>
 __global__ __launch_bounds__(256) void dbf_quantise_rows_block_kernel(const QuantArgs a) {
+    zero_share(a);
     __shared__ float wmax[4];
     __shared__ int wsum[4];
     const int token = blockIdx.x;
@@ -309,12 +324,22 @@ struct StageArgs {
     void* out;                  // OUT_F32: float [T][ldo]; else fp16 [T][ldo]
     int n_rt, n_ct, T, Tp, ldo;
     int n_valid;                // output rows to store
+    // column splits (SPLIT kernels only): grid.z workgroups share the column steps of a (row group, token block);
+    // each adds its exact integer sums into slab, the last one to arrive (cnt) scales and stores them and leaves
+    // both at zero
+    int splits;
+    int* slab;                  // int32 [token blocks][row groups][QI_WAVES][QI_TB * 8 * 4][64 lanes], zero on entry
+    unsigned* cnt;              // [token blocks][row groups], zero on entry
 };
 
-template <bool OUT_F32>
+// SPLIT: few tokens leave most of the chip idle (a workgroup per 256 rows x 64 tokens walks all column steps:
+// 16 workgroups for 64 tokens of a 4096-row stage), so grid.z workgroups take a share of the column steps each.
+// Their sums are exact integers, so adding them in any order gives the bits of the unsplit kernel.
+template <bool OUT_F32, bool SPLIT>
 __global__ __launch_bounds__(QI_THREADS) __attribute__((amdgpu_waves_per_eu(QI_OCC, QI_OCC)))
 void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     __shared__ __align__(16) unsigned char xs[2][2 * QI_PLANE];
+    __shared__ int last_split;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -364,6 +389,9 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     static_assert(QI_DEPTH == 4 && QI_STAGE_BYTES == 32, "the wait counts below are written for this pipeline");
     v4u bq[QI_DEPTH], x0[QI_DEPTH], x1[QI_DEPTH];
     const int last_ct = a.n_ct - 1;
+    // this workgroup's column steps: all of them, or the blockIdx.z-th share
+    const int kt_lo = SPLIT ? (int)((long long)a.n_ct * blockIdx.z / a.splits) : 0;
+    const int kt_hi = SPLIT ? (int)((long long)a.n_ct * (blockIdx.z + 1) / a.splits) : a.n_ct;
     const unsigned x_voff = (unsigned)(SB * tid), t_voff = (unsigned)(lane * 16);
     const signed char* x_base = a.xq + (size_t)token0 * 128;
     const uint8_t* t_base = a.bits + (size_t)rt * a.n_ct * DBF_TILE_BYTES;
@@ -375,7 +403,7 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
         asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(bq[j]) : "v"(t_voff), "s"(ts_) : "memory");
     };
 #pragma unroll
-    for (int j = 0; j < QI_DEPTH; ++j) request(j, min(j, last_ct));
+    for (int j = 0; j < QI_DEPTH; ++j) request(j, min(kt_lo + j, last_ct));
     asm volatile("s_waitcnt vmcnt(10)" : "+v"(x0[0]), "+v"(x1[0]) : : "memory");
     *reinterpret_cast<v4u*>(s_dst0) = x0[0];
     *reinterpret_cast<v4u*>(s_dst0 + 16) = x1[0];
@@ -383,7 +411,7 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
 
     const unsigned char* xlane = xs[0] + (16 * QI_TB * th + c) * QI_TROW + 16 * g;
 
-    for (int kt0 = 0; kt0 < a.n_ct; kt0 += QI_DEPTH) {
+    for (int kt0 = kt_lo; kt0 < kt_hi; kt0 += QI_DEPTH) {
 #pragma unroll
         for (int j = 0; j < QI_DEPTH; ++j) {
             const int kt = kt0 + j;
@@ -397,7 +425,7 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
             }
             // A step beyond the matrix contributes nothing if its sign operand is zero (no branch around
             // the matrix instructions); `live` is the same for all lanes and is folded into the plane masks.
-            const unsigned live = kt < a.n_ct ? 0xFFFFFFFFu : 0u;
+            const unsigned live = kt < kt_hi ? 0xFFFFFFFFu : 0u;
             const unsigned char* xb = xlane + (j & 1) * (2 * QI_PLANE);
             v4i xop[QI_TB][2];
 #pragma unroll
@@ -433,6 +461,39 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
     for (int j = 0; j < QI_DEPTH; ++j) asm volatile("" : "+v"(bq[j]), "+v"(x0[j]), "+v"(x1[j]));
 
     // ---- epilogue: acc[s][tb][p][i] of lane (g, c) is row 16*s + 4*g + i, token 32*th + 16*tb + c ----
+    // (vh * 256 + vl below: the sum of q over the set bits of the row, exact)
+    int* const my_sums = SPLIT ? a.slab + (((size_t)by * gridDim.x + bx) * QI_WAVES + w) * (QI_TB * 8 * 4 * 64) + lane : nullptr;
+    if (SPLIT) {
+        // add this share's sums (lane-major: a wavefront's adds of one value are 64 consecutive words), count the
+        // workgroup in, and go on only if it is the last of its (row group, token block)
+#pragma unroll
+        for (int tb = 0; tb < QI_TB; ++tb) {
+            const int token = token0 + 16 * QI_TB * th + 16 * tb + c;
+            if (!active || token >= a.T) continue;
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int vh = acc[s][tb][0][i] >> s, vl = acc[s][tb][1][i] >> s;
+                    if (s == 7) {
+                        vh = -vh;
+                        vl = -vl;
+                    }
+                    __hip_atomic_fetch_add(my_sums + ((tb * 8 + s) * 4 + i) * 64, vh * 256 + vl, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's adds have been performed ...
+        __syncthreads();                                  // ... and so have the workgroup's
+        if (tid == 0) {
+            unsigned* cnt = a.cnt + (size_t)by * gridDim.x + bx;
+            const unsigned before = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            last_split = before == (unsigned)a.splits - 1u;
+            if (last_split) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!last_split) return;
+    }
     if (!active) return;
 #pragma unroll
     for (int tb = 0; tb < QI_TB; ++tb) {
@@ -451,8 +512,12 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
                     vh = -vh;
                     vl = -vl;
                 }
+                // (the last share reads the sums of all shares and leaves zeros for the next call)
+                const int set_sum = SPLIT ? __hip_atomic_exchange(my_sums + ((tb * 8 + s) * 4 + i) * 64, 0, __ATOMIC_RELAXED,
+                                                                  __HIP_MEMORY_SCOPE_AGENT)
+                                          : vh * 256 + vl;
                 // (2 * the sum of the set bits' q may pass 2^31 on the way to a total that fits: modular arithmetic)
-                const int total = (int)(2u * (unsigned)(vh * 256 + vl) - (unsigned)tsigma);
+                const int total = (int)(2u * (unsigned)set_sum - (unsigned)tsigma);
                 const float rs = (float)__builtin_bit_cast(_Float16, a.row_scale[n0 + i]);
                 v[i] = (float)total * tscale * rs;
             }
@@ -498,9 +563,38 @@ void launch_quantise(const QuantArgs& q, size_t kp, int T, hipStream_t stream) {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Column splits: in calls of up to SPLIT_MAX_T tokens a stage that would start at most SPLIT_UP_TO_WGS workgroups cuts
+// its column steps into SPLIT_SHARES shares (of at least SPLIT_MIN_STEPS steps).  What a share saves is column steps
+// (0.6 us each); what it costs is an atomic add per output and share, so it pays only while the stage has few
+// outputs.  Measured, microseconds per call without / with 4 shares (2 and 8 in brackets where they differ much):
+//   4096 x 4096, k = 4096      33 tokens 65.8 / 46.5   64: 67.2 / 50.6   128: 68.1 / 57.3 (8: 67.6)   256: 69.8 / 67.0
+//                              512: 72.0 / 92.9 (2: 81.1)
+//   11008 -> 4096, k = 5970    33: 121.5 / 64.1 (8: 61.0)   64: 123.0 / 69.0   128: 123.5 / 75.3   256: 124.3 / 92.5
+//                              512: 129.4 / 136.2
+//   4096 -> 11008, k = 2985    33: 60.6 / 48.2   64: 61.7 / 53.3   128: 62.6 / 63.5   256: 65.2 / 86.7
+constexpr int SPLIT_MAX_T = 512;
+constexpr int SPLIT_UP_TO_WGS = 64;
+constexpr int SPLIT_SHARES = 4;
+constexpr int SPLIT_MIN_STEPS = 8;
+
+int pick_splits(int row_groups, unsigned tok_blocks, int n_ct) {
+    const int forced = dbf_tune(DBF_TUNE_GEMM_SPLITS);
+    int s = 1;
+    if (forced > 0) {
+        s = forced;
+    } else {
+        if ((long long)row_groups * tok_blocks > SPLIT_UP_TO_WGS) return 1;
+        s = SPLIT_SHARES;
+        if (s > n_ct / SPLIT_MIN_STEPS) s = n_ct / SPLIT_MIN_STEPS;
+    }
+    if (s > n_ct) s = n_ct;
+    if (s > 65535) s = 65535;
+    return s < 1 ? 1 : s;
+}
+
 // workspace carve-up (all sections 256-byte aligned)
 struct I8Workspace {
-    size_t xq1, sc1, sg1, mid, xq2, sc2, sg2, total;
+    size_t xq1, sc1, sg1, mid, xq2, sc2, sg2, slab, cnt, total, total_without_splits;
 };
 inline I8Workspace i8_workspace(const dbf_layer* L, int T) {
     const size_t kp1 = (size_t)dbf_col_tiles(L->n_in) * DBF_TILE_COLS;
@@ -516,19 +610,45 @@ inline I8Workspace i8_workspace(const dbf_layer* L, int T) {
     w.xq2 = off;  off = align256(off + Tp * 2 * kp2);
     w.sc2 = off;  off = align256(off + (size_t)T * 4);
     w.sg2 = off;  off = align256(off + (size_t)T * 4);
+    w.total_without_splits = off;
+    // the column splits' sums (one int per output of the larger stage, whole 256 x 64 blocks) and arrival counters
+    w.slab = w.cnt = off;
+    if (T <= SPLIT_MAX_T) {
+        const size_t rg1 = (dbf_row_tiles(L->k) + QI_ROWTILES - 1) / QI_ROWTILES;
+        const size_t rg2 = (dbf_row_tiles(L->n_out) + QI_ROWTILES - 1) / QI_ROWTILES;
+        const size_t rg = rg1 > rg2 ? rg1 : rg2, tb = Tp / QI_TOKENS;
+        off = align256(off + rg * tb * (QI_ROWTILES * DBF_TILE_ROWS) * QI_TOKENS * 4);
+        w.cnt = off;  off = align256(off + rg * tb * 4);
+    }
     w.total = off;
     return w;
+}
+
+template <bool OUT_F32>
+void launch_stage(StageArgs& s, unsigned tok_blocks, bool may_split, int* slab, unsigned* cnt, hipStream_t stream) {
+    const int row_groups = (s.n_rt + QI_ROWTILES - 1) / QI_ROWTILES;
+    s.splits = may_split ? pick_splits(row_groups, tok_blocks, s.n_ct) : 1;
+    s.slab = slab;
+    s.cnt = cnt;
+    if (s.splits > 1)
+        hipLaunchKernelGGL((dbf_gemm_i8_stage_kernel<OUT_F32, true>), dim3(row_groups, tok_blocks, s.splits), dim3(QI_THREADS), 0,
+                           stream, s);
+    else
+        hipLaunchKernelGGL((dbf_gemm_i8_stage_kernel<OUT_F32, false>), dim3(row_groups, tok_blocks), dim3(QI_THREADS), 0, stream, s);
 }
 
 }  // namespace
 
 size_t dbf_gemm_i8_workspace_bytes(const dbf_layer* L, int T) { return i8_workspace(L, T).total; }
+size_t dbf_gemm_i8_workspace_bytes_without_splits(const dbf_layer* L, int T) { return i8_workspace(L, T).total_without_splits; }
 
 // Launches quantise -> stage 1 -> quantise -> stage 2 on `stream`.  Arguments are validated by
-// the caller (dbf_gemm); `ws` holds at least dbf_gemm_i8_workspace_bytes(L, T) bytes.
-hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* ws,
+// the caller (dbf_gemm); `ws` holds ws_bytes >= dbf_gemm_i8_workspace_bytes_without_splits(L, T) bytes; the stages
+// of a call of few tokens cut their columns into shares if it also holds dbf_gemm_i8_workspace_bytes(L, T).
+hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* ws, size_t ws_bytes,
                               hipStream_t stream) {
     const I8Workspace w = i8_workspace(L, T);
+    const bool may_split = T <= SPLIT_MAX_T && ws_bytes >= w.total;
     uint8_t* base = static_cast<uint8_t*>(ws);
     const int ks = dbf_row_tiles(L->k) * DBF_TILE_ROWS;
     const int kp1 = dbf_col_tiles(L->n_in) * DBF_TILE_COLS, kp2 = dbf_col_tiles(L->k) * DBF_TILE_COLS;
@@ -540,6 +660,10 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     q1.scale = reinterpret_cast<float*>(base + w.sc1);  q1.sigma = reinterpret_cast<int*>(base + w.sg1);
     q1.T = T;  q1.Tp = (T + 63) & ~63;  q1.cols = L->n_in;  q1.kp = kp1;  q1.ld = L->n_in;
     q1.vec_ok = ((L->n_in & 7) == 0 && (reinterpret_cast<uintptr_t>(X_dev) & 15) == 0) ? 1 : 0;
+    q1.zero = may_split ? reinterpret_cast<v4u*>(base + w.slab) : nullptr;
+    q1.zero_v4 = may_split ? (unsigned)((w.total - w.slab) / 16) : 0u;
+    int* slab = reinterpret_cast<int*>(base + w.slab);
+    unsigned* cnt = reinterpret_cast<unsigned*>(base + w.cnt);
     launch_quantise<false>(q1, kp1, T, stream);
 
     StageArgs s1;
@@ -548,8 +672,7 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     s1.out = base + w.mid;
     s1.n_rt = dbf_row_tiles(L->k);  s1.n_ct = dbf_col_tiles(L->n_in);  s1.T = T;  s1.Tp = q1.Tp;  s1.ldo = ks;
     s1.n_valid = ks;  // padded rows have m = 0 and are written as zeros: the second quantisation reads them
-    hipLaunchKernelGGL(dbf_gemm_i8_stage_kernel<true>,
-                       dim3((s1.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(QI_THREADS), 0, stream, s1);
+    launch_stage<true>(s1, tok_blocks, may_split, slab, cnt, stream);
 
     QuantArgs q2;
     q2.src = base + w.mid;  q2.col_scale = nullptr;
@@ -557,6 +680,7 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     q2.scale = reinterpret_cast<float*>(base + w.sc2);  q2.sigma = reinterpret_cast<int*>(base + w.sg2);
     q2.T = T;  q2.Tp = q1.Tp;  q2.cols = kp2 < ks ? kp2 : ks;  q2.kp = kp2;  q2.ld = ks;
     q2.vec_ok = 1;
+    q2.zero = nullptr;  q2.zero_v4 = 0;
     launch_quantise<true>(q2, kp2, T, stream);
 
     StageArgs s2;
@@ -565,7 +689,6 @@ hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev
     s2.out = Y_dev;
     s2.n_rt = dbf_row_tiles(L->n_out);  s2.n_ct = dbf_col_tiles(L->k);  s2.T = T;  s2.Tp = q1.Tp;  s2.ldo = L->n_out;
     s2.n_valid = L->n_out;
-    hipLaunchKernelGGL(dbf_gemm_i8_stage_kernel<false>,
-                       dim3((s2.n_rt + QI_ROWTILES - 1) / QI_ROWTILES, tok_blocks), dim3(QI_THREADS), 0, stream, s2);
+    launch_stage<false>(s2, tok_blocks, may_split, slab, cnt, stream);
     return hipGetLastError();
 }

@@ -35,7 +35,7 @@ extern "C" int dbf_gemm_static(const dbf_layer* L, const void* X_dev, void* Y_de
     if (!L || !X_dev || !Y_dev || T < 1) return DBF_EINVAL;
     if ((T + 63) / 64 > 65535) return DBF_EINVAL;
     if (L->n_in > DBF_INT_PATH_MAX_COLS || L->k > DBF_INT_PATH_MAX_COLS) return DBF_ESHAPE;  // (int32 sums: see dbf.h)
-    const size_t need = dbf_gemm_i8_workspace_bytes(L, T);
+    const size_t need = dbf_gemm_i8_workspace_bytes_without_splits(L, T);  // (column splits only where they fit as well)
     if (need > DBF_GEMM_STATIC_BYTES) return DBF_EWORKSPACE;  // beyond the static scratch: use dbf_gemm
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess) {
@@ -48,7 +48,7 @@ extern "C" int dbf_gemm_static(const dbf_layer* L, const void* X_dev, void* Y_de
         (void)hipGetLastError();
         return DBF_EHIP;
     }
-    if (dbf_gemm_i8_launch(L, X_dev, Y_dev, T, ws, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+    if (dbf_gemm_i8_launch(L, X_dev, Y_dev, T, ws, DBF_GEMM_STATIC_BYTES, static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
         (void)hipGetLastError();
         return DBF_EHIP;
     }

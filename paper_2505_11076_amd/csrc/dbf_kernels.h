@@ -44,9 +44,13 @@ hipError_t dbf_mfma_prepare();
 // operand, the activations rounded per token to 16-bit fixed point and split into two int8 planes), exact
 // integer sums, middle activations in fp32.
 struct dbf_layer;
+// (calls of few tokens cut the columns of a stage into shares over more workgroups; the integer sums they add up
+//  need room of their own, which _bytes counts and _bytes_without_splits does not: the launcher splits only where
+//  workspace_bytes covers it)
 size_t dbf_gemm_i8_workspace_bytes(const dbf_layer* L, int T);
+size_t dbf_gemm_i8_workspace_bytes_without_splits(const dbf_layer* L, int T);
 hipError_t dbf_gemm_i8_launch(const dbf_layer* L, const void* X_dev, void* Y_dev, int T, void* workspace_dev,
-                              hipStream_t stream);
+                              size_t workspace_bytes, hipStream_t stream);
 
 // Middle-channel pruning: fills the sign tiles and vectors of `dst` (a freshly created layer with
 // k = n_keep on the same device) from `src` and the kept middle indices keep_dev (device, increasing,

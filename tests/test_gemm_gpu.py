@@ -88,6 +88,50 @@ def test_up_to_32_tokens_run_as_decode_batches_with_the_same_bits(shape):
         layer.close()
 
 
+def _decode_in_batches(layer, X):
+    return np.concatenate([G.run_gemv(layer, X[t0:t0 + B.MAX_BATCH], B.GEMV_MFMA_SPLIT) for t0 in range(0, X.shape[0], B.MAX_BATCH)])
+
+
+@pytest.mark.parametrize("shape", [(512, 512, 256), (1000, 130, 77), (4100, 333, 600), (700, 2600, 1500)])
+def test_column_splits_of_calls_of_few_tokens(shape):
+    """Up to 512 tokens, a stage that would start fewer than 256 workgroups cuts its column steps into shares over
+    grid.z workgroups, which add exact integer sums and let the last to arrive finish (the sums and counters live in
+    the workspace, cleared by the first quantiser launch: the workspace here is pre-filled with a byte pattern).
+    Every token of every call equals the decode kernels' result bit for bit -- with the built-in number of shares,
+    with 2, 5 and as many as there are column steps, and with none -- and is within the gate of the oracle; a second
+    call on the same workspace finds what the first left."""
+    n_in, n_out, k = shape
+    L = I.make_layer(n_in, n_out, k, seed=I.seed_for(4, 80 + k))
+    X = I.make_activations(513, n_in, I.seed_for(4, 81 + k))
+    ref = O.forward_from_packed(X, L, "staged")
+    layer = G.pack(L)
+    try:
+        want = _decode_in_batches(layer, X)
+        for T in (33, 64, 100, 256, 512, 513):
+            for splits in (-1, 1, 2, 5, 1024):
+                B.dbf_tuning_set(B.TUNE_GEMM_SPLITS, splits)
+                what = "gemm n_in=%d n_out=%d k=%d T=%d splits knob %d" % (n_in, n_out, k, T, splits)
+                G.say("start " + what)
+                y = G.run_gemm(layer, X[:T], B.GEMM_I8)
+                assert np.array_equal(y, want[:T]), what
+                if splits == -1:
+                    G.check(y, ref[:T], what)
+        # two calls in a row on ONE workspace, the second smaller: the sums and counters the first call left are zero
+        B.dbf_tuning_set(B.TUNE_GEMM_SPLITS, 3)
+        T1, T2 = 200, 70
+        wsb = B.dbf_gemm_workspace_bytes(layer, T1)
+        ws = torch.full((wsb,), 0x5A, dtype=torch.uint8, device="cuda")
+        for T in (T1, T2):
+            x = G.f16_to_dev(X[:T])
+            y = torch.full((T, n_out), float("nan"), dtype=torch.float16, device="cuda")
+            B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), wsb, G.stream_handle(), B.GEMM_I8)
+            torch.cuda.synchronize()
+            assert np.array_equal(G.dev_to_f64(y), want[:T]), (T1, T2, T)
+    finally:
+        B.dbf_tuning_reset()
+        layer.close()
+
+
 @pytest.mark.parametrize("idx", [0, 1])
 def test_config4_prefill_every_token(idx):
     """Both prefill shapes at T = 2048, every one of the 2048 x 4096 outputs against the oracle's staged
