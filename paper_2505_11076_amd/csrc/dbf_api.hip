@@ -272,6 +272,48 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     phase = 0;
     for (int i = 0; i < n; ++i)
         append_items(items_s, sA[i], i, true, sB[i].n_rt, shared_pattern_for(span_a, sA[i], tiles_A), &phase);
+    // Workgroups are handed to the 8 compute dies in turn (linear workgroup id modulo 8) and each die has an L2 of
+    // its own.  In the lists of stacks the items of a layer are placed so that they run on ONE die, one after the
+    // other: the layer's inputs (x and b, the middle activations) then come from that die's L2 for every item but
+    // the first.  Layers are dealt to the dies by sign bytes; list position p of a launch belongs to die p mod 8, and
+    // a die whose queue has run dry takes from the longest.  Only the order of the items changes (B items still
+    // before A items, and a layer's items still in order).  Measured on one box: the 224-layer Llama-2-7B stack
+    // 5.97 -> 6.03 TB/s, the 512-layer stream at batch 4 / 16 5.08 -> 5.10 / 3.32 -> 3.37, at batch 1 6.02 -> 6.01.
+    if (n >= 16) {
+        std::vector<int> die_of(n);
+        double load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int i = 0; i < n; ++i) {
+            int best = 0;
+            for (int d = 1; d < 8; ++d)
+                if (load[d] < load[best]) best = d;
+            die_of[i] = best;
+            load[best] += (double)sB[i].n_rt * sB[i].n_ct + (double)sA[i].n_rt * sA[i].n_ct;
+        }
+        // (`first`: the list position that is workgroup 0 of the launch the part runs in)
+        auto by_die = [&](std::vector<DbfItem>& list, int begin, int end, int first) {
+            std::vector<std::vector<DbfItem>> q(8);
+            for (int pos = begin; pos < end; ++pos) q[die_of[list[pos].layer]].push_back(list[pos]);
+            size_t at[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int pos = begin; pos < end; ++pos) {
+                int d = (pos - first) & 7;
+                if (at[d] >= q[d].size()) {
+                    size_t most = 0;
+                    for (int e = 0; e < 8; ++e)
+                        if (q[e].size() - at[e] > most) {
+                            most = q[e].size() - at[e];
+                            d = e;
+                        }
+                }
+                list[pos] = q[d][at[d]++];
+            }
+        };
+        // items_n runs as one launch (B and A items together) unless the plan quantises its inputs in launches of
+        // their own; items_s always runs as a launch per stage
+        by_die(items_n, 0, nBn, 0);
+        by_die(items_n, nBn, (int)items_n.size(), p->long_rows ? nBn : 0);
+        by_die(items_s, 0, nBs, 0);
+        by_die(items_s, nBs, (int)items_s.size(), nBs);
+    }
     phase = 0;
     for (int i = 0; i < n; ++i) append_items(items_1, sB[i], i, false, 0, one, &phase);
     nB1 = (int)items_1.size();
