@@ -132,6 +132,44 @@ def test_column_splits_of_calls_of_few_tokens(shape):
         layer.close()
 
 
+@pytest.mark.parametrize("T", [24, 64, 600])
+def test_prefill_call_replayed_from_a_captured_graph(T):
+    """dbf_gemm allocates nothing, synchronises nothing and clears what it needs with its own kernels (no memset), in all
+    three regimes -- decode batches (24 tokens), column shares with their sums and counters in the workspace (64), the
+    plain four launches (600) -- so a call can be captured into a HIP graph.  Every replay, with new inputs written and
+    eager work in between, must give what the eager call gives for those inputs, bit for bit."""
+    n_in, n_out, k = 1000, 390, 520
+    L = I.make_layer(n_in, n_out, k, seed=I.seed_for(4, 90))
+    layer = G.pack(L)
+    try:
+        wsb = B.dbf_gemm_workspace_bytes(layer, T)
+        ws = torch.full((max(wsb, 256),), 0x3C, dtype=torch.uint8, device="cuda")
+        x = G.f16_to_dev(I.make_activations(T, n_in, I.seed_for(4, 91)))
+        y = torch.full((T, n_out), float("nan"), dtype=torch.float16, device="cuda")
+        B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), wsb, G.stream_handle())   # (first call outside the capture)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph.capture_begin()
+            B.dbf_gemm(layer, x.data_ptr(), y.data_ptr(), T, ws.data_ptr(), wsb, side.cuda_stream)
+            graph.capture_end()
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(4):
+            X = I.make_activations(T, n_in, I.seed_for(4, 92 + rep))
+            want = G.run_gemm(layer, X, B.GEMM_AUTO)          # eager, on a workspace of its own
+            x.copy_(G.f16_to_dev(X))
+            y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(G.dev_to_f64(y), want), (T, rep)
+        del graph
+    finally:
+        layer.close()
+
+
 @pytest.mark.parametrize("idx", [0, 1])
 def test_config4_prefill_every_token(idx):
     """Both prefill shapes at T = 2048, every one of the 2048 x 4096 outputs against the oracle's staged
