@@ -63,9 +63,12 @@ enum {
 
 /* Which decode kernel dbf_gemv_kind runs. */
 enum {
-    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses.  Batch 1: DBF_GEMV_MFMA for a group of layers,
-                          DBF_GEMV_MFMA_SPLIT for a single layer (measured faster there), long rows
-                          of short launches cut into column pieces.  Batches of 2 and more -- and
+    DBF_GEMV_AUTO = 0, /* what dbf_gemv uses.  Batch 1: DBF_GEMV_MFMA for a group of layers whose B stage
+                          alone fills the chip (about 1300 workgroups: 80 layers of 4096 x 4096,
+                          k = 2048), DBF_GEMV_MFMA_SPLIT for a single layer and shorter groups (measured
+                          faster there: in one launch their A-stage workgroups would all sit waiting
+                          next to the B stage), long rows of short launches cut into column pieces.
+                          Batches of 2 and more -- and
                           groups of layers with long stage inputs at batch 1 too, see
                           DBF_TUNE_LONG_ROWS -- quantise each stage input once per call: four
                           launches (quantise x, B stage, quantise t, A stage).  Every choice gives
@@ -290,8 +293,8 @@ int dbf_admm_prepare(const void* bits_dev, const void* m2_dev, const void* b_dev
 /* ---- a group of independent layer products in one launch -------------------------------
  * Decode of several layers whose inputs do not depend on each other (q/k/v, gate/up, or a
  * benchmark stream of layers): the B and A stages of all layers run in one launch (two for
- * DBF_GEMV_VALU and DBF_GEMV_MFMA_SPLIT, four where DBF_GEMV_AUTO quantises the stage inputs once
- * per call), so the sign bits stream from HBM without a launch gap per layer.
+ * DBF_GEMV_VALU, DBF_GEMV_MFMA_SPLIT and short groups under DBF_GEMV_AUTO, four where DBF_GEMV_AUTO
+ * quantises the stage inputs once per call), so the sign bits stream from HBM without a launch gap per layer.
  *
  * dbf_stack_create: layers[0..n_layers) must stay alive while the stack exists; the stack
  * only holds a device table describing them.  n_layers >= 1.  A layer may appear only once
@@ -388,7 +391,10 @@ enum {
                                          would start at most 64 workgroups (256 rows x 64 tokens each) cuts its
                                          columns into 4 shares; 1: never; N in 2..1024: N shares (at most one per
                                          64 columns)                                                               */
-    DBF_TUNE_COUNT_ = 13
+    DBF_TUNE_FUSED_MIN_B_ITEMS = 13,  /* DBF_GEMV_AUTO at batch 1 runs both stages of a group of layers in one launch
+                                         only if the B stage has at least this many workgroups, else in a launch per
+                                         stage; 0..2^20 (default 1280: a quarter more than the chip holds at once)   */
+    DBF_TUNE_COUNT_ = 14
 };
 int dbf_tuning_set(int knob, int value);
 int dbf_tuning_get(int knob);

@@ -76,6 +76,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {250000, 250000, 0, 10000000},// DBF_TUNE_WAIT_LIMIT_US
     {-1, -1, -1, 1},              // DBF_TUNE_LONG_ROWS
     {-1, -1, -1, 1024},           // DBF_TUNE_GEMM_SPLITS
+    {1280, 1280, 0, 1 << 20},     // DBF_TUNE_FUSED_MIN_B_ITEMS
 };
 
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
@@ -159,6 +160,13 @@ int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows) {
     if (!long_rows && st.cols > dbf_mfma_one_pass_cols()) return 4;
     long long item_tiles = stage_tiles / WANT_ITEMS;
     if (item_tiles > 256) item_tiles = 256;
+    // (small stages: items of up to 48 KiB as long as that leaves a thousand of them -- 256 layers of 1024 x 4096 at
+    //  1 / 1.5 / 2.3 bits per weight 4.05 / 4.52 / 5.19 -> 4.36 / 4.66 / 5.43 TB/s, 64 layers of 4096 x 4096, k = 2048
+    //  4.35 -> 4.47)
+    if (!long_rows) {
+        const long long roomy = stage_tiles / 1024 < 48 ? stage_tiles / 1024 : 48;
+        if (item_tiles < roomy) item_tiles = roomy;
+    }
     int span = (int)((2 * item_tiles + st.n_ct) / (2 * st.n_ct));  // item_tiles / n_ct, rounded to nearest
     if (span < 1) span = 1;
     if (span > MAX_AUTO_SPAN) span = MAX_AUTO_SPAN;
@@ -560,9 +568,13 @@ inline bool kind_ok(int kind) {
 // B-stage launch and the A-stage launch of the two-launch kinds (timed entry point only).
 int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, hipStream_t stream,
                 hipEvent_t mid = nullptr) {
-    // AUTO: a group of layers runs as one fused launch; a single layer is faster as two launches
-    // (measured 14.3 vs 15.5 us at 4096 x 4096, k = 2048: the second launch's set-up overlaps the
-    // first kernel instead of its workgroups polling).
+    // AUTO: one fused launch for both stages only where the B items alone fill the chip (FUSED_MIN_B_ITEMS), else a
+    // launch per stage.  In a short list every A item is resident from the start and sits polling its layer's counter
+    // next to the B items it waits for; measured per call, one launch against two:
+    //   4096 x 4096, k = 2048    1 layer 15.5 / 14.3 us   3: 13.6 / 11.0   8: 19.7 / 11.3   24: 43.0 / 16.6   48: 53.4 / 22.8
+    //                            64 (1024 B items): 29.8 / 28.5   96 (1536): 39.1 / 40.6
+    //   4096 -> 11008, k = 2985  3 layers 19.1 / 13.8   8: 30.6 / 16.7   32: 103.9 / 40.4   48 (1152 B items): 56.4 / 54.4
+    //                            56 (1344): 60.0 / 61.3   96: 97.4 / 99.6
     // Stage inputs too long for exact int32 sums (DBF_INT_PATH_MAX_COLS): the vector-ALU kernel, or an error for the
     // kinds that name the matrix-core kernel.
     const int longest = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
@@ -570,8 +582,9 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
         if (kind == DBF_GEMV_MFMA || kind == DBF_GEMV_MFMA_SPLIT) return DBF_ESHAPE;
         kind = DBF_GEMV_VALU;
     }
+    const int FUSED_MIN_B_ITEMS = dbf_tune(DBF_TUNE_FUSED_MIN_B_ITEMS);
     const bool pieces_ok = kind == DBF_GEMV_AUTO;  // the named kinds keep their one-workgroup-per-row-tile lists
-    if (kind == DBF_GEMV_AUTO) kind = p.n_layers > 1 ? DBF_GEMV_MFMA : DBF_GEMV_MFMA_SPLIT;
+    if (kind == DBF_GEMV_AUTO) kind = DBF_GEMV_MFMA_SPLIT;  // (until the list is known, below)
     const int wait_us = dbf_tune(DBF_TUNE_WAIT_LIMIT_US);
     if (kind == DBF_GEMV_VALU) {
         DBF_HIP_TRY(dbf_launch_stage_valu(false, p.d_stagesB, p.d_workB1, p.blocksB1, x, y, batch, stream));
@@ -608,6 +621,7 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
         nA = p.nAp;
         pieces = 1;
     }
+    if (pieces_ok && p.n_layers > 1 && nB >= FUSED_MIN_B_ITEMS) kind = DBF_GEMV_MFMA;
     if (shared_q) {
         // Four launches: quantise x, B items, quantise t, A items.
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesB, p.n_layers, 0, x, batch, stream));

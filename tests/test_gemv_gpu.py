@@ -327,7 +327,7 @@ def test_stack_call_replayed_from_a_captured_graph(batch):
     try:
         x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
         n_y = batch * sum(L.n_out for L in Ls)
-        for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA_SPLIT, "mfma_split")):
+        for kind, name in ((B.GEMV_AUTO, "auto"), (B.GEMV_MFMA, "mfma"), (B.GEMV_MFMA_SPLIT, "mfma_split")):
             G.say("graph capture [%s]" % name)
             y_eager = torch.full((n_y,), float("nan"), dtype=torch.float16, device="cuda")
             B.dbf_stack_gemv(stack, x_all.data_ptr(), y_eager.data_ptr(), batch, G.stream_handle(), kind)
@@ -627,6 +627,7 @@ def test_a_wait_that_gives_up_is_visible_in_y_and_leaves_the_counters_consistent
     Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 1300 + i)) for i, L in enumerate(Ls)]
     if pieces:
         B.dbf_tuning_set(B.TUNE_COL_PIECES, pieces)
+        B.dbf_tuning_set(B.TUNE_FUSED_MIN_B_ITEMS, 0)   # (only the default kind takes the piece list: make it take one launch)
     layers = [G.pack(L) for L in Ls]
     stack = B.dbf_stack_create(layers)
     try:
@@ -675,6 +676,7 @@ def test_one_launch_calls_may_switch_between_the_lists_of_a_plan():
     Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 1400 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
     B.dbf_tuning_set(B.TUNE_STACK_SPAN_B, 3)
     B.dbf_tuning_set(B.TUNE_STACK_SPAN_A, 2)
+    B.dbf_tuning_set(B.TUNE_FUSED_MIN_B_ITEMS, 0)     # (the default kind, too, in one launch: a stack this short would take two)
     layers = [G.pack(L) for L in Ls]
     stack = B.dbf_stack_create(layers)
     try:
