@@ -595,14 +595,16 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     // several row tiles per workgroup only if all columns of both stages fit one LDS chunk
     const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
     const bool use_pieces = pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH && !p.long_rows;
-    // Batches of 2 and more: every stage input is quantised once per call; the items copy it into LDS (1)
-    // or, if a whole row does not fit there at this batch, read it from memory tile by tile (2).
+    // Batches of 2 and more: every stage input is quantised once per call; the items read it from memory tile by tile,
+    // in the ring of the sign tiles (2), with a row tile per wavefront where the list has long items (3).
     int shared_q = 0;
     if (pieces_ok && !use_pieces && (batch >= dbf_tune(DBF_TUNE_SHARED_MIN_BATCH) || p.long_rows)) {
-        shared_q = dbf_mfma_chunk_tiles(batch, max_cols, 1) >= dbf_col_tiles(max_cols) ? 1 : 2;
-        // (batch 1 of a long-rows plan: no LDS copy, more workgroups per compute unit; 4096 x 14336 and 8192 x 8192
-        //  streams ran 2-5 % faster than with the copy)
-        if (p.long_rows && batch == 1) shared_q = 2;
+        // (the LDS copy, form 1, is left to the knob: where the operand fits LDS -- batch 2-4 at 4096 columns -- reading
+        //  it from memory with the tiles was faster on every list that is too short for form 3: a layer alone at batch
+        //  2 / 3 / 4 17.1 / 18.4 / 19.3 -> 15.0 / 15.6 / 15.7 us, 16 layers 18.7 / 19.7 / 20.4 -> 17.9 / 18.2 / 18.5,
+        //  32 layers of 4096 -> 11008 51.4 / 53.3 / 54.0 -> 48.1 / 50.4 / 51.5)
+        //  (long-rows plans at batch 1 too: 4096 x 14336 and 8192 x 8192 streams ran 2-5 % faster than with the copy)
+        shared_q = 2;
         // (a list of long items: a row tile per wavefront, the four wavefronts of a workgroup reading the same
         //  operand from memory at the same time.  512 layers of 4096 x 4096, k = 2048: 5.63 / 5.27 / 4.61 / 3.34 TB/s
         //  at batch 2 / 4 / 8 / 16 against 5.42 / 4.80 with the LDS copy and 3.98 / 2.60 with every wavefront
