@@ -138,6 +138,9 @@ def main():
                     help="only the SVID projection measurement (dbf_svid on a 4096 x 4096 and an 11008 x 4096 matrix)")
     ap.add_argument("--admm", action="store_true",
                     help="only the ADMM update measurement (dbf_admm_step for a 4096 x 4096 weight at 1 and 2 bits)")
+    ap.add_argument("--stack-sizes", action="store_true",
+                    help="only the call time of stacks of 1 ... 128 layers at batch 1 ... 16 (default kind): where a call "
+                         "is bound by its launches and where by the stream")
     ap.add_argument("--stream-only", action="store_true",
                     help="only the timed stream of layers (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--cold-series", type=int, default=0, metavar="N",
@@ -184,6 +187,9 @@ def main():
         return
     if args.admm:
         print(json.dumps({"admm": admm_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream, proto)}))
+        return
+    if args.stack_sizes:
+        print(json.dumps({"stack_sizes": stack_sizes_bench(B, I, torch, np, kind, torch.cuda.current_stream().cuda_stream, proto)}))
         return
     if args.table4:
         print(json.dumps({"table4": table4_bench(B, I, torch, np, args.batch, kind,
@@ -589,6 +595,32 @@ def table4_bench(B, I, torch, np, batch, kind, stream, proto, bits_only=None, cf
             "note": "isolated = one dbf_gemv call, cache warm (p50 of 200 event pairs); stream = distinct copies of "
                     "the layer in one dbf_stack_gemv call per step, signs read from HBM; paper column: its Table 4 "
                     "on an RTX 4090, another machine, context only"}
+
+
+def stack_sizes_bench(B, I, torch, np, kind, stream, proto):
+    """One dbf_stack_gemv per step on stacks of 1 ... 128 copies of a layer (independent inputs), batch 1 ... 16:
+    microseconds per call, back to back.  Short stacks are bound by their launches (two at batch 1, four above),
+    long ones by the stream."""
+    res = {}
+    for n_in, n_out, k in ((4096, 4096, 2048), (4096, 11008, 2985), (11008, 4096, 2985)):
+        base = [I.make_layer(n_in, n_out, k, seed=I.seed_for(6, i)) for i in range(4)]
+        rows = {}
+        for R in (1, 3, 8, 24, 64, 128):
+            layers = [B.dbf_pack_bits(n_in, n_out, k, base[i % 4].A_bits, base[i % 4].B_bits, base[i % 4].a, base[i % 4].m,
+                                      base[i % 4].b) for i in range(R)]
+            stack = B.dbf_stack_create(layers)
+            row = {}
+            for batch in (1, 2, 4, 8, 16):
+                x = torch.randn(R * batch * n_in, device="cuda").half()
+                y = torch.zeros(R * batch * n_out, dtype=torch.float16, device="cuda")
+                ms, _ = proto.run(lambda: B.dbf_stack_gemv(stack, x.data_ptr(), y.data_ptr(), batch, stream, kind))
+                row["batch%d" % batch] = round(ms * 1e3, 1)
+            rows["layers%d" % R] = row
+            stack.close()
+            for l in layers:
+                l.close()
+        res["%dx%d_k%d" % (n_in, n_out, k)] = rows
+    return {"us_per_call": res, "protocol": {"steps": proto.steps, "warmup": proto.warmup, "settle_ms": proto.settle_ms}}
 
 
 def prune_bench(B, I, torch, np):

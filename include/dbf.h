@@ -370,7 +370,7 @@ enum {
                                          has more than 256 row tiles); else that many workgroups per stage, 1..65536 */
     DBF_TUNE_PIECE_MIN_TILES = 2,     /* smallest piece in column tiles, 1..4096 (default 24)                      */
     DBF_TUNE_PIECE_NEVER_TILES = 3,   /* rows of at most this many column tiles are never cut, 0..65536 (default 64) */
-    DBF_TUNE_PIECE_MAX_ROW_TILES = 4, /* plans with more row tiles per stage are never cut, 0..2^20 (default 1024)  */
+    DBF_TUNE_PIECE_MAX_ROW_TILES = 4, /* plans with more row tiles per stage are never cut, 0..2^20 (default 768)   */
     DBF_TUNE_STACK_SPAN_B = 5,        /* row tiles per B-stage workgroup in stacks: 0 (default) = chosen per layer  */
     DBF_TUNE_STACK_SPAN_A = 6,        /*   from the launch size, else 1..16; the same for the A stage              */
     /* LAUNCH knobs */

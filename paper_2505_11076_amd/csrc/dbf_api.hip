@@ -67,7 +67,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {0, 0, 0, 65536},             // DBF_TUNE_PIECE_TARGET
     {24, 24, 1, 4096},            // DBF_TUNE_PIECE_MIN_TILES
     {64, 64, 0, 65536},           // DBF_TUNE_PIECE_NEVER_TILES
-    {1024, 1024, 0, 1 << 20},     // DBF_TUNE_PIECE_MAX_ROW_TILES
+    {768, 768, 0, 1 << 20},       // DBF_TUNE_PIECE_MAX_ROW_TILES
     {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_B
     {0, 0, 0, DBF_MAX_SPAN},      // DBF_TUNE_STACK_SPAN_A
     {-1, -1, -1, 3},              // DBF_TUNE_SHARED_Q
@@ -347,6 +347,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
             cut = cut || pcB[i] > 1 || pcA[i] > 1;
         }
     }
+    p->piece_row_tiles = (int)(rtB > rtA ? rtB : rtA);
     const size_t acc_ints = cut ? (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * (size_t)(rtB + rtA) : 0;
     const size_t cnt_ints = cut ? (size_t)(rtB + rtA) : 0;
 
@@ -594,7 +595,11 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
     }
     // several row tiles per workgroup only if all columns of both stages fit one LDS chunk
     const int max_cols = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
-    const bool use_pieces = pieces_ok && p.d_items_p && batch <= DBF_PIECES_MAX_BATCH && !p.long_rows;
+    // (column pieces at batch 2 only for a layer or three.  Wide rows, us per call with / without pieces at
+    //  batch 2: 1 layer of 11008 -> 4096 23.5 / 26.8, 3 layers 26.9 / 27.0, 4 layers 27.8 / 24.6, 8: 31.3 / 26.0,
+    //  16: 51.0 / 30.9, 32: 113.8 / 48.8)
+    const bool use_pieces = pieces_ok && p.d_items_p && !p.long_rows &&
+                            (batch == 1 || (batch <= DBF_PIECES_MAX_BATCH && p.piece_row_tiles <= 96));
     // Batches of 2 and more: every stage input is quantised once per call; the items read it from memory tile by tile,
     // in the ring of the sign tiles (2), with a row tile per wavefront where the list has long items (3).
     int shared_q = 0;

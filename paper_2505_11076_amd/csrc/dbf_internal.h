@@ -94,6 +94,7 @@ struct DbfPlan {
     int nB1, nA1;               // a stage do not fit one LDS chunk at the requested batch)
     DbfItem* d_items_p;         // one row tile per item, row tiles cut into column pieces: built for plans
     int nBp, nAp;               // with few row tiles (a layer alone, a short stack); NULL otherwise
+    int piece_row_tiles;        // row tiles of the larger stage over all layers (batch 2 takes d_items_p only for few)
     int rows_ok;                // the items of d_items_s are long enough to give each wavefront a row tile of its own
     int long_rows;              // stage inputs are quantised once per call at every batch (see build_plan)
     // Counters of the one-launch kernel, 64 bits each, zero when the plan is built and only ever growing
