@@ -583,7 +583,10 @@ int pick_splits(int row_groups, unsigned tok_blocks, int n_ct) {
     if (forced > 0) {
         s = forced;
     } else {
-        if ((long long)row_groups * tok_blocks > SPLIT_UP_TO_WGS) return 1;
+        // (a long column walk -- 128 steps and more, i.e. 8192 columns -- still pays at twice as many workgroups:
+        //  11008 -> 4096, k = 5970 at 256 tokens 114 -> 93 us)
+        const long long wgs = (long long)row_groups * tok_blocks;
+        if (wgs > SPLIT_UP_TO_WGS && !(wgs <= 2 * SPLIT_UP_TO_WGS && n_ct >= 128)) return 1;
         s = SPLIT_SHARES;
         if (s > n_ct / SPLIT_MIN_STEPS) s = n_ct / SPLIT_MIN_STEPS;
     }
