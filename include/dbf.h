@@ -388,9 +388,9 @@ enum {
                                          call instead of one); 0: no plan does; 1: every plan does                  */
     /* LAUNCH knob */
     DBF_TUNE_GEMM_SPLITS = 12,        /* dbf_gemm / dbf_gemm_static of up to 512 tokens: -1 (default): a stage that
-                                         would start at most 64 workgroups (256 rows x 64 tokens each) cuts its
-                                         columns into 4 shares; 1: never; N in 2..1024: N shares (at most one per
-                                         64 columns)                                                               */
+                                         would start at most 64 workgroups (256 rows x 64 tokens each; 128 if it
+                                         has 8192 columns or more) cuts its columns into 4 shares; 1: never; N in
+                                         2..1024: N shares (at most one per 64 columns)                            */
     DBF_TUNE_FUSED_MIN_B_ITEMS = 13,  /* DBF_GEMV_AUTO at batch 1 runs both stages of a group of layers in one launch
                                          only if the B stage has at least this many workgroups, else in a launch per
                                          stage; 0..2^20 (default 1280: a quarter more than the chip holds at once)   */
