@@ -64,7 +64,7 @@ enum {
 /* Which decode kernel dbf_gemv_kind runs. */
 enum {
     DBF_GEMV_AUTO = 0, /* what dbf_gemv uses.  Batch 1: DBF_GEMV_MFMA for a group of layers whose B stage
-                          alone fills the chip (about 1300 workgroups: 80 layers of 4096 x 4096,
+                          alone fills the chip (1024 workgroups: 64 layers of 4096 x 4096,
                           k = 2048), DBF_GEMV_MFMA_SPLIT for a single layer and shorter groups (measured
                           faster there: in one launch their A-stage workgroups would all sit waiting
                           next to the B stage), long rows of short launches cut into column pieces.
@@ -393,7 +393,7 @@ enum {
                                          2..1024: N shares (at most one per 64 columns)                            */
     DBF_TUNE_FUSED_MIN_B_ITEMS = 13,  /* DBF_GEMV_AUTO at batch 1 runs both stages of a group of layers in one launch
                                          only if the B stage has at least this many workgroups, else in a launch per
-                                         stage; 0..2^20 (default 1280: a quarter more than the chip holds at once)   */
+                                         stage; 0..2^20 (default 1024: what the chip holds at once)                  */
     DBF_TUNE_COUNT_ = 14
 };
 int dbf_tuning_set(int knob, int value);

@@ -76,7 +76,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {250000, 250000, 0, 10000000},// DBF_TUNE_WAIT_LIMIT_US
     {-1, -1, -1, 1},              // DBF_TUNE_LONG_ROWS
     {-1, -1, -1, 1024},           // DBF_TUNE_GEMM_SPLITS
-    {1280, 1280, 0, 1 << 20},     // DBF_TUNE_FUSED_MIN_B_ITEMS
+    {1024, 1024, 0, 1 << 20},     // DBF_TUNE_FUSED_MIN_B_ITEMS
 };
 
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
@@ -359,7 +359,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     const size_t o_in = off;  off = align_up(off + sizeof(DbfItem) * items_n.size(), 256);
     const size_t o_i1 = off;  off = align_up(off + sizeof(DbfItem) * items_1.size(), 256);
     const size_t o_is = off;  off = align_up(off + sizeof(DbfItem) * items_s.size(), 256);
-    const size_t o_sy = off;  off = align_up(off + sizeof(unsigned long long) * (2 * (size_t)n + 1), 256);
+    const size_t o_sy = off;  off = align_up(off + sizeof(unsigned long long) * (2 * (size_t)n + 1) * DBF_SYNC_STRIDE, 256);
     const size_t o_ac = off;  off = align_up(off + sizeof(int) * acc_ints, 256);
     const size_t o_cn = off;  off = align_up(off + sizeof(int) * cnt_ints, 256);
     std::vector<DbfItem> items_p;
@@ -569,13 +569,15 @@ inline bool kind_ok(int kind) {
 // B-stage launch and the A-stage launch of the two-launch kinds (timed entry point only).
 int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, hipStream_t stream,
                 hipEvent_t mid = nullptr) {
-    // AUTO: one fused launch for both stages only where the B items alone fill the chip (FUSED_MIN_B_ITEMS), else a
-    // launch per stage.  In a short list every A item is resident from the start and sits polling its layer's counter
-    // next to the B items it waits for; measured per call, one launch against two:
-    //   4096 x 4096, k = 2048    1 layer 15.5 / 14.3 us   3: 13.6 / 11.0   8: 19.7 / 11.3   24: 43.0 / 16.6   48: 53.4 / 22.8
-    //                            64 (1024 B items): 29.8 / 28.5   96 (1536): 39.1 / 40.6
-    //   4096 -> 11008, k = 2985  3 layers 19.1 / 13.8   8: 30.6 / 16.7   32: 103.9 / 40.4   48 (1152 B items): 56.4 / 54.4
-    //                            56 (1344): 60.0 / 61.3   96: 97.4 / 99.6
+    // AUTO: one fused launch for both stages only where the B items alone fill the chip (DBF_TUNE_FUSED_MIN_B_ITEMS), else
+    // a launch per stage.  In a short list every A item is resident from the start and sits polling its layer's
+    // counter next to the B items it waits for.  Per call, one launch against two, us:
+    //   4096 x 4096, k = 2048    1 layer 12.0 / 11.0   3: 12.3 / 11.2   8: 12.6 / 11.3   24: 20.5 / 16.6   48: 27.3 / 22.8
+    //                            56 (896 B items): 28.6 / 26.7   64 (1024): 27.0 / 27.6   96: 39.6 / 40.8   128: 52.0 / 53.5
+    //   4096 -> 11008, k = 2985  3 layers 15.4 / 13.6   24: 34.3 / 32.8   40 (960 B items): 43.5 / 44.5   56: 59.7 / 62.2
+    //                            128: 122.8 / 128.6
+    // (with the layers' counters side by side in memory instead of 512 bytes apart the one launch took 19.4 us at 8
+    //  layers, 42.9 at 24, 88 at 24 layers of the second shape: every poll went to the same memory channel)
     // Stage inputs too long for exact int32 sums (DBF_INT_PATH_MAX_COLS): the vector-ALU kernel, or an error for the
     // kinds that name the matrix-core kernel.
     const int longest = p.max_cols_B > p.max_cols_A ? p.max_cols_B : p.max_cols_A;
@@ -652,7 +654,7 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
 int read_timeouts(const DbfPlan& p, int* timeouts) {
     unsigned long long v = 0;
     DBF_HIP_TRY(hipDeviceSynchronize());
-    DBF_HIP_TRY(hipMemcpy(&v, p.d_sync + 2 * p.n_layers, sizeof(v), hipMemcpyDeviceToHost));
+    DBF_HIP_TRY(hipMemcpy(&v, p.d_sync + (size_t)(2 * p.n_layers) * DBF_SYNC_STRIDE, sizeof(v), hipMemcpyDeviceToHost));
     if (timeouts) *timeouts = v > 0x7fffffffull ? 0x7fffffff : (int)v;
     return DBF_OK;
 }

@@ -494,6 +494,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #endif
     };
     // ---- fused launch: an A-stage item waits for the layer's B stage ---------------------
+    // (Counter i is sync[i * DBF_SYNC_STRIDE]: 512 bytes apart, so that the workgroups polling different layers'
+    // counters do not all queue at one memory channel.)
     // sync[layer] counts the B-stage row tiles published over all one-launch calls of this plan, sync[n_layers +
     // layer] the A-stage row tiles finished: what one call adds to either (it.need, it.peers: the layer's B and A
     // row tiles) does not depend on how the call's list cuts the layer into items, so calls may switch lists.
@@ -503,13 +505,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     if (tid == 0) misc->gave_up = 0;
     if (use_sync && stage_a) {
         if (tid == 0) {
-            const unsigned long long fin = __hip_atomic_load(&sync[n_layers + it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned long long fin = __hip_atomic_load(&sync[(size_t)(n_layers + it.layer) * DBF_SYNC_STRIDE], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const unsigned long long target = (fin / (unsigned)it.peers + 1ull) * (unsigned)it.need;
             const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
             const unsigned long long limit = 100ull * (unsigned)wait_limit_us;
-            while (__hip_atomic_load(&sync[it.layer], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            while (__hip_atomic_load(&sync[(size_t)it.layer * DBF_SYNC_STRIDE], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
                 if (__builtin_amdgcn_s_memrealtime() - t0 >= limit) {  // never expected; keeps every wave finite
-                    __hip_atomic_fetch_add(&sync[2 * n_layers], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_fetch_add(&sync[(size_t)(2 * n_layers) * DBF_SYNC_STRIDE], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     misc->gave_up = 1;
                     break;
                 }
@@ -826,10 +828,10 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             __syncthreads();  // ... and so have those of the whole workgroup
             // (of the pieces of a row tile only the one that stored the result publishes it)
             if (tid == 0 && (n_pieces == 1 || misc->last))
-                __hip_atomic_fetch_add(&sync[it.layer], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&sync[(size_t)it.layer * DBF_SYNC_STRIDE], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else if (tid == 0 && (n_pieces == 1 || misc->last)) {
             // (of the pieces of a row tile only the one that stored the result counts it)
-            __hip_atomic_fetch_add(&sync[n_layers + it.layer], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(&sync[(size_t)(n_layers + it.layer) * DBF_SYNC_STRIDE], (unsigned long long)it.nrt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

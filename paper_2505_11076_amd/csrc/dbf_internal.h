@@ -8,6 +8,8 @@
 #define DBF_TILE_COLS 64
 #define DBF_TILE_BYTES 1024
 #define DBF_MAX_SPAN 16  /* most row tiles one workgroup takes */
+#define DBF_SYNC_STRIDE 64  /* 64-bit words between the per-layer counters of a plan (DbfPlan::d_sync): 512 bytes, so
+                              that polls of different counters spread over the memory channels */
 #define DBF_PIECES_MAX_BATCH 2  /* largest batch for which row tiles may be cut into column pieces */
 
 static inline int dbf_row_tiles(int rows) { return (rows + DBF_TILE_ROWS - 1) / DBF_TILE_ROWS; }
@@ -104,6 +106,7 @@ struct DbfPlan {
     //                      the number of completed launches, i.e. how much of the first counter is old
     // (what a launch adds is the same whichever of the plan's lists it uses)
     //   [2 n_layers]       waits given up (sticky)
+    // (indices in units of DBF_SYNC_STRIDE words: each counter has 512 bytes to itself)
     unsigned long long* d_sync;
     int span;                   // row tiles per item in d_items_n
     int max_cols_B, max_cols_A;

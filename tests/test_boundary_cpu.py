@@ -244,7 +244,7 @@ def test_tuning_hooks_have_defaults_ranges_and_a_reset():
     defaults = {B.TUNE_COL_PIECES: -1, B.TUNE_PIECE_TARGET: 0, B.TUNE_PIECE_MIN_TILES: 24, B.TUNE_PIECE_NEVER_TILES: 64,
                 B.TUNE_PIECE_MAX_ROW_TILES: 768, B.TUNE_STACK_SPAN_B: 0, B.TUNE_STACK_SPAN_A: 0, B.TUNE_SHARED_Q: -1,
                 B.TUNE_SHARED_MIN_BATCH: 2, B.TUNE_SHARED_LDS_KB: 52, B.TUNE_WAIT_LIMIT_US: 250000,
-                B.TUNE_LONG_ROWS: -1, B.TUNE_GEMM_SPLITS: -1, B.TUNE_FUSED_MIN_B_ITEMS: 1280}
+                B.TUNE_LONG_ROWS: -1, B.TUNE_GEMM_SPLITS: -1, B.TUNE_FUSED_MIN_B_ITEMS: 1024}
     assert len(defaults) == 14
     for knob, val in defaults.items():
         assert B.dbf_tuning_get(knob) == val
