@@ -68,11 +68,10 @@ enum {
                           k = 2048), DBF_GEMV_MFMA_SPLIT for a single layer and shorter groups (measured
                           faster there: in one launch their A-stage workgroups would all sit waiting
                           next to the B stage), long rows of short launches cut into column pieces.
-                          Batches of 2 and more -- and
-                          groups of layers with long stage inputs at batch 1 too, see
-                          DBF_TUNE_LONG_ROWS -- quantise each stage input once per call: four
-                          launches (quantise x, B stage, quantise t, A stage).  Every choice gives
-                          the same bits as DBF_GEMV_MFMA and DBF_GEMV_MFMA_SPLIT                  */
+                          Batches of 2 and more -- and groups of layers with long stage inputs at
+                          batch 1 too, see DBF_TUNE_LONG_ROWS -- quantise each stage input once per
+                          call: four launches (quantise x, B stage, quantise t, A stage).  Every
+                          choice gives the same bits as DBF_GEMV_MFMA and DBF_GEMV_MFMA_SPLIT     */
     DBF_GEMV_VALU = 1, /* fp32 add/subtract per sign bit on the vector ALU (exact fp32 sums) */
     DBF_GEMV_MFMA = 2, /* sign bytes fed to the int8 matrix cores as the adder; the input
                           vector of each stage is rounded once to 16-bit fixed point.  Both
