@@ -132,7 +132,7 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
             it.pieces = pieces;
             it.acc_stride = acc_stride;
             it.acc = acc + (size_t)rt * DBF_TILE_ROWS;
-            it.cnt = cnt + rt;
+            it.cnt = cnt + (size_t)rt * DBF_PIECE_CNT_STRIDE;
             it.q_in = st.q_in;
             out.push_back(it);
         }
@@ -349,7 +349,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     p->piece_row_tiles = (int)(rtB > rtA ? rtB : rtA);
     const size_t acc_ints = cut ? (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * (size_t)(rtB + rtA) : 0;
-    const size_t cnt_ints = cut ? (size_t)(rtB + rtA) : 0;
+    const size_t cnt_ints = cut ? (size_t)(rtB + rtA) * DBF_PIECE_CNT_STRIDE : 0;
 
     size_t off = 0;
     const size_t o_sB = off;  off = align_up(off + sizeof(DbfStage) * n, 256);
@@ -374,7 +374,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
             const int stride = sB[i].n_rt * DBF_TILE_ROWS;
             append_piece_items(items_p, sB[i], i, false, 0, pcB[i],
                                acc0 + (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * row_tiles_before, stride,
-                               cnt0 + row_tiles_before);
+                               cnt0 + (size_t)row_tiles_before * DBF_PIECE_CNT_STRIDE);
             row_tiles_before += sB[i].n_rt;
         }
         nBp = (int)items_p.size();
@@ -382,7 +382,7 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
             const int stride = sA[i].n_rt * DBF_TILE_ROWS;
             append_piece_items(items_p, sA[i], i, true, sB[i].n_rt, pcA[i],
                                acc0 + (size_t)DBF_PIECES_MAX_BATCH * DBF_TILE_ROWS * row_tiles_before, stride,
-                               cnt0 + row_tiles_before);
+                               cnt0 + (size_t)row_tiles_before * DBF_PIECE_CNT_STRIDE);
             row_tiles_before += sA[i].n_rt;
         }
     }

@@ -48,6 +48,7 @@ constexpr int QI_TSPLIT = QI_TOKENS / (16 * QI_TB);       // token slices of a r
 constexpr int QI_WAVES = QI_ROWTILES * QI_TSPLIT;
 constexpr int QI_OCC = 2;           // wavefronts per SIMD (the accumulators leave room for no more)
 constexpr int QI_THREADS = 64 * QI_WAVES;
+constexpr int SPLIT_CNT_STRIDE = 32;  // unsigned ints between the arrival counters of two column-split groups: 128 bytes
 constexpr int QI_STAGE_BYTES = 2 * QI_TOKENS * 64 / QI_THREADS;  // operand bytes a thread stages per step
 static_assert(QI_STAGE_BYTES == 32, "staging is two 16-byte pieces per thread");
 
@@ -486,7 +487,7 @@ void dbf_gemm_i8_stage_kernel(const StageArgs a) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's adds have been performed ...
         __syncthreads();                                  // ... and so have the workgroup's
         if (tid == 0) {
-            unsigned* cnt = a.cnt + (size_t)by * gridDim.x + bx;
+            unsigned* cnt = a.cnt + ((size_t)by * gridDim.x + bx) * SPLIT_CNT_STRIDE;  // (a cache line per counter)
             const unsigned before = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             last_split = before == (unsigned)a.splits - 1u;
             if (last_split) __hip_atomic_store(cnt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -621,7 +622,7 @@ inline I8Workspace i8_workspace(const dbf_layer* L, int T) {
         const size_t rg2 = (dbf_row_tiles(L->n_out) + QI_ROWTILES - 1) / QI_ROWTILES;
         const size_t rg = rg1 > rg2 ? rg1 : rg2, tb = Tp / QI_TOKENS;
         off = align256(off + rg * tb * (QI_ROWTILES * DBF_TILE_ROWS) * QI_TOKENS * 4);
-        w.cnt = off;  off = align256(off + rg * tb * 4);
+        w.cnt = off;  off = align256(off + rg * tb * 4 * SPLIT_CNT_STRIDE);
     }
     w.total = off;
     return w;

@@ -11,6 +11,9 @@
 #define DBF_SYNC_STRIDE 64  /* 64-bit words between the per-layer counters of a plan (DbfPlan::d_sync): 512 bytes, so
                               that polls of different counters spread over the memory channels */
 #define DBF_PIECES_MAX_BATCH 2  /* largest batch for which row tiles may be cut into column pieces */
+#define DBF_PIECE_CNT_STRIDE 32 /* ints between the arrival counters of two row tiles: 128 bytes, a cache line each (side by side
+                                   the finishing atomics of a launch's workgroups queued at one line: a 4096 x 11008 layer
+                                   alone 18.1 -> 17.0 us, 4096 x 14336 19.2 -> 18.0) */
 
 static inline int dbf_row_tiles(int rows) { return (rows + DBF_TILE_ROWS - 1) / DBF_TILE_ROWS; }
 static inline int dbf_col_tiles(int cols) { return (cols + DBF_TILE_COLS - 1) / DBF_TILE_COLS; }
