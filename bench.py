@@ -138,6 +138,9 @@ def main():
                     help="only the SVID projection measurement (dbf_svid on a 4096 x 4096 and an 11008 x 4096 matrix)")
     ap.add_argument("--admm", action="store_true",
                     help="only the ADMM update measurement (dbf_admm_step for a 4096 x 4096 weight at 1 and 2 bits)")
+    ap.add_argument("--decoder-pass", action="store_true",
+                    help="only the dependent token pass: the 224 linear layers of the Llama-2-7B-shaped decoder as 128 dependent "
+                         "calls (q,k,v / o / gate,up / down per block), eager and as one captured graph, batch 1, 4, 16")
     ap.add_argument("--stack-sizes", action="store_true",
                     help="only the call time of stacks of 1 ... 128 layers at batch 1 ... 16 (default kind): where a call "
                          "is bound by its launches and where by the stream")
@@ -187,6 +190,9 @@ def main():
         return
     if args.admm:
         print(json.dumps({"admm": admm_bench(B, I, torch, np, torch.cuda.current_stream().cuda_stream, proto)}))
+        return
+    if args.decoder_pass:
+        print(json.dumps({"decoder_pass": decoder_pass_bench(B, I, torch, np, proto)}))
         return
     if args.stack_sizes:
         print(json.dumps({"stack_sizes": stack_sizes_bench(B, I, torch, np, kind, torch.cuda.current_stream().cuda_stream, proto)}))
@@ -369,6 +375,13 @@ def main():
             out["config5_stack"] = config5_bench(B, I, torch, np, batch, kind, stream, proto)
         except Exception as exc:  # reported, never hidden
             out["config5_stack"] = {"error": repr(exc)}
+
+    # ---- the same 224 layers as a decoder has to call them: 128 dependent calls per token pass -------------------
+    if args.workload == "config2" and not args.no_config5 and not args.stream_only and batch == 1:
+        try:
+            out["decoder_pass_dependent_calls"] = decoder_pass_bench(B, I, torch, np, proto)
+        except Exception as exc:
+            out["decoder_pass_dependent_calls"] = {"error": repr(exc)}
 
     # ---- the MLP shapes of configuration 3 (gate / up and down projection at ~1 and ~2 bits per weight) ----------
     if args.workload == "config2" and not args.no_table4 and not args.stream_only:
@@ -595,6 +608,71 @@ def table4_bench(B, I, torch, np, batch, kind, stream, proto, bits_only=None, cf
             "note": "isolated = one dbf_gemv call, cache warm (p50 of 200 event pairs); stream = distinct copies of "
                     "the layer in one dbf_stack_gemv call per step, signs read from HBM; paper column: its Table 4 "
                     "on an RTX 4090, another machine, context only"}
+
+
+def decoder_pass_bench(B, I, torch, np, proto, n_blocks=32):
+    """The linear layers of a Llama-2-7B-shaped decoder at 1.5 bits per weight run the way a decoder has to run them:
+    per block four DEPENDENT calls -- the group q, k, v on one input, o on (a stand-in for) the attention output, the
+    group gate, up on o's output, down on gate's output, whose result is the next block's input -- i.e. 128 calls and
+    (at batch 1) 256 launches per token pass, against ONE launch when the 224 layers are independent (config 5).
+    Timed eagerly and as one captured HIP graph; attention, norms and activations are left out (stand-ins read what
+    the previous call wrote, so every call waits for its predecessor)."""
+    shapes = dict(sq=dict(n_in=4096, n_out=4096, k=3072), up=dict(n_in=4096, n_out=11008, k=4477),
+                  down=dict(n_in=11008, n_out=4096, k=4477))
+    layers, blocks = [], []
+    for b in range(n_blocks):
+        def mk(name, idx):
+            sp = shapes[name]
+            L = I.make_layer(sp["n_in"], sp["n_out"], sp["k"], seed=I.seed_for(5, 2000 + 8 * b + idx))
+            layer = B.dbf_pack_bits(sp["n_in"], sp["n_out"], sp["k"], L.A_bits, L.B_bits, L.a, L.m, L.b)
+            layers.append(layer)
+            return layer
+        q, k_, v, o = mk("sq", 0), mk("sq", 1), mk("sq", 2), mk("sq", 3)
+        g, u, d = mk("up", 4), mk("up", 5), mk("down", 6)
+        blocks.append((B.dbf_stack_create_grouped([q, k_, v], [3]), B.dbf_stack_create([o]),
+                       B.dbf_stack_create_grouped([g, u], [2]), B.dbf_stack_create([d])))
+    nbytes1 = float(n_blocks * (4 * algorithmic_bytes(4096, 4096, 3072, 1)[0] + 2 * algorithmic_bytes(4096, 11008, 4477, 1)[0]
+                                + algorithmic_bytes(11008, 4096, 4477, 1)[0]))
+    res = {"blocks": n_blocks, "calls_per_pass": 4 * n_blocks}
+    try:
+        for batch in (1, 4, 16):
+            h = [torch.randn(batch * 4096, device="cuda").half() for _ in range(2)]
+            yqkv = torch.zeros(3 * batch * 4096, dtype=torch.float16, device="cuda")
+            yo = torch.zeros(batch * 4096, dtype=torch.float16, device="cuda")
+            ygu = torch.zeros(2 * batch * 11008, dtype=torch.float16, device="cuda")
+
+            def token_pass(stream):
+                for i, (s1, s2, s3, s4) in enumerate(blocks):
+                    B.dbf_stack_gemv(s1, h[i & 1].data_ptr(), yqkv.data_ptr(), batch, stream)
+                    B.dbf_stack_gemv(s2, yqkv.data_ptr(), yo.data_ptr(), batch, stream)
+                    B.dbf_stack_gemv(s3, yo.data_ptr(), ygu.data_ptr(), batch, stream)
+                    B.dbf_stack_gemv(s4, ygu.data_ptr(), h[(i + 1) & 1].data_ptr(), batch, stream)
+
+            cur = torch.cuda.current_stream().cuda_stream
+            ms_eager, protocol = proto.run(lambda: token_pass(cur))
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                graph.capture_begin()
+                token_pass(side.cuda_stream)
+                graph.capture_end()
+            torch.cuda.current_stream().wait_stream(side)
+            ms_graph, _ = proto.run(graph.replay)
+            del graph
+            res["batch%d" % batch] = {"eager_us_per_pass": round(ms_eager * 1e3, 1), "graph_us_per_pass": round(ms_graph * 1e3, 1),
+                                      "graph_us_per_call": round(ms_graph * 1e3 / (4 * n_blocks), 2),
+                                      "tokens_per_s_graph": round(batch * 1e3 / ms_graph, 1), "protocol": protocol}
+        res["sign_and_vector_bytes_per_pass"] = nbytes1
+        res["note"] = ("dependent calls: each reads what the previous one wrote; the independent 224-layer stack of config 5 "
+                       "streams the same bytes in one launch (config5_stack)")
+        return res
+    finally:
+        for st in blocks:
+            for s_ in st:
+                s_.close()
+        for l in layers:
+            l.close()
 
 
 def stack_sizes_bench(B, I, torch, np, kind, stream, proto):
