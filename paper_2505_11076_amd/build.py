@@ -34,6 +34,9 @@ FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    # kernel arguments arrive in scalar registers with the wavefront instead of being loaded by its first
+    # instructions: one memory round trip less at the head of every kernel (0.25 us per launch of a lone layer)
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
 ]
 
 
