@@ -262,9 +262,10 @@ def main():
         # duration is taken from the HIP events around the back-to-back timed steps (the
         # per-launch events of the timed entry point add a few microseconds of launch latency).
         if batch == 1 or args.kind != "auto":
-            # (<operand column groups, column pieces, shared quantised input, single chunk>: rows of up to
-            #  14080 columns stay in LDS as one chunk at batch 1, which all benchmark shapes are)
-            dom, dom_ms, dom_bytes = ("dbf_items_mfma_kernel<%d, false, 0, %s> (B and A stages fused)"
+            # (<operand column groups, column pieces, shared quantised input, single chunk, wavefronts per
+            #  workgroup>: rows of up to 14080 columns stay in LDS as one chunk at batch 1, which all benchmark
+            #  shapes are)
+            dom, dom_ms, dom_bytes = ("dbf_items_mfma_kernel<%d, false, 0, %s, 4> (B and A stages fused)"
                                       % (ncg, "true" if batch == 1 else "true|false")), ms_per_step, bytes_layer * R
         elif msB_avg >= msA_avg:  # batches of 2 and more: input quantiser + items, per stage
             dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2|3, false>)" % ncg, msB_avg, bytes_b * R

@@ -393,7 +393,10 @@ enum {
     DBF_TUNE_FUSED_MIN_B_ITEMS = 13,  /* DBF_GEMV_AUTO at batch 1 runs both stages of a group of layers in one launch
                                          only if the B stage has at least this many workgroups, else in a launch per
                                          stage; 0..2^20 (default 1024: what the chip holds at once)                  */
-    DBF_TUNE_COUNT_ = 14
+    DBF_TUNE_WIDE_WG_MAX_ITEMS = 14,  /* a launch of at most this many self-quantising whole-row workgroups at batch
+                                         1..8, over stage inputs of 2048 columns or more, gives each 8 wavefronts
+                                         instead of 4; 0..2^20 (default 256: one workgroup per compute unit at most) */
+    DBF_TUNE_COUNT_ = 15
 };
 int dbf_tuning_set(int knob, int value);
 int dbf_tuning_get(int knob);

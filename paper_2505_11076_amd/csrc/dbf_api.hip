@@ -77,6 +77,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {-1, -1, -1, 1},              // DBF_TUNE_LONG_ROWS
     {-1, -1, -1, 1024},           // DBF_TUNE_GEMM_SPLITS
     {1024, 1024, 0, 1 << 20},     // DBF_TUNE_FUSED_MIN_B_ITEMS
+    {256, 256, 0, 1 << 20},       // DBF_TUNE_WIDE_WG_MAX_ITEMS
 };
 
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads

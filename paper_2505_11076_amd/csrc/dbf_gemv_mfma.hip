@@ -101,7 +101,8 @@ struct Misc {
     float scale[DBF_MAX_BATCH];    // u ~= q * scale
     float inv[DBF_MAX_BATCH];      // q = rint(u * inv)
     int sigma[DBF_MAX_BATCH];      // sum over all columns of q
-    float wmax[4][DBF_MAX_BATCH];  // per-wavefront max|u|
+    float wmax[8][DBF_MAX_BATCH];  // per-wavefront max|u| (wavefronts 4-7, where a workgroup has them, take no part in
+                                   // the input passes and leave zeros)
     uint16_t rscale[DBF_MAX_SPAN * DBF_TILE_ROWS];  // fp16 row scales of this workgroup's rows
     int last;                      // column pieces: this workgroup was the last of its row tile to arrive
     int gave_up;                   // the wait for the layer's B stage ended at its bound: outputs become NaN
@@ -334,11 +335,16 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // SINGLE: every item of the launch streams its columns as one chunk (the launcher knows): the first group of
 // tiles of a row tile then starts from zero accumulators by giving the matrix instructions a zero addend,
 // and the 32 accumulator registers are never cleared (2 of 47 vector instructions per tile).
-template <int NCG, bool PIECES, int SHARED, bool SINGLE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
+// WAVES: wavefronts per workgroup.  Eight for launches of so few items that a compute unit gets one workgroup at
+// most (a layer alone, a group of three): a wavefront then walks every eighth column tile of a row tile instead of
+// every fourth, and two wavefronts per SIMD fill each other's waits.  Wavefronts 4-7 only stream tiles: the input
+// passes and the epilogue are those of the four-wavefront kernel, done by threads 0-255.
+template <int NCG, bool PIECES, int SHARED, bool SINGLE, int WAVES = 4>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
                            uint16_t* __restrict__ y_base, int batch, int ch_tiles, int wait_limit_us) {
+    static_assert(WAVES == 4 || (WAVES == 8 && SHARED == 0 && !PIECES), "eight wavefronts: self-quantising whole-row items only");
     extern __shared__ __align__(16) unsigned char smem[];
     const int ncols = 2 * batch;
     const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
@@ -385,7 +391,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     const unsigned lane_off = lane * 16;
 
     // Tile cursor of the prefetcher: row tile p_rt (local), step p_i of the chunk.  Step i of a
-    // wavefront is column tile c0 + w + 4*i; steps are padded to a multiple of PF per row tile.
+    // wavefront is column tile c0 + w + WAVES*i; steps are padded to a multiple of PF per row tile.
     //
     // The loads are issued by inline assembly and waited for by hand (wait_slot): the compiler
     // does not see them, so it cannot serialise the pipeline with a full vmcnt(0) wait at the
@@ -399,8 +405,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     const int n_pieces = PIECES ? it.pieces : 1;
     int c0 = ct_first;
     int cend = min(ct_end, c0 + ch_tiles);
-    // (steps of a wavefront per row tile and chunk: every fourth column tile, or with ROWS every one)
-    auto steps_of = [&](int n_tiles) { return ((ROWS ? n_tiles : (n_tiles + 3) >> 2) + PF - 1) / PF * PF; };
+    // (steps of a wavefront per row tile and chunk: every WAVES-th column tile, or with ROWS every one)
+    auto steps_of = [&](int n_tiles) { return ((ROWS ? n_tiles : (n_tiles + WAVES - 1) / WAVES) + PF - 1) / PF * PF; };
     int steps = steps_of(cend - c0);
     int p_rt = 0, p_i = 0;  // (ROWS: p_rt counts groups of four row tiles, of which this wavefront takes the w-th)
     v4u buf[PF];
@@ -452,7 +458,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     };
     auto fetch = [&](int j) {
         v4u& dst = buf[j];
-        const int ct = ROWS ? c0 + p_i : c0 + w + 4 * p_i;
+        const int ct = ROWS ? c0 + p_i : c0 + w + WAVES * p_i;
         const int rt = ROWS ? 4 * p_rt + w : p_rt;
         const int ok = (int)(rt < it.nrt) & (int)(ct < cend);
         const unsigned off = (unsigned)(rt * it.n_ct + ct) * DBF_TILE_BYTES;
@@ -524,7 +530,11 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     // ---- prologue ------------------------------------------------------------------------------
     Ctx cx;
     cx.misc = misc;  cx.xq = xq;  cx.x = x;  cx.chs = chs;  cx.tstride = 0;
-    cx.tid = tid;  cx.lane = lane;  cx.w = w;  cx.batch = batch;
+    // (wavefronts 4-7 of an eight-wavefront workgroup stream tiles only.  For the input passes they get a thread index
+    //  beyond every range those test, so they only keep the barriers company; of the prologue's loads they issue
+    //  the tiles alone -- its wait counts back from the youngest load)
+    const bool streams_only = WAVES > 4 && tid >= 256;
+    cx.tid = streams_only ? (1 << 28) : tid;  cx.lane = lane;  cx.w = w;  cx.batch = batch;
     cx.nvec = it.n_ct * 8;
     cx.nvec_x = it.cols >> 3;
     cx.fast = stage_a || ((it.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
@@ -541,7 +551,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     constexpr int RS_WORDS = DBF_MAX_SPAN * DBF_TILE_ROWS / 2 / 256;
     unsigned rs_reg[RS_WORDS];
     v4u in0[UNR], in1[UNR];
-    {
+    if (!streams_only) {
         const int rs_last = it.nrt * (DBF_TILE_ROWS / 2) - 1;
 #pragma unroll
         for (int q = 0; q < RS_WORDS; ++q) {
@@ -576,13 +586,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
     for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(in0[j]), "+v"(in1[j]));
 
-    for (int i = tid; i < N_RED * RB_STRIDE * ncols; i += 256) red[i] = 0;
+    for (int i = tid; i < N_RED * RB_STRIDE * ncols; i += 64 * WAVES) red[i] = 0;
     if (tid < DBF_MAX_BATCH) misc->sigma[tid] = 0;
     // row scales: read by the epilogues, which come after several barriers
 #pragma unroll
     for (int q = 0; q < RS_WORDS; ++q) {
         const int idx = tid + 256 * q;
-        if (2 * idx < it.nrt * DBF_TILE_ROWS) reinterpret_cast<unsigned*>(misc->rscale)[idx] = rs_reg[q];
+        if (!streams_only && 2 * idx < it.nrt * DBF_TILE_ROWS) reinterpret_cast<unsigned*>(misc->rscale)[idx] = rs_reg[q];
     }
 
     if (SHARED) {
@@ -658,16 +668,16 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             // (one group = PF tiles; `fresh`: the group's first tile starts the row tile's sums)
             auto group = [&](auto fresh) {
                 constexpr bool FRESH = decltype(fresh)::value;
-                constexpr int CT_STEP = ROWS ? 1 : 4;  // column tiles from one step of a wavefront to the next
+                constexpr int CT_STEP = ROWS ? 1 : WAVES;  // column tiles from one step of a wavefront to the next
                 const int g_rt = ROWS ? 4 * p_rt + w : p_rt;
                 const int g_ok = (int)(g_rt < it.nrt);
-                const int g_ct = ROWS ? c0 + p_i : c0 + w + 4 * p_i;
+                const int g_ct = ROWS ? c0 + p_i : c0 + w + WAVES * p_i;
                 const unsigned g_off = (unsigned)(g_rt * it.n_ct + g_ct) * DBF_TILE_BYTES;
 #pragma unroll
                 for (int j = 0; j < PF; ++j) {
 #pragma unroll
                     for (int gi = 0; gi < NCG; ++gi)
-                        if (!RING) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * 4 * DBF_TILE_COLS);
+                        if (!RING) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * WAVES * DBF_TILE_COLS);
                     wait_slot(j);
 #pragma unroll
                     for (int s = 0; s < 8; ++s) {
@@ -687,7 +697,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                              g_ok & (int)(g_ct + CT_STEP * j < cend));
                 }
 #pragma unroll
-                for (int gi = 0; gi < NCG; ++gi) xp[gi] += PF * 4 * DBF_TILE_COLS;
+                for (int gi = 0; gi < NCG; ++gi) xp[gi] += PF * WAVES * DBF_TILE_COLS;
                 const int wrap = (int)(p_i + PF == steps);  // (steps is a multiple of PF)
                 p_i = wrap ? 0 : p_i + PF;
                 p_rt += wrap;
@@ -706,7 +716,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             if (rtl + RT_STEP >= it.nrt) retire_ring();
             if (!last_chunk) continue;  // (only with nrt == 1) keep accumulating over chunks
 
-            // ---- combine the four wavefronts (integer adds: exact, order independent) -----
+            // ---- combine the wavefronts (integer adds: exact, order independent) -----
             // acc[gi][s][i] of lane (g, c) is row 16*s + 4*g + i, column 16*gi + c.  The two
             // reduction buffers alternate, so one barrier per row tile is enough: a buffer is
             // cleared by its readers one barrier before anybody adds to it again.
@@ -735,7 +745,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                 if (ROWS) rb = red + r4 * RB_STRIDE * ncols;
                 const int row = it.row0 + rte * DBF_TILE_ROWS + rho;
                 const float rscale = half_bits_to_float(misc->rscale[rte * DBF_TILE_ROWS + rho]);
-                for (int bi = tid >> 7; bi < batch; bi += 2) {
+                // (threads 0-255; those of wavefronts 4-7 start beyond the batch)
+                for (int bi = streams_only ? batch : tid >> 7; bi < batch; bi += 2) {
                     int* ph = &rb[(2 * bi) * RB_STRIDE + rho];  // column-major: [operand column][row of the tile]
                     int vh = ph[0], vl = ph[RB_STRIDE];
                     ph[0] = 0;
@@ -895,6 +906,9 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
     }
 }
 
+constexpr size_t WIDE_WG_SLACK = 32 * DBF_TILE_COLS;  // extra LDS of an eight-wavefront workgroup (see the launcher)
+constexpr int WIDE_WG_MIN_COL_TILES = 32;         // rows shorter than this keep four wavefronts
+
 size_t mfma_smem_bytes(int batch, int ch_tiles, int shared_q) {
     const int ncols = 2 * batch;
     const size_t xq = shared_q >= 2 ? 0 : ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
@@ -989,6 +1003,14 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned lon
     else if (pieces)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
+    else if (batch <= 8 && ch_tiles >= dbf_col_tiles(max_cols) && n_items <= dbf_tune(DBF_TUNE_WIDE_WG_MAX_ITEMS) &&
+             dbf_col_tiles(max_cols) >= WIDE_WG_MIN_COL_TILES)
+        // (few items of long rows: eight wavefronts each.  One layer alone, back to back: 4096 x 4096 11.6 -> 11.1 us,
+        //  2048 columns 9.4 -> 9.1, 512 columns 8.3 -> 9.1: the wider workgroup costs 0.4 us to start.  A wavefront's
+        //  operand reads for the padded steps at the end of a row tile run up to 31 column tiles past the operand
+        //  row: LDS the workgroup owns)
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, true, 8>), dim3(n_items), dim3(512), smem + WIDE_WG_SLACK,
+                           stream, items, sync, n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
     else if (batch <= 8 && ch_tiles >= dbf_col_tiles(max_cols))
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, true>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);

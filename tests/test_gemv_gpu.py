@@ -412,6 +412,57 @@ def test_column_pieces_equal_whole_rows_bit_for_bit(batch):
                 "whole rows %dx%d" % (L.n_out, L.n_in))
 
 
+@pytest.mark.parametrize("batch", [1, 3, 4])
+def test_eight_wavefront_workgroups_equal_four_bit_for_bit(batch):
+    """A launch of few whole-row items over long stage inputs gives every workgroup eight wavefronts instead of
+    four (wavefronts 4-7 only stream tiles; integer sums, so the order of the adds does not matter).  The results
+    must not depend on the width: a layer alone and a stack of three, every workgroup quantising its own input
+    (at batches 3 and 4 too, by the knob), rows in one pass and rows in the general two-pass prologue."""
+    shapes = [(4096, 600, 2100), (2300, 520, 3100), (6500, 300, 2050)]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 1200 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(batch, L.n_in, I.seed_for(5, 1210 + i)) for i, L in enumerate(Ls)]
+
+    def run(max_items):
+        B.dbf_tuning_reset()
+        B.dbf_tuning_set(B.TUNE_COL_PIECES, 0)
+        B.dbf_tuning_set(B.TUNE_SHARED_MIN_BATCH, 17)
+        B.dbf_tuning_set(B.TUNE_WIDE_WG_MAX_ITEMS, max_items)
+        layers = [G.pack(L) for L in Ls]
+        stack = B.dbf_stack_create(layers)
+        outs = []
+        try:
+            for rep in range(2):
+                for L, X, layer in zip(Ls, Xs, layers):
+                    y = torch.full((batch, L.n_out), float("nan"), dtype=torch.float16, device="cuda")
+                    B.dbf_gemv(layer, G.f16_to_dev(X).data_ptr(), y.data_ptr(), batch, G.stream_handle())
+                    torch.cuda.synchronize()
+                    outs.append(y.cpu().view(torch.int16).numpy().copy())
+                x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+                y_all = torch.full((sum(batch * L.n_out for L in Ls),), float("nan"), dtype=torch.float16, device="cuda")
+                for kind in (B.GEMV_AUTO, B.GEMV_MFMA):
+                    B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), batch, G.stream_handle(), kind)
+                    torch.cuda.synchronize()
+                    outs.append(y_all.cpu().view(torch.int16).numpy().copy())
+            assert B.dbf_stack_sync_timeouts(stack) == 0
+        finally:
+            stack.close()
+            for l in layers:
+                l.close()
+            B.dbf_tuning_reset()
+        return outs
+
+    G.say("workgroup width: four wavefronts")
+    four = run(0)
+    G.say("workgroup width: eight wavefronts")
+    eight = run(1 << 20)
+    assert len(four) == len(eight)
+    for i, (a, b) in enumerate(zip(four, eight)):
+        assert np.array_equal(a, b), i
+    for L, X, y_bits in zip(Ls, Xs, eight[:3]):
+        G.check(O.f16_bits_to_f64(y_bits.view(np.uint16)).reshape(batch, L.n_out), O.forward_from_packed(X, L, "staged"),
+                "eight wavefronts %dx%d" % (L.n_out, L.n_in))
+
+
 @pytest.mark.parametrize("batch", [1, 3])
 def test_groups_of_layers_sharing_one_input(batch):
     """q, k, v read one activation vector, gate and up another: a grouped stack takes one x block
