@@ -396,7 +396,12 @@ enum {
     DBF_TUNE_WIDE_WG_MAX_ITEMS = 14,  /* a launch of at most this many self-quantising whole-row workgroups at batch
                                          1..8, over stage inputs of 2048 columns or more, gives each 8 wavefronts
                                          instead of 4; 0..2^20 (default 256: one workgroup per compute unit at most) */
-    DBF_TUNE_COUNT_ = 15
+    DBF_TUNE_FP4_MAX_ITEMS = 15,      /* batch-1 launches of at most this many whole-row workgroups over stage inputs of at
+                                         most 4096 columns (2048 at least), all readable in 16-byte pieces, feed the matrix cores fp4
+                                         sign operands and bf6 digits of the input (same bits out, half the
+                                         instructions per tile, but two workgroups per compute unit at most: for
+                                         launches that do not fill the chip); 0..2^20 (default 256), 0: never       */
+    DBF_TUNE_COUNT_ = 16
 };
 int dbf_tuning_set(int knob, int value);
 int dbf_tuning_get(int knob);

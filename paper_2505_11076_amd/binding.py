@@ -22,7 +22,8 @@ GEMV_AUTO, GEMV_VALU, GEMV_MFMA, GEMV_MFMA_SPLIT = 0, 1, 2, 3
 GEMM_AUTO, GEMM_I8 = 0, 2
 (TUNE_COL_PIECES, TUNE_PIECE_TARGET, TUNE_PIECE_MIN_TILES, TUNE_PIECE_NEVER_TILES, TUNE_PIECE_MAX_ROW_TILES,
  TUNE_STACK_SPAN_B, TUNE_STACK_SPAN_A, TUNE_SHARED_Q, TUNE_SHARED_MIN_BATCH, TUNE_SHARED_LDS_KB,
- TUNE_WAIT_LIMIT_US, TUNE_LONG_ROWS, TUNE_GEMM_SPLITS, TUNE_FUSED_MIN_B_ITEMS, TUNE_WIDE_WG_MAX_ITEMS) = range(15)
+ TUNE_WAIT_LIMIT_US, TUNE_LONG_ROWS, TUNE_GEMM_SPLITS, TUNE_FUSED_MIN_B_ITEMS, TUNE_WIDE_WG_MAX_ITEMS,
+ TUNE_FP4_MAX_ITEMS) = range(16)
 MAX_BATCH = 16
 GEMM_STATIC_BYTES = 32 << 20  # DBF_GEMM_STATIC_BYTES
 

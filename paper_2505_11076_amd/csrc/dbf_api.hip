@@ -78,6 +78,7 @@ Knob g_knobs[DBF_TUNE_COUNT_] = {
     {-1, -1, -1, 1024},           // DBF_TUNE_GEMM_SPLITS
     {1024, 1024, 0, 1 << 20},     // DBF_TUNE_FUSED_MIN_B_ITEMS
     {256, 256, 0, 1 << 20},       // DBF_TUNE_WIDE_WG_MAX_ITEMS
+    {256, 256, 0, 1 << 20},       // DBF_TUNE_FP4_MAX_ITEMS
 };
 
 // Column pieces.  Cutting pays only for long rows: every piece pays the workgroup's prologue (it reads
@@ -245,6 +246,9 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
         }
         p->long_rows = lr == 1 || (lr < 0 && n > 1 && 2 * bytes_long > bytes_all);
     }
+    p->x_vec_ok = 1;
+    for (int i = 0; i < n; ++i)
+        if ((sB[i].cols & 7) != 0 || (sB[i].x_off & 7) != 0) p->x_vec_ok = 0;
     const std::vector<int> one(1, 1);
     // row tiles per item: the given pattern, or (empty pattern) chosen per layer from the size of the launch
     long long tiles_B = 0, tiles_A = 0;
@@ -632,23 +636,25 @@ int launch_plan(int kind, const DbfPlan& p, const void* x, void* y, int batch, h
         pieces = 1;
     }
     if (pieces_ok && p.n_layers > 1 && nB >= FUSED_MIN_B_ITEMS) kind = DBF_GEMV_MFMA;
+    // (batch 1: can every x row be read in 16-byte pieces?  Then rows of up to 6144 columns all take the one-pass prologue)
+    const int one_pass_rows = batch == 1 && p.x_vec_ok && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
     if (shared_q) {
         // Four launches: quantise x, B items, quantise t, A items.
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesB, p.n_layers, 0, x, batch, stream));
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, wait_us, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, 0, wait_us, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         DBF_HIP_TRY(dbf_launch_quantise_inputs(p.d_stagesA, p.n_layers, 1, x, batch, stream));
-        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, wait_us, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, 0, shared_q, 0, wait_us, stream));
         return DBF_OK;
     }
     if (kind == DBF_GEMV_MFMA) {
-        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, 0, wait_us, stream));
+        DBF_HIP_TRY(dbf_launch_items_mfma(items, nB + nA, p.d_sync, p.n_layers, 1, x, y, batch, max_cols, pieces, 0, one_pass_rows, wait_us, stream));
         if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
         return DBF_OK;
     }
-    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, wait_us, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items, nB, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, one_pass_rows, wait_us, stream));
     if (mid) DBF_HIP_TRY(hipEventRecord(mid, stream));
-    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, wait_us, stream));
+    DBF_HIP_TRY(dbf_launch_items_mfma(items + nB, nA, p.d_sync, p.n_layers, 0, x, y, batch, max_cols, pieces, 0, one_pass_rows, wait_us, stream));
     return DBF_OK;
 }
 

@@ -73,8 +73,20 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned int v6u __attribute__((ext_vector_type(6)));
 
-constexpr int PF = DBF_PF;         // tiles of sign bits kept in flight per wavefront
+constexpr int PF_DEFAULT = DBF_PF;  // tiles of sign bits kept in flight per wavefront
+#ifndef DBF_PF_F4
+#define DBF_PF_F4 4
+#endif
+#ifndef DBF_WAVES_F4
+#define DBF_WAVES_F4 8
+#endif
+constexpr int WAVES_F4 = DBF_WAVES_F4;  // wavefronts per workgroup of the fp4 x bf6 form
+constexpr int PF_F4 = DBF_PF_F4;    // the same in the fp4 x bf6 form, whose 48 KiB of operand rows leave room for two workgroups
+                                    // per compute unit only: fewer wavefronts, each with more in flight
 constexpr int UNR = DBF_UNR;       // independent 16-byte loads per thread in the prologue
 constexpr int WIDE = 3;            // the same in the input passes of the kernel variant for wide rows and column pieces
 constexpr float QMAX = 32512.f;    // 127*256: largest |q| so that hi and lo fit int8
@@ -87,6 +99,17 @@ constexpr int XQ_PAD = 16;         // bytes of padding per operand row (LDS bank
 // operand columns share a bank, which at 16 live columns (batch 8) made the reduction as long as the streaming.
 constexpr int RB_STRIDE = DBF_RB_STRIDE;
 constexpr unsigned OOB = 0x80000000u;  // buffer offset that is out of range for any span
+// The fp4 x bf6 form of the operand (F4, batch 1): a stage input value q = d0 + 16 d1 + 256 d2 + 4096 d3 with signed hexadecimal
+// digits (d0..d2 in -8..7, d3 in -8..8), each a bf6 (E3M2) number, which holds the integers up to 8 exactly.  LDS keeps eight
+// operand rows: row p (0..3) has, per column, the pair (d_p, 0) of 6-bit fields, row 4 + p the pair (0, d_p) -- 12 bits per
+// column, 96 bytes per column tile.  The pair lines up with the two nibbles of a sign byte (planes 0-3, planes 4-7).
+// In LDS a column tile's 768 bytes are laid out word by word for the lanes that read them: lane (row r, 16-column group
+// g) finds word k (0..5) of its 24 bytes at k * 128 + (4 r + g) * 4, so that every read instruction of a wavefront takes
+// 32 different words from 32 different banks (with whole 24-byte runs per lane, however arranged, the reads cost
+// three times their minimum in bank conflicts, and the LDS bounded the kernel).  A tile's block starts 784 bytes after
+// the previous one's, which spreads the prologue's writes over the banks.
+constexpr int F4_TILE_BYTES = 784;
+constexpr int F4_MAX_COL_TILES = 64;   // 8 rows of 64 column tiles: 48 KiB, three workgroups per compute unit
 constexpr uint16_t HALF_QNAN = 0x7E00; // what a workgroup that gave up its wait stores
 
 __device__ inline float half_bits_to_float(uint16_t h) {
@@ -180,6 +203,43 @@ struct InputVec {
         *reinterpret_cast<uint2*>(lo_dst) = make_uint2(lo4[0], lo4[1]);
         return sum;
     }
+    // The same eight q as signed hexadecimal digits in bf6, into the eight operand rows of the fp4 x bf6 form (row r at
+    // the words the lanes of the matrix instruction read, see F4_TILE_BYTES); returns the sum of the q.  The conversion
+    // instruction takes two vectors of 16 floats and interleaves them: (digits, zeros) gives the pairs (d, 0) of two rows
+    // -- eight columns of digit plane p in elements 0-7, of plane p + 1 in elements 8-15 -- and (zeros, digits) the pairs (0, d).
+    __device__ inline int quantise_f4(signed char* dst, float inv) const {
+        float u[8];
+        get(u);
+        v16f d01, d23;
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int q = (int)__builtin_amdgcn_fmed3f(rintf(u[i] * inv), -QMAX, QMAX);
+            sum += q;
+            const int q1 = (q + 8) >> 4, q2 = (q1 + 8) >> 4;  // (the extract below is signed; the builtin's type is not)
+            d01[i] = (float)(int)__builtin_amdgcn_sbfe(q, 0, 4);
+            d01[8 + i] = (float)(int)__builtin_amdgcn_sbfe(q1, 0, 4);
+            d23[i] = (float)(int)__builtin_amdgcn_sbfe(q2, 0, 4);
+            d23[8 + i] = (float)((q2 + 8) >> 4);
+        }
+        v16f zero;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+        const v6u lo01 = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(d01, zero, 1.0f);
+        const v6u lo23 = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(d23, zero, 1.0f);
+        const v6u hi01 = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(zero, d01, 1.0f);
+        const v6u hi23 = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(zero, d23, 1.0f);
+        // (dst: word 0 of row 0 for this item's 16-column group; its eight columns are three of the group's six words)
+        auto put = [&](int row, unsigned a, unsigned b, unsigned c) {
+            unsigned* o = reinterpret_cast<unsigned*>(dst) + 4 * row;
+            o[0] = a;  o[32] = b;  o[64] = c;
+        };
+        put(0, lo01[0], lo01[1], lo01[2]);  put(1, lo01[3], lo01[4], lo01[5]);
+        put(2, lo23[0], lo23[1], lo23[2]);  put(3, lo23[3], lo23[4], lo23[5]);
+        put(4, hi01[0], hi01[1], hi01[2]);  put(5, hi01[3], hi01[4], hi01[5]);
+        put(6, hi23[0], hi23[1], hi23[2]);  put(7, hi23[3], hi23[4], hi23[5]);
+        return sum;
+    }
 };
 
 template <bool STAGE_A>
@@ -234,6 +294,30 @@ __device__ inline void input_one_pass(const Ctx& c, const v4u (&r0)[UNR], const 
         const int at = TILED ? (v >> 3) * c.tstride + (v & 7) * 8 : v * 8;
         if (v < c.nvec) local += iv[j].quantise_to(c.xq + at, c.xq + c.chs + at, inv);
     }
+    local = dbf_wave_sum(local);
+    if (c.lane == 0) atomicAdd(&c.misc->sigma[0], local);
+}
+
+// The same for the fp4 x bf6 form: all T threads of the workgroup take part, one vector item each (rows of up to 8 T
+// values), and the destination is the eight-row digit form.
+template <bool STAGE_A, int T>
+__device__ inline void input_one_pass_f4(const Ctx& c, const v4u& r0, const v4u& r1) {
+    InputVec<STAGE_A> iv;
+    const int v = c.tid;
+    iv.r0 = (STAGE_A || v < c.nvec_x) ? r0 : (v4u){0, 0, 0, 0};  // beyond x the product is zero
+    iv.r1 = r1;
+    float mx = v < c.nvec ? iv.absmax() : 0.f;
+    mx = dbf_wave_max(mx);
+    if (c.lane == 0) c.misc->wmax[c.w][0] = mx;
+    __syncthreads();
+    mx = 0.f;
+#pragma unroll
+    for (int i = 0; i < T / 64; ++i) mx = fmaxf(mx, c.misc->wmax[i][0]);
+    const float inv = mx > 0.f ? QMAX / mx : 0.f;
+    if (c.tid == 0) c.misc->scale[0] = mx / QMAX;
+    int local = 0;
+    // (vector item v: column tile v >> 3, 16-column group (v & 7) >> 1, first or second half of that group's six words)
+    if (v < c.nvec) local = iv.quantise_f4(c.xq + (v >> 3) * F4_TILE_BYTES + 4 * ((v & 7) >> 1) + 384 * (v & 1), inv);
     local = dbf_wave_sum(local);
     if (c.lane == 0) atomicAdd(&c.misc->sigma[0], local);
 }
@@ -339,15 +423,23 @@ __device__ inline void input_quantise_chunk(const DbfItem& it, const Ctx& c, int
 // most (a layer alone, a group of three): a wavefront then walks every eighth column tile of a row tile instead of
 // every fourth, and two wavefronts per SIMD fill each other's waits.  Wavefronts 4-7 only stream tiles: the input
 // passes and the epilogue are those of the four-wavefront kernel, done by threads 0-255.
-template <int NCG, bool PIECES, int SHARED, bool SINGLE, int WAVES = 4>
+// F4 (batch 1, rows of up to 4096 columns that take the one-pass prologue): the sign operand goes to the matrix cores as
+// fp4 and the stage input as bf6 digits, v_mfma_f32_16x16x128_f8f6f4.  A nibble mask over a tile's bytes makes TWO bit
+// planes an operand at once (the two nibbles of a byte are neighbouring K slots; the input rows (d, 0) and (0, d) send
+// them to different output columns), so a tile costs 4 matrix instructions of 4 passes and 20 vector instructions
+// instead of 8 and 32.  The sums are integers below 2^24 in fp32: exact, and the result is bit for bit that of the
+// int8 form.
+template <int NCG, bool PIECES, int SHARED, bool SINGLE, int WAVES = 4, bool F4 = false>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(NCG == 1 ? DBF_WAVES_PER_EU : 2)))
 void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long* __restrict__ sync, int n_layers,
                            int use_sync, const uint16_t* __restrict__ x_base,
                            uint16_t* __restrict__ y_base, int batch, int ch_tiles, int wait_limit_us) {
     static_assert(WAVES == 4 || (WAVES == 8 && SHARED == 0 && !PIECES), "eight wavefronts: self-quantising whole-row items only");
+    static_assert(!F4 || (NCG == 1 && !PIECES && SHARED == 0 && SINGLE), "fp4 x bf6: batch 1, whole rows in one chunk");
+    constexpr int PF = F4 ? PF_F4 : PF_DEFAULT;
     extern __shared__ __align__(16) unsigned char smem[];
     const int ncols = 2 * batch;
-    const int chs = ch_tiles * DBF_TILE_COLS + XQ_PAD;
+    const int chs = F4 ? 16 : ch_tiles * DBF_TILE_COLS + XQ_PAD;  // (F4: row r of a tile's block starts at word 4 r)
     Misc* misc = reinterpret_cast<Misc*>(smem);
     signed char* xq = reinterpret_cast<signed char*>(smem + sizeof(Misc));           // [ncols][chs]
     // RING: the operand comes from memory with the tile (SHARED 2 and 3).  ROWS (SHARED 3): the four wavefronts
@@ -357,7 +449,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     constexpr bool RING = SHARED >= 2, ROWS = SHARED == 3;
     constexpr int N_RED = ROWS ? 4 : 2;  // reduction buffers
     constexpr int RT_STEP = ROWS ? 4 : 1;  // row tiles the workgroup works on at a time
-    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + (RING ? 0 : ((ncols * chs + 15) & ~15)));  // [N_RED][ncols][128]
+    int* red = reinterpret_cast<int*>(smem + sizeof(Misc) + (RING ? 0 : F4 ? ch_tiles * F4_TILE_BYTES : ((ncols * chs + 15) & ~15)));  // [N_RED][ncols][128]
 
 #if DBF_PROLOGUE_PRIO
     // (experiment: wavefront priority raised for the prologue.  The arbiter favours older
@@ -533,12 +625,14 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     // (wavefronts 4-7 of an eight-wavefront workgroup stream tiles only.  For the input passes they get a thread index
     //  beyond every range those test, so they only keep the barriers company; of the prologue's loads they issue
     //  the tiles alone -- its wait counts back from the youngest load)
-    const bool streams_only = WAVES > 4 && tid >= 256;
+    const bool streams_only = WAVES > 4 && !F4 && tid >= 256;  // (F4: every thread has a vector item of the input)
+    constexpr int IN_T = F4 ? 64 * WAVES : 256;  // threads that take part in the input passes ...
+    constexpr int IN_U = F4 ? 1 : UNR;           // ... and vector items each of them holds in the one-pass prologue
     cx.tid = streams_only ? (1 << 28) : tid;  cx.lane = lane;  cx.w = w;  cx.batch = batch;
     cx.nvec = it.n_ct * 8;
     cx.nvec_x = it.cols >> 3;
     cx.fast = stage_a || ((it.cols & 7) == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0);
-    const bool one_pass = !SHARED && cx.fast && batch == 1 && cx.nvec <= 256 * UNR && it.n_ct <= ch_tiles;
+    const bool one_pass = !SHARED && cx.fast && batch == 1 && cx.nvec <= IN_T * IN_U && it.n_ct <= ch_tiles;
 
     // Every load of the prologue is issued here, back to back and in order of urgency: the row
     // scales and the input vector FIRST (the workgroup cannot start without them), then the first
@@ -548,19 +642,19 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     // destination named by the wait: addresses are clamped instead of branching, and whatever a
     // lane loaded beyond its range is ignored later.  (The general path below does not use the
     // input registers; for it the loads are merely harmless.)
-    constexpr int RS_WORDS = DBF_MAX_SPAN * DBF_TILE_ROWS / 2 / 256;
+    constexpr int RS_WORDS = DBF_MAX_SPAN * DBF_TILE_ROWS / 2 / IN_T;
     unsigned rs_reg[RS_WORDS];
     v4u in0[UNR], in1[UNR];
     if (!streams_only) {
         const int rs_last = it.nrt * (DBF_TILE_ROWS / 2) - 1;
 #pragma unroll
         for (int q = 0; q < RS_WORDS; ++q) {
-            const unsigned* p = reinterpret_cast<const unsigned*>(it.row_scale) + min(tid + 256 * q, rs_last);
+            const unsigned* p = reinterpret_cast<const unsigned*>(it.row_scale) + min(tid + IN_T * q, rs_last);
             asm volatile("global_load_dword %0, %1, off" : "=v"(rs_reg[q]) : "v"(p) : "memory");
         }
 #pragma unroll
-        for (int j = 0; j < UNR; ++j) {
-            const int v = min(256 * j + tid, cx.nvec - 1);
+        for (int j = 0; j < IN_U; ++j) {
+            const int v = min(IN_T * j + tid, cx.nvec - 1);
             const int vx = max(min(v, cx.nvec_x - 1), 0);
             // A stage: 8 fp32 of t (agent scope: maybe written by another compute die during this
             // launch).  B stage: 8 fp16 of x and of b; if x cannot be read in 16-byte pieces
@@ -584,14 +678,15 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
     for (int q = 0; q < RS_WORDS; ++q) asm volatile("" : "+v"(rs_reg[q]));
 #pragma unroll
-    for (int j = 0; j < UNR; ++j) asm volatile("" : "+v"(in0[j]), "+v"(in1[j]));
+    for (int j = 0; j < IN_U; ++j) asm volatile("" : "+v"(in0[j]), "+v"(in1[j]));
 
-    for (int i = tid; i < N_RED * RB_STRIDE * ncols; i += 64 * WAVES) red[i] = 0;
+    const int rcols = F4 ? 4 : ncols;  // operand columns of a reduction buffer (F4: the four digits)
+    for (int i = tid; i < N_RED * RB_STRIDE * rcols; i += 64 * WAVES) red[i] = 0;
     if (tid < DBF_MAX_BATCH) misc->sigma[tid] = 0;
     // row scales: read by the epilogues, which come after several barriers
 #pragma unroll
     for (int q = 0; q < RS_WORDS; ++q) {
-        const int idx = tid + 256 * q;
+        const int idx = tid + IN_T * q;
         if (!streams_only && 2 * idx < it.nrt * DBF_TILE_ROWS) reinterpret_cast<unsigned*>(misc->rscale)[idx] = rs_reg[q];
     }
 
@@ -600,22 +695,30 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             misc->scale[tid] = reinterpret_cast<const float*>(it.q_in)[tid];
             misc->sigma[tid] = reinterpret_cast<const int*>(it.q_in + 64)[tid];
         }
+    } else if (one_pass && F4) {
+        if (stage_a) input_one_pass_f4<true, IN_T>(cx, in0[0], in1[0]); else input_one_pass_f4<false, IN_T>(cx, in0[0], in1[0]);
     } else if (one_pass) {
         if (stage_a) input_one_pass<true>(cx, in0, in1); else input_one_pass<false>(cx, in0, in1);
+    } else if (F4) {
+        // (the launcher takes this form only for launches whose rows all take the one-pass prologue; should one not, its
+        //  outputs say so like those of a wait that gave up)
+        if (tid == 0) misc->gave_up = 1;
     } else {
         if (stage_a) input_scales<true, IN_W>(it, cx); else input_scales<false, IN_W>(it, cx);
     }
 
     v4i acc[NCG][8];
+    v4f accf[4];  // F4: sums of bit planes s and 4 + s (operand columns 0-3 and 4-7: the four digits)
     // operand row this lane feeds to the matrix instruction (unused columns alias a valid row)
     int xrow[NCG];
 #pragma unroll
     for (int gi = 0; gi < NCG; ++gi) {
         const int col = 16 * gi + c;
-        xrow[gi] = (col < ncols ? col : col % ncols) * chs + 16 * g;
+        xrow[gi] = F4 ? (c & 7) * chs + 4 * g : (col < ncols ? col : col % ncols) * chs + 16 * g;
     }
     // one pass: the whole row is in LDS at its own column offsets; otherwise LDS holds the current chunk
-    const int xo_base = one_pass ? ct_first * 64 : 0;
+    constexpr int X_TILE = F4 ? F4_TILE_BYTES : DBF_TILE_COLS;  // operand bytes per column tile and row
+    const int xo_base = one_pass ? ct_first * X_TILE : 0;
     // epilogue coordinates: thread -> (row rho of the tile, batch rows bi = tid>>7, +2, ...)
     const int rho = tid & 127;
     const int e_s = rho >> 4;
@@ -630,6 +733,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     for (int gi = 0; gi < NCG; ++gi)
 #pragma unroll
         for (int s = 0; s < 8; ++s) acc[gi][s] = (v4i){0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) accf[s] = (v4f){0.f, 0.f, 0.f, 0.f};
     for (;;) {  // chunks of columns (a single one unless the batch is large)
         if (SHARED == 1) {
             // columns [64 c0, 64 cend) of the 2 * batch planes, 16 bytes per thread and round
@@ -659,11 +764,17 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             // registers; per tile only the lane offset is added.
             static_assert(PF % 2 == 0, "two operand register sets alternate");
             v4i xr[2][NCG];
+            v8i xr6[2];  // F4: 32 bf6 values, 24 bytes
             const signed char* xp[NCG];
+            auto read6 = [&](int set, const signed char* at) {
+                const int* p = reinterpret_cast<const int*>(at);  // (six words, 128 bytes apart)
+                xr6[set] = (v8i){p[0], p[32], p[64], p[96], p[128], p[160], 0, 0};
+            };
 #pragma unroll
             for (int gi = 0; gi < NCG; ++gi) {
-                xp[gi] = xq + xrow[gi] + xo_base + w * 64;
-                if (!RING) xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
+                xp[gi] = xq + xrow[gi] + xo_base + w * X_TILE;
+                if (F4) read6(0, xp[gi]);
+                else if (!RING) xr[0][gi] = *reinterpret_cast<const v4i*>(xp[gi]);
             }
             // (one group = PF tiles; `fresh`: the group's first tile starts the row tile's sums)
             auto group = [&](auto fresh) {
@@ -676,11 +787,26 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
 #pragma unroll
                 for (int j = 0; j < PF; ++j) {
 #pragma unroll
-                    for (int gi = 0; gi < NCG; ++gi)
-                        if (!RING) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * WAVES * DBF_TILE_COLS);
+                    for (int gi = 0; gi < NCG; ++gi) {
+                        if (F4) read6((j + 1) & 1, xp[gi] + (j + 1) * WAVES * X_TILE);
+                        else if (!RING) xr[(j + 1) & 1][gi] = *reinterpret_cast<const v4i*>(xp[gi] + (j + 1) * WAVES * DBF_TILE_COLS);
+                    }
                     wait_slot(j);
+                    if (F4) {
+                        // planes s and 4 + s: the nibble mask 0x1 << s leaves fp4 0.5 / 1 / 2 in both nibbles of a byte; bit 3 of
+                        // a nibble alone would be the sign of a zero, so planes 3 and 7 are moved to bit 2 first (2 again)
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) {
+                        for (int s = 0; s < 4; ++s) {
+                            const uint32_t msk = s < 3 ? 0x11111111u << s : 0x44444444u;
+                            const int sh = s < 3 ? 0 : 1;
+                            const v8i a = {(int)((buf[j].x >> sh) & msk), (int)((buf[j].y >> sh) & msk),
+                                           (int)((buf[j].z >> sh) & msk), (int)((buf[j].w >> sh) & msk), 0, 0, 0, 0};
+                            // (formats: A fp4, B bf6; no scales)
+                            accf[s] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, xr6[j & 1], accf[s], 4, 3, 0, 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int s = 0; s < (F4 ? 0 : 8); ++s) {
                         const uint32_t msk = 0x01010101u << s;
                         v4i a;
                         a.x = (int)(buf[j].x & msk);
@@ -697,7 +823,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                              g_ok & (int)(g_ct + CT_STEP * j < cend));
                 }
 #pragma unroll
-                for (int gi = 0; gi < NCG; ++gi) xp[gi] += PF * WAVES * DBF_TILE_COLS;
+                for (int gi = 0; gi < NCG; ++gi) xp[gi] += PF * WAVES * X_TILE;
                 const int wrap = (int)(p_i + PF == steps);  // (steps is a multiple of PF)
                 p_i = wrap ? 0 : p_i + PF;
                 p_rt += wrap;
@@ -722,9 +848,23 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             // cleared by its readers one barrier before anybody adds to it again.
             // (ROWS: nothing to combine -- every wavefront has a row tile's whole sums -- but the buffers bring them
             // into the layout of the epilogue: one per wavefront, and a second barrier before they are reused.)
-            int* rb = red + (ROWS ? w : (tile_no & 1)) * RB_STRIDE * ncols;
+            int* rb = red + (ROWS ? w : (tile_no & 1)) * RB_STRIDE * rcols;
+            if (F4) {
+                // accf[s][i] of lane (g, c): row 4 g + i of plane s (c < 4) or 4 + s (c in 4..7), digit c & 3, times the
+                // operand value of the plane's bit (0.5, 1, 2, 2).  Doubled they are integers; the four digits keep a
+                // reduction column each (32 lanes add to 32 different words), and the epilogue puts them together.
+                if (c < 8) {
+                    int* col = rb + (c & 3) * RB_STRIDE + ((c & 4) ? 64 : 0) + 4 * g;
 #pragma unroll
-            for (int gi = 0; gi < NCG; ++gi) {
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) atomicAdd(&col[16 * s + i], (int)(accf[s][i] + accf[s][i]));
+                }
+#pragma unroll
+                for (int s = 0; s < 4; ++s) accf[s] = (v4f){0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int gi = 0; gi < (F4 ? 0 : NCG); ++gi) {
                 const int col = 16 * gi + c;
                 if (col < ncols) {
 #pragma unroll
@@ -742,7 +882,7 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             __syncthreads();
             for (int r4 = 0; r4 < RT_STEP && rtl + r4 < it.nrt; ++r4) {  // the row tiles just finished
                 const int rte = rtl + r4;
-                if (ROWS) rb = red + r4 * RB_STRIDE * ncols;
+                if (ROWS) rb = red + r4 * RB_STRIDE * rcols;
                 const int row = it.row0 + rte * DBF_TILE_ROWS + rho;
                 const float rscale = half_bits_to_float(misc->rscale[rte * DBF_TILE_ROWS + rho]);
                 // (threads 0-255; those of wavefronts 4-7 start beyond the batch)
@@ -751,7 +891,18 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                     int vh = ph[0], vl = ph[RB_STRIDE];
                     ph[0] = 0;
                     ph[RB_STRIDE] = 0;
-                    if (e_s < 7) {
+                    if (F4) {
+                        // four digit columns, each twice the operand value of the row's plane (1, 2, 4, 4) times the digit
+                        // sum: v = d0 + 16 d1 + 256 d2 + 4096 d3; vh * 256 + vl below gives it back
+                        const int d2 = ph[2 * RB_STRIDE], d3 = ph[3 * RB_STRIDE];
+                        ph[2 * RB_STRIDE] = 0;
+                        ph[3 * RB_STRIDE] = 0;
+                        const int down = (e_s & 3) < 2 ? (e_s & 3) : 2;
+                        const int v = (int)((unsigned)(vh >> down) + ((unsigned)(vl >> down) << 4) + ((unsigned)(d2 >> down) << 8) +
+                                            ((unsigned)(d3 >> down) << 12));
+                        vl = v & 255;
+                        vh = v >> 8;
+                    } else if (e_s < 7) {
                         vh >>= e_s;
                         vl >>= e_s;
                     } else {
@@ -776,7 +927,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                         // agent-scope store: written through to memory, where the A-stage
                         // workgroups of other compute dies read it (padded rows have scale 0)
                         __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + (size_t)bi * it.t_stride + row,
-                                           __builtin_bit_cast(unsigned, val), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                           (F4 && misc->gave_up) ? 0x7FC00000u : __builtin_bit_cast(unsigned, val),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
             }
@@ -909,8 +1061,17 @@ __global__ __launch_bounds__(256) void dbf_quantise_inputs_kernel(const DbfStage
 constexpr size_t WIDE_WG_SLACK = 32 * DBF_TILE_COLS;  // extra LDS of an eight-wavefront workgroup (see the launcher)
 constexpr int WIDE_WG_MIN_COL_TILES = 32;         // rows shorter than this keep four wavefronts
 
-size_t mfma_smem_bytes(int batch, int ch_tiles, int shared_q) {
+size_t mfma_smem_bytes(int batch, int ch_tiles, int shared_q, bool f4 = false) {
     const int ncols = 2 * batch;
+    // (F4: one operand column per reduction buffer; the operand reads of a row tile's padded steps run past the last
+    //  operand row, further than the buffers reach if the row is short: slack for those)
+    if (f4) {
+        const size_t red = 2 * 4 * (size_t)RB_STRIDE * sizeof(int);  // two buffers of four digit columns
+        const int steps = ((ch_tiles + WAVES_F4 - 1) / WAVES_F4 + PF_F4 - 1) / PF_F4 * PF_F4;  // of a wavefront per row tile, padded
+        const long over = (long)(WAVES_F4 - 1 + WAVES_F4 * steps + 1 - ch_tiles) * F4_TILE_BYTES;
+        const size_t slack = over > (long)red ? (size_t)((over - (long)red + 15) & ~15L) : 0;
+        return sizeof(Misc) + (size_t)ch_tiles * F4_TILE_BYTES + red + slack;
+    }
     const size_t xq = shared_q >= 2 ? 0 : ((size_t)ncols * (ch_tiles * DBF_TILE_COLS + XQ_PAD) + 15) & ~(size_t)15;
     return sizeof(Misc) + xq + (shared_q == 3 ? 4 : 2) * (size_t)RB_STRIDE * ncols * sizeof(int);
 }
@@ -951,6 +1112,9 @@ hipError_t dbf_mfma_prepare() {
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<2, false, 3, false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dbf_items_mfma_kernel<1, false, 0, true, WAVES_F4, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         if (e != hipSuccess) (void)hipGetLastError();
         return e;
     }();
@@ -970,7 +1134,8 @@ hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, in
 
 hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned long long* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, int pieces, int shared_q, int wait_limit_us, hipStream_t stream) {
+                                 int max_cols, int pieces, int shared_q, int one_pass_rows, int wait_limit_us,
+                                 hipStream_t stream) {
     if (n_items <= 0) return hipSuccess;
     const uint16_t* x = static_cast<const uint16_t*>(x_base);
     uint16_t* y = static_cast<uint16_t*>(y_base);
@@ -1003,7 +1168,21 @@ hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned lon
     else if (pieces)
         hipLaunchKernelGGL((dbf_items_mfma_kernel<1, true, 0, false>), dim3(n_items), dim3(256), smem, stream, items, sync,
                            n_layers, use_sync, x, y, batch, ch_tiles, wait_limit_us);
-    else if (batch <= 8 && ch_tiles >= dbf_col_tiles(max_cols) && n_items <= dbf_tune(DBF_TUNE_WIDE_WG_MAX_ITEMS) &&
+    else if (batch == 1 && one_pass_rows && dbf_col_tiles(max_cols) <= F4_MAX_COL_TILES &&
+             dbf_col_tiles(max_cols) >= WIDE_WG_MIN_COL_TILES && n_items <= dbf_tune(DBF_TUNE_FP4_MAX_ITEMS)) {
+        // (every row of the launch takes the one-pass prologue, and the launch does not fill the chip: the fp4 x bf6 form.
+        //  One layer alone, back to back, int8 form with four / eight wavefronts / this form: 4096 x 4096 at k = 4096 11.6 /
+        //  11.0 / 10.8 us, k = 2048 10.5 / 10.1 / 9.8, 2048 columns 9.3 / 9.0 / 8.7, 4096 -> 11008 11.2 / 11.2 / 10.9; 1024 columns
+        //  8.4 / 8.4 / 8.6, hence the column limit.  Streams lose with it -- 512 layers of 4096 x 4096 5.9 against 6.1 TB/s, 256 layers
+        //  5.5 / 5.9, 1024 x 4096 at 1 bit 3.3 / 4.3 -- its operand rows fill LDS at two workgroups per compute unit, and
+        //  its prologue is the longer one)
+        const hipError_t raised = dbf_mfma_prepare();  // (done when the plan was built; repeated calls cost nothing)
+        if (raised != hipSuccess) return raised;
+        const int tiles4 = (dbf_col_tiles(max_cols) + 3) & ~3;
+        hipLaunchKernelGGL((dbf_items_mfma_kernel<1, false, 0, true, WAVES_F4, true>), dim3(n_items), dim3(64 * WAVES_F4),
+                           mfma_smem_bytes(1, tiles4, 0, true), stream, items, sync, n_layers, use_sync, x, y, batch, tiles4,
+                           wait_limit_us);
+    } else if (batch <= 8 && ch_tiles >= dbf_col_tiles(max_cols) && n_items <= dbf_tune(DBF_TUNE_WIDE_WG_MAX_ITEMS) &&
              dbf_col_tiles(max_cols) >= WIDE_WG_MIN_COL_TILES)
         // (few items of long rows: eight wavefronts each.  One layer alone, back to back: 4096 x 4096 11.6 -> 11.1 us,
         //  2048 columns 9.4 -> 9.1, 512 columns 8.3 -> 9.1: the wider workgroup costs 0.4 us to start.  A wavefront's

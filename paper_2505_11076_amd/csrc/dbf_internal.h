@@ -102,6 +102,7 @@ struct DbfPlan {
     int piece_row_tiles;        // row tiles of the larger stage over all layers (batch 2 takes d_items_p only for few)
     int rows_ok;                // the items of d_items_s are long enough to give each wavefront a row tile of its own
     int long_rows;              // stage inputs are quantised once per call at every batch (see build_plan)
+    int x_vec_ok;               // every layer's x row at batch 1 starts at a multiple of 8 values and has a multiple of 8 columns
     // Counters of the one-launch kernel, 64 bits each, zero when the plan is built and only ever growing
     // (nothing is reset, so a workgroup that gives up its wait leaves them consistent):
     //   [layer]            B-stage row tiles published so far, over all launches of this plan

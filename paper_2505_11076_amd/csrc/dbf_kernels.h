@@ -25,9 +25,13 @@ hipError_t dbf_launch_stage_valu(bool stage_a, const DbfStage* table, const DbfW
 //   shared_q != 0: the input of the items' stage has been quantised for the whole launch by
 //   dbf_launch_quantise_inputs (same stream, earlier); the items copy it instead of quantising it themselves.
 //   Only with use_sync == 0 and pieces == 0.
+//   one_pass_rows != 0: the caller has checked that every B-stage row of the launch can be read in 16-byte pieces
+//   (columns a multiple of 8, 16-byte aligned address at this batch), so that at batch 1 rows of up to
+//   dbf_mfma_one_pass_cols() columns all take the one-pass prologue -- which the fp4 x bf6 form of the kernel needs.
 hipError_t dbf_launch_items_mfma(const DbfItem* items, int n_items, unsigned long long* sync, int n_layers,
                                  int use_sync, const void* x_base, void* y_base, int batch,
-                                 int max_cols, int pieces, int shared_q, int wait_limit_us, hipStream_t stream);
+                                 int max_cols, int pieces, int shared_q, int one_pass_rows, int wait_limit_us,
+                                 hipStream_t stream);
 // Quantises the input of one stage (stage_a = 0: x times b of every layer, 1: the middle activations) of the
 // n_layers stages in d_stages for `batch` rows into the stages' q_in buffers.
 hipError_t dbf_launch_quantise_inputs(const DbfStage* d_stages, int n_layers, int stage_a, const void* x_base,

@@ -245,15 +245,15 @@ def test_tuning_hooks_have_defaults_ranges_and_a_reset():
                 B.TUNE_PIECE_MAX_ROW_TILES: 768, B.TUNE_STACK_SPAN_B: 0, B.TUNE_STACK_SPAN_A: 0, B.TUNE_SHARED_Q: -1,
                 B.TUNE_SHARED_MIN_BATCH: 2, B.TUNE_SHARED_LDS_KB: 52, B.TUNE_WAIT_LIMIT_US: 250000,
                 B.TUNE_LONG_ROWS: -1, B.TUNE_GEMM_SPLITS: -1, B.TUNE_FUSED_MIN_B_ITEMS: 1024,
-                B.TUNE_WIDE_WG_MAX_ITEMS: 256}
-    assert len(defaults) == 15
+                B.TUNE_WIDE_WG_MAX_ITEMS: 256, B.TUNE_FP4_MAX_ITEMS: 256}
+    assert len(defaults) == 16
     for knob, val in defaults.items():
         assert B.dbf_tuning_get(knob) == val
     for knob, bad in ((B.TUNE_COL_PIECES, -2), (B.TUNE_COL_PIECES, 65), (B.TUNE_STACK_SPAN_B, 17), (B.TUNE_SHARED_Q, 4),
                       (B.TUNE_SHARED_MIN_BATCH, 0), (B.TUNE_SHARED_LDS_KB, 65), (B.TUNE_WAIT_LIMIT_US, -1),
-                      (B.TUNE_PIECE_MIN_TILES, 0), (B.TUNE_LONG_ROWS, 2), (B.TUNE_GEMM_SPLITS, 1025), (B.TUNE_GEMM_SPLITS, -2), (B.TUNE_FUSED_MIN_B_ITEMS, -1), (B.TUNE_WIDE_WG_MAX_ITEMS, -1), (15, 0), (-1, 0)):
+                      (B.TUNE_PIECE_MIN_TILES, 0), (B.TUNE_LONG_ROWS, 2), (B.TUNE_GEMM_SPLITS, 1025), (B.TUNE_GEMM_SPLITS, -2), (B.TUNE_FUSED_MIN_B_ITEMS, -1), (B.TUNE_WIDE_WG_MAX_ITEMS, -1), (B.TUNE_FP4_MAX_ITEMS, -1), (16, 0), (-1, 0)):
         assert lib.dbf_tuning_set(knob, bad) == B.DBF_EINVAL
-    assert B.dbf_tuning_get(15) == -2 ** 31 and B.dbf_tuning_get(-1) == -2 ** 31
+    assert B.dbf_tuning_get(16) == -2 ** 31 and B.dbf_tuning_get(-1) == -2 ** 31
     B.dbf_tuning_set(B.TUNE_WAIT_LIMIT_US, 0)
     B.dbf_tuning_set(B.TUNE_COL_PIECES, 3)
     assert B.dbf_tuning_get(B.TUNE_WAIT_LIMIT_US) == 0 and B.dbf_tuning_get(B.TUNE_COL_PIECES) == 3

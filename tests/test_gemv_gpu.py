@@ -463,6 +463,68 @@ def test_eight_wavefront_workgroups_equal_four_bit_for_bit(batch):
                 "eight wavefronts %dx%d" % (L.n_out, L.n_in))
 
 
+def test_fp4_sign_operands_equal_the_int8_form_bit_for_bit():
+    """Batch-1 launches of few items over stage inputs of 2048-4096 columns feed the matrix cores fp4 sign operands
+    and the stage input as four signed hexadecimal digits in bf6; the sums are integers below 2^24 in fp32, so the
+    result must be the int8 form's bit for bit: a layer alone, stacks in one launch and in two, launches larger than
+    the rule would give this form (by the knob), repeated calls, and an x that cannot be read in 16-byte pieces
+    (which takes the int8 form whatever the knob says)."""
+    shapes = [(4096, 600, 2100), (2304, 520, 4096), (4096, 300, 2056), (2048, 1000, 3000)]
+    Ls = [I.make_layer(n_in, n_out, k, seed=I.seed_for(5, 1300 + i)) for i, (n_in, n_out, k) in enumerate(shapes)]
+    Xs = [I.make_activations(1, L.n_in, I.seed_for(5, 1310 + i)) for i, L in enumerate(Ls)]
+    # an outlier and exact zeros in one input: digits at both ends of their range
+    Xs[0] = Xs[0].copy()
+    Xs[0][0, 5] = np.array([60000.0], np.float16).view(np.uint16)[0]
+    Xs[0][0, 100:200] = 0
+
+    def run(max_items):
+        B.dbf_tuning_reset()
+        B.dbf_tuning_set(B.TUNE_FP4_MAX_ITEMS, max_items)
+        layers = [G.pack(L) for L in Ls]
+        stack = B.dbf_stack_create(layers)
+        outs = []
+        try:
+            for rep in range(2):
+                for L, X, layer in zip(Ls, Xs, layers):
+                    y = torch.full((1, L.n_out), float("nan"), dtype=torch.float16, device="cuda")
+                    B.dbf_gemv(layer, G.f16_to_dev(X).data_ptr(), y.data_ptr(), 1, G.stream_handle())
+                    torch.cuda.synchronize()
+                    outs.append(y.cpu().view(torch.int16).numpy().copy())
+                x_all = torch.cat([G.f16_to_dev(X).reshape(-1) for X in Xs])
+                y_all = torch.full((sum(L.n_out for L in Ls),), float("nan"), dtype=torch.float16, device="cuda")
+                for kind in (B.GEMV_AUTO, B.GEMV_MFMA, B.GEMV_MFMA_SPLIT):
+                    B.dbf_stack_gemv(stack, x_all.data_ptr(), y_all.data_ptr(), 1, G.stream_handle(), kind)
+                    torch.cuda.synchronize()
+                    outs.append(y_all.cpu().view(torch.int16).numpy().copy())
+            # x two bytes off a 16-byte boundary
+            L, X, layer = Ls[0], Xs[0], layers[0]
+            buf = torch.zeros(L.n_in + 8, dtype=torch.float16, device="cuda")
+            buf[1:1 + L.n_in] = G.f16_to_dev(X).reshape(-1)
+            y = torch.full((1, L.n_out), float("nan"), dtype=torch.float16, device="cuda")
+            B.dbf_gemv(layer, buf.data_ptr() + 2, y.data_ptr(), 1, G.stream_handle())
+            torch.cuda.synchronize()
+            outs.append(y.cpu().view(torch.int16).numpy().copy())
+            assert B.dbf_stack_sync_timeouts(stack) == 0
+        finally:
+            stack.close()
+            for l in layers:
+                l.close()
+            B.dbf_tuning_reset()
+        return outs
+
+    G.say("sign operands: int8")
+    int8 = run(0)
+    G.say("sign operands: fp4, every eligible launch")
+    fp4 = run(1 << 20)
+    assert len(int8) == len(fp4)
+    for i, (a, b) in enumerate(zip(int8, fp4)):
+        assert np.array_equal(a, b), i
+    assert np.array_equal(fp4[-1], fp4[0])  # the misaligned call gives what the aligned one gave
+    for L, X, y_bits in zip(Ls, Xs, fp4[:4]):
+        G.check(O.f16_bits_to_f64(y_bits.view(np.uint16)).reshape(1, L.n_out), O.forward_from_packed(X, L, "staged"),
+                "fp4 operands %dx%d" % (L.n_out, L.n_in))
+
+
 @pytest.mark.parametrize("batch", [1, 3])
 def test_groups_of_layers_sharing_one_input(batch):
     """q, k, v read one activation vector, gate and up another: a grouped stack takes one x block
