@@ -158,6 +158,8 @@ def main():
                          "same counters read for the 1 GiB copy / 1 GiB read of that run, and write profiles/traffic.json "
                          "for the workload named by the other flags")
     ap.add_argument("--no-table4", action="store_true", help="skip the 1- and 2-bit rows of the second workload")
+    ap.add_argument("--knob", action="append", default=[], metavar="K=V",
+                    help="set tuning knob K (number, include/dbf.h) to V before anything is packed; repeatable; for A/B runs")
     args = ap.parse_args()
     if args.traffic_from:
         print(json.dumps(traffic_from(args)))
@@ -176,6 +178,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.lib()
+    for kv in args.knob:
+        knob, val = kv.split("=")
+        B.dbf_tuning_set(int(knob), int(val))
     kind = {"auto": B.GEMV_AUTO, "valu": B.GEMV_VALU, "mfma": B.GEMV_MFMA, "mfma_split": B.GEMV_MFMA_SPLIT}[args.kind]
     proto = Protocol(torch, args.steps, args.warmup, args.settle_ms)
     if args.prefill_only:
@@ -263,9 +268,9 @@ def main():
         # per-launch events of the timed entry point add a few microseconds of launch latency).
         if batch == 1 or args.kind != "auto":
             # (<operand column groups, column pieces, shared quantised input, single chunk, wavefronts per
-            #  workgroup>: rows of up to 14080 columns stay in LDS as one chunk at batch 1, which all benchmark
-            #  shapes are)
-            dom, dom_ms, dom_bytes = ("dbf_items_mfma_kernel<%d, false, 0, %s, 4> (B and A stages fused)"
+            #  workgroup, fp4 sign operands>: rows of up to 14080 columns stay in LDS as one chunk at batch 1,
+            #  which all benchmark shapes are)
+            dom, dom_ms, dom_bytes = ("dbf_items_mfma_kernel<%d, false, 0, %s, 4, false> (B and A stages fused)"
                                       % (ncg, "true" if batch == 1 else "true|false")), ms_per_step, bytes_layer * R
         elif msB_avg >= msA_avg:  # batches of 2 and more: input quantiser + items, per stage
             dom, dom_ms, dom_bytes = "B-stage launches (dbf_quantise_inputs_kernel + dbf_items_mfma_kernel<%d, false, 1|2|3, false>)" % ncg, msB_avg, bytes_b * R
