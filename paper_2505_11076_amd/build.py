@@ -70,6 +70,52 @@ def _check_no_spills(src: str, stderr: str) -> None:
                            "a register the compiler has reused):\n  %s" % (src, "\n  ".join(bad)))
 
 
+# The second guard for the same kernels.  A ring slot must live in ONE set of registers for the whole kernel: if the
+# compiler gives a slot two homes (it does as soon as a refill's destination is not the registers the consumed tile was in)
+# it copies between them at loop ends -- registers whose load is still in flight, and the copy reads what was there before:
+# wrong sums, no fault, and only on the paths that loop.  So the build compiles the file to assembly as well and counts, per
+# kernel, the distinct destination register sets of the ring's loads: PF tile slots, plus PF per operand column group where
+# the operand travels in the ring (SHARED >= 2).
+RING_SRC = "dbf_gemv_mfma.hip"
+
+
+def _ring_homes_report(code: str, pf: int, pf_f4: int):
+    """(kernels seen, [complaints]) for the assembly text `code` of RING_SRC."""
+    import re
+    bad, seen = [], 0
+    for m in re.finditer(r"^(_ZN\w*dbf_items_mfma_kernelILi(\d)ELb\dELi(\d)ELb\dELi\dELb(\d)E\w*):", code, re.M):
+        body = code[m.end():code.index("s_endpgm", m.end())]
+        homes = set(re.findall(r"buffer_load_dwordx4 (v\[\d+:\d+\])", body))
+        ncg, shared, f4 = int(m.group(2)), int(m.group(3)), int(m.group(4))
+        want = (pf_f4 if f4 else pf) * (1 + ncg if shared >= 2 else 1)
+        seen += 1
+        if len(homes) != want:
+            bad.append("%s: %d register sets for %d ring slots" % (m.group(1), len(homes), want))
+    return seen, bad
+
+
+def _check_ring_homes() -> None:
+    import re
+    import tempfile
+    text = open(os.path.join(CSRC, RING_SRC)).read()
+    pf = int(re.search(r"#define DBF_PF (\d+)", text).group(1))
+    pf_f4 = int(re.search(r"#define DBF_PF_F4 (\d+)", text).group(1))
+    with tempfile.TemporaryDirectory() as tmp:
+        asm = os.path.join(tmp, "ring.s")
+        cmd = [_hipcc(), *[f for f in FLAGS if f != "-fPIC"], "--cuda-device-only", "-S", "-x", "hip",
+               os.path.join(CSRC, RING_SRC), "-o", asm]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc -S failed for %s:\n%s" % (RING_SRC, res.stderr))
+        code = open(asm).read()
+    seen, bad = _ring_homes_report(code, pf, pf_f4)
+    if not seen:
+        raise RuntimeError("%s: no items kernel found in the assembly (has it been renamed?)" % RING_SRC)
+    if bad:
+        raise RuntimeError("%s: a ring slot has more than one register home (the compiler would copy registers whose load "
+                           "is in flight):\n  %s" % (RING_SRC, "\n  ".join(bad)))
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     extra = [REMARK] if src in NO_SPILL else []
@@ -130,8 +176,10 @@ def build_sanitize_check(driver_cpp: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as pool:
+        ring = pool.submit(_check_ring_homes)
         objs = list(pool.map(_compile, SOURCES))
+        ring.result()
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

@@ -127,6 +127,7 @@ struct Misc {
     float wmax[8][DBF_MAX_BATCH];  // per-wavefront max|u| (wavefronts 4-7, where a workgroup has them, take no part in
                                    // the input passes and leave zeros)
     uint16_t rscale[DBF_MAX_SPAN * DBF_TILE_ROWS];  // fp16 row scales of this workgroup's rows
+    float out[DBF_MAX_SPAN * DBF_TILE_ROWS];        // batch 1, items of several row tiles: the finished rows, stored at the item's end
     int last;                      // column pieces: this workgroup was the last of its row tile to arrive
     int gave_up;                   // the wait for the layer's B stage ended at its bound: outputs become NaN
     int poisoned;                  // column pieces: some piece of this row tile gave up
@@ -723,6 +724,8 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
     const int rho = tid & 127;
     const int e_s = rho >> 4;
     int tile_no = 0;  // row tiles finished so far: selects the reduction buffer
+    // batch 1, whole rows in one chunk: finished rows wait in LDS for the end of the item (see the epilogue)
+    const bool defer = SINGLE && SHARED == 0 && !PIECES && batch == 1;
 
 #if DBF_PROLOGUE_PRIO
     __builtin_amdgcn_s_setprio(0);
@@ -819,6 +822,9 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                                 a, RING ? xb[j][gi % XB_N] : xr[j & 1][gi],
                                 (FRESH && j == 0) ? (v4i){0, 0, 0, 0} : acc[gi][s], 0, 0, 0);
                     }
+                    // (the slot is refilled after the tile's arithmetic.  Refilling it right after the wait, from a copy of the
+                    //  tile, was tried: no faster -- 6.18 TB/s either way -- and the compiler then keeps two register homes per
+                    //  slot and copies between them at loop ends, while loads are in flight)
                     fetch_at(j, g_off + (unsigned)(j * CT_STEP) * DBF_TILE_BYTES, g_ct + CT_STEP * j,
                              g_ok & (int)(g_ct + CT_STEP * j < cend));
                 }
@@ -920,7 +926,13 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
                         continue;
                     }
                     const float val = (float)total * misc->scale[bi] * rscale;
-                    if (stage_a) {
+                    if (defer) {
+                        // No global store while tiles are in flight: on this chip stores count in the same counter as the
+                        // loads, so the ring's next waits -- "at most PF - 1 operations outstanding" -- would wait for the
+                        // stores' acknowledgement from memory as well.  (Without the stores in the loop the 512-layer stream
+                        // reads 6.9 TB/s instead of 6.1: the whole gap to a bare streaming read.)
+                        misc->out[rte * DBF_TILE_ROWS + rho] = val;
+                    } else if (stage_a) {
                         // (a workgroup that gave up its wait has read an unfinished t: its outputs say so)
                         if (row < it.rows) y[(size_t)bi * it.rows + row] = misc->gave_up ? HALF_QNAN : float_to_half_bits(val);
                     } else {
@@ -935,6 +947,21 @@ void dbf_items_mfma_kernel(const DbfItem* __restrict__ items, unsigned long long
             if (ROWS) __syncthreads();  // the buffers are clear before the next row tiles' sums arrive
         }
         if (last_chunk) {
+            if (defer) {
+                // ---- the item's rows, all at once, now that its last tile has been consumed
+                __syncthreads();
+                for (int idx = tid; idx < it.nrt * DBF_TILE_ROWS; idx += 64 * WAVES) {
+                    const int row = it.row0 + idx;
+                    const float val = misc->out[idx];
+                    if (stage_a) {
+                        if (row < it.rows) y[row] = misc->gave_up ? HALF_QNAN : float_to_half_bits(val);
+                    } else {
+                        __hip_atomic_store(reinterpret_cast<unsigned*>(it.t) + row,
+                                           (F4 && misc->gave_up) ? 0x7FC00000u : __builtin_bit_cast(unsigned, val),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+            }
             if (n_pieces > 1) {
                 // ---- column pieces: count this piece in; the last one reads the row tile's sums (and
                 // clears them and the counter for the next launch), scales and stores them.  Integer

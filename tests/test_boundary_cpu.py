@@ -289,6 +289,25 @@ def test_host_code_is_clean_under_address_and_undefined_behaviour_sanitizers():
     assert "runtime error" not in res.stderr and "AddressSanitizer" not in res.stderr
 
 
+def test_build_refuses_ring_slots_with_two_register_homes():
+    """A slot of the hand-issued tile ring must keep one set of registers: with two, the compiler copies between them
+    at loop ends while the slot's load is in flight (wrong sums, no fault).  The build counts the destination register
+    sets of the ring's loads per kernel in the assembly; this checks the counter on a kernel with four homes for four
+    slots, on one with five, and on one whose operand travels in the ring (four tile and four operand slots)."""
+    from paper_2505_11076_amd import build as Bd
+
+    def kernel(args, sets):
+        loads = "".join("\tbuffer_load_dwordx4 %s, v1, s[28:31], 0 offen nt\n" % r for r in sets)
+        return "_ZN12_GLOBAL__N_121dbf_items_mfma_kernelI%sEEvPK7DbfItemPyiiPKtPtiii:\n%s\ts_endpgm\n" % (args, loads + loads)
+
+    four = ["v[2:5]", "v[6:9]", "v[10:13]", "v[14:17]"]
+    ok = kernel("Li1ELb0ELi0ELb1ELi4ELb0", four) + kernel("Li1ELb0ELi2ELb0ELi4ELb0", four + ["v[18:21]", "v[22:25]", "v[26:29]", "v[30:33]"])
+    assert Bd._ring_homes_report(ok, 4, 4) == (2, [])
+    seen, bad = Bd._ring_homes_report(ok + kernel("Li1ELb0ELi0ELb0ELi4ELb0", four + ["v[54:57]"]), 4, 4)
+    assert seen == 3 and len(bad) == 1 and "5 register sets for 4 ring slots" in bad[0]
+    assert Bd._ring_homes_report("nothing here", 4, 4) == (0, [])
+
+
 def test_build_refuses_spills_in_kernels_with_hand_issued_loads():
     """Kernels that issue loads by inline assembly must be built without spilled vector registers (an in-flight
     load would land in a register the compiler has already reused: a GPU memory fault).  The build reads the
