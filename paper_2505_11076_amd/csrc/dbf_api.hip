@@ -156,12 +156,19 @@ void append_piece_items(std::vector<DbfItem>& out, const DbfStage& st, int layer
 // to within one row tile (balanced_spans).  Asking for half as many items of twice the size helped where it left
 // whole rounds of equal items (512 layers of 4096 x 4096, k = 2048: +2.3 %; 64 of them: +7 %) and cost 2.5-7 % on
 // streams of k = 3072-4096 and of 8192 x 8192 layers: not taken.
-int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows) {
-    const long long WANT_ITEMS = long_rows ? 1024 : 2048;
+int auto_span(const DbfStage& st, long long stage_tiles, bool long_rows, bool uniform) {
+    // (a stage large enough for a thousand items of 512 KiB gets those: one long item per workgroup slot of the chip instead
+    //  of two rounds of 256 KiB -- since an item stores its rows once, at its end, its head and tail weigh more than an
+    //  uneven last round.  512 / 1024 layers of 4096 x 4096, k = 2048, same box: 6.11 -> 6.23-6.29 / 6.24 -> 6.28-6.31 TB/s.
+    //  Eight row tiles forced on smaller launches lose, by up to half on wide rows; and only where all layers have one shape:
+    //  the 224 mixed layers of a 7B decoder at 1.5 bits fell from 6.2 to 5.4 TB/s with it -- one round of items of very
+    //  different lengths.)
+    const bool huge = !long_rows && uniform && stage_tiles >= (1LL << 19);
+    const long long WANT_ITEMS = (long_rows || huge) ? 1024 : 2048;
     const int MAX_AUTO_SPAN = long_rows ? 4 : 8;
     if (!long_rows && st.cols > dbf_mfma_one_pass_cols()) return 4;
     long long item_tiles = stage_tiles / WANT_ITEMS;
-    if (item_tiles > 256) item_tiles = 256;
+    if (item_tiles > (huge ? 512 : 256)) item_tiles = huge ? 512 : 256;
     // (small stages: items of up to 48 KiB as long as that leaves a thousand of them -- 256 layers of 1024 x 4096 at
     //  1 / 1.5 / 2.3 bits per weight 4.05 / 4.52 / 5.19 -> 4.36 / 4.66 / 5.43 TB/s, 64 layers of 4096 x 4096, k = 2048
     //  4.35 -> 4.47)
@@ -258,10 +265,13 @@ int build_plan(const std::vector<DbfStage>& sB, const std::vector<DbfStage>& sA,
     }
     int max_span = 1;
     int phase = 0;
+    bool uniform = true;  // every layer has the shape of the first
+    for (int i = 1; i < n; ++i)
+        if (sB[i].rows != sB[0].rows || sB[i].cols != sB[0].cols || sA[i].rows != sA[0].rows) uniform = false;
     auto pattern_for = [&](const std::vector<int>& given, const DbfStage& st, long long stage_tiles) {
         std::vector<int> v = given;
         if (given.empty()) {  // (a pattern of this layer's own: it starts at its first item)
-            v = balanced_spans(st.n_rt, auto_span(st, stage_tiles, p->long_rows != 0));
+            v = balanced_spans(st.n_rt, auto_span(st, stage_tiles, p->long_rows != 0, uniform));
             phase = 0;
         }
         for (int x : v) max_span = x > max_span ? x : max_span;
